@@ -1,0 +1,202 @@
+"""Python face of the CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this module.  It wraps ``masked_conv_oracle.c`` (built with gcc into
+``liboracle.so`` beside it) and adds the layer-by-layer interpreter for the small test
+networks.  It imports nothing from the HIP package.
+
+Semantics follow the paper's Sec. 3 / Sec. 3.2 / App. A (Alg. 2); see the header of the C
+file for every reading taken where the paper is silent.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "masked_conv_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O3, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O3", "-march=x86-64-v2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+               "-ffp-contract=off", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        lib.oc_param_count.restype = ctypes.c_int
+        lib.oc_out_size.restype = ctypes.c_int
+        lib.oc_out_size.argtypes = [ctypes.c_int] * 5
+        lib.oc_kept_count.restype = ctypes.c_int64
+        lib.oc_kept_count.argtypes = [ctypes.c_double, ctypes.c_int64]
+        lib.oc_compact_rows.restype = ctypes.c_int64
+        lib.oc_compact_rows.argtypes = [u8p, ctypes.c_int64, i32p]
+        lib.oc_masked_conv2d.restype = ctypes.c_int
+        lib.oc_masked_conv2d.argtypes = [i32p, f32p, f32p, f32p, u8p, f32p, f64p]
+        lib.oc_masked_conv2d_rows.restype = ctypes.c_int
+        lib.oc_masked_conv2d_rows.argtypes = [i32p, f32p, f32p, f32p, u8p, i64p, ctypes.c_int64, f32p, f64p]
+        lib.oc_round_bf16.restype = None
+        lib.oc_round_bf16.argtypes = [f32p, ctypes.c_int64]
+        lib.oc_round_f16.restype = None
+        lib.oc_round_f16.argtypes = [f32p, ctypes.c_int64]
+        lib.oc_maxpool2d_nhwc.restype = ctypes.c_int
+        lib.oc_maxpool2d_nhwc.argtypes = [f32p] + [ctypes.c_int] * 7 + [f32p]
+        lib.oc_add_relu.restype = None
+        lib.oc_add_relu.argtypes = [f32p, f32p, ctypes.c_int64, f32p]
+        assert lib.oc_param_count() == 17
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    if a is None:
+        return ctypes.cast(None, ctypes.POINTER(ctype))
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _params(spec) -> np.ndarray:
+    return np.array(
+        [spec.n, spec.c_in, spec.h, spec.w, spec.c_out, spec.kh, spec.kw, spec.stride_h, spec.stride_w,
+         spec.pad_h, spec.pad_w, spec.dil_h, spec.dil_w, 1 if spec.layout == "nchw" else 0,
+         1 if spec.has_bias else 0, 1 if spec.relu else 0, 1 if spec.mask_mode == "spatial" else 0],
+        dtype=np.int32,
+    )
+
+
+def out_size(inp: int, k: int, stride: int, pad: int, dil: int) -> int:
+    return int(_load().oc_out_size(inp, k, stride, pad, dil))
+
+
+def kept_count(sparsity: float, output_size: int) -> int:
+    """Rows that stay in the contraction: output_size - sparsity*output_size (Sec. 3.2), half up."""
+    return int(_load().oc_kept_count(float(sparsity), int(output_size)))
+
+
+def compact_rows(mask: np.ndarray) -> np.ndarray:
+    """Ascending list of the positions whose mask is 1 (Alg. 2, indirection init)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).ravel()
+    idx = np.empty(mask.size, dtype=np.int32)
+    kept = _load().oc_compact_rows(_ptr(mask, ctypes.c_uint8), mask.size, _ptr(idx, ctypes.c_int32))
+    if kept < 0:
+        raise ValueError("mask bytes must be 0 or 1")
+    return idx[:kept].copy()
+
+
+def masked_conv2d(spec, x, w, bias, mask, want_absum: bool = False):
+    """Dense-layout output of the masked convolution (float32, double accumulation).
+
+    Returns ``y`` or ``(y, absum)``; ``absum`` is sum|x*w| + |bias| per output element.
+    """
+    lib = _load()
+    x, w = _f32(x), _f32(w)
+    assert x.shape == tuple(spec.x_shape()) and w.shape == tuple(spec.w_shape())
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).ravel()
+    assert mask.size == spec.mask_len
+    b = _f32(bias) if spec.has_bias else None
+    if spec.has_bias:
+        assert b.shape == (spec.c_out,)
+    y = np.empty(spec.y_shape(), dtype=np.float32)
+    absum = np.empty(spec.y_shape(), dtype=np.float64) if want_absum else None
+    p = _params(spec)
+    rc = lib.oc_masked_conv2d(_ptr(p, ctypes.c_int32), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
+                              _ptr(b, ctypes.c_float), _ptr(mask, ctypes.c_uint8), _ptr(y, ctypes.c_float),
+                              _ptr(absum, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the problem (code {rc})")
+    return (y, absum) if want_absum else y
+
+
+def masked_conv2d_rows(spec, x, w, bias, mask, rows, want_absum: bool = False):
+    """Output of selected rows r = (n*Ho + oy)*Wo + ox, shape [len(rows), Cout]."""
+    lib = _load()
+    x, w = _f32(x), _f32(w)
+    assert x.shape == tuple(spec.x_shape()) and w.shape == tuple(spec.w_shape())
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).ravel()
+    assert mask.size == spec.mask_len
+    b = _f32(bias) if spec.has_bias else None
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    y = np.empty((rows.size, spec.c_out), dtype=np.float32)
+    absum = np.empty((rows.size, spec.c_out), dtype=np.float64) if want_absum else None
+    p = _params(spec)
+    rc = lib.oc_masked_conv2d_rows(_ptr(p, ctypes.c_int32), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
+                                   _ptr(b, ctypes.c_float), _ptr(mask, ctypes.c_uint8), _ptr(rows, ctypes.c_int64),
+                                   rows.size, _ptr(y, ctypes.c_float), _ptr(absum, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the problem (code {rc})")
+    return (y, absum) if want_absum else y
+
+
+def round_storage(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float32 values to the storage type of a layer output (nearest even), widened back."""
+    a = np.array(a, dtype=np.float32, order="C", copy=True)
+    if dtype == "bf16":
+        _load().oc_round_bf16(_ptr(a, ctypes.c_float), a.size)
+    elif dtype == "f16":
+        _load().oc_round_f16(_ptr(a, ctypes.c_float), a.size)
+    elif dtype != "f32":
+        raise ValueError(dtype)
+    return a
+
+
+def maxpool2d_nhwc(x: np.ndarray, k: int = 3, s: int = 2, p: int = 1) -> np.ndarray:
+    x = _f32(x)
+    n, h, w, c = x.shape
+    ho, wo = out_size(h, k, s, p, 1), out_size(w, k, s, p, 1)
+    y = np.empty((n, ho, wo, c), dtype=np.float32)
+    rc = _load().oc_maxpool2d_nhwc(_ptr(x, ctypes.c_float), n, h, w, c, k, s, p, _ptr(y, ctypes.c_float))
+    if rc != 0:
+        raise ValueError("bad pooling geometry")
+    return y
+
+
+def add_relu(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    a, b = _f32(a), _f32(b)
+    assert a.shape == b.shape
+    y = np.empty_like(a)
+    _load().oc_add_relu(_ptr(a, ctypes.c_float), _ptr(b, ctypes.c_float), a.size, _ptr(y, ctypes.c_float))
+    return y
+
+
+def run_network(ops, tensors: Dict[str, np.ndarray], layer_inputs) -> Dict[str, np.ndarray]:
+    """Interpret a list of workload ops on the CPU.
+
+    ``tensors`` holds the named inputs (float32, values representable in the storage dtype);
+    ``layer_inputs(spec)`` returns (w, bias, mask) for a conv.  Every op's result is rounded to
+    the storage dtype, as a runtime that keeps activations in that dtype would.
+    """
+    t = dict(tensors)
+    for op in ops:
+        if op.kind == "conv":
+            w, b, m = layer_inputs(op.spec)
+            y = masked_conv2d(op.spec, t[op.src], w, b, m)
+            t[op.out] = round_storage(y, op.spec.dtype)
+        elif op.kind == "maxpool":
+            t[op.out] = maxpool2d_nhwc(t[op.src], 3, 2, 1)
+        elif op.kind == "add_relu":
+            dt = next(o.spec.dtype for o in ops if o.kind == "conv")
+            t[op.out] = round_storage(add_relu(t[op.src], t[op.src2]), dt)
+        else:
+            raise ValueError(op.kind)
+    return t
