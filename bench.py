@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the masked-convolution hot path on one MI355X.
+
+Workload (config.workload): the ResNet18 stage-1 convolution of the benchmark description --
+batch 32, 64->64 channels at 56x56, 3x3 stride 1 pad 1, bf16 with float accumulation, half of
+the lowered rows masked out (seeded synthetic tensors, already resident in HBM).
+
+A step is one `sparse_conv_run`: gather of the kept rows, contraction on the matrix cores and
+placement into the dense output with zero fill, one fused launch.  The mask -> row-index
+compaction belongs to operator setup (the mask is frozen after training) and is timed
+separately (`plan_ms`).  `value` = 2*kept*K*Cout / time, the algorithmic TFLOP/s of the kept rows.
+
+Also printed in the same JSON line: the dense run of the same kernels and the speed-up over it
+at s in {0.25, 0.5, 0.7}, the roofline of the fused kernel, and the CPU oracle timed on the host
+cores (a baseline for scale, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+# HBM bytes per launch of the fused kernel on the benchmark workload, from the rocprofv3 --pmc
+# runs summarised under profiles/ (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel); None until
+# such a run exists for the current kernel.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def algorithmic_bytes(spec, keep: int) -> float:
+    """Bytes the method itself must move for one launch: the input pixels covered by at least one
+    kept window, the filters once, the dense output (zero fill included), the mask bytes and the
+    row list."""
+    eb = 4 if spec.dtype == "f32" else 2
+    s = 1.0 - keep / spec.m
+    if spec.kh == 1 and spec.kw == 1 and spec.stride_h == 1:
+        cov = keep / spec.m
+    elif spec.kh == 3 and spec.stride_h == 1:
+        cov = 1.0 - s ** 9
+    else:
+        cov = 1.0
+    return (cov * spec.n * spec.h * spec.w * spec.c_in * eb + spec.k * spec.c_out * eb
+            + spec.m * spec.c_out * eb + spec.m + 4 * keep)
+
+
+def time_launches(fn, steps: int, warmup: int):
+    """Wall-clock and HIP-event time of `steps` back-to-back launches on the current stream."""
+    import torch
+
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def cpu_baseline(spec, ci, budget_s: float = 12.0):
+    """The oracle as it stands, on the host cores, repeated on the benchmark layer until the budget is used."""
+    from oracle import oracle
+
+    oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask)  # warm-up (page-in, thread pool)
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or reps >= 200:
+            break
+    flops = 2.0 * ci.keep * spec.k * spec.c_out
+    return {"value": flops * reps / el / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"whole benchmark layer (kept {ci.keep} of {spec.m} rows), {reps} passes in {el:.1f} s, "
+                      "double accumulation"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile", type=str, default="", help="force the sparse tile, e.g. 128x64 (tuning)")
+    ap.add_argument("--dense-tile", type=str, default="", help="force the dense tile (tuning)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (the rows of the lowered matrix "
+              "are independent, so more GPUs would only split the batch). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd import runtime as R
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+
+    results = {}
+    headline = None
+    for s in (0.5, 0.25, 0.7):
+        spec = W.config2(s)
+        ci = W.make_conv_inputs(spec, W.base_seed(2))
+        t0 = time.perf_counter()
+        layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+        torch.cuda.synchronize()
+        plan_ms = (time.perf_counter() - t0) * 1e3
+        if args.tile:
+            B.sparse_conv_plan_set_tiles(layer.plan, 0, *map(int, args.tile.split("x")))
+        if args.dense_tile:
+            B.sparse_conv_plan_set_tiles(layer.plan, 1, *map(int, args.dense_tile.split("x")))
+        x = R.to_device(ci.x, spec.dtype)
+        y = layer.new_output()
+        steps = args.steps if s == 0.5 else max(args.steps // 4, 50)
+        warm = args.warmup if s == 0.5 else max(args.warmup // 4, 10)
+        wall_s, ev_s = time_launches(lambda: layer.sparse(x, y), steps, warm)
+        wall_d, ev_d = time_launches(lambda: layer.dense(x, y), max(steps // 4, 50), max(warm // 4, 10))
+        results[s] = dict(spec=spec, ci=ci, layer=layer, wall=wall_s, ev=ev_s, wall_dense=wall_d, ev_dense=ev_d,
+                          plan_ms=plan_ms, steps=steps, warm=warm)
+        if s == 0.5:
+            headline = results[s]
+
+    r = headline
+    spec, ci = r["spec"], r["ci"]
+    flops = 2.0 * ci.keep * spec.k * spec.c_out
+    flops_dense = 2.0 * spec.m * spec.k * spec.c_out
+    value = flops / r["wall"] / 1e12
+    abytes = algorithmic_bytes(spec, ci.keep)
+    achieved = abytes / r["ev"] / 1e9
+    tm, tn, wgs = B.sparse_conv_plan_tiles(r["layer"].plan, 0)
+    dm, dn, dwgs = B.sparse_conv_plan_tiles(r["layer"].plan, 1)
+    out = {
+        "metric": "sparse-conv TFLOP/s (algorithmic, kept rows) at s=0.5; speed-up vs dense at s in {0.25,0.5,0.7}",
+        "value": value,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": r["steps"],
+        "warmup": r["warm"],
+        "ms_per_step": r["wall"] * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: ResNet18 stage-1 conv, batch 32, 64->64 @56x56, 3x3 s1 p1, bf16, "
+                               "row mask s=0.5 (kept 50176 of 100352 rows), NHWC, bias+ReLU, zero fill",
+                   "m": spec.m, "k": spec.k, "c_out": spec.c_out, "kept": ci.keep,
+                   "tile_sparse": f"{tm}x{tn}", "workgroups_sparse": wgs,
+                   "tile_dense": f"{dm}x{dn}", "workgroups_dense": dwgs},
+        "kernel_us": r["ev"] * 1e6,
+        "dense_kernel_us": r["ev_dense"] * 1e6,
+        "dense_tflops": flops_dense / r["wall_dense"] / 1e12,
+        "speedup_vs_dense": {str(s): results[s]["ev_dense"] / results[s]["ev"] for s in (0.25, 0.5, 0.7)},
+        "sparse_tflops_by_s": {str(s): 2.0 * results[s]["ci"].keep * spec.k * spec.c_out / results[s]["wall"] / 1e12
+                               for s in (0.25, 0.5, 0.7)},
+        "mfma_peak_frac": flops / r["ev"] / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        "plan_ms": r["plan_ms"],
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "algorithmic_bytes": abytes, "kernel": "igemm_kernel<bf16> (fused gather+MFMA+scatter)"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec, ci)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,155 @@
+/*
+ * sparse_conv.h -- C ABI of the MI355X (gfx950) masked-convolution library.
+ *
+ * The operation (paper Sec. 3, Fig. 1-2; Sec. 3.2; App. A, Alg. 2): a convolution is the
+ * product of a lowered activation matrix A[M x K] (one row per output position
+ * r = (n*Ho + oy)*Wo + ox, K = kh*kw*Cin window entries) with the filter matrix
+ * B[K x Cout].  A fixed binary mask over output positions removes whole rows of A; the
+ * contraction runs over the surviving rows only and the results are placed back into the
+ * dense output layout, with zeros at the removed positions.
+ *
+ * Conventions
+ *   - mask byte != 0 keeps the row, 0 drops it (Alg. 1 getMask; Alg. 2 both functions);
+ *   - a dropped position holds +0.0 (all bits zero) in every output channel: no bias, no
+ *     activation (Alg. 2, post-process);  bias and ReLU act on kept rows only;
+ *   - zero padding, cross-correlation, Ho = floor((H + 2*pad - dil*(kh-1) - 1)/stride) + 1;
+ *   - SC_NHWC: x[N,H,W,Cin], w[Cout,kh,kw,Cin], y[N,Ho,Wo,Cout]   (fast path)
+ *     SC_NCHW: x[N,Cin,H,W], w[Cout,Cin,kh,kw], y[N,Cout,Ho,Wo]   (element-wise gather path)
+ *   - x, w and y share one element type; bias is always float; accumulation is float.
+ *
+ * Memory and ownership
+ *   Every pointer named *_dev is DEVICE memory allocated and owned by the caller; the
+ *   library never allocates, frees or keeps device memory of its own.  Derived data (row
+ *   index list, packed filters, gather table) lives in the caller's workspace, which must
+ *   stay alive and untouched for as long as the plan is used.  The plan object itself is
+ *   host memory owned by the library until sparse_conv_plan_destroy.
+ *   `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *
+ * Errors
+ *   Every entry point returns a status code and never throws or aborts.  All argument
+ *   checks happen on the host before the first HIP call.  sparse_conv_plan synchronises the
+ *   stream once (it needs the kept-row count on the host); the *_run calls only enqueue
+ *   work: no allocation, no host synchronisation.
+ */
+#ifndef SPARSE_CONV_H_
+#define SPARSE_CONV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SC_OK = 0,
+  SC_ERR_NULL = 1,        /* a required pointer is NULL */
+  SC_ERR_BAD_SHAPE = 2,   /* non-positive extent, empty output, or a tensor too large for 32-bit element offsets */
+  SC_ERR_UNSUPPORTED = 3, /* groups != 1, unknown dtype/layout/mode */
+  SC_ERR_MASK_COUNT = 4,  /* popcount(mask) differs from the count the sparsity ratio demands */
+  SC_ERR_WORKSPACE = 5,   /* workspace smaller than sparse_conv_workspace_bytes() */
+  SC_ERR_ALIGN = 6,       /* a device pointer is not aligned to 16 bytes */
+  SC_ERR_HIP = 7          /* a HIP call failed; sc_last_hip_error() holds its code */
+} sc_status;
+
+typedef enum { SC_F32 = 0, SC_F16 = 1, SC_BF16 = 2 } sc_dtype;
+typedef enum { SC_NHWC = 0, SC_NCHW = 1 } sc_layout;
+
+/* Scope of the mask over the batch.  The paper trains one 2-D mask per layer that every
+ * image shares (Sec. 3.1; Alg. 2 indexes the mask by output y/x only) = SC_MASK_SPATIAL.
+ * SC_MASK_ROW carries one byte per row of the lowered matrix of the whole batch. */
+typedef enum { SC_MASK_ROW = 0, SC_MASK_SPATIAL = 1 } sc_mask_mode;
+
+/* SC_OUT_ZERO_FILL: the run writes every element of y (zeros at dropped positions), as
+ * Alg. 2's post-processing does.  SC_OUT_SCATTER_ONLY: the run writes kept rows only; the
+ * caller guarantees the dropped positions of y already hold zeros (the mask is frozen after
+ * training, Sec. 3.1, so a buffer zeroed once keeps them). */
+typedef enum { SC_OUT_ZERO_FILL = 0, SC_OUT_SCATTER_ONLY = 1 } sc_out_mode;
+
+typedef struct {
+  int32_t n, c_in, h, w, c_out;
+  int32_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+  int32_t groups;      /* must be 1 */
+  int32_t dtype;       /* sc_dtype of x, w, y */
+  int32_t layout;      /* sc_layout of x, w, y */
+  int32_t has_bias;    /* 0/1 */
+  int32_t relu;        /* 0/1, applied after bias on kept rows */
+  int32_t mask_mode;   /* sc_mask_mode */
+  int32_t out_mode;    /* sc_out_mode */
+  float sparsity;      /* s in [0,1): plan fails with SC_ERR_MASK_COUNT unless
+                          popcount(mask) == floor((1-s)*len + 0.5) (Sec. 3.2: the GEMM range is
+                          output_size - sparsity*output_size);  s < 0 disables the check.
+                          The mask, never this number, decides which rows run. */
+} sc_conv_desc;
+
+typedef struct sc_plan sc_plan; /* opaque, host memory */
+
+/* Output extents and row count M = N*Ho*Wo of a descriptor (host only). */
+sc_status sparse_conv_output_shape(const sc_conv_desc* desc, int32_t* ho, int32_t* wo, int64_t* m);
+
+/* Bytes of device workspace sparse_conv_plan needs for this descriptor (host only). */
+sc_status sparse_conv_workspace_bytes(const sc_conv_desc* desc, size_t* bytes);
+
+/*
+ * Build a plan (Alg. 2, indirection init, done once per layer because the mask is frozen):
+ *   - compacts the mask into the ascending list of kept rows (device, wavefront ballot scan);
+ *   - packs the filters into the K-major layout the GEMM reads;
+ *   - builds the per-K gather table; chooses tile shapes for the reduced and the full M.
+ * mask_dev: uint8[N*Ho*Wo] (SC_MASK_ROW) or uint8[Ho*Wo] (SC_MASK_SPATIAL), device.
+ * w_dev:    filters in the descriptor's layout and dtype, device; read during this call only.
+ * workspace_dev: at least sparse_conv_workspace_bytes() bytes, 256-byte aligned, device.
+ * Synchronises `hip_stream` before returning.  On failure *out is NULL.
+ */
+sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, const void* w_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream, sc_plan** out);
+
+/*
+ * Masked convolution (Sec. 3.2 stages i-iii fused into one launch): gather the kept rows'
+ * receptive fields, contract with the filters on the matrix cores, add bias / apply ReLU,
+ * and store each result at its dense position; dropped positions receive zeros (or are
+ * left alone in SC_OUT_SCATTER_ONLY mode).
+ * x_dev: activations; bias_dev: float[Cout] or NULL when has_bias == 0; y_dev: output, fully
+ * overwritten in SC_OUT_ZERO_FILL mode.  x_dev and y_dev must not overlap.
+ */
+sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
+                          void* hip_stream);
+
+/* The same kernels with the identity row map: the ordinary dense convolution (the paper's
+ * baseline; its GEMM is unchanged, App. A).  Ignores the mask. */
+sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
+                         void* hip_stream);
+
+/* Plan facts.  Any output pointer may be NULL.  *row_idx_dev points into the workspace:
+ * int32[kept], ascending. */
+sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, int32_t* ho, int32_t* wo,
+                                const int32_t** row_idx_dev);
+
+/* Tile shape chosen for the sparse (which = 0) or dense (which = 1) launch:
+ * rows x couts per workgroup, and the number of workgroups. */
+sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* tile_m, int32_t* tile_n,
+                                 int64_t* workgroups);
+
+/* Tuning hook: force the tile shape of later runs (0,0 restores the automatic choice).
+ * Returns SC_ERR_UNSUPPORTED when the library has no kernel of that shape. */
+sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
+
+void sparse_conv_plan_destroy(sc_plan* plan);
+
+const char* sc_status_string(sc_status s);
+int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread */
+
+/*
+ * Glue operators of the test networks (ResNet-style stacks), NHWC device tensors of `dtype`.
+ * They are not part of the paper's method; they only connect conv layers in network runs.
+ *   sc_maxpool2d_nhwc: window k, stride s, zero-free padding p (padded taps never win).
+ *   sc_add_relu:       y = max(a + b, 0), element-wise; y may alias a or b.
+ */
+sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32_t n, int32_t h, int32_t w,
+                            int32_t c, int32_t k, int32_t s, int32_t p, void* hip_stream);
+sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
+                      void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSE_CONV_H_ */

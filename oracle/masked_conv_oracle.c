@@ -31,6 +31,7 @@
  * kept-count goldens).
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -45,6 +46,9 @@ enum {
 };
 
 int oc_param_count(void) { return P_COUNT; }
+
+/* threads the parallel loops will use (reported beside timings) */
+int oc_num_threads(void) { return omp_get_max_threads(); }
 
 /* output extent of one spatial axis */
 int oc_out_size(int in, int k, int stride, int pad, int dil) {

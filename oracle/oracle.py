@@ -43,6 +43,7 @@ def _load():
         f64p = ctypes.POINTER(ctypes.c_double)
         u8p = ctypes.POINTER(ctypes.c_uint8)
         lib.oc_param_count.restype = ctypes.c_int
+        lib.oc_num_threads.restype = ctypes.c_int
         lib.oc_out_size.restype = ctypes.c_int
         lib.oc_out_size.argtypes = [ctypes.c_int] * 5
         lib.oc_kept_count.restype = ctypes.c_int64
@@ -83,6 +84,11 @@ def _params(spec) -> np.ndarray:
          1 if spec.has_bias else 0, 1 if spec.relu else 0, 1 if spec.mask_mode == "spatial" else 0],
         dtype=np.int32,
     )
+
+
+def num_threads() -> int:
+    """OpenMP threads the oracle's loops run on."""
+    return int(_load().oc_num_threads())
 
 
 def out_size(inp: int, k: int, stride: int, pad: int, dil: int) -> int:

@@ -1,0 +1,238 @@
+"""ctypes binding of libsparse_conv.so: argument marshalling only.
+
+Every function has the name and meaning of its C entry point (include/sparse_conv.h).  PyTorch
+supplies device memory (tensors) and the stream handle; all arithmetic runs in the HIP kernels.
+There is no CPU fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch  # must be imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsparse_conv.so")
+
+SC_OK = 0
+SC_ERR_NULL, SC_ERR_BAD_SHAPE, SC_ERR_UNSUPPORTED, SC_ERR_MASK_COUNT = 1, 2, 3, 4
+SC_ERR_WORKSPACE, SC_ERR_ALIGN, SC_ERR_HIP = 5, 6, 7
+SC_F32, SC_F16, SC_BF16 = 0, 1, 2
+SC_NHWC, SC_NCHW = 0, 1
+SC_MASK_ROW, SC_MASK_SPATIAL = 0, 1
+SC_OUT_ZERO_FILL, SC_OUT_SCATTER_ONLY = 0, 1
+
+DTYPE_CODE = {"f32": SC_F32, "f16": SC_F16, "bf16": SC_BF16}
+TORCH_DTYPE = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+_CODE_OF_TORCH = {torch.float32: SC_F32, torch.float16: SC_F16, torch.bfloat16: SC_BF16}
+
+
+class sc_conv_desc(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in (
+        "n", "c_in", "h", "w", "c_out", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
+        "groups", "dtype", "layout", "has_bias", "relu", "mask_mode", "out_mode")] + [("sparsity", ctypes.c_float)]
+
+
+class ScError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().sc_status_string(status).decode()
+        if status == SC_ERR_HIP:
+            msg += f" [hipError {lib().sc_last_hip_error()}]"
+        super().__init__(f"{where}: {msg}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2309_06626_amd.build` "
+                "(there is no fallback implementation)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        pd = ctypes.POINTER(sc_conv_desc)
+        L.sparse_conv_output_shape.restype = ctypes.c_int
+        L.sparse_conv_output_shape.argtypes = [pd, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]
+        L.sparse_conv_workspace_bytes.restype = ctypes.c_int
+        L.sparse_conv_workspace_bytes.argtypes = [pd, ctypes.POINTER(ctypes.c_size_t)]
+        L.sparse_conv_plan.restype = ctypes.c_int
+        L.sparse_conv_plan.argtypes = [pd, vp, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+        L.sparse_conv_run.restype = ctypes.c_int
+        L.sparse_conv_run.argtypes = [vp, vp, vp, vp, vp]
+        L.dense_conv_run.restype = ctypes.c_int
+        L.dense_conv_run.argtypes = [vp, vp, vp, vp, vp]
+        L.sparse_conv_plan_info.restype = ctypes.c_int
+        L.sparse_conv_plan_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32),
+                                            ctypes.POINTER(i32), ctypes.POINTER(vp)]
+        L.sparse_conv_plan_tiles.restype = ctypes.c_int
+        L.sparse_conv_plan_tiles.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]
+        L.sparse_conv_plan_set_tiles.restype = ctypes.c_int
+        L.sparse_conv_plan_set_tiles.argtypes = [vp, i32, i32, i32]
+        L.sparse_conv_plan_destroy.restype = None
+        L.sparse_conv_plan_destroy.argtypes = [vp]
+        L.sc_status_string.restype = ctypes.c_char_p
+        L.sc_status_string.argtypes = [ctypes.c_int]
+        L.sc_last_hip_error.restype = i32
+        L.sc_last_hip_error.argtypes = []
+        L.sc_maxpool2d_nhwc.restype = ctypes.c_int
+        L.sc_maxpool2d_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
+        L.sc_add_relu.restype = ctypes.c_int
+        L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
+        _lib = L
+    return _lib
+
+
+def make_desc(n, c_in, h, w, c_out, kh=3, kw=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, dil_h=1, dil_w=1,
+              groups=1, dtype=SC_BF16, layout=SC_NHWC, has_bias=1, relu=1, mask_mode=SC_MASK_ROW,
+              out_mode=SC_OUT_ZERO_FILL, sparsity=-1.0) -> sc_conv_desc:
+    return sc_conv_desc(n, c_in, h, w, c_out, kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, groups,
+                        dtype, layout, int(has_bias), int(relu), mask_mode, out_mode, float(sparsity))
+
+
+def desc_from_spec(spec, out_mode=SC_OUT_ZERO_FILL, check_count=True) -> sc_conv_desc:
+    """Descriptor of a workloads.ConvSpec."""
+    return make_desc(spec.n, spec.c_in, spec.h, spec.w, spec.c_out, spec.kh, spec.kw, spec.stride_h, spec.stride_w,
+                     spec.pad_h, spec.pad_w, spec.dil_h, spec.dil_w, 1, DTYPE_CODE[spec.dtype],
+                     SC_NCHW if spec.layout == "nchw" else SC_NHWC, spec.has_bias, spec.relu,
+                     SC_MASK_SPATIAL if spec.mask_mode == "spatial" else SC_MASK_ROW, out_mode,
+                     spec.sparsity if check_count else -1.0)
+
+
+def _check(status: int, where: str):
+    if status != SC_OK:
+        raise ScError(status, where)
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev_ptr(t: Optional[torch.Tensor], what: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a device tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t.data_ptr()
+
+
+def sparse_conv_output_shape(desc: sc_conv_desc) -> Tuple[int, int, int]:
+    ho, wo, m = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+    _check(lib().sparse_conv_output_shape(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo), ctypes.byref(m)),
+           "sparse_conv_output_shape")
+    return ho.value, wo.value, m.value
+
+
+def sparse_conv_workspace_bytes(desc: sc_conv_desc) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().sparse_conv_workspace_bytes(ctypes.byref(desc), ctypes.byref(n)), "sparse_conv_workspace_bytes")
+    return n.value
+
+
+class Plan:
+    """Owner of an sc_plan handle and of the tensors the plan points into."""
+
+    def __init__(self, handle: int, desc: sc_conv_desc, workspace: torch.Tensor):
+        self.handle = handle
+        self.desc = desc
+        self.workspace = workspace  # keeps the device memory alive
+
+    def close(self):
+        if self.handle:
+            lib().sparse_conv_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def sparse_conv_plan(desc: sc_conv_desc, mask: torch.Tensor, w: torch.Tensor,
+                     workspace: Optional[torch.Tensor] = None, stream=None) -> Plan:
+    """mask: uint8 device tensor; w: filters in the descriptor's layout/dtype (device)."""
+    if mask.dtype != torch.uint8:
+        raise ValueError("mask must be uint8")
+    if _CODE_OF_TORCH.get(w.dtype) != desc.dtype:
+        raise ValueError("filter dtype does not match the descriptor")
+    nbytes = sparse_conv_workspace_bytes(desc)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=mask.device)
+    out = ctypes.c_void_p()
+    st = lib().sparse_conv_plan(ctypes.byref(desc), _dev_ptr(mask, "mask"), _dev_ptr(w, "w"),
+                                _dev_ptr(workspace, "workspace"), workspace.numel(), _stream_handle(stream),
+                                ctypes.byref(out))
+    _check(st, "sparse_conv_plan")
+    return Plan(out.value, desc, workspace)
+
+
+def _run(fn, name, plan: Plan, x, bias, y, stream):
+    for t, what in ((x, "x"), (y, "y")):
+        if _CODE_OF_TORCH.get(t.dtype) != plan.desc.dtype:
+            raise ValueError(f"{what} dtype does not match the plan")
+    if bias is not None and bias.dtype != torch.float32:
+        raise ValueError("bias must be float32")
+    _check(fn(plan.handle, _dev_ptr(x, "x"), _dev_ptr(bias, "bias"), _dev_ptr(y, "y"), _stream_handle(stream)), name)
+    return y
+
+
+def sparse_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):
+    return _run(lib().sparse_conv_run, "sparse_conv_run", plan, x, bias, y, stream)
+
+
+def dense_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):
+    return _run(lib().dense_conv_run, "dense_conv_run", plan, x, bias, y, stream)
+
+
+def sparse_conv_plan_info(plan: Plan) -> dict:
+    m, kept, ho, wo, rows = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_void_p()
+    _check(lib().sparse_conv_plan_info(plan.handle, ctypes.byref(m), ctypes.byref(kept), ctypes.byref(ho),
+                                       ctypes.byref(wo), ctypes.byref(rows)), "sparse_conv_plan_info")
+    return {"m": m.value, "kept": kept.value, "ho": ho.value, "wo": wo.value, "row_idx_ptr": rows.value}
+
+
+def plan_row_idx(plan: Plan) -> torch.Tensor:
+    """Copy of the kept-row list (int32, ascending) as a device tensor."""
+    info = sparse_conv_plan_info(plan)
+    off = info["row_idx_ptr"] - plan.workspace.data_ptr()
+    return plan.workspace[off: off + 4 * info["kept"]].view(torch.int32).clone()
+
+
+def sparse_conv_plan_tiles(plan: Plan, which: int) -> Tuple[int, int, int]:
+    tm, tn, wg = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int64()
+    _check(lib().sparse_conv_plan_tiles(plan.handle, which, ctypes.byref(tm), ctypes.byref(tn), ctypes.byref(wg)),
+           "sparse_conv_plan_tiles")
+    return tm.value, tn.value, wg.value
+
+
+def sparse_conv_plan_set_tiles(plan: Plan, which: int, tile_m: int, tile_n: int):
+    _check(lib().sparse_conv_plan_set_tiles(plan.handle, which, tile_m, tile_n), "sparse_conv_plan_set_tiles")
+
+
+def sc_maxpool2d_nhwc(x: torch.Tensor, k: int = 3, s: int = 2, p: int = 1, stream=None) -> torch.Tensor:
+    n, h, w, c = x.shape
+    ho, wo = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+    y = torch.empty((n, ho, wo, c), dtype=x.dtype, device=x.device)
+    _check(lib().sc_maxpool2d_nhwc(_dev_ptr(x, "x"), _dev_ptr(y, "y"), _CODE_OF_TORCH[x.dtype], n, h, w, c, k, s, p,
+                                   _stream_handle(stream)), "sc_maxpool2d_nhwc")
+    return y
+
+
+def sc_add_relu(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if a.shape != b.shape or a.dtype != b.dtype:
+        raise ValueError("operands differ in shape or dtype")
+    if y is None:
+        y = torch.empty_like(a)
+    _check(lib().sc_add_relu(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), _CODE_OF_TORCH[a.dtype],
+                             a.numel(), _stream_handle(stream)), "sc_add_relu")
+    return y

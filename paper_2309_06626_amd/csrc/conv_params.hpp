@@ -1,0 +1,64 @@
+// Kernel-side description of one masked-convolution launch (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sc {
+
+// One entry of the gather table: where a group of consecutive K entries of the lowered
+// matrix sits relative to the top-left tap of a window (paper Sec. 3, Fig. 1: each row of
+// the lowered matrix lists the kh*kw*Cin entries of one sliding window).
+struct KEntry {
+  int32_t off;   // element offset  dy*xs_h + dx*xs_w + ci*xs_c
+  int32_t dydx;  // dy | (dx << 16); dy = ky*dil_h, dx = kx*dil_w; 0x7fff marks padding of K
+};
+
+struct ConvParams {
+  const void* x;
+  const void* wp;          // packed filters [cout_pad][k_pad], K contiguous
+  const float* bias;       // may be null
+  void* y;
+  const int32_t* row_idx;  // ascending kept rows; null = identity (dense run)
+  const uint8_t* mask;     // used for the zero fill only
+  const KEntry* ktab;      // per 16-byte K group (vector gather) or per K element (element gather)
+  int32_t rows;            // rows of the (compacted) GEMM: kept, or M for a dense run
+  int32_t m_total;         // M = N*Ho*Wo
+  int32_t h, w, ho_wo, wo;
+  int32_t sh, sw, ph, pw;
+  int32_t c_out;
+  int32_t k_pad;           // K rounded up to the K tile
+  int32_t k_tiles;
+  int64_t xs_n;            // element strides of x
+  int32_t xs_h, xs_w;
+  int64_t ys_n;            // element strides of y: batch, position within image, channel
+  int32_t ys_p, ys_c;
+  int32_t relu;
+  int32_t zero_fill;       // write zeros at dropped rows
+  int32_t mask_spatial;    // mask has ho_wo entries shared by the batch
+  int32_t vec_out;         // y rows are channel-contiguous and 16-byte groups are aligned
+  int32_t m_tiles, n_tiles;
+};
+
+enum Dtype { kF32 = 0, kF16 = 1, kBF16 = 2 };
+
+constexpr int kThreads = 256;
+constexpr int kRowBytes = 128;  // bytes of K per LDS tile row (K tile = 128 B / element size)
+
+struct TileShape { int bm, bn; };
+
+// launcher signature shared by every instantiation
+using LaunchFn = hipError_t (*)(const ConvParams&, hipStream_t);
+
+struct KernelEntry {
+  int bm, bn;
+  LaunchFn vec;   // 16-byte gather (NHWC, Cin*eb % 16 == 0)
+  LaunchFn elem;  // element gather (any layout)
+  size_t lds_bytes;
+};
+
+// per-dtype kernel tables (defined in igemm_<dtype>.hip)
+const KernelEntry* kernels_bf16(int* count);
+const KernelEntry* kernels_f16(int* count);
+const KernelEntry* kernels_f32(int* count);
+
+}  // namespace sc

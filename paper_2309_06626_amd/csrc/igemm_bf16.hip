@@ -1,0 +1,22 @@
+// Instantiations of the fused masked-convolution kernel for bf16 operands (float accumulate).
+#include "igemm_kernel.hpp"
+
+namespace sc {
+
+static const KernelEntry g_table[] = {
+    SC_KERNEL_ENTRY(kBF16, 256, 128, 2, 2),
+    SC_KERNEL_ENTRY(kBF16, 128, 128, 2, 2),
+    SC_KERNEL_ENTRY(kBF16, 256, 64, 4, 1),
+    SC_KERNEL_ENTRY(kBF16, 128, 64, 2, 2),
+    SC_KERNEL_ENTRY(kBF16, 64, 128, 2, 2),
+    SC_KERNEL_ENTRY(kBF16, 64, 64, 2, 2),
+    SC_KERNEL_ENTRY(kBF16, 128, 32, 4, 1),
+    SC_KERNEL_ENTRY(kBF16, 32, 128, 1, 4),
+};
+
+const KernelEntry* kernels_bf16(int* count) {
+  *count = (int)(sizeof(g_table) / sizeof(g_table[0]));
+  return g_table;
+}
+
+}  // namespace sc

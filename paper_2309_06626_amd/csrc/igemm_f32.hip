@@ -1,0 +1,22 @@
+// Instantiations of the fused masked-convolution kernel for f32 operands (float accumulate).
+#include "igemm_kernel.hpp"
+
+namespace sc {
+
+static const KernelEntry g_table[] = {
+    SC_KERNEL_ENTRY(kF32, 256, 128, 2, 2),
+    SC_KERNEL_ENTRY(kF32, 128, 128, 2, 2),
+    SC_KERNEL_ENTRY(kF32, 256, 64, 4, 1),
+    SC_KERNEL_ENTRY(kF32, 128, 64, 2, 2),
+    SC_KERNEL_ENTRY(kF32, 64, 128, 2, 2),
+    SC_KERNEL_ENTRY(kF32, 64, 64, 2, 2),
+    SC_KERNEL_ENTRY(kF32, 128, 32, 4, 1),
+    SC_KERNEL_ENTRY(kF32, 32, 128, 1, 4),
+};
+
+const KernelEntry* kernels_f32(int* count) {
+  *count = (int)(sizeof(g_table) / sizeof(g_table[0]));
+  return g_table;
+}
+
+}  // namespace sc

@@ -1,0 +1,325 @@
+// Fused masked-convolution kernel for gfx950: implicit lowering of the kept rows
+// (paper Sec. 3.2 stage i), matrix-core contraction on the compacted row dimension
+// (stage ii) and placement into the dense output with zero fill (stage iii; App. A, Alg. 2),
+// in one launch.
+//
+// Work decomposition
+//   workgroup = BM kept rows x BN output channels, 256 threads = 4 wavefronts of 64 lanes
+//   arranged WAVES_M x WAVES_N; every wavefront owns (BM/WAVES_M) x (BN/WAVES_N) outputs as
+//   32x32 MFMA blocks.  K advances in tiles of 128 bytes per row.
+//
+// Operand orientation
+//   The MFMA computes D = Wt * Xt with filters as the row operand and window entries as the
+//   column operand, so a lane ends up holding 16 output channels of ONE output position.
+//   Filter rows are stored pre-permuted (see pack kernel) such that those 16 channels are
+//   consecutive: lane (p, h) register v  <->  position p, channel 16*h + v of the 32-block.
+//   The store of a kept row is then 16 consecutive channels per lane.
+//
+// LDS layout
+//   A tile [BM][128 B] and B tile [BN][128 B], double buffered; the eight 16-byte groups of
+//   a row are XOR-swizzled with (row & 7) so that the 128-bit reads of eight consecutive
+//   rows hit distinct banks.
+#pragma once
+#include "conv_params.hpp"
+
+namespace sc {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+template <int DT> struct Elem;
+template <> struct Elem<kBF16> {
+  using T = __bf16;
+  static constexpr int V = 8;  // elements per 16 bytes
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf), __builtin_bit_cast(bf16x8, xf),
+                                                  acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return (__bf16)f; }
+};
+template <> struct Elem<kF16> {
+  using T = _Float16;
+  static constexpr int V = 8;
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, wf), __builtin_bit_cast(f16x8, xf),
+                                                 acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return (_Float16)f; }
+};
+template <> struct Elem<kF32> {
+  using T = float;
+  static constexpr int V = 4;
+  // A 16-byte group holds 4 consecutive K entries; the two lane halves hold two different
+  // groups, so MFMA number e contracts entry e of both groups (any consistent pairing of K
+  // entries between the two operands is a valid order of the sum).
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    v4f a = __builtin_bit_cast(v4f, wf), b = __builtin_bit_cast(v4f, xf);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return f; }
+};
+
+template <int BM, int BN>
+constexpr size_t igemm_lds_bytes() { return 2 * (size_t)(BM + BN) * kRowBytes + BM * sizeof(int32_t); }
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+__global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
+  using E = Elem<DT>;
+  using T = typename E::T;
+  constexpr int V = E::V;
+  constexpr int EB = sizeof(T);
+  constexpr int BK = 8 * V;  // K entries per tile (128 bytes)
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;
+  static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four wavefronts");
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "32x32 MFMA blocks");
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned char* s_a = smem;                              // [2][BM][128]
+  unsigned char* s_b = smem + 2 * BM * kRowBytes;         // [2][BN][128]
+  int32_t* s_rows = reinterpret_cast<int32_t*>(smem + 2 * (BM + BN) * kRowBytes);  // [BM]
+
+  // Workgroup -> tile.  Consecutive workgroup ids land on different XCDs (8 per device); give
+  // each XCD one contiguous run of tiles so neighbouring windows share that XCD's L2.
+  const int nwg = p.m_tiles * p.n_tiles;
+  const int per_xcd = (nwg + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= nwg) return;
+  const int tile_m = logical / p.n_tiles;
+  const int tile_n = logical - tile_m * p.n_tiles;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  const int t = threadIdx.x;
+  const int lane = t & 63, wave = t >> 6;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+
+  for (int i = t; i < BM; i += kThreads) {
+    int ic = m0 + i;
+    s_rows[i] = ic < p.rows ? (p.row_idx ? p.row_idx[ic] : ic) : -1;
+  }
+  __syncthreads();
+
+  T* __restrict__ y = static_cast<T*>(p.y);
+
+  // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) ----------
+  // Ownership: the dense rows from this tile's first kept row up to the next tile's first kept
+  // row (first tile starts at row 0, last tile ends at M), restricted to this tile's channels.
+  if (p.zero_fill) {
+    const int lo = tile_m == 0 ? 0 : s_rows[0];
+    const int hi = (m0 + BM >= p.rows) ? p.m_total : p.row_idx[m0 + BM];
+    if (p.vec_out) {
+      constexpr int CPR = BN * EB / 16;  // 16-byte groups per row slice
+      const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
+      const int total = (hi - lo) * CPR;
+      for (int idx = t; idx < total; idx += kThreads) {
+        int r = lo + idx / CPR, c = idx % CPR;
+        int mr = p.mask_spatial ? r % p.ho_wo : r;
+        if (c < valid && p.mask[mr] == 0) {
+          v4i z = {0, 0, 0, 0};
+          *reinterpret_cast<v4i*>(reinterpret_cast<unsigned char*>(y) + ((int64_t)r * p.c_out + n0) * EB + c * 16) = z;
+        }
+      }
+    } else {
+      const int total = (hi - lo) * BN;
+      for (int idx = t; idx < total; idx += kThreads) {
+        int r = lo + idx / BN, c = n0 + idx % BN;
+        int mr = p.mask_spatial ? r % p.ho_wo : r;
+        if (c < p.c_out && p.mask[mr] == 0) {
+          int n = r / p.ho_wo, rem = r - n * p.ho_wo;
+          y[n * p.ys_n + (int64_t)rem * p.ys_p + (int64_t)c * p.ys_c] = E::from_float(0.0f);
+        }
+      }
+    }
+  }
+
+  // ---- per-thread gather state: the rows this thread stages, fixed for the whole K loop -------
+  const int c16 = t & 7;      // which 16-byte group of the 128-byte K tile
+  const int lrow = t >> 3;    // 0..31
+  int32_t a_base[A_LOADS], a_iy0[A_LOADS], a_ix0[A_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    int rr = s_rows[lrow + 32 * j];
+    if (rr >= 0) {
+      int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
+      int oy = rem / p.wo, ox = rem - oy * p.wo;
+      a_iy0[j] = oy * p.sh - p.ph;
+      a_ix0[j] = ox * p.sw - p.pw;
+      a_base[j] = (int32_t)(n * p.xs_n + (int64_t)a_iy0[j] * p.xs_h + (int64_t)a_ix0[j] * p.xs_w);
+    } else {
+      a_iy0[j] = -(1 << 30);
+      a_ix0[j] = 0;
+      a_base[j] = 0;
+    }
+  }
+  const T* __restrict__ x = static_cast<const T*>(p.x);
+  const T* __restrict__ wp = static_cast<const T*>(p.wp) + (int64_t)(n0 + lrow) * p.k_pad + c16 * V;
+
+  v4i ra[A_LOADS], rb[B_LOADS];
+
+  auto load_tile = [&](int kt) {
+    if constexpr (VEC) {
+      KEntry e = p.ktab[kt * 8 + c16];
+      int dy = e.dydx & 0xffff, dx = e.dydx >> 16;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        bool ok = (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
+        v4i v = {0, 0, 0, 0};
+        if (ok) v = *reinterpret_cast<const v4i*>(x + (a_base[j] + e.off));
+        ra[j] = v;
+      }
+    } else {
+      const KEntry* kt_e = p.ktab + kt * BK + c16 * V;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        T tmp[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          KEntry ke = kt_e[e];
+          int dy = ke.dydx & 0xffff, dx = ke.dydx >> 16;
+          bool ok = (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
+          tmp[e] = ok ? x[a_base[j] + ke.off] : E::from_float(0.0f);
+        }
+        v4i v;
+        __builtin_memcpy(&v, tmp, 16);
+        ra[j] = v;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j)
+      rb[j] = *reinterpret_cast<const v4i*>(wp + (int64_t)(32 * j) * p.k_pad + kt * BK);
+  };
+
+  const int st_off = lrow * kRowBytes + ((c16 ^ (lrow & 7)) << 4);
+  auto store_tile = [&](int buf) {
+    unsigned char* a = s_a + buf * BM * kRowBytes + st_off;
+    unsigned char* b = s_b + buf * BN * kRowBytes + st_off;
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) *reinterpret_cast<v4i*>(a + j * 32 * kRowBytes) = ra[j];
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) *reinterpret_cast<v4i*>(b + j * 32 * kRowBytes) = rb[j];
+  };
+
+  floatx16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+  const int fp = lane & 31, fh = lane >> 5;
+  int frag_off[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) frag_off[ks] = fp * kRowBytes + (((2 * ks + fh) ^ (fp & 7)) << 4);
+
+  auto compute_tile = [&](int buf) {
+    const unsigned char* a = s_a + buf * BM * kRowBytes + wm0 * kRowBytes;
+    const unsigned char* b = s_b + buf * BN * kRowBytes + wn0 * kRowBytes;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      v4i xf[MI], wf[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        xf[mi] = *reinterpret_cast<const v4i*>(a + mi * 32 * kRowBytes + frag_off[ks]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        wf[ni] = *reinterpret_cast<const v4i*>(b + ni * 32 * kRowBytes + frag_off[ks]);
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) E::mma(acc[mi][ni], wf[ni], xf[mi]);
+    }
+  };
+
+  // ---- main loop: global -> registers -> LDS, double buffered, one barrier per K tile ---------
+  load_tile(0);
+  store_tile(0);
+  __syncthreads();
+  for (int kt = 0; kt < p.k_tiles; ++kt) {
+    const int cur = kt & 1;
+    const bool more = kt + 1 < p.k_tiles;
+    if (more) load_tile(kt + 1);
+    compute_tile(cur);
+    if (more) store_tile(cur ^ 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: bias, ReLU, convert, store every kept row at its dense position --------------
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    const int rr = s_rows[wm0 + mi * 32 + fp];
+    if (rr < 0) continue;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
+      if (c0 >= p.c_out) continue;
+      float vals[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) vals[v] = acc[mi][ni][v];
+      if (p.vec_out) {
+        if (p.bias) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            v4f b4 = *reinterpret_cast<const v4f*>(p.bias + c0 + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
+          }
+        }
+        if (p.relu) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
+        }
+        T outv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
+        v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * p.c_out + c0));
+        v4i pk[16 * EB / 16];
+        __builtin_memcpy(pk, outv, 16 * EB);
+#pragma unroll
+        for (int q = 0; q < 16 * EB / 16; ++q) dst[q] = pk[q];
+      } else {
+        const int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
+        T* dst = y + n * p.ys_n + (int64_t)rem * p.ys_p;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int c = c0 + v;
+          if (c < p.c_out) {
+            float f = vals[v] + (p.bias ? p.bias[c] : 0.0f);
+            if (p.relu) f = fmaxf(f, 0.0f);
+            dst[(int64_t)c * p.ys_c] = E::from_float(f);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
+  constexpr size_t lds = igemm_lds_bytes<BM, BN>();
+  auto kern = igemm_kernel<DT, BM, BN, WAVES_M, WAVES_N, VEC>;
+  static bool attr_set = false;
+  if (lds > 64 * 1024 && !attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int nwg = p.m_tiles * p.n_tiles;
+  const int grid = ((nwg + 7) / 8) * 8;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, p);
+  return hipGetLastError();
+}
+
+#define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_)                                             \
+  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true>,                        \
+                igemm_launch<DT, BM, BN, WM_, WN_, false>, igemm_lds_bytes<BM, BN>() }
+
+}  // namespace sc

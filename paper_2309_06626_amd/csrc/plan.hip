@@ -1,0 +1,557 @@
+// Host side of the C ABI (validation, workspace carving, tile choice, launches) and the small
+// plan-time kernels: mask -> row-index compaction, filter packing, gather-table build, and
+// the glue operators of the test networks.
+#include "../../include/sparse_conv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "conv_params.hpp"
+
+namespace sc {
+
+static thread_local int32_t g_last_hip = 0;
+
+static inline bool hip_failed(hipError_t e) {
+  if (e != hipSuccess) { g_last_hip = (int32_t)e; return true; }
+  return false;
+}
+#define SC_HIP(expr) do { if (hip_failed((expr))) return SC_ERR_HIP; } while (0)
+
+// ------------------------------------------------------------------------------------------------
+// Mask -> ascending list of kept rows (Alg. 2, indirection init: positions are visited in
+// ascending order and appended only where the mask is set).  Two passes, no inter-workgroup
+// waiting: each wavefront owns a segment of kSeg rows; pass 1 counts with ballots, pass 2 sums
+// the counts of the earlier segments and scatters with ballot + lane rank.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSeg = 1024;
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+__global__ __launch_bounds__(256) void mask_count_kernel(const uint8_t* __restrict__ mask, int m, int period,
+                                                         int nseg, int32_t* __restrict__ counts) {
+  const int lane = threadIdx.x & 63;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= nseg) return;
+  const int r0 = seg * kSeg;
+  int cnt = 0;
+  for (int it = 0; it < kSeg / 64; ++it) {
+    int r = r0 + it * 64 + lane;
+    bool keep = r < m && mask[period ? r % period : r] != 0;
+    cnt += __popcll(__ballot(keep));
+  }
+  if (lane == 0) counts[seg] = cnt;
+}
+
+__global__ __launch_bounds__(256) void mask_scatter_kernel(const uint8_t* __restrict__ mask, int m, int period,
+                                                           int nseg, const int32_t* __restrict__ counts,
+                                                           int32_t* __restrict__ row_idx,
+                                                           int32_t* __restrict__ kept_out) {
+  const int lane = threadIdx.x & 63;
+  const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (seg >= nseg) return;
+  int part = 0;
+  for (int i = lane; i < seg; i += 64) part += counts[i];
+  int base = wave_sum(part);
+  const int r0 = seg * kSeg;
+  for (int it = 0; it < kSeg / 64; ++it) {
+    int r = r0 + it * 64 + lane;
+    bool keep = r < m && mask[period ? r % period : r] != 0;
+    unsigned long long b = __ballot(keep);
+    int rank = __popcll(b & ((1ull << lane) - 1ull));
+    if (keep) row_idx[base + rank] = r;
+    base += __popcll(b);
+  }
+  if (seg == nseg - 1 && lane == 0) *kept_out = base;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Filter packing: [cout_pad][k_pad] with K = (ky, kx, ci) contiguous, zero padded.  Inside every
+// group of 32 output channels the rows are permuted so that MFMA output row 8j + 4h + i holds
+// channel 16h + 4j + i: a lane of the result then owns 16 consecutive channels.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void pack_filters_kernel(const T* __restrict__ w, T* __restrict__ wp, int c_out, int c_in, int kh, int kw,
+                                    int k, int k_pad, int cout_pad, int nchw) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)cout_pad * k_pad) return;
+  int prow = (int)(idx / k_pad), kk = (int)(idx % k_pad);
+  int rho = prow & 31;
+  int co = (prow & ~31) + 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
+  T v = (T)0.0f;
+  if (co < c_out && kk < k) {
+    int tap = kk / c_in, ci = kk % c_in;
+    int ky = tap / kw, kx = tap % kw;
+    int64_t src = nchw ? (((int64_t)co * c_in + ci) * kh + ky) * kw + kx
+                       : (((int64_t)co * kh + ky) * kw + kx) * c_in + ci;
+    v = w[src];
+  }
+  wp[idx] = v;
+}
+
+// Gather table: entry g covers K entries [g*vec, (g+1)*vec) (vec = 1 for the element gather).
+__global__ void build_ktab_kernel(KEntry* __restrict__ tab, int entries, int vec, int k, int c_in, int kw, int dil_h,
+                                  int dil_w, int xs_h, int xs_w, int xs_c) {
+  int g = blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= entries) return;
+  int kk = g * vec;
+  KEntry e;
+  if (kk < k) {
+    int tap = kk / c_in, ci = kk % c_in;
+    int dy = (tap / kw) * dil_h, dx = (tap % kw) * dil_w;
+    e.off = dy * xs_h + dx * xs_w + ci * xs_c;
+    e.dydx = dy | (dx << 16);
+  } else {
+    e.off = 0;
+    e.dydx = 0x7fff;  // row offset no image reaches: the padded K entries read as zero
+  }
+  tab[g] = e;
+}
+
+__global__ void fill_zero_kernel(uint4* __restrict__ dst, int64_t n16, unsigned char* tail, int ntail) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = make_uint4(0, 0, 0, 0);
+  if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Glue operators for network runs
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void maxpool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, int n, int h, int w, int c, int k,
+                                    int s, int p, int ho, int wo) {
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t total = (int64_t)n * ho * wo * c;
+  if (idx >= total) return;
+  int ch = (int)(idx % c);
+  int64_t pos = idx / c;
+  int ox = (int)(pos % wo);
+  int oy = (int)((pos / wo) % ho);
+  int b = (int)(pos / ((int64_t)wo * ho));
+  float best = -INFINITY;
+  for (int ky = 0; ky < k; ++ky) {
+    int iy = oy * s - p + ky;
+    if (iy < 0 || iy >= h) continue;
+    for (int kx = 0; kx < k; ++kx) {
+      int ix = ox * s - p + kx;
+      if (ix < 0 || ix >= w) continue;
+      float v = (float)x[(((int64_t)b * h + iy) * w + ix) * c + ch];
+      best = fmaxf(best, v);
+    }
+  }
+  y[idx] = (T)best;
+}
+
+template <typename T>
+__global__ void add_relu_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t count) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) {
+    float v = (float)a[i] + (float)b[i];
+    y[i] = (T)fmaxf(v, 0.0f);
+  }
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
+
+struct Geometry {
+  int32_t ho, wo;
+  int64_t m;
+  int32_t k, k_pad, k_tiles, vec, cout_pad;
+  bool vec_gather, vec_out;
+  int64_t x_elems, y_elems, mask_len;
+  int32_t nseg;
+  // workspace carve (byte offsets)
+  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, total;
+};
+
+static int out_extent(int in, int k, int stride, int pad, int dil) {
+  int64_t eff = (int64_t)in + 2 * (int64_t)pad - (int64_t)dil * (k - 1) - 1;
+  if (eff < 0) return 0;
+  return (int)(eff / stride) + 1;
+}
+
+static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
+  if (!d) return SC_ERR_NULL;
+  if (d->groups != 1) return SC_ERR_UNSUPPORTED;
+  if (d->dtype != SC_F32 && d->dtype != SC_F16 && d->dtype != SC_BF16) return SC_ERR_UNSUPPORTED;
+  if (d->layout != SC_NHWC && d->layout != SC_NCHW) return SC_ERR_UNSUPPORTED;
+  if (d->mask_mode != SC_MASK_ROW && d->mask_mode != SC_MASK_SPATIAL) return SC_ERR_UNSUPPORTED;
+  if (d->out_mode != SC_OUT_ZERO_FILL && d->out_mode != SC_OUT_SCATTER_ONLY) return SC_ERR_UNSUPPORTED;
+  if (d->n < 1 || d->c_in < 1 || d->h < 1 || d->w < 1 || d->c_out < 1 || d->kh < 1 || d->kw < 1 ||
+      d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0 || d->dil_h < 1 || d->dil_w < 1)
+    return SC_ERR_BAD_SHAPE;
+  if (!(d->sparsity < 1.0f)) return SC_ERR_BAD_SHAPE;  // also rejects NaN
+  // the gather table packs window offsets into 15 bits
+  if (d->h > 16000 || d->w > 16000 || d->pad_h > 16000 || d->pad_w > 16000 ||
+      (int64_t)(d->kh - 1) * d->dil_h > 16000 || (int64_t)(d->kw - 1) * d->dil_w > 16000)
+    return SC_ERR_BAD_SHAPE;
+  g->ho = out_extent(d->h, d->kh, d->stride_h, d->pad_h, d->dil_h);
+  g->wo = out_extent(d->w, d->kw, d->stride_w, d->pad_w, d->dil_w);
+  if (g->ho < 1 || g->wo < 1) return SC_ERR_BAD_SHAPE;
+  const int64_t lim = (int64_t)1 << 31;
+  g->m = (int64_t)d->n * g->ho * g->wo;
+  g->x_elems = (int64_t)d->n * d->h * d->w * d->c_in;
+  g->y_elems = g->m * d->c_out;
+  int64_t k = (int64_t)d->kh * d->kw * d->c_in;
+  if (g->m >= lim || g->x_elems >= lim - (1 << 20) || g->y_elems >= lim || k >= (1 << 24) || d->c_out >= (1 << 24))
+    return SC_ERR_BAD_SHAPE;
+  const int eb = elem_bytes(d->dtype);
+  g->vec = 16 / eb;
+  g->k = (int32_t)k;
+  const int bk = 8 * g->vec;
+  g->k_pad = (int32_t)((k + bk - 1) / bk * bk);
+  g->k_tiles = g->k_pad / bk;
+  g->cout_pad = (d->c_out + 255) / 256 * 256;
+  g->vec_gather = d->layout == SC_NHWC && d->c_in % g->vec == 0;
+  g->vec_out = d->layout == SC_NHWC && d->c_out % 16 == 0;
+  g->mask_len = d->mask_mode == SC_MASK_ROW ? g->m : (int64_t)g->ho * g->wo;
+  g->nseg = (int32_t)((g->m + kSeg - 1) / kSeg);
+  size_t off = 0;
+  g->off_rows = off;   off = align_up(off + (size_t)g->m * 4, 256);
+  g->off_counts = off; off = align_up(off + (size_t)g->nseg * 4, 256);
+  g->off_kept = off;   off += 256;
+  g->off_mask = off;   off = align_up(off + (size_t)g->mask_len, 256);
+  g->off_wp = off;     off = align_up(off + (size_t)g->cout_pad * g->k_pad * eb, 256);
+  g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
+  g->total = off;
+  return SC_OK;
+}
+
+}  // namespace sc
+
+using namespace sc;
+
+struct sc_plan {
+  sc_conv_desc desc;
+  Geometry geo;
+  unsigned char* ws;
+  int64_t kept;
+  const KernelEntry* table;
+  int table_count;
+  int tile_sparse, tile_dense;     // chosen indices into table
+  int forced[2];                   // -1 = automatic
+};
+
+namespace sc {
+
+// Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a
+// heavily masked layer gets narrower tiles than its dense twin (Sec. 3.2: the GEMM range
+// shrinks with the sparsity).  Cost = tiles on the busiest CU x tile volume / tile efficiency;
+// efficiency falls with the LDS reads per MFMA of the wavefront tile.
+static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out) {
+  const double cus = 256.0;
+  int best = 0;
+  double best_cost = 1e300;
+  for (int i = 0; i < count; ++i) {
+    const int bm = tab[i].bm, bn = tab[i].bn;
+    int64_t mt = (rows + bm - 1) / bm, nt = (c_out + bn - 1) / bn;
+    double nwg = (double)mt * nt;
+    double per_cu = std::ceil(nwg / cus);
+    // wavefront tile is (bm/2 x bn/2) except for the 4x1 / 1x4 shapes; use the square guess
+    double mi = bm >= 64 ? bm / 64.0 : 1.0, ni = bn >= 64 ? bn / 64.0 : 1.0;
+    if (bm == 256 && bn == 64) { mi = 2; ni = 2; }
+    if (bm == 128 && bn == 32) { mi = 1; ni = 1; }
+    if (bm == 32) { mi = 1; ni = 1; }
+    double reads_per_mfma = (mi + ni) / (mi * ni);
+    double eff = 1.0 / (1.0 + 0.45 * reads_per_mfma);
+    double fixed = 6000.0;  // prologue/epilogue per tile, in units of MFMA-volume
+    double cost = per_cu * ((double)bm * bn / eff + fixed);
+    if (cost < best_cost) { best_cost = cost; best = i; }
+  }
+  return best;
+}
+
+static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
+                             hipStream_t stream) {
+  const sc_conv_desc& d = pl->desc;
+  const Geometry& g = pl->geo;
+  const int which = dense ? 1 : 0;
+  const int64_t rows = dense ? g.m : pl->kept;
+  const bool zero_fill = !dense && d.out_mode == SC_OUT_ZERO_FILL && pl->kept < g.m;
+  const int eb = elem_bytes(d.dtype);
+  if (rows == 0) {
+    if (d.out_mode == SC_OUT_ZERO_FILL) {
+      int64_t bytes = g.y_elems * eb;
+      int64_t n16 = bytes / 16;
+      int ntail = (int)(bytes - n16 * 16);
+      int grid = (int)std::min<int64_t>((n16 + 255) / 256 + 1, 4096);
+      hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, stream, (uint4*)y, n16,
+                         (unsigned char*)y + n16 * 16, ntail);
+      SC_HIP(hipGetLastError());
+    }
+    return SC_OK;
+  }
+  int ti = pl->forced[which] >= 0 ? pl->forced[which] : (dense ? pl->tile_dense : pl->tile_sparse);
+  const KernelEntry& ke = pl->table[ti];
+  ConvParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.x = x;
+  p.wp = pl->ws + g.off_wp;
+  p.bias = d.has_bias ? bias : nullptr;
+  p.y = y;
+  p.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+  p.mask = pl->ws + g.off_mask;
+  p.ktab = reinterpret_cast<const KEntry*>(pl->ws + g.off_ktab);
+  p.rows = (int32_t)rows;
+  p.m_total = (int32_t)g.m;
+  p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
+  p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+  p.c_out = d.c_out;
+  p.k_pad = g.k_pad; p.k_tiles = g.k_tiles;
+  if (d.layout == SC_NHWC) {
+    p.xs_n = (int64_t)d.h * d.w * d.c_in; p.xs_h = d.w * d.c_in; p.xs_w = d.c_in;
+    p.ys_n = (int64_t)p.ho_wo * d.c_out; p.ys_p = d.c_out; p.ys_c = 1;
+  } else {
+    p.xs_n = (int64_t)d.c_in * d.h * d.w; p.xs_h = d.w; p.xs_w = 1;
+    p.ys_n = (int64_t)d.c_out * p.ho_wo; p.ys_p = 1; p.ys_c = p.ho_wo;
+  }
+  p.relu = d.relu;
+  p.zero_fill = zero_fill ? 1 : 0;
+  p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
+  p.vec_out = g.vec_out ? 1 : 0;
+  p.m_tiles = (int32_t)((rows + ke.bm - 1) / ke.bm);
+  p.n_tiles = (d.c_out + ke.bn - 1) / ke.bn;
+  LaunchFn fn = g.vec_gather ? ke.vec : ke.elem;
+  SC_HIP(fn(p, stream));
+  return SC_OK;
+}
+
+static sc_status check_run_args(const sc_plan* plan, const void* x, const float* bias, void* y) {
+  if (!plan || !x || !y) return SC_ERR_NULL;
+  if (plan->desc.has_bias && !bias) return SC_ERR_NULL;
+  if (((uintptr_t)x & 15) || ((uintptr_t)y & 15) || (plan->desc.has_bias && ((uintptr_t)bias & 15)))
+    return SC_ERR_ALIGN;
+  return SC_OK;
+}
+
+}  // namespace sc
+
+extern "C" {
+
+sc_status sparse_conv_output_shape(const sc_conv_desc* desc, int32_t* ho, int32_t* wo, int64_t* m) {
+  Geometry g;
+  sc_status s = check_desc(desc, &g);
+  if (s != SC_OK) return s;
+  if (ho) *ho = g.ho;
+  if (wo) *wo = g.wo;
+  if (m) *m = g.m;
+  return SC_OK;
+}
+
+sc_status sparse_conv_workspace_bytes(const sc_conv_desc* desc, size_t* bytes) {
+  if (!bytes) return SC_ERR_NULL;
+  Geometry g;
+  sc_status s = check_desc(desc, &g);
+  if (s != SC_OK) return s;
+  *bytes = g.total;
+  return SC_OK;
+}
+
+sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, const void* w_dev,
+                           void* workspace_dev, size_t workspace_bytes, void* hip_stream, sc_plan** out) {
+  if (!out) return SC_ERR_NULL;
+  *out = nullptr;
+  Geometry g;
+  sc_status s = check_desc(desc, &g);
+  if (s != SC_OK) return s;
+  if (!mask_dev || !w_dev || !workspace_dev) return SC_ERR_NULL;
+  if (workspace_bytes < g.total) return SC_ERR_WORKSPACE;
+  if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)w_dev & 15)) return SC_ERR_ALIGN;
+
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace_dev);
+  const sc_conv_desc& d = *desc;
+  const int eb = elem_bytes(d.dtype);
+
+  // a private copy of the mask (the zero fill of every run reads it)
+  SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
+
+  // compaction
+  const int period = d.mask_mode == SC_MASK_SPATIAL ? g.ho * g.wo : 0;
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + g.off_counts);
+  int32_t* rows = reinterpret_cast<int32_t*>(ws + g.off_rows);
+  int32_t* kept_dev = reinterpret_cast<int32_t*>(ws + g.off_kept);
+  const int cgrid = (g.nseg + 3) / 4;
+  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
+                     g.nseg, counts);
+  SC_HIP(hipGetLastError());
+  hipLaunchKernelGGL(mask_scatter_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
+                     g.nseg, counts, rows, kept_dev);
+  SC_HIP(hipGetLastError());
+
+  // filters
+  {
+    int64_t total = (int64_t)g.cout_pad * g.k_pad;
+    int grid = (int)((total + 255) / 256);
+    const int nchw = d.layout == SC_NCHW;
+    if (d.dtype == SC_F32)
+      hipLaunchKernelGGL(pack_filters_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)w_dev,
+                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_pad, g.cout_pad, nchw);
+    else  // 16-bit patterns are moved verbatim
+      hipLaunchKernelGGL(pack_filters_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, (const _Float16*)w_dev,
+                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_pad, g.cout_pad, nchw);
+    SC_HIP(hipGetLastError());
+  }
+
+  // gather table
+  {
+    const int vec = g.vec_gather ? g.vec : 1;
+    const int entries = g.k_pad / vec;
+    int xs_h, xs_w, xs_c;
+    if (d.layout == SC_NHWC) { xs_h = d.w * d.c_in; xs_w = d.c_in; xs_c = 1; }
+    else { xs_h = d.w; xs_w = 1; xs_c = d.h * d.w; }
+    hipLaunchKernelGGL(build_ktab_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<KEntry*>(ws + g.off_ktab), entries, vec, g.k, d.c_in, d.kw, d.dil_h, d.dil_w,
+                       xs_h, xs_w, xs_c);
+    SC_HIP(hipGetLastError());
+  }
+
+  int32_t kept_host = -1;
+  SC_HIP(hipMemcpyAsync(&kept_host, kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  SC_HIP(hipStreamSynchronize(stream));
+
+  if (d.sparsity >= 0.0f) {
+    // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up)
+    int64_t want = (int64_t)std::floor((1.0 - (double)d.sparsity) * (double)g.mask_len + 0.5);
+    int64_t have = d.mask_mode == SC_MASK_ROW ? kept_host : kept_host / d.n;
+    if (want != have) return SC_ERR_MASK_COUNT;
+  }
+
+  sc_plan* pl = new (std::nothrow) sc_plan;
+  if (!pl) return SC_ERR_NULL;
+  pl->desc = d;
+  pl->geo = g;
+  pl->ws = ws;
+  pl->kept = kept_host;
+  pl->table = d.dtype == SC_BF16 ? kernels_bf16(&pl->table_count)
+              : d.dtype == SC_F16 ? kernels_f16(&pl->table_count)
+                                  : kernels_f32(&pl->table_count);
+  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out);
+  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out);
+  pl->forced[0] = pl->forced[1] = -1;
+  (void)eb;
+  *out = pl;
+  return SC_OK;
+}
+
+sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
+                          void* hip_stream) {
+  sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (s != SC_OK) return s;
+  return launch_conv(plan, false, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
+                         void* hip_stream) {
+  sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (s != SC_OK) return s;
+  return launch_conv(plan, true, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, int32_t* ho, int32_t* wo,
+                                const int32_t** row_idx_dev) {
+  if (!plan) return SC_ERR_NULL;
+  if (m) *m = plan->geo.m;
+  if (kept) *kept = plan->kept;
+  if (ho) *ho = plan->geo.ho;
+  if (wo) *wo = plan->geo.wo;
+  if (row_idx_dev) *row_idx_dev = reinterpret_cast<const int32_t*>(plan->ws + plan->geo.off_rows);
+  return SC_OK;
+}
+
+sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* tile_m, int32_t* tile_n,
+                                 int64_t* workgroups) {
+  if (!plan) return SC_ERR_NULL;
+  if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
+  int ti = plan->forced[which] >= 0 ? plan->forced[which] : (which ? plan->tile_dense : plan->tile_sparse);
+  const KernelEntry& ke = plan->table[ti];
+  int64_t rows = which ? plan->geo.m : plan->kept;
+  if (tile_m) *tile_m = ke.bm;
+  if (tile_n) *tile_n = ke.bn;
+  if (workgroups) *workgroups = ((rows + ke.bm - 1) / ke.bm) * ((plan->desc.c_out + ke.bn - 1) / ke.bn);
+  return SC_OK;
+}
+
+sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n) {
+  if (!plan) return SC_ERR_NULL;
+  if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
+  if (tile_m == 0 && tile_n == 0) { plan->forced[which] = -1; return SC_OK; }
+  for (int i = 0; i < plan->table_count; ++i)
+    if (plan->table[i].bm == tile_m && plan->table[i].bn == tile_n) { plan->forced[which] = i; return SC_OK; }
+  return SC_ERR_UNSUPPORTED;
+}
+
+void sparse_conv_plan_destroy(sc_plan* plan) { delete plan; }
+
+const char* sc_status_string(sc_status s) {
+  switch (s) {
+    case SC_OK: return "ok";
+    case SC_ERR_NULL: return "a required pointer is NULL";
+    case SC_ERR_BAD_SHAPE: return "bad shape (non-positive extent, empty output or tensor too large)";
+    case SC_ERR_UNSUPPORTED: return "unsupported (groups != 1 or unknown dtype/layout/mode/tile)";
+    case SC_ERR_MASK_COUNT: return "mask popcount differs from the count the sparsity ratio demands";
+    case SC_ERR_WORKSPACE: return "workspace too small";
+    case SC_ERR_ALIGN: return "device pointer not sufficiently aligned";
+    case SC_ERR_HIP: return "a HIP call failed (see sc_last_hip_error)";
+  }
+  return "unknown status";
+}
+
+int32_t sc_last_hip_error(void) { return sc::g_last_hip; }
+
+sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32_t n, int32_t h, int32_t w,
+                            int32_t c, int32_t k, int32_t s, int32_t p, void* hip_stream) {
+  if (!x_dev || !y_dev) return SC_ERR_NULL;
+  if (dtype != SC_F32 && dtype != SC_F16 && dtype != SC_BF16) return SC_ERR_UNSUPPORTED;
+  if (n < 1 || h < 1 || w < 1 || c < 1 || k < 1 || s < 1 || p < 0 || 2 * p > k) return SC_ERR_BAD_SHAPE;
+  int ho = out_extent(h, k, s, p, 1), wo = out_extent(w, k, s, p, 1);
+  if (ho < 1 || wo < 1) return SC_ERR_BAD_SHAPE;
+  int64_t total = (int64_t)n * ho * wo * c;
+  if (total >= ((int64_t)1 << 31) * 256) return SC_ERR_BAD_SHAPE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (dtype == SC_F32)
+    hipLaunchKernelGGL(maxpool_nhwc_kernel<float>, grid, block, 0, stream, (const float*)x_dev, (float*)y_dev, n, h,
+                       w, c, k, s, p, ho, wo);
+  else if (dtype == SC_F16)
+    hipLaunchKernelGGL(maxpool_nhwc_kernel<_Float16>, grid, block, 0, stream, (const _Float16*)x_dev,
+                       (_Float16*)y_dev, n, h, w, c, k, s, p, ho, wo);
+  else
+    hipLaunchKernelGGL(maxpool_nhwc_kernel<__bf16>, grid, block, 0, stream, (const __bf16*)x_dev, (__bf16*)y_dev, n,
+                       h, w, c, k, s, p, ho, wo);
+  SC_HIP(hipGetLastError());
+  return SC_OK;
+}
+
+sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
+                      void* hip_stream) {
+  if (!a_dev || !b_dev || !y_dev) return SC_ERR_NULL;
+  if (dtype != SC_F32 && dtype != SC_F16 && dtype != SC_BF16) return SC_ERR_UNSUPPORTED;
+  if (count < 0) return SC_ERR_BAD_SHAPE;
+  if (count == 0) return SC_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  dim3 grid((unsigned)std::min<int64_t>((count + 255) / 256, 65536)), block(256);
+  if (dtype == SC_F32)
+    hipLaunchKernelGGL(add_relu_kernel<float>, grid, block, 0, stream, (const float*)a_dev, (const float*)b_dev,
+                       (float*)y_dev, count);
+  else if (dtype == SC_F16)
+    hipLaunchKernelGGL(add_relu_kernel<_Float16>, grid, block, 0, stream, (const _Float16*)a_dev,
+                       (const _Float16*)b_dev, (_Float16*)y_dev, count);
+  else
+    hipLaunchKernelGGL(add_relu_kernel<__bf16>, grid, block, 0, stream, (const __bf16*)a_dev, (const __bf16*)b_dev,
+                       (__bf16*)y_dev, count);
+  SC_HIP(hipGetLastError());
+  return SC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,74 @@
+"""Tensor marshalling and layer / network drivers on top of the C-ABI binding.
+
+Nothing here computes: host arrays are encoded and copied to the device, the library is
+called, results are copied back.
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def to_device(values_f32: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Host float32 values (already representable in `dtype`) -> device tensor of `dtype`."""
+    t = torch.from_numpy(np.ascontiguousarray(values_f32, dtype=np.float32))
+    return t.to(B.TORCH_DTYPE[dtype]).to(device).contiguous()
+
+
+def to_host_f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def bits_of(t: torch.Tensor) -> np.ndarray:
+    """Raw bit patterns of a device tensor (uint16 / uint32) on the host."""
+    view = {2: torch.int16, 4: torch.int32}[t.element_size()]
+    a = t.detach().contiguous().view(view).cpu().numpy()
+    return a.view({2: np.uint16, 4: np.uint32}[t.element_size()])
+
+
+class ConvLayer:
+    """One planned layer: device filters/bias/mask, workspace, plan handle, output buffer."""
+
+    def __init__(self, spec, w: np.ndarray, bias: Optional[np.ndarray], mask: np.ndarray, device="cuda:0",
+                 out_mode=B.SC_OUT_ZERO_FILL, check_count=True):
+        self.spec = spec
+        self.device = device
+        self.w = to_device(w, spec.dtype, device)
+        self.bias = torch.from_numpy(np.ascontiguousarray(bias, np.float32)).to(device) if spec.has_bias else None
+        self.mask = torch.from_numpy(np.ascontiguousarray(mask, np.uint8)).to(device)
+        self.desc = B.desc_from_spec(spec, out_mode=out_mode, check_count=check_count)
+        self.plan = B.sparse_conv_plan(self.desc, self.mask, self.w)
+        self.info = B.sparse_conv_plan_info(self.plan)
+
+    def new_output(self, fill_nan: bool = False) -> torch.Tensor:
+        y = torch.empty(self.spec.y_shape(), dtype=B.TORCH_DTYPE[self.spec.dtype], device=self.device)
+        if fill_nan:
+            y.fill_(float("nan"))
+        return y
+
+    def sparse(self, x: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+        y = self.new_output() if y is None else y
+        return B.sparse_conv_run(self.plan, x, self.bias, y)
+
+    def dense(self, x: torch.Tensor, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+        y = self.new_output() if y is None else y
+        return B.dense_conv_run(self.plan, x, self.bias, y)
+
+
+def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer]) -> Dict[str, torch.Tensor]:
+    """Interpret a workload op list on the device (conv = sparse_conv_run, plus the glue ops)."""
+    t = dict(tensors)
+    for op in ops:
+        if op.kind == "conv":
+            t[op.out] = layers[op.spec.name].sparse(t[op.src])
+        elif op.kind == "maxpool":
+            t[op.out] = B.sc_maxpool2d_nhwc(t[op.src], 3, 2, 1)
+        elif op.kind == "add_relu":
+            t[op.out] = B.sc_add_relu(t[op.src], t[op.src2])
+        else:
+            raise ValueError(op.kind)
+    return t

@@ -1,0 +1,237 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import oracle
+from paper_2309_06626_amd import binding as B
+from paper_2309_06626_amd import runtime as R
+from parity import TOL, assert_close, check_layer, rows_view
+
+pytestmark = pytest.mark.gpu
+
+ALL_TILES = [(256, 128), (128, 128), (256, 64), (128, 64), (64, 128), (64, 64), (128, 32), (32, 128)]
+
+
+def spec_of(n, cin, h, w, cout, k=3, s=1, p=1, d=1, dtype="bf16", layout="nhwc", bias=True, relu=True, sp=0.5,
+            mask_mode="row", kw=None, sw=None, pw=None, dw=None, name="t"):
+    return W.ConvSpec(name, n=n, c_in=cin, h=h, w=w, c_out=cout, kh=k, kw=k if kw is None else kw, stride_h=s,
+                      stride_w=s if sw is None else sw, pad_h=p, pad_w=p if pw is None else pw, dil_h=d,
+                      dil_w=d if dw is None else dw, dtype=dtype, layout=layout, has_bias=bias, relu=relu,
+                      sparsity=sp, mask_mode=mask_mode)
+
+
+def test_config1_fp32():
+    ci = W.make_conv_inputs(W.config1(), W.base_seed(1))
+    assert ci.keep == 128
+    check_layer(ci)
+
+
+SMALL = [
+    # several tiles and a ragged tail in M; channel counts off the vector widths; every conv knob
+    dict(n=3, cin=16, h=19, w=19, cout=32),
+    dict(n=2, cin=24, h=17, w=23, cout=48, sp=0.3),
+    dict(n=2, cin=5, h=14, w=11, cout=7, sp=0.4),                      # element gather, ragged channels
+    dict(n=1, cin=3, h=37, w=41, cout=64, k=7, s=2, p=3, sp=0.5),      # stem-like
+    dict(n=2, cin=32, h=15, w=15, cout=40, k=1, p=0, sp=0.5),          # pointwise
+    dict(n=2, cin=16, h=20, w=13, cout=16, k=3, s=2, p=1, sp=0.25),
+    dict(n=1, cin=8, h=21, w=18, cout=24, k=3, s=1, p=2, d=2, sp=0.6),
+    dict(n=2, cin=8, h=16, w=12, cout=16, k=3, kw=2, s=2, sw=1, p=0, pw=1, d=1, dw=1, sp=0.5),
+    dict(n=4, cin=64, h=9, w=9, cout=160, k=1, p=0, s=2, sp=0.5),      # strided pointwise (downsample)
+    dict(n=1, cin=16, h=6, w=6, cout=16, sp=0.9),                      # very few rows
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_layers(case, layout, dtype):
+    spec = spec_of(dtype=dtype, layout=layout, **SMALL[case])
+    check_layer(W.make_conv_inputs(spec, 500 + case))
+
+
+@pytest.mark.parametrize("bias,relu", [(False, False), (True, False), (False, True)])
+def test_bias_relu_switches(bias, relu):
+    spec = spec_of(2, 16, 12, 12, 32, dtype="bf16", bias=bias, relu=relu, sp=0.5)
+    check_layer(W.make_conv_inputs(spec, 77))
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("tile", ALL_TILES)
+def test_every_tile_shape(tile, dtype):
+    # kept = 1444 rows: several tiles of every height plus a ragged last tile; Cout = 160 leaves a
+    # ragged channel tile for the 64- and 128-wide shapes
+    spec = spec_of(8, 32, 19, 19, 160, dtype=dtype, sp=0.5)
+    layer = check_layer(W.make_conv_inputs(spec, 31), tiles=tile)
+    assert B.sparse_conv_plan_tiles(layer.plan, 0)[:2] == tile
+
+
+def test_tile_choice_follows_the_reduced_row_count():
+    spec = spec_of(8, 64, 28, 28, 128, sp=0.0)
+    wide = R.ConvLayer(spec, *_wbm(spec, 5))
+    spec9 = spec.with_(sparsity=0.97)
+    narrow = R.ConvLayer(spec9, *_wbm(spec9, 5))
+    tm0, tn0, wg0 = B.sparse_conv_plan_tiles(wide.plan, 0)
+    tm1, tn1, wg1 = B.sparse_conv_plan_tiles(narrow.plan, 0)
+    assert tm1 * tn1 <= tm0 * tn0
+    assert B.sparse_conv_plan_tiles(narrow.plan, 1)[:2] == (tm0, tn0)   # its dense run keeps the wide tile
+    with pytest.raises(B.ScError):
+        B.sparse_conv_plan_set_tiles(wide.plan, 0, 48, 48)
+
+
+def _wbm(spec, seed):
+    ci = W.make_conv_inputs(spec, seed, x=np.zeros(1, np.float32))
+    return ci.w, ci.bias, ci.mask
+
+
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+def test_spatial_mask_shared_by_the_batch(layout):
+    spec = spec_of(3, 16, 13, 17, 32, dtype="bf16", layout=layout, sp=0.4, mask_mode="spatial")
+    ci = W.make_conv_inputs(spec, 11)
+    assert ci.mask.size == spec.ho * spec.wo
+    check_layer(ci)
+
+
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+def test_scatter_only_leaves_dropped_rows_alone(layout):
+    spec = spec_of(2, 16, 15, 15, 32, dtype="bf16", layout=layout, sp=0.5)
+    check_layer(W.make_conv_inputs(spec, 13), out_mode=B.SC_OUT_SCATTER_ONLY)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_all_rows_dropped_and_all_rows_kept(dtype):
+    spec = spec_of(2, 16, 9, 9, 24, dtype=dtype, sp=0.5)
+    ci = W.make_conv_inputs(spec, 17)
+    ci.mask[:] = 0
+    check_layer(ci, check_count=False)
+    ci.mask[:] = 1
+    check_layer(ci, check_count=False)
+    ci.mask[:] = 0
+    ci.mask[-1] = 1                                    # a single kept row, the last one
+    check_layer(ci, check_count=False)
+    ci.mask[:] = 1
+    ci.mask[0] = 0
+    check_layer(ci, check_count=False)
+
+
+def test_any_nonzero_mask_byte_keeps_the_row():
+    spec = spec_of(1, 16, 8, 8, 16, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 19)
+    odd = ci.mask.copy()
+    odd[odd == 1] = np.random.default_rng(0).integers(1, 256, int(odd.sum())).astype(np.uint8)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, odd)
+    assert np.array_equal(B.plan_row_idx(layer.plan).cpu().numpy(), oracle.compact_rows(ci.mask))
+
+
+def test_mask_count_must_match_the_sparsity_ratio():
+    spec = spec_of(1, 16, 8, 8, 16, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 23)
+    bad = ci.mask.copy()
+    bad[np.flatnonzero(bad)[0]] = 0
+    with pytest.raises(B.ScError) as e:
+        R.ConvLayer(spec, ci.w, ci.bias, bad)
+    assert e.value.status == B.SC_ERR_MASK_COUNT
+    R.ConvLayer(spec, ci.w, ci.bias, bad, check_count=False)      # a negative ratio disables the check
+
+
+@pytest.mark.parametrize("m", [1, 63, 64, 65, 1023, 1024, 1025, 4096, 100352, 802816])
+def test_compaction_sizes(m):
+    # a0 on its own: m one-pixel "images" of a pointwise layer; the row list must equal the oracle's
+    spec = W.ConvSpec("cmp", n=m, c_in=8, h=1, w=1, c_out=16, kh=1, kw=1, pad_h=0, pad_w=0, dtype="bf16", sparsity=0.37)
+    mask = W.gen_mask(m, W.n_keep(0.37, m), 3 + m)
+    w = np.zeros(spec.w_shape(), np.float32)
+    layer = R.ConvLayer(spec, w, np.zeros(16, np.float32), mask)
+    want = oracle.compact_rows(mask)
+    assert layer.info["kept"] == want.size == oracle.kept_count(0.37, m)
+    assert np.array_equal(B.plan_row_idx(layer.plan).cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("s", W.C2_SPARSITIES)
+def test_config2_full_size(s):
+    spec = W.config2(s)
+    ci = W.make_conv_inputs(spec, W.base_seed(2))
+    assert ci.keep == {0.0: 100352, 0.25: 75264, 0.5: 50176, 0.7: 30106}[s]
+    check_layer(ci)
+
+
+@pytest.mark.parametrize("idx", range(16))
+def test_config4_pointwise(idx):
+    spec = W.config4()[idx]
+    check_layer(W.make_conv_inputs(spec, W.base_seed(4)))
+
+
+def test_glue_ops_match_oracle():
+    rng = np.random.default_rng(8)
+    for dtype in ("bf16", "f16", "f32"):
+        x = W.quantize(rng.standard_normal((3, 13, 10, 24)).astype(np.float32), dtype)
+        y = B.sc_maxpool2d_nhwc(R.to_device(x, dtype), 3, 2, 1)
+        assert np.array_equal(R.to_host_f32(y), oracle.maxpool2d_nhwc(x, 3, 2, 1))
+        b = W.quantize(rng.standard_normal(x.shape).astype(np.float32), dtype)
+        z = B.sc_add_relu(R.to_device(x, dtype), R.to_device(b, dtype))
+        assert np.array_equal(R.to_host_f32(z), oracle.round_storage(oracle.add_relu(x, b), dtype))
+
+
+def _run_network_both(ops, bs, batch_note=""):
+    """Run an op list through the HIP path and through the oracle from the same synthetic input."""
+    params = {}
+
+    def layer_inputs(spec):
+        if spec.name not in params:
+            ci = W.make_conv_inputs(spec, bs, x=np.zeros(1, np.float32))
+            params[spec.name] = (ci.w, ci.bias, ci.mask)
+        return params[spec.name]
+
+    dtype = W.conv_specs(ops)[0].dtype
+    host = {"input": W.gen_activations(W.network_input_shape(ops), bs, dtype)}
+    for op in ops:
+        if op.kind == "conv" and op.src.startswith("synthetic:"):
+            host[op.src] = W.gen_activations(op.spec.x_shape(), bs + 500 + op.spec.layer_index, dtype)
+    layers = {s.name: R.ConvLayer(s, *layer_inputs(s)) for s in W.conv_specs(ops)}
+    dev = R.run_network(ops, {k: R.to_device(v, dtype) for k, v in host.items()}, layers)
+    torch.cuda.synchronize()
+    ref = oracle.run_network(ops, host, layer_inputs)
+    return dev, ref, params
+
+
+def _compare_network(ops, dev, ref, params, tol):
+    for op in ops:
+        g, r = R.to_host_f32(dev[op.out]), ref[op.out]
+        assert g.shape == r.shape
+        nr = np.linalg.norm(r.astype(np.float64))
+        err = np.linalg.norm(g.astype(np.float64) - r.astype(np.float64)) / max(nr, 1e-30)
+        assert err <= tol, f"{op.out}: normwise {err:.3e}"
+        assert np.abs(g - r).max() <= tol * max(np.abs(r).max(), 1e-30), op.out
+        if op.kind == "conv":
+            mask = params[op.spec.name][2]
+            bits = rows_view(op.spec, R.bits_of(dev[op.out]))
+            assert (bits[mask == 0] == 0).all(), f"{op.out}: dropped rows must be zero"
+
+
+def test_config3_resnet18_stack_small_batch():
+    ops = W.config3(batch=4)
+    dev, ref, params = _run_network_both(ops, W.base_seed(3))
+    _compare_network(ops, dev, ref, params, TOL["bf16"])
+
+
+def test_config3_resnet18_stack_dense_downsample_variant():
+    ops = W.config3(batch=2, sparse_downsample=False)
+    dev, ref, params = _run_network_both(ops, W.base_seed(3))
+    _compare_network(ops, dev, ref, params, TOL["bf16"])
+
+
+def test_config5_detector_stack():
+    ops = W.config5(batch=16)
+    dev, ref, params = _run_network_both(ops, W.base_seed(5))
+    _compare_network(ops, dev, ref, params, TOL["bf16"])
+
+
+def test_config3_full_batch_sampled_rows():
+    """Every ResNet18 layer at batch 64 (the full configuration), each on synthetic input of its own
+    shape; structure checked everywhere, values on sampled rows the oracle computes one by one."""
+    for spec in W.conv_specs(W.config3(batch=64)):
+        ci = W.make_conv_inputs(spec, W.base_seed(3))
+        check_layer(ci, sample_rows=256)
+        torch.cuda.empty_cache()
