@@ -93,6 +93,8 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--with-copy", action="store_true",
+                    help="also run a plain 64 MiB device copy 20 times (calibrates HBM counters under rocprofv3)")
     ap.add_argument("--tile", type=str, default="", help="force the sparse tile, e.g. 128x64 (tuning)")
     ap.add_argument("--dense-tile", type=str, default="", help="force the dense tile (tuning)")
     args = ap.parse_args()
@@ -135,6 +137,13 @@ def main():
                           plan_ms=plan_ms, steps=steps, warm=warm)
         if s == 0.5:
             headline = results[s]
+
+    if args.with_copy:
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0").zero_()
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     r = headline
     spec, ci = r["spec"], r["ci"]

@@ -194,6 +194,26 @@ def dense_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y:
     return _run(lib().dense_conv_run, "dense_conv_run", plan, x, bias, y, stream)
 
 
+def prepared_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, dense: bool = False,
+                 stream=None):
+    """Validate once and return a zero-argument callable that issues the same run again
+    (launch loops: the per-call marshalling cost of `_run` is paid once)."""
+    fn = lib().dense_conv_run if dense else lib().sparse_conv_run
+    name = "dense_conv_run" if dense else "sparse_conv_run"
+    _run(fn, name, plan, x, bias, y, stream)   # full checks, one real launch
+    h, px, pb, py, st = plan.handle, x.data_ptr(), (bias.data_ptr() if bias is not None else None), y.data_ptr(), \
+        _stream_handle(stream)
+    keep = (plan, x, bias, y)
+
+    def call():
+        rc = fn(h, px, pb, py, st)
+        if rc != SC_OK:
+            raise ScError(rc, name)
+        return keep[3]
+
+    return call
+
+
 def sparse_conv_plan_info(plan: Plan) -> dict:
     m, kept, ho, wo, rows = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32(), ctypes.c_int32(), ctypes.c_void_p()
     _check(lib().sparse_conv_plan_info(plan.handle, ctypes.byref(m), ctypes.byref(kept), ctypes.byref(ho),

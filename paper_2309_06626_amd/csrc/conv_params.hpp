@@ -25,6 +25,7 @@ struct ConvParams {
   int32_t m_total;         // M = N*Ho*Wo
   int32_t h, w, ho_wo, wo;
   int32_t sh, sw, ph, pw;
+  int32_t c_in, kh, kw, dil_h, dil_w;
   int32_t c_out;
   int32_t k_pad;           // K rounded up to the K tile
   int32_t k_tiles;

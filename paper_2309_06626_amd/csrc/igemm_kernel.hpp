@@ -68,7 +68,7 @@ template <> struct Elem<kF32> {
 template <int BM, int BN>
 constexpr size_t igemm_lds_bytes() { return 2 * (size_t)(BM + BN) * kRowBytes + BM * sizeof(int32_t); }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, int DEPTH>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
@@ -100,13 +100,91 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
   const int lane = t & 63, wave = t >> 6;
   const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
 
-  for (int i = t; i < BM; i += kThreads) {
-    int ic = m0 + i;
-    s_rows[i] = ic < p.rows ? (p.row_idx ? p.row_idx[ic] : ic) : -1;
-  }
-  __syncthreads();
-
+  const T* __restrict__ x = static_cast<const T*>(p.x);
   T* __restrict__ y = static_cast<T*>(p.y);
+
+  // ---- per-thread gather state: the rows this thread stages, fixed for the whole K loop -------
+  const int c16 = t & 7;      // which 16-byte group of the 128-byte K tile
+  const int lrow = t >> 3;    // 0..31
+  int32_t a_base[A_LOADS], a_iy0[A_LOADS], a_ix0[A_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int ic = m0 + lrow + 32 * j;
+    int rr = -1;
+    if (ic < p.rows) rr = p.row_idx ? p.row_idx[ic] : ic;
+    s_rows[lrow + 32 * j] = rr;   // eight threads write the same value; read again in the epilogue
+    if (rr >= 0) {
+      int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
+      int oy = rem / p.wo, ox = rem - oy * p.wo;
+      a_iy0[j] = oy * p.sh - p.ph;
+      a_ix0[j] = ox * p.sw - p.pw;
+      a_base[j] = (int32_t)(n * p.xs_n + (int64_t)a_iy0[j] * p.xs_h + (int64_t)a_ix0[j] * p.xs_w);
+    } else {
+      a_iy0[j] = -(1 << 30);
+      a_ix0[j] = 0;
+      a_base[j] = 0;
+    }
+  }
+  const T* __restrict__ wp = static_cast<const T*>(p.wp) + (int64_t)(n0 + lrow) * p.k_pad + c16 * V;
+
+  // Position of this thread's 16-byte group inside the window, advanced by one K tile per load:
+  // channel g_ci of tap (g_ky, g_kx).  Taps past the last one (K padding) read as zero.
+  int g_ci = 0, g_kx = 0, g_ky = 0;
+  if constexpr (VEC) {
+    const int k0 = c16 * V;
+    const int tap = k0 / p.c_in;
+    g_ci = k0 - tap * p.c_in;
+    g_ky = tap / p.kw;
+    g_kx = tap - g_ky * p.kw;
+  }
+
+  v4i ra[DEPTH][A_LOADS], rb[DEPTH][B_LOADS];
+
+  auto load_tile = [&](int kt, v4i (&a)[A_LOADS], v4i (&b)[B_LOADS]) {
+    if constexpr (VEC) {
+      const int dy = g_ky * p.dil_h, dx = g_kx * p.dil_w;
+      const int off = dy * p.xs_h + dx * p.xs_w + g_ci;
+      const bool tap_ok = g_ky < p.kh;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        bool ok = tap_ok && (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
+        v4i v = {0, 0, 0, 0};
+        if (ok) v = *reinterpret_cast<const v4i*>(x + (a_base[j] + off));
+        a[j] = v;
+      }
+      g_ci += BK;
+      while (g_ci >= p.c_in) {
+        g_ci -= p.c_in;
+        if (++g_kx == p.kw) { g_kx = 0; ++g_ky; }
+      }
+    } else {
+      const KEntry* kt_e = p.ktab + kt * BK + c16 * V;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        T tmp[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          KEntry ke = kt_e[e];
+          int dy = ke.dydx & 0xffff, dx = ke.dydx >> 16;
+          bool ok = (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
+          tmp[e] = ok ? x[a_base[j] + ke.off] : E::from_float(0.0f);
+        }
+        v4i v;
+        __builtin_memcpy(&v, tmp, 16);
+        a[j] = v;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j)
+      b[j] = *reinterpret_cast<const v4i*>(wp + (int64_t)(32 * j) * p.k_pad + kt * BK);
+  };
+
+  // prefetch the first DEPTH K tiles before anything else so their latency overlaps the set-up
+#pragma unroll
+  for (int s = 0; s < DEPTH; ++s)
+    if (s < p.k_tiles) load_tile(s, ra[s], rb[s]);
+
+  __syncthreads();  // s_rows visible
 
   // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) ----------
   // Ownership: the dense rows from this tile's first kept row up to the next tile's first kept
@@ -139,71 +217,14 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     }
   }
 
-  // ---- per-thread gather state: the rows this thread stages, fixed for the whole K loop -------
-  const int c16 = t & 7;      // which 16-byte group of the 128-byte K tile
-  const int lrow = t >> 3;    // 0..31
-  int32_t a_base[A_LOADS], a_iy0[A_LOADS], a_ix0[A_LOADS];
-#pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) {
-    int rr = s_rows[lrow + 32 * j];
-    if (rr >= 0) {
-      int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
-      int oy = rem / p.wo, ox = rem - oy * p.wo;
-      a_iy0[j] = oy * p.sh - p.ph;
-      a_ix0[j] = ox * p.sw - p.pw;
-      a_base[j] = (int32_t)(n * p.xs_n + (int64_t)a_iy0[j] * p.xs_h + (int64_t)a_ix0[j] * p.xs_w);
-    } else {
-      a_iy0[j] = -(1 << 30);
-      a_ix0[j] = 0;
-      a_base[j] = 0;
-    }
-  }
-  const T* __restrict__ x = static_cast<const T*>(p.x);
-  const T* __restrict__ wp = static_cast<const T*>(p.wp) + (int64_t)(n0 + lrow) * p.k_pad + c16 * V;
-
-  v4i ra[A_LOADS], rb[B_LOADS];
-
-  auto load_tile = [&](int kt) {
-    if constexpr (VEC) {
-      KEntry e = p.ktab[kt * 8 + c16];
-      int dy = e.dydx & 0xffff, dx = e.dydx >> 16;
-#pragma unroll
-      for (int j = 0; j < A_LOADS; ++j) {
-        bool ok = (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
-        v4i v = {0, 0, 0, 0};
-        if (ok) v = *reinterpret_cast<const v4i*>(x + (a_base[j] + e.off));
-        ra[j] = v;
-      }
-    } else {
-      const KEntry* kt_e = p.ktab + kt * BK + c16 * V;
-#pragma unroll
-      for (int j = 0; j < A_LOADS; ++j) {
-        T tmp[V];
-#pragma unroll
-        for (int e = 0; e < V; ++e) {
-          KEntry ke = kt_e[e];
-          int dy = ke.dydx & 0xffff, dx = ke.dydx >> 16;
-          bool ok = (unsigned)(a_iy0[j] + dy) < (unsigned)p.h && (unsigned)(a_ix0[j] + dx) < (unsigned)p.w;
-          tmp[e] = ok ? x[a_base[j] + ke.off] : E::from_float(0.0f);
-        }
-        v4i v;
-        __builtin_memcpy(&v, tmp, 16);
-        ra[j] = v;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j)
-      rb[j] = *reinterpret_cast<const v4i*>(wp + (int64_t)(32 * j) * p.k_pad + kt * BK);
-  };
-
   const int st_off = lrow * kRowBytes + ((c16 ^ (lrow & 7)) << 4);
-  auto store_tile = [&](int buf) {
-    unsigned char* a = s_a + buf * BM * kRowBytes + st_off;
-    unsigned char* b = s_b + buf * BN * kRowBytes + st_off;
+  auto store_tile = [&](int buf, const v4i (&a)[A_LOADS], const v4i (&b)[B_LOADS]) {
+    unsigned char* pa = s_a + buf * BM * kRowBytes + st_off;
+    unsigned char* pb = s_b + buf * BN * kRowBytes + st_off;
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) *reinterpret_cast<v4i*>(a + j * 32 * kRowBytes) = ra[j];
+    for (int j = 0; j < A_LOADS; ++j) *reinterpret_cast<v4i*>(pa + j * 32 * kRowBytes) = a[j];
 #pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) *reinterpret_cast<v4i*>(b + j * 32 * kRowBytes) = rb[j];
+    for (int j = 0; j < B_LOADS; ++j) *reinterpret_cast<v4i*>(pb + j * 32 * kRowBytes) = b[j];
   };
 
   floatx16 acc[MI][NI];
@@ -238,17 +259,22 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     }
   };
 
-  // ---- main loop: global -> registers -> LDS, double buffered, one barrier per K tile ---------
-  load_tile(0);
-  store_tile(0);
+  // ---- main loop: global -> registers (DEPTH K tiles in flight) -> LDS (double buffered) -> MFMA,
+  // one barrier per K tile.  Tile kt sits in register slot kt % DEPTH; the loop is unrolled by
+  // DEPTH so that every slot index is a compile-time constant.
+  store_tile(0, ra[0], rb[0]);
   __syncthreads();
-  for (int kt = 0; kt < p.k_tiles; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < p.k_tiles;
-    if (more) load_tile(kt + 1);
-    compute_tile(cur);
-    if (more) store_tile(cur ^ 1);
-    __syncthreads();
+#pragma unroll 1
+  for (int kt0 = 0; kt0 < p.k_tiles; kt0 += DEPTH) {
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) {
+      const int kt = kt0 + s;
+      if (kt >= p.k_tiles) break;
+      if (kt + DEPTH < p.k_tiles) load_tile(kt + DEPTH, ra[s], rb[s]);   // slot s was drained last iteration
+      compute_tile(kt & 1);
+      if (kt + 1 < p.k_tiles) store_tile((kt + 1) & 1, ra[(s + 1) % DEPTH], rb[(s + 1) % DEPTH]);
+      __syncthreads();
+    }
   }
 
   // ---- epilogue: bias, ReLU, convert, store every kept row at its dense position --------------
@@ -301,10 +327,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
   }
 }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC>
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, int DEPTH>
 hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
   constexpr size_t lds = igemm_lds_bytes<BM, BN>();
-  auto kern = igemm_kernel<DT, BM, BN, WAVES_M, WAVES_N, VEC>;
+  auto kern = igemm_kernel<DT, BM, BN, WAVES_M, WAVES_N, VEC, DEPTH>;
   static bool attr_set = false;
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -318,8 +344,8 @@ hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-#define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_)                                             \
-  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true>,                        \
-                igemm_launch<DT, BM, BN, WM_, WN_, false>, igemm_lds_bytes<BM, BN>() }
+#define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_, DEPTH)                                      \
+  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
+                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>, igemm_lds_bytes<BM, BN>() }
 
 }  // namespace sc

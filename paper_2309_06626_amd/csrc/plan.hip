@@ -306,6 +306,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.m_total = (int32_t)g.m;
   p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
   p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+  p.c_in = d.c_in; p.kh = d.kh; p.kw = d.kw; p.dil_h = d.dil_h; p.dil_w = d.dil_w;
   p.c_out = d.c_out;
   p.k_pad = g.k_pad; p.k_tiles = g.k_tiles;
   if (d.layout == SC_NHWC) {
