@@ -124,13 +124,16 @@ sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bi
 sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, int32_t* ho, int32_t* wo,
                                 const int32_t** row_idx_dev);
 
-/* Tile shape chosen for the sparse (which = 0) or dense (which = 1) launch:
- * rows x couts per workgroup, and the number of workgroups. */
+/* Tile shape chosen for the sparse (which = 0) or dense (which = 1) launch: rows x couts per
+ * workgroup, and the number of workgroups.  The library has two kernels: the tiled gather kernel
+ * (tile_m > 0 kept rows per workgroup) and the band kernel, which stages a band of input rows of
+ * one image in LDS (reported as tile_m = -BH, BH = output rows per band). */
 sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* tile_m, int32_t* tile_n,
                                  int64_t* workgroups);
 
-/* Tuning hook: force the tile shape of later runs (0,0 restores the automatic choice).
- * Returns SC_ERR_UNSUPPORTED when the library has no kernel of that shape. */
+/* Tuning hook: force the kernel of later runs.  (0,0) restores the automatic choice; tile_m > 0
+ * selects the tiled gather kernel of that shape; tile_m < 0 selects the band kernel (band height
+ * stays automatic).  Returns SC_ERR_UNSUPPORTED when the library has no such kernel for the layer. */
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
 
 void sparse_conv_plan_destroy(sc_plan* plan);

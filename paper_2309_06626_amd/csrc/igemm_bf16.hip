@@ -1,4 +1,5 @@
 // Instantiations of the fused masked-convolution kernel for bf16 operands (float accumulate).
+#include "band_kernel.hpp"
 #include "igemm_kernel.hpp"
 
 namespace sc {
@@ -18,5 +19,8 @@ const KernelEntry* kernels_bf16(int* count) {
   *count = (int)(sizeof(g_table) / sizeof(g_table[0]));
   return g_table;
 }
+
+static const BandTable g_band = SC_BAND_TABLE(kBF16);
+const BandTable* band_bf16() { return &g_band; }
 
 }  // namespace sc

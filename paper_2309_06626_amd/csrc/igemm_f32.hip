@@ -1,4 +1,5 @@
 // Instantiations of the fused masked-convolution kernel for f32 operands (float accumulate).
+#include "band_kernel.hpp"
 #include "igemm_kernel.hpp"
 
 namespace sc {
@@ -18,5 +19,8 @@ const KernelEntry* kernels_f32(int* count) {
   *count = (int)(sizeof(g_table) / sizeof(g_table[0]));
   return g_table;
 }
+
+static const BandTable g_band = SC_BAND_TABLE(kF32);
+const BandTable* band_f32() { return &g_band; }
 
 }  // namespace sc

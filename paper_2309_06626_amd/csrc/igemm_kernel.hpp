@@ -21,49 +21,9 @@
 //   rows hit distinct banks.
 #pragma once
 #include "conv_params.hpp"
+#include "mma_common.hpp"
 
 namespace sc {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-
-template <int DT> struct Elem;
-template <> struct Elem<kBF16> {
-  using T = __bf16;
-  static constexpr int V = 8;  // elements per 16 bytes
-  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf), __builtin_bit_cast(bf16x8, xf),
-                                                  acc, 0, 0, 0);
-  }
-  static __device__ __forceinline__ T from_float(float f) { return (__bf16)f; }
-};
-template <> struct Elem<kF16> {
-  using T = _Float16;
-  static constexpr int V = 8;
-  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, wf), __builtin_bit_cast(f16x8, xf),
-                                                 acc, 0, 0, 0);
-  }
-  static __device__ __forceinline__ T from_float(float f) { return (_Float16)f; }
-};
-template <> struct Elem<kF32> {
-  using T = float;
-  static constexpr int V = 4;
-  // A 16-byte group holds 4 consecutive K entries; the two lane halves hold two different
-  // groups, so MFMA number e contracts entry e of both groups (any consistent pairing of K
-  // entries between the two operands is a valid order of the sum).
-  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
-    v4f a = __builtin_bit_cast(v4f, wf), b = __builtin_bit_cast(v4f, xf);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
-  }
-  static __device__ __forceinline__ T from_float(float f) { return f; }
-};
 
 template <int BM, int BN>
 constexpr size_t igemm_lds_bytes() { return 2 * (size_t)(BM + BN) * kRowBytes + BM * sizeof(int32_t); }
@@ -286,43 +246,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
-      float vals[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) vals[v] = acc[mi][ni][v];
-      if (p.vec_out) {
-        if (p.bias) {
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            v4f b4 = *reinterpret_cast<const v4f*>(p.bias + c0 + 4 * q);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
-          }
-        }
-        if (p.relu) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
-        }
-        T outv[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
-        v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * p.c_out + c0));
-        v4i pk[16 * EB / 16];
-        __builtin_memcpy(pk, outv, 16 * EB);
-#pragma unroll
-        for (int q = 0; q < 16 * EB / 16; ++q) dst[q] = pk[q];
-      } else {
-        const int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
-        T* dst = y + n * p.ys_n + (int64_t)rem * p.ys_p;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int c = c0 + v;
-          if (c < p.c_out) {
-            float f = vals[v] + (p.bias ? p.bias[c] : 0.0f);
-            if (p.relu) f = fmaxf(f, 0.0f);
-            dst[(int64_t)c * p.ys_c] = E::from_float(f);
-          }
-        }
-      }
+      store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, p.vec_out, p.c_out, p.ho_wo, p.ys_n, p.ys_p,
+                           p.ys_c);
     }
   }
 }

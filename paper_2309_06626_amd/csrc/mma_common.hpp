@@ -1,0 +1,98 @@
+// Types, MFMA wrappers and the kept-row store shared by the masked-convolution kernels.
+#pragma once
+#include "conv_params.hpp"
+
+namespace sc {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+template <int DT> struct Elem;
+template <> struct Elem<kBF16> {
+  using T = __bf16;
+  static constexpr int V = 8;  // elements per 16 bytes
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf), __builtin_bit_cast(bf16x8, xf),
+                                                  acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return (__bf16)f; }
+};
+template <> struct Elem<kF16> {
+  using T = _Float16;
+  static constexpr int V = 8;
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, wf), __builtin_bit_cast(f16x8, xf),
+                                                 acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return (_Float16)f; }
+};
+template <> struct Elem<kF32> {
+  using T = float;
+  static constexpr int V = 4;
+  // A 16-byte group holds 4 consecutive K entries; the two lane halves hold two different
+  // groups, so MFMA number e contracts entry e of both groups (any consistent pairing of K
+  // entries between the two operands is a valid order of the sum).
+  static __device__ __forceinline__ void mma(floatx16& acc, v4i wf, v4i xf) {
+    v4f a = __builtin_bit_cast(v4f, wf), b = __builtin_bit_cast(v4f, xf);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[2], acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[3], acc, 0, 0, 0);
+  }
+  static __device__ __forceinline__ T from_float(float f) { return f; }
+};
+
+// Bias, ReLU, conversion and store of one 32x32 MFMA block for the lane's output position:
+// `acc` holds 16 consecutive output channels c0..c0+15 of dense row rr (Alg. 2, copy branch: the
+// result of a kept row goes to its dense slot).  bias[bias_at + v] belongs to channel c0 + v.
+template <int DT>
+__device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* __restrict__ y,
+                                                 const float* __restrict__ bias, int bias_at, int relu, int vec_out,
+                                                 int c_out,
+                                                 int ho_wo, int64_t ys_n, int ys_p, int ys_c) {
+  using E = Elem<DT>;
+  using T = typename E::T;
+  constexpr int EB = sizeof(T);
+  float vals[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) vals[v] = acc[v];
+  if (vec_out) {
+    if (bias) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
+      }
+    }
+    if (relu) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
+    }
+    T outv[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
+    v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * c_out + c0));
+    v4i pk[16 * EB / 16];
+    __builtin_memcpy(pk, outv, 16 * EB);
+#pragma unroll
+    for (int q = 0; q < 16 * EB / 16; ++q) dst[q] = pk[q];
+  } else {
+    const int n = rr / ho_wo, rem = rr - n * ho_wo;
+    T* dst = y + n * ys_n + (int64_t)rem * ys_p;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      int c = c0 + v;
+      if (c < c_out) {
+        float f = vals[v] + (bias ? bias[bias_at + v] : 0.0f);
+        if (relu) f = fmaxf(f, 0.0f);
+        dst[(int64_t)c * ys_c] = E::from_float(f);
+      }
+    }
+  }
+}
+
+}  // namespace sc

@@ -9,11 +9,15 @@
 #include <cstring>
 #include <new>
 
+#include "band_kernel.hpp"
 #include "conv_params.hpp"
 
 namespace sc {
 
 static thread_local int32_t g_last_hip = 0;
+#ifdef SC_TIMING
+static long long* g_dbg = nullptr;   // development builds only
+#endif
 
 static inline bool hip_failed(hipError_t e) {
   if (e != hipSuccess) { g_last_hip = (int32_t)e; return true; }
@@ -122,6 +126,28 @@ __global__ void fill_zero_kernel(uint4* __restrict__ dst, int64_t n16, unsigned 
   if (blockIdx.x == 0 && (int)threadIdx.x < ntail) tail[threadIdx.x] = 0;
 }
 
+// First compacted row of every band: lower bound of the band's first dense row in the kept-row list.
+__global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
+                                  int32_t* __restrict__ band_i0, int n_bands, int bands_per_image, int bh, int ho,
+                                  int wo) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b > n_bands) return;
+  const int kept = *kept_dev;
+  int target;
+  if (b == n_bands) {
+    target = 0x7fffffff;
+  } else {
+    int img = b / bands_per_image, oy0 = (b - img * bands_per_image) * bh;
+    target = (img * ho + oy0) * wo;
+  }
+  int lo = 0, hi = kept;
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (row_idx[mid] < target) lo = mid + 1; else hi = mid;
+  }
+  band_i0[b] = lo;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Glue operators for network runs
 // ------------------------------------------------------------------------------------------------
@@ -166,12 +192,12 @@ static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
 struct Geometry {
   int32_t ho, wo;
   int64_t m;
-  int32_t k, k_pad, k_tiles, vec, cout_pad;
+  int32_t k, k_pad, k_stride, k_tiles, vec, cout_pad;
   bool vec_gather, vec_out;
   int64_t x_elems, y_elems, mask_len;
   int32_t nseg;
   // workspace carve (byte offsets)
-  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, total;
+  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, off_band, total;
 };
 
 static int out_extent(int in, int k, int stride, int pad, int dil) {
@@ -211,6 +237,8 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   const int bk = 8 * g->vec;
   g->k_pad = (int32_t)((k + bk - 1) / bk * bk);
   g->k_tiles = g->k_pad / bk;
+  // filter rows are spaced by an odd number of K tiles: the band kernel's LDS swizzle relies on it
+  g->k_stride = (g->k_tiles & 1) ? g->k_pad : g->k_pad + bk;
   g->cout_pad = (d->c_out + 255) / 256 * 256;
   g->vec_gather = d->layout == SC_NHWC && d->c_in % g->vec == 0;
   g->vec_out = d->layout == SC_NHWC && d->c_out % 16 == 0;
@@ -221,10 +249,56 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->off_counts = off; off = align_up(off + (size_t)g->nseg * 4, 256);
   g->off_kept = off;   off += 256;
   g->off_mask = off;   off = align_up(off + (size_t)g->mask_len, 256);
-  g->off_wp = off;     off = align_up(off + (size_t)g->cout_pad * g->k_pad * eb, 256);
+  g->off_wp = off;     off = align_up(off + (size_t)g->cout_pad * g->k_stride * eb, 256);
   g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
+  g->off_band = off;   off = align_up(off + ((size_t)d->n * g->ho + 1) * 4, 256);
   g->total = off;
   return SC_OK;
+}
+
+// Band kernel applicability and band height.
+struct BandPlan {
+  bool ok;
+  int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
+  size_t b_bytes, x_bytes, lds;
+};
+
+constexpr size_t kLdsLimit = 160 * 1024;
+// behind the band kernel's slabs: a zeroed KiB and 128 bias floats
+constexpr size_t kBandExtraLds = 1024 + 128 * 4;
+
+static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
+  BandPlan bp;
+  std::memset(&bp, 0, sizeof(bp));
+  const int eb = elem_bytes(d.dtype);
+  if (d.layout != SC_NHWC || !g.vec_gather || !g.vec_out) return bp;
+  if ((d.c_in / g.vec) % 2 != 0) return bp;      // a K step of two 16-byte groups must stay inside one tap
+  if (d.kh * d.kw == 1) return bp;               // no window overlap to exploit: gather kept rows directly
+  bp.ni = d.c_out <= 32 ? 1 : d.c_out <= 64 ? 2 : 4;
+  bp.ni_idx = bp.ni == 1 ? 0 : bp.ni == 2 ? 1 : 2;
+  bp.n_tiles = (d.c_out + 32 * bp.ni - 1) / (32 * bp.ni);
+  bp.b_bytes = (size_t)32 * bp.ni * g.k_stride * eb;
+  if (bp.b_bytes > 96 * 1024) return bp;         // leave room for a band worth staging
+  double best = 1e300;
+  for (int bh = 1; bh <= g.ho; ++bh) {
+    int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
+    size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
+    if (bp.b_bytes + xbytes + kBandExtraLds > kLdsLimit) break;
+    int bpi = (g.ho + bh - 1) / bh;
+    int64_t nb = (int64_t)d.n * bpi * bp.n_tiles;
+    double rounds = std::ceil((double)nb / 256.0);
+    double cost = rounds * ((double)xbytes + (double)bp.b_bytes + 64.0 * bh * g.wo);
+    if (cost <= best) {
+      best = cost;
+      bp.ok = true;
+      bp.bh = bh;
+      bp.bands_per_image = bpi;
+      bp.n_bands = d.n * bpi;
+      bp.x_bytes = xbytes;
+      bp.lds = bp.b_bytes + xbytes + kBandExtraLds;
+    }
+  }
+  return bp;
 }
 
 }  // namespace sc
@@ -234,13 +308,16 @@ using namespace sc;
 struct sc_plan {
   sc_conv_desc desc;
   Geometry geo;
+  BandPlan band;
+  const BandTable* band_table;
   unsigned char* ws;
   int64_t kept;
   const KernelEntry* table;
   int table_count;
   int tile_sparse, tile_dense;     // chosen indices into table
-  int forced[2];                   // -1 = automatic
+  int forced[2];                   // -1 = automatic, >= 0 generic tile index, kForceBand = band kernel
 };
+constexpr int kForceBand = -2;
 
 namespace sc {
 
@@ -291,6 +368,39 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     }
     return SC_OK;
   }
+  const bool use_band = pl->band.ok && (pl->forced[which] == kForceBand || pl->forced[which] == -1);
+  if (use_band) {
+    const BandPlan& b = pl->band;
+    BandParams q;
+    std::memset(&q, 0, sizeof(q));
+    q.x = x;
+    q.wp = pl->ws + g.off_wp;
+    q.bias = d.has_bias ? bias : nullptr;
+    q.y = y;
+    q.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+    q.mask = pl->ws + g.off_mask;
+    q.band_i0 = reinterpret_cast<const int32_t*>(pl->ws + g.off_band);
+    q.h = d.h; q.w = d.w; q.c_in = d.c_in; q.ho = g.ho; q.wo = g.wo; q.c_out = d.c_out;
+    q.kh = d.kh; q.kw = d.kw; q.sh = d.stride_h; q.sw = d.stride_w; q.ph = d.pad_h; q.pw = d.pad_w;
+    q.dil_h = d.dil_h; q.dil_w = d.dil_w;
+    q.k_stride = g.k_stride;
+    q.bh = b.bh; q.bands_per_image = b.bands_per_image; q.n_bands = b.n_bands; q.n_tiles = b.n_tiles;
+    q.b_bytes = (int32_t)b.b_bytes;
+    q.x_groups = (int32_t)(b.x_bytes / 16);
+    q.relu = d.relu;
+    q.zero_fill = zero_fill ? 1 : 0;
+    q.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
+#ifdef SC_TIMING
+    q.dbg = g_dbg;
+#endif
+    // rows per wavefront decide how many 32-row MFMA blocks share one filter fragment
+    const double per_wave = (double)rows / b.n_bands / 4.0;
+    const int mi_idx = per_wave > 32.0 ? 1 : 0;
+    const int cpp = d.c_in / g.vec;
+    const int shape = (d.kh == 3 && d.kw == 3 && cpp == 8) ? 1 : (d.kh == 3 && d.kw == 3 && cpp == 4) ? 2 : 0;
+    SC_HIP(pl->band_table->fn[shape][b.ni_idx][mi_idx](q, b.lds, stream));
+    return SC_OK;
+  }
   int ti = pl->forced[which] >= 0 ? pl->forced[which] : (dense ? pl->tile_dense : pl->tile_sparse);
   const KernelEntry& ke = pl->table[ti];
   ConvParams p;
@@ -308,7 +418,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
   p.c_in = d.c_in; p.kh = d.kh; p.kw = d.kw; p.dil_h = d.dil_h; p.dil_w = d.dil_w;
   p.c_out = d.c_out;
-  p.k_pad = g.k_pad; p.k_tiles = g.k_tiles;
+  p.k_pad = g.k_stride; p.k_tiles = g.k_tiles;
   if (d.layout == SC_NHWC) {
     p.xs_n = (int64_t)d.h * d.w * d.c_in; p.xs_h = d.w * d.c_in; p.xs_w = d.c_in;
     p.ys_n = (int64_t)p.ho_wo * d.c_out; p.ys_p = d.c_out; p.ys_c = 1;
@@ -392,15 +502,15 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
 
   // filters
   {
-    int64_t total = (int64_t)g.cout_pad * g.k_pad;
+    int64_t total = (int64_t)g.cout_pad * g.k_stride;
     int grid = (int)((total + 255) / 256);
     const int nchw = d.layout == SC_NCHW;
     if (d.dtype == SC_F32)
       hipLaunchKernelGGL(pack_filters_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)w_dev,
-                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_pad, g.cout_pad, nchw);
+                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw);
     else  // 16-bit patterns are moved verbatim
       hipLaunchKernelGGL(pack_filters_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, (const _Float16*)w_dev,
-                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_pad, g.cout_pad, nchw);
+                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw);
     SC_HIP(hipGetLastError());
   }
 
@@ -414,6 +524,13 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     hipLaunchKernelGGL(build_ktab_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream,
                        reinterpret_cast<KEntry*>(ws + g.off_ktab), entries, vec, g.k, d.c_in, d.kw, d.dil_h, d.dil_w,
                        xs_h, xs_w, xs_c);
+    SC_HIP(hipGetLastError());
+  }
+
+  BandPlan bp = plan_band(d, g);
+  if (bp.ok) {
+    hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
+                       reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
     SC_HIP(hipGetLastError());
   }
 
@@ -440,6 +557,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out);
   pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out);
   pl->forced[0] = pl->forced[1] = -1;
+  pl->band = bp;
+  pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   (void)eb;
   *out = pl;
   return SC_OK;
@@ -474,6 +593,12 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups) {
   if (!plan) return SC_ERR_NULL;
   if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
+  if (plan->band.ok && (plan->forced[which] == kForceBand || plan->forced[which] == -1)) {
+    if (tile_m) *tile_m = -plan->band.bh;
+    if (tile_n) *tile_n = 32 * plan->band.ni;
+    if (workgroups) *workgroups = (int64_t)plan->band.n_bands * plan->band.n_tiles;
+    return SC_OK;
+  }
   int ti = plan->forced[which] >= 0 ? plan->forced[which] : (which ? plan->tile_dense : plan->tile_sparse);
   const KernelEntry& ke = plan->table[ti];
   int64_t rows = which ? plan->geo.m : plan->kept;
@@ -487,6 +612,11 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
   if (!plan) return SC_ERR_NULL;
   if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
   if (tile_m == 0 && tile_n == 0) { plan->forced[which] = -1; return SC_OK; }
+  if (tile_m < 0) {
+    if (!plan->band.ok) return SC_ERR_UNSUPPORTED;
+    plan->forced[which] = kForceBand;
+    return SC_OK;
+  }
   for (int i = 0; i < plan->table_count; ++i)
     if (plan->table[i].bm == tile_m && plan->table[i].bn == tile_n) { plan->forced[which] = i; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
@@ -509,6 +639,10 @@ const char* sc_status_string(sc_status s) {
 }
 
 int32_t sc_last_hip_error(void) { return sc::g_last_hip; }
+
+#ifdef SC_TIMING
+void sc_debug_set_buffer(void* p) { sc::g_dbg = static_cast<long long*>(p); }
+#endif
 
 sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32_t n, int32_t h, int32_t w,
                             int32_t c, int32_t k, int32_t s, int32_t p, void* hip_stream) {

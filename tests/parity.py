@@ -56,7 +56,7 @@ def check_layer(ci: W.ConvInputs, tiles=None, out_mode=B.SC_OUT_ZERO_FILL, check
     spec = ci.spec
     tol = TOL[spec.dtype]
     layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, device=device, out_mode=out_mode, check_count=check_count)
-    if tiles is not None:
+    if tiles is not None:   # (tile_m, tile_n) of the tiled kernel, or (-1, 0) for the band kernel
         B.sparse_conv_plan_set_tiles(layer.plan, 0, *tiles)
         B.sparse_conv_plan_set_tiles(layer.plan, 1, *tiles)
     rm = row_mask(spec, ci.mask)

@@ -70,7 +70,7 @@ def test_every_tile_shape(tile, dtype):
 
 
 def test_tile_choice_follows_the_reduced_row_count():
-    spec = spec_of(8, 64, 28, 28, 128, sp=0.0)
+    spec = spec_of(8, 72, 28, 28, 128, sp=0.0)     # 72 channels: only the tiled gather kernel applies
     wide = R.ConvLayer(spec, *_wbm(spec, 5))
     spec9 = spec.with_(sparsity=0.97)
     narrow = R.ConvLayer(spec9, *_wbm(spec9, 5))
@@ -80,6 +80,42 @@ def test_tile_choice_follows_the_reduced_row_count():
     assert B.sparse_conv_plan_tiles(narrow.plan, 1)[:2] == (tm0, tn0)   # its dense run keeps the wide tile
     with pytest.raises(B.ScError):
         B.sparse_conv_plan_set_tiles(wide.plan, 0, 48, 48)
+
+
+BAND_CASES = [
+    dict(n=3, cin=64, h=20, w=20, cout=64),                         # 3x3, two filter blocks
+    dict(n=2, cin=32, h=23, w=17, cout=32, sp=0.3),                 # one filter block, ragged band at the bottom
+    dict(n=2, cin=16, h=19, w=31, cout=128, sp=0.6),                # four filter blocks
+    dict(n=2, cin=32, h=21, w=21, cout=160, sp=0.5),                # two channel tiles, the second ragged
+    dict(n=2, cin=16, h=22, w=18, cout=48, k=3, s=2, p=1, sp=0.4),  # stride 2
+    dict(n=1, cin=16, h=24, w=20, cout=32, k=3, p=2, d=2, sp=0.5),  # dilation 2
+    dict(n=2, cin=16, h=18, w=26, cout=32, k=5, p=2, sp=0.5),       # 5x5
+    dict(n=2, cin=32, h=17, w=15, cout=64, k=3, kw=1, p=1, pw=0, sp=0.5),   # 3x1 window
+    dict(n=1, cin=64, h=12, w=12, cout=64, sp=0.95),                # bands with almost no kept rows
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("case", range(len(BAND_CASES)))
+def test_band_kernel(case, mask_mode, dtype):
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **BAND_CASES[case])
+    eb = 4 if dtype == "f32" else 2
+    if min(spec.c_out, 128) * spec.k * eb > 96 * 1024:
+        pytest.skip("filter slab too large for the band kernel at this element size")
+    layer = check_layer(W.make_conv_inputs(spec, 900 + case), tiles=(-1, 0))
+    assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] < 0          # really the band kernel
+    # and the tiled kernel on the same layer
+    check_layer(W.make_conv_inputs(spec, 900 + case), tiles=(64, 64))
+
+
+def test_band_kernel_scatter_only_and_empty():
+    spec = spec_of(2, 32, 16, 16, 64, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 41)
+    check_layer(ci, tiles=(-1, 0), out_mode=B.SC_OUT_SCATTER_ONLY)
+    ci.mask[:] = 0
+    ci.mask[100] = 1
+    check_layer(ci, tiles=(-1, 0), check_count=False)
 
 
 def _wbm(spec, seed):
