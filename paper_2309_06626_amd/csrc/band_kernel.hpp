@@ -11,8 +11,8 @@
 //   workgroup  = one band (BH output rows x all Wo columns of one image) x 32*NI output channels
 //   wavefront  = a contiguous quarter of the band's kept rows, 32*MI rows per MFMA block
 //   LDS        = filter slab, then the input slab; 16-byte groups are XOR-swizzled
-//                (q ^ ((q >> 3) & 7)) so that eight lanes reading the same group of eight
-//                consecutive pixels / filter rows hit eight different bank groups
+//                (q ^ ((q >> 4) & 7)) so that sixteen lanes reading the same channel group of
+//                sixteen consecutive pixels / filter rows hit sixteen different bank groups
 //   ownership  = the band's dense rows are exactly its output rows: the workgroup writes every
 //                element of them once (results for kept rows, zeros for dropped rows).
 #pragma once
@@ -29,6 +29,7 @@ struct BandParams {
   const int32_t* row_idx;    // ascending kept rows; null = dense run
   const uint8_t* mask;
   const int32_t* band_i0;    // [n_bands + 1]: first compacted row of every band (sparse runs)
+  const int32_t* band_rows;  // [M]: the kept rows of band b, ascending, stored from index r_lo(b) on
   int32_t h, w, c_in, ho, wo, c_out;
   int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
   int32_t k_stride;          // elements between packed filter rows (odd multiple of the K tile)
@@ -47,7 +48,14 @@ struct BandParams {
 #define SC_STAMP(slot) do { } while (0)
 #endif
 
-__device__ __forceinline__ int swz(int q) { return q ^ ((q >> 3) & 7); }
+// LDS has 64 banks of 4 bytes: a 128-bit read is conflict-free when 16 consecutive lanes cover 16
+// different 16-byte bank groups.  Bit 3 of a group index already selects the bank half, so the low
+// three bits are XORed with bits 4..6.
+// tallest band (output rows x width) the band kernel accepts: its kept-row numbers are fetched up
+// front into registers, kBandMaxRows / 256 per lane
+constexpr int kBandMaxRows = 1024;
+
+__device__ __forceinline__ int swz(int q) { return q ^ ((q >> 4) & 7); }
 
 // 32-bit LDS addressing (keeps the per-fragment address arithmetic out of 64-bit registers)
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
@@ -104,18 +112,30 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   const T* __restrict__ x = static_cast<const T*>(p.x);
   T* __restrict__ y = static_cast<T*>(p.y);
 
-  // ---- small, latency-critical loads first: the band's slice of the kept-row list and its mask ----
-  const int i_lo = p.row_idx ? p.band_i0[band] : r_lo;
-  const int i_hi = p.row_idx ? p.band_i0[band + 1] : r_hi;
+  // ---- small, latency-critical loads first, all independent of each other -----------------------
+  // kept rows of the band: count from the band table, row numbers from the band-ordered list (its
+  // address depends only on the band, not on the count); 64*MI rows per block, blocks dealt to the
+  // wavefronts round robin; the first RB blocks of a wavefront are fetched here.
+  constexpr int RB = kBandMaxRows / (4 * 32 * MI);   // blocks per wavefront that cover the tallest band
+  int cnt = r_hi - r_lo;
+  if (p.row_idx) cnt = p.band_i0[band + 1] - p.band_i0[band];
+  int r_pre[RB][MI];
+#pragma unroll
+  for (int b = 0; b < RB; ++b)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int j = ((b * 4 + wave) * MI + mi) * 32 + fp;     // position in the band's list (< band rows)
+      const int jc = min(j, r_hi - r_lo - 1);
+      r_pre[b][mi] = p.row_idx ? p.band_rows[r_lo + jc] : r_lo + jc;
+    }
   // zero fill: thread (zr, zc) covers 16-byte group zc of rows r_lo + zr + u*RPI
   const int zc = t % CPR, zr = t / CPR;
   unsigned char mk[ZIT];
   if (p.zero_fill) {
 #pragma unroll
     for (int u = 0; u < ZIT; ++u) {
-      const int r = r_lo + zr + u * RPI;
-      mk[u] = 1;
-      if (r < r_hi) mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
+      const int r = min(r_lo + zr + u * RPI, r_hi - 1);       // clamped: the loads stay unconditional
+      mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
     }
   }
 
@@ -129,21 +149,6 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   const int nx = max(iy_hi - iy_lo, 0) * p.w * cpp;
   const int qx0 = (iy_lo - iy_base) * p.w * cpp;   // LDS group of the first staged input group
 
-  // the kept rows of the band, split evenly over the four wavefronts
-  const int nrows = i_hi - i_lo;
-  const int per_wave = (nrows + 3) >> 2;
-  const int w_lo = i_lo + wave * per_wave;
-  const int w_hi = min(w_lo + per_wave, i_hi);
-
-  // kept-row numbers of this lane for the wavefront's first block, fetched before the slabs
-  int r_first[MI];
-#pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    const int i = w_lo + mi * 32 + fp;
-    r_first[mi] = -1;
-    if (i < w_hi) r_first[mi] = p.row_idx ? p.row_idx[i] : i;
-  }
-
   auto zero_fill = [&]() {
     // Alg. 2, mask == 0 branch: consecutive lanes write consecutive 16-byte groups of a dropped row
     const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
@@ -153,7 +158,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
 #pragma unroll
       for (int u = 0; u < ZIT; ++u) {
         const int r = r_lo + zr + u * RPI;
-        if (mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+        if (r < r_hi && mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
       }
       for (int r = r_lo + zr + ZIT * RPI; r < r_hi; r += RPI)   // bands taller than ZIT passes
         if (p.mask[p.mask_spatial ? r - img * ho_wo : r] == 0)
@@ -165,6 +170,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   // instruction fills 64 consecutive 16-byte LDS groups, lane l the group base + l.  The swizzle is
   // an involution inside every aligned block of 64 groups, so the lane that owns LDS group q fetches
   // global group swz(q); the 64 fetches still cover one contiguous KiB.
+  __builtin_amdgcn_sched_barrier(0);   // the small loads above stay ahead of the slab transfers
   auto dma16 = [](const v4i* src, v4i* lds_base) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
@@ -195,18 +201,21 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   // the zero stores are issued now and drain while the matrix cores work; nothing waits for them
   if (p.zero_fill) zero_fill();
 
-  const int bkey = fp * (kgr >> 3);   // swizzle key of this lane's filter row
   const int zq = p.x_groups;          // a zeroed 16-byte group behind the input slab
-  for (int blk = w_lo; blk < w_hi; blk += 32 * MI) {
+  const int nblk = (cnt + 32 * MI - 1) / (32 * MI);
+#pragma unroll
+  for (int bi = 0; bi < RB; ++bi) {
+    const int blk = bi * 4 + wave;
+    if (blk >= nblk) break;
     int rr[MI], ly0[MI], lx0[MI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-      const int i = blk + mi * 32 + fp;
+      const int j = (blk * MI + mi) * 32 + fp;
       rr[mi] = -1;
       ly0[mi] = 0;
       lx0[mi] = -(1 << 28);   // no tap of an absent row is ever in range
-      if (i < w_hi) {
-        const int r = blk == w_lo ? r_first[mi] : (p.row_idx ? p.row_idx[i] : i);
+      if (j < cnt) {
+        const int r = r_pre[bi][mi];
         const int rem = r - img * ho_wo;
         const int oy = rem / p.wo, ox = rem - oy * p.wo;
         rr[mi] = r;
@@ -230,9 +239,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
       const bool ok = (unsigned)(iy_base + ly) < (unsigned)p.h && (unsigned)ix < (unsigned)p.w;
       return ok ? swz((ly * p.w + ix) * cpp + c) : zq;
     };
-    auto wgroup = [&](int ni, int kc) -> int {
-      return (ni * 32 + fp) * kgr + (kc ^ ((bkey + ni * 32 * (kgr >> 3) + (kc >> 3)) & 7));
-    };
+    auto wgroup = [&](int ni, int kc) -> int { return swz((ni * 32 + fp) * kgr + kc); };
 
     if constexpr (KH > 0) {
       // K steps of 32 bytes per row, in groups of G; the fragments of group g+1 are read while the
@@ -256,18 +263,14 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
           for (int kx = 0; kx < KW; ++kx) {
             const bool ok = oky && (unsigned)(lx0[mi] + kx * p.dil_w) < (unsigned)p.w;
             const unsigned g0 = (unsigned)(pb + ky * p.dil_h * p.w + kx * p.dil_w) * CPP;
-            const unsigned rel = ((g0 ^ ((g0 >> 3) & 7u)) << 4) ^ ((unsigned)fh << 4);
+            const unsigned rel = ((g0 ^ ((g0 >> 4) & 7u)) << 4) ^ ((unsigned)fh << 4);
             tap_addr[mi][ky * KW + kx] = ok ? xbase + rel : zaddr;
           }
         }
       }
-      unsigned w_addr[NI];                    // address of K group 0 of this lane's filter rows
-      unsigned w_key[NI];
+      unsigned w_q0[NI];                      // LDS group of K group 0 of this lane's filter rows
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        w_addr[ni] = bbase + (unsigned)((ni * 32 + fp) * kgr) * 16u;
-        w_key[ni] = (unsigned)((ni * 32 + fp) * (kgr >> 3));
-      }
+      for (int ni = 0; ni < NI; ++ni) w_q0[ni] = (unsigned)((ni * 32 + fp) * kgr);
       v4i xb[2][G][MI], wb[2][G][NI];
       auto load_group = [&](int g, v4i (&xd)[G][MI], v4i (&wd)[G][NI]) {
 #pragma unroll
@@ -279,18 +282,21 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
             for (int mi = 0; mi < MI; ++mi) xd[e][mi] = lds_load16(tap_addr[mi][tp] ^ ((unsigned)j << 4));
             const unsigned kc = (unsigned)(tp * CPP + j) + (unsigned)fh;
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-              wd[e][ni] = lds_load16(w_addr[ni] + ((kc ^ ((w_key[ni] + (kc >> 3)) & 7u)) << 4));
+            for (int ni = 0; ni < NI; ++ni) {
+              const unsigned q = w_q0[ni] + kc;
+              wd[e][ni] = lds_load16(bbase + ((q ^ ((q >> 4) & 7u)) << 4));
+            }
           }
         }
       };
       load_group(0, xb[0], wb[0]);
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        // keep the compiler's scheduler from sinking the read-ahead next to its uses
+        // One scheduling region per group: the read-ahead of group g+1 is interleaved with the MFMAs
+        // of group g, one LDS read behind every MFMA, so neither the LDS queue nor the matrix pipe
+        // waits for a burst of the other.
         __builtin_amdgcn_sched_barrier(0);
         if (g + 1 < NG) load_group(g + 1, xb[(g + 1) & 1], wb[(g + 1) & 1]);
-        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int e = 0; e < G; ++e) {
           if (g * G + e < S) {
@@ -300,7 +306,15 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
               for (int ni = 0; ni < NI; ++ni) E::mma(acc[mi][ni], wb[g & 1][e][ni], xb[g & 1][e][mi]);
           }
         }
+        if (g + 1 < NG) {
+#pragma unroll
+          for (int i = 0; i < G * MI * NI; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+          }
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);
     } else {
       // run-time window: one K step at a time, the next step's fragments read ahead
       int ky = 0, kx = 0, j = 0;

@@ -17,8 +17,9 @@
 //
 // LDS layout
 //   A tile [BM][128 B] and B tile [BN][128 B], double buffered; the eight 16-byte groups of
-//   a row are XOR-swizzled with (row & 7) so that the 128-bit reads of eight consecutive
-//   rows hit distinct banks.
+//   a row are XOR-swizzled with ((row >> 1) & 7): LDS has 64 banks, odd and even 128-byte rows
+//   sit in different bank halves, so the 128-bit reads of sixteen consecutive rows hit sixteen
+//   distinct 16-byte bank groups.
 #pragma once
 #include "conv_params.hpp"
 #include "mma_common.hpp"
@@ -177,7 +178,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     }
   }
 
-  const int st_off = lrow * kRowBytes + ((c16 ^ (lrow & 7)) << 4);
+  const int st_off = lrow * kRowBytes + ((c16 ^ ((lrow >> 1) & 7)) << 4);
   auto store_tile = [&](int buf, const v4i (&a)[A_LOADS], const v4i (&b)[B_LOADS]) {
     unsigned char* pa = s_a + buf * BM * kRowBytes + st_off;
     unsigned char* pb = s_b + buf * BN * kRowBytes + st_off;
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
   const int fp = lane & 31, fh = lane >> 5;
   int frag_off[4];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) frag_off[ks] = fp * kRowBytes + (((2 * ks + fh) ^ (fp & 7)) << 4);
+  for (int ks = 0; ks < 4; ++ks) frag_off[ks] = fp * kRowBytes + (((2 * ks + fh) ^ ((fp >> 1) & 7)) << 4);
 
   auto compute_tile = [&](int buf) {
     const unsigned char* a = s_a + buf * BM * kRowBytes + wm0 * kRowBytes;

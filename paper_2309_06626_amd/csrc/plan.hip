@@ -148,6 +148,21 @@ __global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int
   band_i0[b] = lo;
 }
 
+// Band-ordered copy of the kept-row list: the kept rows of band b, ascending, stored from index
+// r_lo(b) (the band's first dense row) on, so the band kernel finds them without knowing counts.
+__global__ void band_rows_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
+                                 const int32_t* __restrict__ band_i0, int32_t* __restrict__ band_rows,
+                                 int bands_per_image, int bh, int ho, int wo) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= *kept_dev) return;
+  const int r = row_idx[i];
+  const int ho_wo = ho * wo;
+  const int img = r / ho_wo, oy = (r - img * ho_wo) / wo;
+  const int bi = oy / bh;
+  const int band = img * bands_per_image + bi;
+  band_rows[(img * ho + bi * bh) * wo + (i - band_i0[band])] = r;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Glue operators for network runs
 // ------------------------------------------------------------------------------------------------
@@ -197,7 +212,7 @@ struct Geometry {
   int64_t x_elems, y_elems, mask_len;
   int32_t nseg;
   // workspace carve (byte offsets)
-  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, off_band, total;
+  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, off_band, off_band_rows, total;
 };
 
 static int out_extent(int in, int k, int stride, int pad, int dil) {
@@ -252,6 +267,7 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->off_wp = off;     off = align_up(off + (size_t)g->cout_pad * g->k_stride * eb, 256);
   g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
   g->off_band = off;   off = align_up(off + ((size_t)d->n * g->ho + 1) * 4, 256);
+  g->off_band_rows = off; off = align_up(off + (size_t)g->m * 4, 256);
   g->total = off;
   return SC_OK;
 }
@@ -284,6 +300,7 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
     int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
     size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
     if (bp.b_bytes + xbytes + kBandExtraLds > kLdsLimit) break;
+    if ((int64_t)bh * g.wo > kBandMaxRows) break;
     int bpi = (g.ho + bh - 1) / bh;
     int64_t nb = (int64_t)d.n * bpi * bp.n_tiles;
     double rounds = std::ceil((double)nb / 256.0);
@@ -380,6 +397,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
     q.mask = pl->ws + g.off_mask;
     q.band_i0 = reinterpret_cast<const int32_t*>(pl->ws + g.off_band);
+    q.band_rows = reinterpret_cast<const int32_t*>(pl->ws + g.off_band_rows);
     q.h = d.h; q.w = d.w; q.c_in = d.c_in; q.ho = g.ho; q.wo = g.wo; q.c_out = d.c_out;
     q.kh = d.kh; q.kw = d.kw; q.sh = d.stride_h; q.sw = d.stride_w; q.ph = d.pad_h; q.pw = d.pad_w;
     q.dil_h = d.dil_h; q.dil_w = d.dil_w;
@@ -531,6 +549,10 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   if (bp.ok) {
     hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
+    SC_HIP(hipGetLastError());
+    hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
+                       reinterpret_cast<const int32_t*>(ws + g.off_band),
+                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, g.ho, g.wo);
     SC_HIP(hipGetLastError());
   }
 
