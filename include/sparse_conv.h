@@ -136,6 +136,12 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
  * stays automatic).  Returns SC_ERR_UNSUPPORTED when the library has no such kernel for the layer. */
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
 
+/* Tuning hook: SC_OPT_GATHER_PIPELINE selects how the tiled gather kernel moves its K tiles:
+ * 0 = automatic, 1 = global -> registers -> LDS, 2 = global -> LDS directly (NHWC with 16-byte
+ * channel groups only; other layers ignore it).  Unknown options return SC_ERR_UNSUPPORTED. */
+enum { SC_OPT_GATHER_PIPELINE = 0 };
+sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
+
 void sparse_conv_plan_destroy(sc_plan* plan);
 
 const char* sc_status_string(sc_status s);

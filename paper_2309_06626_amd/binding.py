@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_plan_tiles.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]
         L.sparse_conv_plan_set_tiles.restype = ctypes.c_int
         L.sparse_conv_plan_set_tiles.argtypes = [vp, i32, i32, i32]
+        L.sparse_conv_plan_set_option.restype = ctypes.c_int
+        L.sparse_conv_plan_set_option.argtypes = [vp, i32, i32]
         L.sparse_conv_plan_destroy.restype = None
         L.sparse_conv_plan_destroy.argtypes = [vp]
         L.sc_status_string.restype = ctypes.c_char_p
@@ -237,6 +239,13 @@ def sparse_conv_plan_tiles(plan: Plan, which: int) -> Tuple[int, int, int]:
 
 def sparse_conv_plan_set_tiles(plan: Plan, which: int, tile_m: int, tile_n: int):
     _check(lib().sparse_conv_plan_set_tiles(plan.handle, which, tile_m, tile_n), "sparse_conv_plan_set_tiles")
+
+
+SC_OPT_GATHER_PIPELINE = 0
+
+
+def sparse_conv_plan_set_option(plan: Plan, option: int, value: int):
+    _check(lib().sparse_conv_plan_set_option(plan.handle, option, value), "sparse_conv_plan_set_option")
 
 
 def sc_maxpool2d_nhwc(x: torch.Tensor, k: int = 3, s: int = 2, p: int = 1, stream=None) -> torch.Tensor:

@@ -20,7 +20,8 @@ struct ConvParams {
   void* y;
   const int32_t* row_idx;  // ascending kept rows; null = identity (dense run)
   const uint8_t* mask;     // used for the zero fill only
-  const KEntry* ktab;      // per 16-byte K group (vector gather) or per K element (element gather)
+  const KEntry* ktab;      // per K element (element gather only)
+  const void* zeros;       // 256 bytes of zeros (source of padded window entries for direct-to-LDS gathers)
   int32_t rows;            // rows of the (compacted) GEMM: kept, or M for a dense run
   int32_t m_total;         // M = N*Ho*Wo
   int32_t h, w, ho_wo, wo;
@@ -52,8 +53,9 @@ using LaunchFn = hipError_t (*)(const ConvParams&, hipStream_t);
 
 struct KernelEntry {
   int bm, bn;
-  LaunchFn vec;   // 16-byte gather (NHWC, Cin*eb % 16 == 0)
+  LaunchFn vec;   // 16-byte gather through registers (NHWC, Cin*eb % 16 == 0)
   LaunchFn elem;  // element gather (any layout)
+  LaunchFn dma;   // 16-byte gather straight into LDS (additionally needs channel-contiguous stores)
   size_t lds_bytes;
 };
 

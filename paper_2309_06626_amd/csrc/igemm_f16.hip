@@ -5,14 +5,14 @@
 namespace sc {
 
 static const KernelEntry g_table[] = {
-    SC_KERNEL_ENTRY(kF16, 256, 128, 2, 2, 2),
-    SC_KERNEL_ENTRY(kF16, 128, 128, 2, 2, 3),
-    SC_KERNEL_ENTRY(kF16, 256, 64, 4, 1, 2),
-    SC_KERNEL_ENTRY(kF16, 128, 64, 2, 2, 4),
-    SC_KERNEL_ENTRY(kF16, 64, 128, 2, 2, 4),
-    SC_KERNEL_ENTRY(kF16, 64, 64, 2, 2, 4),
-    SC_KERNEL_ENTRY(kF16, 128, 32, 4, 1, 4),
-    SC_KERNEL_ENTRY(kF16, 32, 128, 1, 4, 4),
+    SC_KERNEL_ENTRY(kF16, 256, 128, 2, 2, 2, 3),
+    SC_KERNEL_ENTRY(kF16, 128, 128, 2, 2, 3, 3),
+    SC_KERNEL_ENTRY(kF16, 256, 64, 4, 1, 2, 3),
+    SC_KERNEL_ENTRY(kF16, 128, 64, 2, 2, 4, 3),
+    SC_KERNEL_ENTRY(kF16, 64, 128, 2, 2, 4, 3),
+    SC_KERNEL_ENTRY(kF16, 64, 64, 2, 2, 4, 3),
+    SC_KERNEL_ENTRY(kF16, 128, 32, 4, 1, 4, 3),
+    SC_KERNEL_ENTRY(kF16, 32, 128, 1, 4, 4, 3),
 };
 
 const KernelEntry* kernels_f16(int* count) {

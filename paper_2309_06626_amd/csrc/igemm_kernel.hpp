@@ -23,6 +23,7 @@
 #pragma once
 #include "conv_params.hpp"
 #include "mma_common.hpp"
+#include "igemm_dma_kernel.hpp"
 
 namespace sc {
 
@@ -270,8 +271,9 @@ hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-#define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_, DEPTH)                                      \
+#define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_, DEPTH, STAGES)                              \
   KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
-                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>, igemm_lds_bytes<BM, BN>() }
+                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>, igemm_lds_bytes<BM, BN>() }
 
 }  // namespace sc

@@ -212,7 +212,7 @@ struct Geometry {
   int64_t x_elems, y_elems, mask_len;
   int32_t nseg;
   // workspace carve (byte offsets)
-  size_t off_rows, off_counts, off_kept, off_mask, off_wp, off_ktab, off_band, off_band_rows, total;
+  size_t off_rows, off_counts, off_kept, off_zeros, off_mask, off_wp, off_ktab, off_band, off_band_rows, total;
 };
 
 static int out_extent(int in, int k, int stride, int pad, int dil) {
@@ -263,6 +263,7 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->off_rows = off;   off = align_up(off + (size_t)g->m * 4, 256);
   g->off_counts = off; off = align_up(off + (size_t)g->nseg * 4, 256);
   g->off_kept = off;   off += 256;
+  g->off_zeros = off;  off += 256;
   g->off_mask = off;   off = align_up(off + (size_t)g->mask_len, 256);
   g->off_wp = off;     off = align_up(off + (size_t)g->cout_pad * g->k_stride * eb, 256);
   g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
@@ -333,36 +334,31 @@ struct sc_plan {
   int table_count;
   int tile_sparse, tile_dense;     // chosen indices into table
   int forced[2];                   // -1 = automatic, >= 0 generic tile index, kForceBand = band kernel
+  int gather_pipeline;             // 0 = automatic, 1 = through registers, 2 = straight into LDS
 };
 constexpr int kForceBand = -2;
 
 namespace sc {
 
-// Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a
-// heavily masked layer gets narrower tiles than its dense twin (Sec. 3.2: the GEMM range
-// shrinks with the sparsity).  Cost = tiles on the busiest CU x tile volume / tile efficiency;
-// efficiency falls with the LDS reads per MFMA of the wavefront tile.
-static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out) {
-  const double cus = 256.0;
-  int best = 0;
-  double best_cost = 1e300;
-  for (int i = 0; i < count; ++i) {
-    const int bm = tab[i].bm, bn = tab[i].bn;
-    int64_t mt = (rows + bm - 1) / bm, nt = (c_out + bn - 1) / bn;
-    double nwg = (double)mt * nt;
-    double per_cu = std::ceil(nwg / cus);
-    // wavefront tile is (bm/2 x bn/2) except for the 4x1 / 1x4 shapes; use the square guess
-    double mi = bm >= 64 ? bm / 64.0 : 1.0, ni = bn >= 64 ? bn / 64.0 : 1.0;
-    if (bm == 256 && bn == 64) { mi = 2; ni = 2; }
-    if (bm == 128 && bn == 32) { mi = 1; ni = 1; }
-    if (bm == 32) { mi = 1; ni = 1; }
-    double reads_per_mfma = (mi + ni) / (mi * ni);
-    double eff = 1.0 / (1.0 + 0.45 * reads_per_mfma);
-    double fixed = 6000.0;  // prologue/epilogue per tile, in units of MFMA-volume
-    double cost = per_cu * ((double)bm * bn / eff + fixed);
-    if (cost < best_cost) { best_cost = cost; best = i; }
+// Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a heavily
+// masked layer gets narrower tiles than its dense twin (Sec. 3.2: the GEMM range shrinks with the
+// sparsity).  The rules come from sweeps over the ResNet18 / pointwise / detector layer shapes on
+// MI355X: the kernels are bound by L2 -> LDS traffic and latency, not by the matrix cores, and many
+// small workgroups per CU hide that latency better than few large ones; 128-wide tiles pay off
+// when they divide c_out, and short GEMMs (few rows) want 32-row tiles to fill 256 CUs.
+static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather) {
+  int bm, bn;
+  if (!vec_gather) { bm = 128; bn = 64; }            // element gather: fewer, fatter workgroups
+  else if (c_out <= 32) { bm = 128; bn = 32; }
+  else if (rows <= 8192) {
+    if (c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
+    else { bm = 64; bn = 64; }
   }
-  return best;
+  else if (c_out % 128 == 0) { bm = 64; bn = 128; }
+  else { bm = 64; bn = 64; }
+  for (int i = 0; i < count; ++i)
+    if (tab[i].bm == bm && tab[i].bn == bn) return i;
+  return 0;
 }
 
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
@@ -430,6 +426,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
   p.mask = pl->ws + g.off_mask;
   p.ktab = reinterpret_cast<const KEntry*>(pl->ws + g.off_ktab);
+  p.zeros = pl->ws + g.off_zeros;
   p.rows = (int32_t)rows;
   p.m_total = (int32_t)g.m;
   p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
@@ -450,7 +447,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.vec_out = g.vec_out ? 1 : 0;
   p.m_tiles = (int32_t)((rows + ke.bm - 1) / ke.bm);
   p.n_tiles = (d.c_out + ke.bn - 1) / ke.bn;
-  LaunchFn fn = g.vec_gather ? ke.vec : ke.elem;
+  LaunchFn fn = !g.vec_gather ? ke.elem : (g.vec_out && pl->gather_pipeline != 1) ? ke.dma : ke.vec;
   SC_HIP(fn(p, stream));
   return SC_OK;
 }
@@ -502,6 +499,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   const sc_conv_desc& d = *desc;
   const int eb = elem_bytes(d.dtype);
 
+  SC_HIP(hipMemsetAsync(ws + g.off_zeros, 0, 256, stream));
   // a private copy of the mask (the zero fill of every run reads it)
   SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
 
@@ -576,9 +574,10 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->table = d.dtype == SC_BF16 ? kernels_bf16(&pl->table_count)
               : d.dtype == SC_F16 ? kernels_f16(&pl->table_count)
                                   : kernels_f32(&pl->table_count);
-  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out);
-  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out);
+  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather);
+  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather);
   pl->forced[0] = pl->forced[1] = -1;
+  pl->gather_pipeline = 0;
   pl->band = bp;
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   (void)eb;
@@ -641,6 +640,12 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
   }
   for (int i = 0; i < plan->table_count; ++i)
     if (plan->table[i].bm == tile_m && plan->table[i].bn == tile_n) { plan->forced[which] = i; return SC_OK; }
+  return SC_ERR_UNSUPPORTED;
+}
+
+sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value) {
+  if (!plan) return SC_ERR_NULL;
+  if (option == SC_OPT_GATHER_PIPELINE && value >= 0 && value <= 2) { plan->gather_pipeline = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }
 

@@ -70,9 +70,9 @@ def test_every_tile_shape(tile, dtype):
 
 
 def test_tile_choice_follows_the_reduced_row_count():
-    spec = spec_of(8, 72, 28, 28, 128, sp=0.0)     # 72 channels: only the tiled gather kernel applies
+    spec = spec_of(16, 72, 28, 28, 128, sp=0.0)    # 72 channels: only the tiled gather kernel applies
     wide = R.ConvLayer(spec, *_wbm(spec, 5))
-    spec9 = spec.with_(sparsity=0.97)
+    spec9 = spec.with_(sparsity=0.9)
     narrow = R.ConvLayer(spec9, *_wbm(spec9, 5))
     tm0, tn0, wg0 = B.sparse_conv_plan_tiles(wide.plan, 0)
     tm1, tn1, wg1 = B.sparse_conv_plan_tiles(narrow.plan, 0)
