@@ -136,6 +136,9 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
  * stays automatic).  Returns SC_ERR_UNSUPPORTED when the library has no such kernel for the layer. */
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
 
+/* Environment (read by sparse_conv_plan; tuning and tests only): SPARSE_CONV_BAND_HEIGHT=<rows> fixes
+ * the band height of the streaming band kernel instead of the automatic choice. */
+
 /* Tuning hook: SC_OPT_GATHER_PIPELINE selects how the tiled gather kernel moves its K tiles:
  * 0 = automatic, 1 = global -> registers -> LDS, 2 = global -> LDS directly (NHWC with 16-byte
  * channel groups only; other layers ignore it).  Unknown options return SC_ERR_UNSUPPORTED. */

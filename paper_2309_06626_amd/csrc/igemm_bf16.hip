@@ -1,5 +1,6 @@
 // Instantiations of the fused masked-convolution kernel for bf16 operands (float accumulate).
 #include "band_kernel.hpp"
+#include "bandstream_kernel.hpp"
 #include "igemm_kernel.hpp"
 
 namespace sc {
@@ -22,5 +23,7 @@ const KernelEntry* kernels_bf16(int* count) {
 
 static const BandTable g_band = SC_BAND_TABLE(kBF16);
 const BandTable* band_bf16() { return &g_band; }
+static const BandStreamTable g_stream = SC_BANDSTREAM_TABLE(kBF16);
+const BandStreamTable* bandstream_bf16() { return &g_stream; }
 
 }  // namespace sc

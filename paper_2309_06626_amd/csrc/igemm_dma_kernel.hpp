@@ -35,6 +35,12 @@ template <int N, int CNT> __device__ __forceinline__ void wait_frags(v4i (&f)[CN
   if constexpr (CNT == 3) asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]) : "n"(N));
   if constexpr (CNT == 4)
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]) : "n"(N));
+  if constexpr (CNT == 5)
+    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]) : "n"(N));
+  if constexpr (CNT == 7)
+    asm volatile("s_waitcnt lgkmcnt(%7)"
+                 : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6])
+                 : "n"(N));
   if constexpr (CNT == 6)
     asm volatile("s_waitcnt lgkmcnt(%6)"
                  : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5])
@@ -43,7 +49,7 @@ template <int N, int CNT> __device__ __forceinline__ void wait_frags(v4i (&f)[CN
     asm volatile("s_waitcnt lgkmcnt(%8)"
                  : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7])
                  : "n"(N));
-  static_assert(CNT == 1 || CNT == 2 || CNT == 3 || CNT == 4 || CNT == 6 || CNT == 8, "fragment count");
+  static_assert(CNT >= 1 && CNT <= 8, "fragment count");
 }
 
 template <int BM, int BN, int STAGES>

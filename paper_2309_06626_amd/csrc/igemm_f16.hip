@@ -1,5 +1,6 @@
 // Instantiations of the fused masked-convolution kernel for f16 operands (float accumulate).
 #include "band_kernel.hpp"
+#include "bandstream_kernel.hpp"
 #include "igemm_kernel.hpp"
 
 namespace sc {
@@ -22,5 +23,7 @@ const KernelEntry* kernels_f16(int* count) {
 
 static const BandTable g_band = SC_BAND_TABLE(kF16);
 const BandTable* band_f16() { return &g_band; }
+static const BandStreamTable g_stream = SC_BANDSTREAM_TABLE(kF16);
+const BandStreamTable* bandstream_f16() { return &g_stream; }
 
 }  // namespace sc

@@ -6,10 +6,12 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
 #include "band_kernel.hpp"
+#include "bandstream_kernel.hpp"
 #include "conv_params.hpp"
 
 namespace sc {
@@ -148,6 +150,12 @@ __global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int
   band_i0[b] = lo;
 }
 
+// Largest number of kept rows in any band (sizes the accumulator blocks of the streaming band kernel).
+__global__ void band_max_kernel(const int32_t* __restrict__ band_i0, int n_bands, int32_t* __restrict__ out) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < n_bands) atomicMax(out, band_i0[b + 1] - band_i0[b]);
+}
+
 // Band-ordered copy of the kept-row list: the kept rows of band b, ascending, stored from index
 // r_lo(b) (the band's first dense row) on, so the band kernel finds them without knowing counts.
 __global__ void band_rows_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
@@ -276,6 +284,8 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
 // Band kernel applicability and band height.
 struct BandPlan {
   bool ok;
+  bool stream;       // filters streamed through an LDS ring instead of resident
+  int max_kept;      // most kept rows in one band (streaming kernel only)
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
   size_t b_bytes, x_bytes, lds;
 };
@@ -295,7 +305,38 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
   bp.ni_idx = bp.ni == 1 ? 0 : bp.ni == 2 ? 1 : 2;
   bp.n_tiles = (d.c_out + 32 * bp.ni - 1) / (32 * bp.ni);
   bp.b_bytes = (size_t)32 * bp.ni * g.k_stride * eb;
-  if (bp.b_bytes > 96 * 1024) return bp;         // leave room for a band worth staging
+  if (bp.b_bytes > 96 * 1024) {
+    // Filters too large to stay resident: stream them (16-bit types, whole 128-byte K tiles per tap,
+    // 64 or 128 channels per workgroup).  Taller bands amortise the filter traffic, which every
+    // workgroup pays in full; rows are capped by the accumulator registers (128 rows per MI step).
+    if (d.dtype == SC_F32 || (d.c_in / g.vec) % 8 != 0 || bp.ni < 2) return bp;
+    bp.stream = true;
+    bp.b_bytes = (size_t)kStreamStages * 32 * bp.ni * kRowBytes;
+    const char* env = std::getenv("SPARSE_CONV_BAND_HEIGHT");
+    const int forced_bh = env ? std::atoi(env) : 0;
+    int best_bh = 0;
+    int64_t best_wg = 0;
+    for (int bh = 1; bh <= g.ho; ++bh) {
+      int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
+      size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
+      if (bp.b_bytes + xbytes + kBandExtraLds > kLdsLimit) break;
+      if ((int64_t)bh * g.wo > (bp.ni == 4 ? 384 : 512)) break;   // accumulator registers: 3 / 4 blocks of 128 rows
+      int bpi = (g.ho + bh - 1) / bh;
+      int64_t nwg = (int64_t)d.n * bpi * bp.n_tiles;
+      // the tallest band that still gives every CU a workgroup; failing that, one output row per
+      // band (the most workgroups); SPARSE_CONV_BAND_HEIGHT overrides (tuning and tests)
+      const bool take = forced_bh > 0 ? bh == forced_bh : (nwg >= 256 || best_bh == 0);
+      if (take) { best_bh = bh; best_wg = nwg; bp.x_bytes = xbytes; }
+    }
+    (void)best_wg;
+    if (best_bh == 0) { bp.stream = false; return bp; }
+    bp.ok = true;
+    bp.bh = best_bh;
+    bp.bands_per_image = (g.ho + best_bh - 1) / best_bh;
+    bp.n_bands = d.n * bp.bands_per_image;
+    bp.lds = bp.b_bytes + bp.x_bytes + kBandExtraLds;
+    return bp;
+  }
   double best = 1e300;
   for (int bh = 1; bh <= g.ho; ++bh) {
     int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
@@ -328,6 +369,7 @@ struct sc_plan {
   Geometry geo;
   BandPlan band;
   const BandTable* band_table;
+  const BandStreamTable* stream_table;
   unsigned char* ws;
   int64_t kept;
   const KernelEntry* table;
@@ -381,7 +423,9 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     }
     return SC_OK;
   }
-  const bool use_band = pl->band.ok && (pl->forced[which] == kForceBand || pl->forced[which] == -1);
+  // the streaming variant measured no faster than the tiled kernel on the benchmark layers, so the
+  // automatic choice takes it only on request
+  const bool use_band = pl->band.ok && (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !pl->band.stream));
   if (use_band) {
     const BandPlan& b = pl->band;
     BandParams q;
@@ -407,6 +451,14 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
 #ifdef SC_TIMING
     q.dbg = g_dbg;
 #endif
+    if (b.stream) {
+      // every kept row of a band sits in accumulators: 128 rows per MI step
+      const int most = dense ? b.bh * g.wo : b.max_kept;
+      const int mi = std::max(1, (most + 127) / 128);
+      if (mi > (b.ni == 4 ? 3 : 4)) return SC_ERR_UNSUPPORTED;   // cannot happen: the planner caps the band rows
+      SC_HIP(pl->stream_table->fn[b.ni == 4 ? 1 : 0][mi - 1](q, b.lds, stream));
+      return SC_OK;
+    }
     // rows per wavefront decide how many 32-row MFMA blocks share one filter fragment
     const double per_wave = (double)rows / b.n_bands / 4.0;
     const int mi_idx = per_wave > 32.0 ? 1 : 0;
@@ -548,15 +600,24 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
     SC_HIP(hipGetLastError());
+    if (bp.stream) {
+      // kept_dev + 1 holds the per-band maximum
+      SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
+      hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
+                         reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
+      SC_HIP(hipGetLastError());
+    }
     hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<const int32_t*>(ws + g.off_band),
                        reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, g.ho, g.wo);
     SC_HIP(hipGetLastError());
   }
 
-  int32_t kept_host = -1;
-  SC_HIP(hipMemcpyAsync(&kept_host, kept_dev, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  int32_t host_vals[2] = {-1, 0};   // kept count, most kept rows in one band
+  SC_HIP(hipMemcpyAsync(host_vals, kept_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
   SC_HIP(hipStreamSynchronize(stream));
+  const int32_t kept_host = host_vals[0];
+  bp.max_kept = host_vals[1];
 
   if (d.sparsity >= 0.0f) {
     // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up)
@@ -580,6 +641,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->gather_pipeline = 0;
   pl->band = bp;
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
+  pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
   (void)eb;
   *out = pl;
   return SC_OK;
@@ -614,7 +676,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups) {
   if (!plan) return SC_ERR_NULL;
   if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
-  if (plan->band.ok && (plan->forced[which] == kForceBand || plan->forced[which] == -1)) {
+  if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream))) {
     if (tile_m) *tile_m = -plan->band.bh;
     if (tile_n) *tile_n = 32 * plan->band.ni;
     if (workgroups) *workgroups = (int64_t)plan->band.n_bands * plan->band.n_tiles;

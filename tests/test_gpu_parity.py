@@ -109,6 +109,34 @@ def test_band_kernel(case, mask_mode, dtype):
     check_layer(W.make_conv_inputs(spec, 900 + case), tiles=(64, 64))
 
 
+STREAM_CASES = [
+    dict(n=2, cin=64, h=14, w=14, cout=128),                         # 128 channels: one channel tile
+    dict(n=1, cin=128, h=12, w=10, cout=256, sp=0.3),                # two channel tiles, two K tiles per tap
+    dict(n=2, cin=64, h=18, w=18, cout=128, k=3, s=2, p=1, sp=0.4),  # stride 2
+    dict(n=1, cin=64, h=13, w=15, cout=192, k=3, p=2, d=2, sp=0.5),  # dilation 2, ragged second channel tile
+    dict(n=1, cin=256, h=9, w=9, cout=128, sp=0.6),                  # four K tiles per tap
+    dict(n=2, cin=64, h=11, w=12, cout=160, k=5, p=2, sp=0.5),       # 5x5 window
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("case", range(len(STREAM_CASES)))
+def test_streaming_band_kernel(case, mask_mode, dtype):
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **STREAM_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 950 + case), tiles=(-1, 0))
+    assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] < 0
+
+
+@pytest.mark.parametrize("bh,sp", [(4, 0.5), (7, 0.5), (10, 0.3), (12, 0.1), (12, 0.6)])
+def test_streaming_band_kernel_tall_bands(bh, sp, monkeypatch):
+    # band heights that put 128 .. 384 rows into one workgroup: 1 .. 3 accumulator blocks per wavefront
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", str(bh))
+    spec = spec_of(2, 64, 32, 32, 128, dtype="bf16", sp=sp)
+    layer = check_layer(W.make_conv_inputs(spec, 970 + bh), tiles=(-1, 0))
+    assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] == -bh
+
+
 def test_band_kernel_scatter_only_and_empty():
     spec = spec_of(2, 32, 16, 16, 64, dtype="bf16", sp=0.5)
     ci = W.make_conv_inputs(spec, 41)
