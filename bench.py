@@ -35,40 +35,6 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 MEASURED_TRAFFIC_BYTES = int(6829.44 * 1024 * 1.999 + 12544 * 1024)
 
 
-def algorithmic_bytes(spec, keep: int) -> float:
-    """Bytes the method itself must move for one launch: the input pixels covered by at least one
-    kept window, the filters once, the dense output (zero fill included), the mask bytes and the
-    row list."""
-    eb = 4 if spec.dtype == "f32" else 2
-    s = 1.0 - keep / spec.m
-    if spec.kh == 1 and spec.kw == 1 and spec.stride_h == 1:
-        cov = keep / spec.m
-    elif spec.kh == 3 and spec.stride_h == 1:
-        cov = 1.0 - s ** 9
-    else:
-        cov = 1.0
-    return (cov * spec.n * spec.h * spec.w * spec.c_in * eb + spec.k * spec.c_out * eb
-            + spec.m * spec.c_out * eb + spec.m + 4 * keep)
-
-
-def time_launches(fn, steps: int, warmup: int):
-    """Wall-clock and HIP-event time of `steps` back-to-back launches on the current stream."""
-    import torch
-
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    return wall / steps, e0.elapsed_time(e1) * 1e-3 / steps
-
-
 def cpu_baseline(spec, ci, budget_s: float = 12.0):
     """The oracle as it stands, on the host cores, repeated on the benchmark layer until the budget is used."""
     from oracle import oracle
@@ -110,6 +76,7 @@ def main():
     import workloads as W
     from paper_2309_06626_amd import binding as B
     from paper_2309_06626_amd import runtime as R
+    from paper_2309_06626_amd.metrics import algorithmic_bytes, time_launches
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)

@@ -56,6 +56,7 @@ struct KernelEntry {
   LaunchFn vec;   // 16-byte gather through registers (NHWC, Cin*eb % 16 == 0)
   LaunchFn elem;  // element gather (any layout)
   LaunchFn dma;   // 16-byte gather straight into LDS (additionally needs channel-contiguous stores)
+  LaunchFn dma2;  // the same with a two-tile ring: less LDS, more workgroups per CU (shallow K)
   size_t lds_bytes;
 };
 

@@ -274,6 +274,7 @@ hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
 #define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_, DEPTH, STAGES)                              \
   KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
                 igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
-                igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>, igemm_lds_bytes<BM, BN>() }
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>,                          \
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>, igemm_lds_bytes<BM, BN>() }
 
 }  // namespace sc

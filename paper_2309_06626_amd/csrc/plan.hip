@@ -499,7 +499,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.vec_out = g.vec_out ? 1 : 0;
   p.m_tiles = (int32_t)((rows + ke.bm - 1) / ke.bm);
   p.n_tiles = (d.c_out + ke.bn - 1) / ke.bn;
-  LaunchFn fn = !g.vec_gather ? ke.elem : (g.vec_out && pl->gather_pipeline != 1) ? ke.dma : ke.vec;
+  // shallow K (pointwise layers): the workgroup lives for one or two K tiles, so residency, not
+  // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
+  LaunchFn fn = !g.vec_gather ? ke.elem
+                : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
   SC_HIP(fn(p, stream));
   return SC_OK;
 }

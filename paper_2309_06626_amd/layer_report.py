@@ -1,0 +1,166 @@
+#!/usr/bin/env python3
+"""Per-layer report over the five benchmark configurations on one MI355X.
+
+    python -m paper_2309_06626_amd.layer_report [--configs 1,2,3,4,5] [--steps 200] [--json out.jsonl]
+
+For every convolution: kernel chosen for the sparse and the dense run, time per launch, algorithmic
+TFLOP/s of the kept rows (2*kept*K*Cout / t) and its share of the MFMA peak, algorithmic GB/s and
+its share of the HBM peak, and the speed-up over the dense run of the same kernels.  Config 2 is
+reported at s in {0, 0.25, 0.5, 0.7} in zero-fill mode and, for s > 0, in scatter-only mode.
+Configs 3 and 5 add the time of the whole chain (conv launches plus the pooling / residual glue).
+Layers are timed one by one on synthetic inputs of their own shape (warm buffers, back-to-back
+launches on one stream).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def kernel_name(tile):
+    tm, tn, wgs = tile
+    return f"band {-tm} rows x {tn} ch ({wgs} wg)" if tm < 0 else f"tile {tm}x{tn} ({wgs} wg)"
+
+
+def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd import runtime as R
+    from paper_2309_06626_amd.metrics import (HBM_PEAK_GBS, MFMA_PEAK_TFLOPS, algorithmic_bytes, algorithmic_flops,
+                                              time_launches)
+
+    ci = W.make_conv_inputs(spec, base_seed, x=x_host)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, out_mode=out_mode)
+    x = R.to_device(ci.x, spec.dtype)
+    y = layer.new_output()
+    y.zero_()
+    warm = max(steps // 10, 5)
+    _, ts = time_launches(B.prepared_run(layer.plan, x, layer.bias, y), steps, warm)
+    _, td = time_launches(B.prepared_run(layer.plan, x, layer.bias, y, dense=True), steps, warm)
+    scatter = out_mode == B.SC_OUT_SCATTER_ONLY
+    fl = algorithmic_flops(spec, ci.keep)
+    by = algorithmic_bytes(spec, ci.keep, scatter_only=scatter)
+    rec = {
+        "layer": spec.name, "dtype": spec.dtype, "m": spec.m, "kept": ci.keep, "k": spec.k, "c_out": spec.c_out,
+        "sparsity": spec.sparsity, "out_mode": "scatter_only" if scatter else "zero_fill",
+        "kernel_sparse": kernel_name(B.sparse_conv_plan_tiles(layer.plan, 0)),
+        "kernel_dense": kernel_name(B.sparse_conv_plan_tiles(layer.plan, 1)),
+        "sparse_us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
+        "tflops": fl / ts / 1e12, "mfma_frac": fl / ts / 1e12 / MFMA_PEAK_TFLOPS[spec.dtype],
+        "dense_tflops": algorithmic_flops(spec, spec.m) / td / 1e12,
+        "gbs": by / ts / 1e9, "hbm_frac": by / ts / 1e9 / HBM_PEAK_GBS,
+        "arithmetic_intensity": fl / by,
+    }
+    del layer, x, y
+    torch.cuda.empty_cache()
+    return rec
+
+
+def chain_time(ops, base_seed, steps):
+    """Whole network: every conv through sparse_conv_run plus the glue kernels, events around the chain."""
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import runtime as R
+
+    dtype = W.conv_specs(ops)[0].dtype
+    layers = {}
+    for s in W.conv_specs(ops):
+        ci = W.make_conv_inputs(s, base_seed, x=np.zeros(1, np.float32))
+        layers[s.name] = R.ConvLayer(s, ci.w, ci.bias, ci.mask)
+    tensors = {"input": R.to_device(W.gen_activations(W.network_input_shape(ops), base_seed, dtype), dtype)}
+    for op in ops:
+        if op.kind == "conv" and op.src.startswith("synthetic:"):
+            tensors[op.src] = R.to_device(W.gen_activations(op.spec.x_shape(), base_seed + 500 + op.spec.layer_index, dtype), dtype)
+    for _ in range(3):
+        R.run_network(ops, tensors, layers)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        R.run_network(ops, tensors, layers)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / steps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="1,2,3,4,5")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--json", default="")
+    args = ap.parse_args()
+
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+
+    if not torch.cuda.is_available():
+        print("layer_report needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    want = {int(c) for c in args.configs.split(",")}
+    records = []
+
+    def emit(cfg, rec):
+        rec["config"] = cfg
+        records.append(rec)
+        print(f"| {cfg} | {rec['layer']} | {rec['m']}x{rec['k']}x{rec['c_out']} | {rec['sparsity']:.2f} {rec['out_mode'][:7]} | "
+              f"{rec['kernel_sparse']} | {rec['sparse_us']:.2f} | {rec['dense_us']:.2f} | {rec['speedup_vs_dense']:.2f} | "
+              f"{rec['tflops']:.1f} | {100 * rec['mfma_frac']:.1f} | {rec['gbs']:.0f} | {100 * rec['hbm_frac']:.1f} | "
+              f"{rec['arithmetic_intensity']:.0f} |", flush=True)
+
+    print("| cfg | layer | M x K x Cout | s, out mode | sparse kernel | sparse us | dense us | speed-up | TFLOP/s | % MFMA | GB/s | % HBM | FLOP/B |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    if 1 in want:
+        emit(1, measure_layer(W.config1(), W.base_seed(1), args.steps, B.SC_OUT_ZERO_FILL))
+    if 2 in want:
+        for s in W.C2_SPARSITIES:
+            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_ZERO_FILL))
+        for s in W.C2_SPARSITIES[1:]:
+            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_SCATTER_ONLY))
+    chains = {}
+    if 3 in want:
+        ops = W.config3()
+        for spec in W.conv_specs(ops):
+            emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL))
+        chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), max(args.steps // 10, 5))
+        chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3),
+                                                               max(args.steps // 10, 5))
+        chains["config 3, every conv dense (s=0)"] = chain_time(W.config3(sparsity=0.0), W.base_seed(3),
+                                                                max(args.steps // 10, 5))
+    if 4 in want:
+        for spec in W.config4():
+            emit(4, measure_layer(spec, W.base_seed(4), args.steps, B.SC_OUT_ZERO_FILL))
+    if 5 in want:
+        ops = W.config5()
+        for spec in W.conv_specs(ops):
+            emit(5, measure_layer(spec, W.base_seed(5), args.steps, B.SC_OUT_ZERO_FILL))
+        chains["config 5 (detector stack, batch 16, s=0.3)"] = chain_time(ops, W.base_seed(5), max(args.steps // 10, 5))
+        chains["config 5, every conv dense (s=0)"] = chain_time(W.config5(sparsity=0.0), W.base_seed(5),
+                                                                max(args.steps // 10, 5))
+    if chains:
+        print()
+        print("| whole chain (conv launches + pooling / residual glue) | us per pass |")
+        print("|---|---|")
+        for k, v in chains.items():
+            print(f"| {k} | {v:.1f} |")
+    if args.json:
+        with open(args.json, "w") as f:
+            for r in records:
+                f.write(json.dumps(r) + "\n")
+            f.write(json.dumps({"chains_us": chains}) + "\n")
+
+
+if __name__ == "__main__":
+    main()
