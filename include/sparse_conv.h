@@ -131,13 +131,23 @@ sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, 
 sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* tile_m, int32_t* tile_n,
                                  int64_t* workgroups);
 
+/* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
+ * "band_alternating", "band_stream", "tile_lds_direct", "tile_registers" or "tile_elements".
+ * A static string; NULL for a NULL plan or an unknown `which`. */
+const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
+
 /* Tuning hook: force the kernel of later runs.  (0,0) restores the automatic choice; tile_m > 0
  * selects the tiled gather kernel of that shape; tile_m < 0 selects the band kernel (band height
  * stays automatic).  Returns SC_ERR_UNSUPPORTED when the library has no such kernel for the layer. */
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
 
-/* Environment (read by sparse_conv_plan; tuning and tests only): SPARSE_CONV_BAND_HEIGHT=<rows> fixes
- * the band height of the streaming band kernel instead of the automatic choice. */
+/* Environment (read by sparse_conv_plan; tuning and tests only):
+ *   SPARSE_CONV_BAND_HEIGHT=<rows>               fixes the band height of the streaming and of the
+ *                                                alternating-group band kernels (automatic otherwise)
+ *   SPARSE_CONV_BAND_KERNEL=single|alternating   band kernel with one band per workgroup, or the
+ *                                                persistent one whose two wavefront groups alternate
+ *                                                between transfer and matrix work (3x3 windows, 16-bit
+ *                                                types, 32 or 64 input channels); automatic otherwise */
 
 /* Tuning hook: SC_OPT_GATHER_PIPELINE selects how the tiled gather kernel moves its K tiles:
  * 0 = automatic, 1 = global -> registers -> LDS, 2 = global -> LDS directly (NHWC with 16-byte

@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                             ctypes.POINTER(i32), ctypes.POINTER(vp)]
         L.sparse_conv_plan_tiles.restype = ctypes.c_int
         L.sparse_conv_plan_tiles.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]
+        L.sparse_conv_plan_kernel.restype = ctypes.c_char_p
+        L.sparse_conv_plan_kernel.argtypes = [vp, i32]
         L.sparse_conv_plan_set_tiles.restype = ctypes.c_int
         L.sparse_conv_plan_set_tiles.argtypes = [vp, i32, i32, i32]
         L.sparse_conv_plan_set_option.restype = ctypes.c_int
@@ -235,6 +237,13 @@ def sparse_conv_plan_tiles(plan: Plan, which: int) -> Tuple[int, int, int]:
     _check(lib().sparse_conv_plan_tiles(plan.handle, which, ctypes.byref(tm), ctypes.byref(tn), ctypes.byref(wg)),
            "sparse_conv_plan_tiles")
     return tm.value, tn.value, wg.value
+
+
+def sparse_conv_plan_kernel(plan: Plan, which: int) -> str:
+    name = lib().sparse_conv_plan_kernel(plan.handle, which)
+    if name is None:
+        raise ScError("sparse_conv_plan_kernel: bad plan or launch selector")
+    return name.decode()
 
 
 def sparse_conv_plan_set_tiles(plan: Plan, which: int, tile_m: int, tile_n: int):

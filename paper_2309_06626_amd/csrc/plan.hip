@@ -11,6 +11,7 @@
 #include <new>
 
 #include "band_kernel.hpp"
+#include "bandpp_kernel.hpp"
 #include "bandstream_kernel.hpp"
 #include "conv_params.hpp"
 
@@ -285,6 +286,8 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
 struct BandPlan {
   bool ok;
   bool stream;       // filters streamed through an LDS ring instead of resident
+  bool pp;           // persistent workgroups, two wavefront groups alternating between transfer and MFMA
+  int pp_grid;       // workgroups of that kernel
   int max_kept;      // most kept rows in one band (streaming kernel only)
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
   size_t b_bytes, x_bytes, lds;
@@ -305,6 +308,52 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
   bp.ni_idx = bp.ni == 1 ? 0 : bp.ni == 2 ? 1 : 2;
   bp.n_tiles = (d.c_out + 32 * bp.ni - 1) / (32 * bp.ni);
   bp.b_bytes = (size_t)32 * bp.ni * g.k_stride * eb;
+  // Alternating-group kernel (persistent workgroups, filters resident, two input slabs): 3x3
+  // windows of 16-bit operands with 4 or 8 channel groups per pixel.  It pays once a workgroup
+  // walks several bands (measured on MI355X: from three steps on); with fewer, one band per
+  // workgroup is faster.  SPARSE_CONV_BAND_KERNEL=single|alternating overrides (tuning and tests).
+  const char* variant = std::getenv("SPARSE_CONV_BAND_KERNEL");
+  const bool want_single = variant && std::strcmp(variant, "single") == 0;
+  const bool want_pp = variant && std::strcmp(variant, "alternating") == 0;
+  if (!want_single && d.kh == 3 && d.kw == 3 && d.dtype != SC_F32 &&
+      (d.c_in / g.vec == 8 || d.c_in / g.vec == 4)) {
+    BandPlan pp = bp;
+    pp.ni = d.c_out <= 32 ? 1 : 2;
+    pp.ni_idx = pp.ni - 1;
+    pp.n_tiles = (d.c_out + 32 * pp.ni - 1) / (32 * pp.ni);
+    pp.b_bytes = (size_t)32 * pp.ni * g.k_stride * eb;
+    const char* env = std::getenv("SPARSE_CONV_BAND_HEIGHT");
+    const int forced_bh = env ? std::atoi(env) : 0;
+    const int lanes_max = std::max(1, 256 / pp.n_tiles);
+    int best_steps = 0;
+    double best = 1e300;
+    for (int bh = 1; bh <= g.ho; ++bh) {
+      int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
+      size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
+      if (pp.b_bytes + 2 * xbytes + kPPFixedLds > kLdsLimit) break;
+      if ((int64_t)bh * g.wo > kPPMaxRows) break;
+      int bpi = (g.ho + bh - 1) / bh;
+      int64_t nb = (int64_t)d.n * bpi;
+      int lanes = (int)std::min<int64_t>(nb, lanes_max);
+      int steps = (int)((nb + lanes - 1) / lanes);
+      // a step costs its band plus a fixed part (halo rows, barrier, transfer latency)
+      double cost = steps * (bh + 1.5);
+      if (forced_bh > 0 ? bh == forced_bh : cost <= best) {
+        best = cost;
+        best_steps = steps;
+        pp.ok = true;
+        pp.pp = true;
+        pp.bh = bh;
+        pp.bands_per_image = bpi;
+        pp.n_bands = (int)nb;
+        pp.x_bytes = xbytes;
+        pp.lds = pp.b_bytes + 2 * xbytes + kPPFixedLds;
+        pp.pp_grid = lanes * pp.n_tiles;
+      }
+    }
+    // two channel tiles would transfer every band twice: measured slower than the tiled kernel
+    if (pp.ok && (want_pp || (best_steps >= 3 && pp.n_tiles == 1))) return pp;
+  }
   if (bp.b_bytes > 96 * 1024) {
     // Filters too large to stay resident: stream them (16-bit types, whole 128-byte K tiles per tap,
     // 64 or 128 channels per workgroup).  Taller bands amortise the filter traffic, which every
@@ -370,6 +419,7 @@ struct sc_plan {
   BandPlan band;
   const BandTable* band_table;
   const BandStreamTable* stream_table;
+  const BandPPTable* pp_table;
   unsigned char* ws;
   int64_t kept;
   const KernelEntry* table;
@@ -410,6 +460,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const int which = dense ? 1 : 0;
   const int64_t rows = dense ? g.m : pl->kept;
   const bool zero_fill = !dense && d.out_mode == SC_OUT_ZERO_FILL && pl->kept < g.m;
+  // a mask that keeps every row makes the row list the identity: skip the indirection
+  const bool identity = dense || pl->kept == g.m;
   const int eb = elem_bytes(d.dtype);
   if (rows == 0) {
     if (d.out_mode == SC_OUT_ZERO_FILL) {
@@ -434,7 +486,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.wp = pl->ws + g.off_wp;
     q.bias = d.has_bias ? bias : nullptr;
     q.y = y;
-    q.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+    q.row_idx = identity ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
     q.mask = pl->ws + g.off_mask;
     q.band_i0 = reinterpret_cast<const int32_t*>(pl->ws + g.off_band);
     q.band_rows = reinterpret_cast<const int32_t*>(pl->ws + g.off_band_rows);
@@ -462,6 +514,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     // rows per wavefront decide how many 32-row MFMA blocks share one filter fragment
     const double per_wave = (double)rows / b.n_bands / 4.0;
     const int mi_idx = per_wave > 32.0 ? 1 : 0;
+    if (b.pp) {
+      SC_HIP(pl->pp_table->fn[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
+      return SC_OK;
+    }
     const int cpp = d.c_in / g.vec;
     const int shape = (d.kh == 3 && d.kw == 3 && cpp == 8) ? 1 : (d.kh == 3 && d.kw == 3 && cpp == 4) ? 2 : 0;
     SC_HIP(pl->band_table->fn[shape][b.ni_idx][mi_idx](q, b.lds, stream));
@@ -475,7 +531,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.wp = pl->ws + g.off_wp;
   p.bias = d.has_bias ? bias : nullptr;
   p.y = y;
-  p.row_idx = dense ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+  p.row_idx = identity ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
   p.mask = pl->ws + g.off_mask;
   p.ktab = reinterpret_cast<const KEntry*>(pl->ws + g.off_ktab);
   p.zeros = pl->ws + g.off_zeros;
@@ -645,6 +701,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->band = bp;
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
+  pl->pp_table = d.dtype == SC_BF16 ? bandpp_bf16() : d.dtype == SC_F16 ? bandpp_f16() : nullptr;
   (void)eb;
   *out = pl;
   return SC_OK;
@@ -682,7 +739,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
   if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream))) {
     if (tile_m) *tile_m = -plan->band.bh;
     if (tile_n) *tile_n = 32 * plan->band.ni;
-    if (workgroups) *workgroups = (int64_t)plan->band.n_bands * plan->band.n_tiles;
+    if (workgroups) *workgroups = plan->band.pp ? plan->band.pp_grid : (int64_t)plan->band.n_bands * plan->band.n_tiles;
     return SC_OK;
   }
   int ti = plan->forced[which] >= 0 ? plan->forced[which] : (which ? plan->tile_dense : plan->tile_sparse);
@@ -692,6 +749,15 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
   if (tile_n) *tile_n = ke.bn;
   if (workgroups) *workgroups = ((rows + ke.bm - 1) / ke.bm) * ((plan->desc.c_out + ke.bn - 1) / ke.bn);
   return SC_OK;
+}
+
+const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
+  if (!plan || (which != 0 && which != 1)) return nullptr;
+  if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream)))
+    return plan->band.stream ? "band_stream" : plan->band.pp ? "band_alternating" : "band";
+  const Geometry& g = plan->geo;
+  if (!g.vec_gather) return "tile_elements";
+  return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
 }
 
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n) {

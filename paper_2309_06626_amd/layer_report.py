@@ -23,9 +23,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
-def kernel_name(tile):
-    tm, tn, wgs = tile
-    return f"band {-tm} rows x {tn} ch ({wgs} wg)" if tm < 0 else f"tile {tm}x{tn} ({wgs} wg)"
+def kernel_name(plan, which):
+    from paper_2309_06626_amd import binding as B
+
+    tm, tn, wgs = B.sparse_conv_plan_tiles(plan, which)
+    shape = f"{-tm} rows x {tn} ch" if tm < 0 else f"{tm}x{tn}"
+    return f"{B.sparse_conv_plan_kernel(plan, which)} {shape} ({wgs} wg)"
 
 
 def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
@@ -51,8 +54,8 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
     rec = {
         "layer": spec.name, "dtype": spec.dtype, "m": spec.m, "kept": ci.keep, "k": spec.k, "c_out": spec.c_out,
         "sparsity": spec.sparsity, "out_mode": "scatter_only" if scatter else "zero_fill",
-        "kernel_sparse": kernel_name(B.sparse_conv_plan_tiles(layer.plan, 0)),
-        "kernel_dense": kernel_name(B.sparse_conv_plan_tiles(layer.plan, 1)),
+        "kernel_sparse": kernel_name(layer.plan, 0),
+        "kernel_dense": kernel_name(layer.plan, 1),
         "sparse_us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
         "tflops": fl / ts / 1e12, "mfma_frac": fl / ts / 1e12 / MFMA_PEAK_TFLOPS[spec.dtype],
         "dense_tflops": algorithmic_flops(spec, spec.m) / td / 1e12,

@@ -98,15 +98,59 @@ BAND_CASES = [
 @pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
 @pytest.mark.parametrize("mask_mode", ["row", "spatial"])
 @pytest.mark.parametrize("case", range(len(BAND_CASES)))
-def test_band_kernel(case, mask_mode, dtype):
+def test_band_kernel(case, mask_mode, dtype, monkeypatch):
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "single")
     spec = spec_of(dtype=dtype, mask_mode=mask_mode, **BAND_CASES[case])
     eb = 4 if dtype == "f32" else 2
     if min(spec.c_out, 128) * spec.k * eb > 96 * 1024:
         pytest.skip("filter slab too large for the band kernel at this element size")
     layer = check_layer(W.make_conv_inputs(spec, 900 + case), tiles=(-1, 0))
-    assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] < 0          # really the band kernel
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"      # really the band kernel
     # and the tiled kernel on the same layer
     check_layer(W.make_conv_inputs(spec, 900 + case), tiles=(64, 64))
+
+
+ALT_CASES = [
+    dict(n=2, cin=64, h=20, w=20, cout=64),                          # 8 channel groups per pixel, two filter blocks
+    dict(n=3, cin=32, h=17, w=19, cout=32, sp=0.3),                  # 4 groups per pixel, one filter block
+    dict(n=2, cin=64, h=18, w=18, cout=128, sp=0.4),                 # two channel tiles per band
+    dict(n=2, cin=32, h=21, w=21, cout=48, k=3, s=2, p=1, sp=0.5),   # stride 2, ragged channel tile
+    dict(n=1, cin=64, h=15, w=13, cout=64, k=3, p=2, d=2, sp=0.6),   # dilation 2
+    dict(n=2, cin=32, h=14, w=14, cout=64, sp=0.0),                  # every row kept
+    dict(n=1, cin=64, h=12, w=12, cout=64, sp=0.95),                 # bands with almost no kept rows
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("case", range(len(ALT_CASES)))
+def test_alternating_band_kernel(case, mask_mode, dtype, monkeypatch):
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **ALT_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 930 + case), tiles=(-1, 0))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
+    assert B.sparse_conv_plan_kernel(layer.plan, 1) == "band_alternating"
+
+
+@pytest.mark.parametrize("bh,h,w,sp", [(1, 100, 8, 0.5), (1, 40, 12, 0.3), (2, 130, 10, 0.6), (3, 100, 16, 0.5)])
+def test_alternating_band_kernel_many_steps(bh, h, w, sp, monkeypatch):
+    # more bands than workgroups: every workgroup walks two to four bands, the last step ragged
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", str(bh))
+    spec = spec_of(8, 32, h, w, 64, dtype="bf16", sp=sp)
+    layer = check_layer(W.make_conv_inputs(spec, 940 + bh + h), tiles=(-1, 0))
+    tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+    assert (tm, tn) == (-bh, 64) and wgs == 256 and 8 * ((h + bh - 1) // bh) > 256
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
+
+
+def test_alternating_band_kernel_is_the_automatic_choice_for_long_band_lists():
+    big = spec_of(64, 64, 56, 56, 64, dtype="bf16", sp=0.5)
+    layer = R.ConvLayer(big, *_wbm(big, 3))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
+    small = spec_of(2, 64, 20, 20, 64, dtype="bf16", sp=0.5)
+    layer = R.ConvLayer(small, *_wbm(small, 3))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 
 
 STREAM_CASES = [
@@ -125,7 +169,7 @@ STREAM_CASES = [
 def test_streaming_band_kernel(case, mask_mode, dtype):
     spec = spec_of(dtype=dtype, mask_mode=mask_mode, **STREAM_CASES[case])
     layer = check_layer(W.make_conv_inputs(spec, 950 + case), tiles=(-1, 0))
-    assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] < 0
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_stream"
 
 
 @pytest.mark.parametrize("bh,sp", [(4, 0.5), (7, 0.5), (10, 0.3), (12, 0.1), (12, 0.6)])
