@@ -209,8 +209,8 @@ def prepared_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: t
         _stream_handle(stream)
     keep = (plan, x, bias, y)
 
-    def call():
-        rc = fn(h, px, pb, py, st)
+    def call(stream_handle=None):
+        rc = fn(h, px, pb, py, st if stream_handle is None else stream_handle)
         if rc != SC_OK:
             raise ScError(rc, name)
         return keep[3]
@@ -264,6 +264,40 @@ def sc_maxpool2d_nhwc(x: torch.Tensor, k: int = 3, s: int = 2, p: int = 1, strea
     _check(lib().sc_maxpool2d_nhwc(_dev_ptr(x, "x"), _dev_ptr(y, "y"), _CODE_OF_TORCH[x.dtype], n, h, w, c, k, s, p,
                                    _stream_handle(stream)), "sc_maxpool2d_nhwc")
     return y
+
+
+def prepared_maxpool(x: torch.Tensor, y: torch.Tensor, k: int = 3, s: int = 2, p: int = 1, stream=None):
+    """Like prepared_run, for sc_maxpool2d_nhwc into a caller-owned output."""
+    n, h, w, c = x.shape
+    ho, wo = (h + 2 * p - k) // s + 1, (w + 2 * p - k) // s + 1
+    if tuple(y.shape) != (n, ho, wo, c) or y.dtype != x.dtype:
+        raise ValueError("output tensor does not match the pooled shape")
+    fn, px, py, code, st = lib().sc_maxpool2d_nhwc, _dev_ptr(x, "x"), _dev_ptr(y, "y"), _CODE_OF_TORCH[x.dtype], \
+        _stream_handle(stream)
+    keep = (x, y)
+
+    def call(stream_handle=None):
+        _check(fn(px, py, code, n, h, w, c, k, s, p, st if stream_handle is None else stream_handle), "sc_maxpool2d_nhwc")
+        return keep[1]
+
+    call()
+    return call
+
+
+def prepared_add_relu(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor, stream=None):
+    """Like prepared_run, for sc_add_relu into a caller-owned output."""
+    if a.shape != b.shape or a.dtype != b.dtype or y.shape != a.shape or y.dtype != a.dtype:
+        raise ValueError("operands differ in shape or dtype")
+    fn, pa, pb, py, code, n, st = lib().sc_add_relu, _dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), \
+        _CODE_OF_TORCH[a.dtype], a.numel(), _stream_handle(stream)
+    keep = (a, b, y)
+
+    def call(stream_handle=None):
+        _check(fn(pa, pb, py, code, n, st if stream_handle is None else stream_handle), "sc_add_relu")
+        return keep[2]
+
+    call()
+    return call
 
 
 def sc_add_relu(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:

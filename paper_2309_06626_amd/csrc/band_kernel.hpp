@@ -86,6 +86,9 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   float* s_bias = reinterpret_cast<float*>(smem + p.b_bytes + (size_t)p.x_groups * 16 + 1024);   // [BN]
 
   SC_STAMP(0);
+#ifdef SC_TIMING
+  const long long wall0 = wall_clock64();
+#endif
   const int nwg = p.n_bands * p.n_tiles;
   const int per_xcd = (nwg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -158,11 +161,11 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
 #pragma unroll
       for (int u = 0; u < ZIT; ++u) {
         const int r = r_lo + zr + u * RPI;
-        if (r < r_hi && mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+        if (r < r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
       }
       for (int r = r_lo + zr + ZIT * RPI; r < r_hi; r += RPI)   // bands taller than ZIT passes
         if (p.mask[p.mask_spatial ? r - img * ho_wo : r] == 0)
-          *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+          sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
     }
   };
 
@@ -356,6 +359,9 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
     }
   }
   SC_STAMP(4);
+#ifdef SC_TIMING
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + 7] = wall_clock64() - wall0;
+#endif
 }
 
 template <int DT, int NI, int MI, int KH, int KW, int CPP>

@@ -72,6 +72,9 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
   };
 
+#ifdef SC_TIMING
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 128 + 120] = wall_clock64();
+#endif
   // ---- once per workgroup: filter slab (all eight wavefronts), zero group, bias slice -------------
   {
     const v4i* gb = reinterpret_cast<const v4i*>(static_cast<const T*>(p.wp) + (int64_t)n0 * p.k_stride);
@@ -154,11 +157,11 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
 #pragma unroll
         for (int u = 0; u < ZIT; ++u) {
           const int r = g.r_lo + zr + u * RPI;
-          if (r < g.r_hi && mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+          if (r < g.r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
         }
         for (int r = g.r_lo + zr + ZIT * RPI; r < g.r_hi; r += RPI)
           if (p.mask[p.mask_spatial ? r - g.img * ho_wo : r] == 0)
-            *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+            sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
       }
     }
   };
@@ -297,6 +300,9 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     SC_PP_STAMP(k, 6);
   }
+#ifdef SC_TIMING
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 128 + 121] = wall_clock64();
+#endif
 }
 
 template <int DT, int NI, int MI, int KH, int KW, int CPP>

@@ -230,7 +230,7 @@ __global__ __launch_bounds__(kThreads) void bandstream_kernel(const BandParams p
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = r0 + u * RPI;
-          if (r < r_hi && mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+          if (r < r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
         }
       }
     }

@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = r0 + u * RPI;
-          if (r < hi && mk[u] == 0) *reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB) = z;
+          if (r < hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
         }
       }
     }

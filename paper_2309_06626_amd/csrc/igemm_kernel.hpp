@@ -163,7 +163,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
         int mr = p.mask_spatial ? r % p.ho_wo : r;
         if (c < valid && p.mask[mr] == 0) {
           v4i z = {0, 0, 0, 0};
-          *reinterpret_cast<v4i*>(reinterpret_cast<unsigned char*>(y) + ((int64_t)r * p.c_out + n0) * EB + c * 16) = z;
+          sc_store16(reinterpret_cast<v4i*>(reinterpret_cast<unsigned char*>(y) + ((int64_t)r * p.c_out + n0) * EB + c * 16), z);
         }
       }
     } else {

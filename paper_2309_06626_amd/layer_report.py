@@ -7,7 +7,8 @@ For every convolution: kernel chosen for the sparse and the dense run, time per 
 TFLOP/s of the kept rows (2*kept*K*Cout / t) and its share of the MFMA peak, algorithmic GB/s and
 its share of the HBM peak, and the speed-up over the dense run of the same kernels.  Config 2 is
 reported at s in {0, 0.25, 0.5, 0.7} in zero-fill mode and, for s > 0, in scatter-only mode.
-Configs 3 and 5 add the time of the whole chain (conv launches plus the pooling / residual glue).
+Configs 3 and 5 add the time of the whole chain (conv launches plus the pooling / residual glue),
+launched call by call and replayed as a HIP graph.
 Layers are timed one by one on synthetic inputs of their own shape (warm buffers, back-to-back
 launches on one stream).
 """
@@ -67,8 +68,8 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
     return rec
 
 
-def chain_time(ops, base_seed, steps):
-    """Whole network: every conv through sparse_conv_run plus the glue kernels, events around the chain."""
+def chain_time(ops, base_seed, steps, dense=False):
+    """Whole network with fixed buffers: (us per pass launched call by call, us per pass as a HIP graph replay)."""
     import numpy as np
     import torch
 
@@ -84,16 +85,23 @@ def chain_time(ops, base_seed, steps):
     for op in ops:
         if op.kind == "conv" and op.src.startswith("synthetic:"):
             tensors[op.src] = R.to_device(W.gen_activations(op.spec.x_shape(), base_seed + 500 + op.spec.layer_index, dtype), dtype)
-    for _ in range(3):
-        R.run_network(ops, tensors, layers)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(steps):
-        R.run_network(ops, tensors, layers)
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / steps
+    net = R.NetworkRunner(ops, tensors, layers, dense=dense)
+
+    def timed(fn):
+        for _ in range(max(steps // 5, 3)):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps
+
+    eager = timed(net.run)
+    graph = net.capture()
+    return eager, timed(graph.replay)
 
 
 def main():
@@ -111,6 +119,8 @@ def main():
     if not torch.cuda.is_available():
         print("layer_report needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if os.environ.get("SPARSE_CONV_LIBRARY"):
+        B.LIB_PATH = os.environ["SPARSE_CONV_LIBRARY"]
     B.lib()
     want = {int(c) for c in args.configs.split(",")}
     records = []
@@ -137,11 +147,10 @@ def main():
         ops = W.config3()
         for spec in W.conv_specs(ops):
             emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL))
-        chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), max(args.steps // 10, 5))
-        chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3),
-                                                               max(args.steps // 10, 5))
-        chains["config 3, every conv dense (s=0)"] = chain_time(W.config3(sparsity=0.0), W.base_seed(3),
-                                                                max(args.steps // 10, 5))
+        cs = max(args.steps // 10, 5)
+        chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), cs)
+        chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3), cs)
+        chains["config 3, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(3), cs, dense=True)
     if 4 in want:
         for spec in W.config4():
             emit(4, measure_layer(spec, W.base_seed(4), args.steps, B.SC_OUT_ZERO_FILL))
@@ -149,15 +158,15 @@ def main():
         ops = W.config5()
         for spec in W.conv_specs(ops):
             emit(5, measure_layer(spec, W.base_seed(5), args.steps, B.SC_OUT_ZERO_FILL))
-        chains["config 5 (detector stack, batch 16, s=0.3)"] = chain_time(ops, W.base_seed(5), max(args.steps // 10, 5))
-        chains["config 5, every conv dense (s=0)"] = chain_time(W.config5(sparsity=0.0), W.base_seed(5),
-                                                                max(args.steps // 10, 5))
+        cs = max(args.steps // 10, 5)
+        chains["config 5 (detector stack, batch 16, s=0.3)"] = chain_time(ops, W.base_seed(5), cs)
+        chains["config 5, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(5), cs, dense=True)
     if chains:
         print()
-        print("| whole chain (conv launches + pooling / residual glue) | us per pass |")
-        print("|---|---|")
+        print("| whole chain (conv launches + pooling / residual glue, fixed buffers) | us per pass, call by call | us per pass, HIP graph replay |")
+        print("|---|---|---|")
         for k, v in chains.items():
-            print(f"| {k} | {v:.1f} |")
+            print(f"| {k} | {v[0]:.1f} | {v[1]:.1f} |")
     if args.json:
         with open(args.json, "w") as f:
             for r in records:

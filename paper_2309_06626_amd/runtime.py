@@ -72,3 +72,44 @@ def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLay
         else:
             raise ValueError(op.kind)
     return t
+
+
+class NetworkRunner:
+    """A workload op list bound to fixed device buffers: every tensor is allocated once and every
+    launch is validated once, so a pass is a plain sequence of C-ABI calls (and can be recorded into
+    a HIP graph: the library launches kernels only, no memsets, no allocations, no synchronisation)."""
+
+    def __init__(self, ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer], dense: bool = False):
+        self.tensors = dict(tensors)
+        self.calls: List[Callable] = []
+        t = self.tensors
+        for op in ops:
+            if op.kind == "conv":
+                layer = layers[op.spec.name]
+                t[op.out] = layer.new_output()
+                self.calls.append(B.prepared_run(layer.plan, t[op.src], layer.bias, t[op.out], dense=dense))
+            elif op.kind == "maxpool":
+                n, h, w, c = t[op.src].shape
+                t[op.out] = torch.empty((n, (h + 2 - 3) // 2 + 1, (w + 2 - 3) // 2 + 1, c), dtype=t[op.src].dtype,
+                                        device=t[op.src].device)
+                self.calls.append(B.prepared_maxpool(t[op.src], t[op.out], 3, 2, 1))
+            elif op.kind == "add_relu":
+                t[op.out] = torch.empty_like(t[op.src])
+                self.calls.append(B.prepared_add_relu(t[op.src], t[op.src2], t[op.out]))
+            else:
+                raise ValueError(op.kind)
+        self.graph = None
+
+    def run(self, stream_handle=None) -> Dict[str, torch.Tensor]:
+        for call in self.calls:
+            call(stream_handle)
+        return self.tensors
+
+    def capture(self) -> "torch.cuda.CUDAGraph":
+        """Record one pass into a HIP graph (replay with .replay()); the buffers stay the same."""
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.run(torch.cuda.current_stream().cuda_stream)
+        self.graph = g
+        return g

@@ -336,6 +336,37 @@ def test_config5_detector_stack():
     _compare_network(ops, dev, ref, params, TOL["bf16"])
 
 
+def test_fixed_buffer_runner_and_graph_replay_match_the_eager_chain():
+    """The same op list through preallocated buffers, call by call and as a HIP graph replayed several
+    times with eager work in between: every pass must reproduce the eager chain bit for bit."""
+    ops = W.config3(batch=2)
+    bs = W.base_seed(3)
+    dtype = "bf16"
+    layers = {}
+    for s in W.conv_specs(ops):
+        ci = W.make_conv_inputs(s, bs, x=np.zeros(1, np.float32))
+        layers[s.name] = R.ConvLayer(s, ci.w, ci.bias, ci.mask)
+    x = R.to_device(W.gen_activations(W.network_input_shape(ops), bs, dtype), dtype)
+    eager = R.run_network(ops, {"input": x}, layers)
+    want = {op.out: R.bits_of(eager[op.out]).copy() for op in ops}
+    net = R.NetworkRunner(ops, {"input": x}, layers)
+
+    def poison_and_check(run):
+        for op in ops:
+            net.tensors[op.out].fill_(float("nan"))
+        run()
+        torch.cuda.synchronize()
+        for op in ops:
+            assert np.array_equal(R.bits_of(net.tensors[op.out]), want[op.out]), op.out
+
+    poison_and_check(net.run)
+    graph = net.capture()
+    for _ in range(3):
+        poison_and_check(graph.replay)
+        scratch = torch.randn(1 << 16, device="cuda:0").sum().item()   # unrelated eager work and a sync between replays
+        assert np.isfinite(scratch)
+
+
 def test_config3_full_batch_sampled_rows():
     """Every ResNet18 layer at batch 64 (the full configuration), each on synthetic input of its own
     shape; structure checked everywhere, values on sampled rows the oracle computes one by one."""
