@@ -132,7 +132,8 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_stream", "tile_lds_direct", "tile_registers" or "tile_elements".
+ * "band_alternating", "band_stream", "tile_split_k", "tile_lds_direct", "tile_registers" or
+ * "tile_elements".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
 
@@ -152,7 +153,11 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
 /* Tuning hook: SC_OPT_GATHER_PIPELINE selects how the tiled gather kernel moves its K tiles:
  * 0 = automatic, 1 = global -> registers -> LDS, 2 = global -> LDS directly (NHWC with 16-byte
  * channel groups only; other layers ignore it).  Unknown options return SC_ERR_UNSUPPORTED. */
-enum { SC_OPT_GATHER_PIPELINE = 0 };
+/* SC_OPT_SPLIT_K: 0 = automatic, 1 = never split K, n >= 2 = divide K among n workgroups per output
+ * tile wherever the split-K kernel applies (16-bit NHWC layers with >= 128 output channels and a
+ * deep K); n is at most 64 and is clamped so that the partial sums fit their 16 MiB buffer and every
+ * split has at least four K tiles.  Partial sums are added in a fixed order: results do not depend on scheduling. */
+enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1 };
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
 
 void sparse_conv_plan_destroy(sc_plan* plan);

@@ -39,6 +39,13 @@ struct ConvParams {
   int32_t mask_spatial;    // mask has ho_wo entries shared by the batch
   int32_t vec_out;         // y rows are channel-contiguous and 16-byte groups are aligned
   int32_t m_tiles, n_tiles;
+  // split-K launches only: the K tiles of an output tile are divided among `splits` workgroups
+  int32_t splits;
+  float* partial;          // [m_tiles * n_tiles][splits][BM * BN] float partial sums
+  int32_t* counters;       // [m_tiles * n_tiles] arrival counters, zero between launches
+#ifdef SC_TIMING
+  long long* dbg;          // development builds only: per-workgroup phase time stamps
+#endif
 };
 
 enum Dtype { kF32 = 0, kF16 = 1, kBF16 = 2 };
@@ -57,6 +64,7 @@ struct KernelEntry {
   LaunchFn elem;  // element gather (any layout)
   LaunchFn dma;   // 16-byte gather straight into LDS (additionally needs channel-contiguous stores)
   LaunchFn dma2;  // the same with a two-tile ring: less LDS, more workgroups per CU (shallow K)
+  LaunchFn splitk; // direct-to-LDS gather, deep ring, K divided among several workgroups (null: no such shape)
   size_t lds_bytes;
 };
 

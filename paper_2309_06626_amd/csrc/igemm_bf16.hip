@@ -7,11 +7,11 @@ namespace sc {
 
 static const KernelEntry g_table[] = {
     SC_KERNEL_ENTRY(kBF16, 256, 128, 2, 2, 2, 3),
-    SC_KERNEL_ENTRY(kBF16, 128, 128, 2, 2, 3, 3),
+    SC_KERNEL_ENTRY_SPLITK(kBF16, 128, 128, 2, 2, 3, 3, 4),
     SC_KERNEL_ENTRY(kBF16, 256, 64, 4, 1, 2, 3),
-    SC_KERNEL_ENTRY(kBF16, 128, 64, 2, 2, 4, 3),
-    SC_KERNEL_ENTRY(kBF16, 64, 128, 2, 2, 4, 3),
-    SC_KERNEL_ENTRY(kBF16, 64, 64, 2, 2, 4, 3),
+    SC_KERNEL_ENTRY_SPLITK(kBF16, 128, 64, 2, 2, 4, 3, 6),
+    SC_KERNEL_ENTRY_SPLITK(kBF16, 64, 128, 2, 2, 4, 3, 6),
+    SC_KERNEL_ENTRY_SPLITK(kBF16, 64, 64, 2, 2, 4, 3, 8),
     SC_KERNEL_ENTRY(kBF16, 128, 32, 4, 1, 4, 3),
     SC_KERNEL_ENTRY(kBF16, 32, 128, 1, 4, 4, 3),
 };

@@ -52,10 +52,20 @@ template <int N, int CNT> __device__ __forceinline__ void wait_frags(v4i (&f)[CN
   static_assert(CNT >= 1 && CNT <= 8, "fragment count");
 }
 
-template <int BM, int BN, int STAGES>
-constexpr size_t igemm_dma_lds_bytes() { return (size_t)STAGES * (BM + BN) * kRowBytes + BM * sizeof(int32_t); }
+#ifdef SC_TIMING
+#define SC_DMA_STAMP(slot) do { if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define SC_DMA_STAMP(slot) do { } while (0)
+#endif
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int BM, int BN, int STAGES>
+constexpr size_t igemm_dma_lds_bytes() { return (size_t)STAGES * (BM + BN) * kRowBytes + (BM + 4) * sizeof(int32_t); }
+
+// SPLITK: grid = output tiles x p.splits; workgroup (tile, split) contracts its share of the K tiles
+// and leaves float partial sums in p.partial; the workgroup that arrives last at the tile's counter
+// adds the partial sums in split order (so the result does not depend on who was last) and runs
+// the epilogue.  Nobody waits for anybody: a workgroup either finishes the tile or leaves.
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool SPLITK = false>
 __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
@@ -72,14 +82,22 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 
   extern __shared__ __align__(16) unsigned char smem[];
   int32_t* s_rows = reinterpret_cast<int32_t*>(smem + STAGES * STAGE_BYTES);   // [BM]
+  SC_DMA_STAMP(0);
 
-  const int nwg = p.m_tiles * p.n_tiles;
+  const int splits = SPLITK ? p.splits : 1;
+  const int nwg = p.m_tiles * p.n_tiles * splits;
   const int per_xcd = (nwg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (logical >= nwg) return;
-  const int tile_m = logical / p.n_tiles;
-  const int tile_n = logical - tile_m * p.n_tiles;
+  // the splits of one tile are neighbours: they run on one XCD and share the tile's rows in its L2
+  const int tile = logical / splits;
+  const int split = logical - tile * splits;
+  const int tile_m = tile / p.n_tiles;
+  const int tile_n = tile - tile_m * p.n_tiles;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int kt_lo = SPLITK ? (int)((int64_t)split * p.k_tiles / splits) : 0;
+  const int kt_hi = SPLITK ? (int)((int64_t)(split + 1) * p.k_tiles / splits) : p.k_tiles;
+  const int n_kt = kt_hi - kt_lo;
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = t >> 6;
@@ -116,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 
   int g_ci, g_kx, g_ky;   // window position of this lane's K group, advanced by one K tile per issue
   {
-    const int k0 = lc * V;
+    const int k0 = kt_lo * BK + lc * V;
     const int tap = k0 / p.c_in;
     g_ci = k0 - tap * p.c_in;
     g_ky = tap / p.kw;
@@ -190,19 +208,21 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
   // ---- main loop ---------------------------------------------------------------------------------------
 #pragma unroll
   for (int s = 0; s < STAGES - 1; ++s)
-    if (s < p.k_tiles) issue_tile(s, s);
+    if (s < n_kt) issue_tile(kt_lo + s, s);
 
+  SC_DMA_STAMP(1);
   int stage = 0;   // kt % STAGES
-  for (int kt = 0; kt < p.k_tiles; ++kt) {
+  for (int kt = 0; kt < n_kt; ++kt) {
+    if (kt == 1) SC_DMA_STAMP(2);
     // tile kt has landed once at most the transfers of the STAGES-2 later tiles are in flight
-    if (kt + STAGES - 2 < p.k_tiles) wait_vmcnt<(STAGES - 2) * LPT>();
+    if (kt + STAGES - 2 < n_kt) wait_vmcnt<(STAGES - 2) * LPT>();
     else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();   // ... for every wavefront; and all have left tile kt-1
     asm volatile("" ::: "memory");
-    if (kt + STAGES - 1 < p.k_tiles) {
+    if (kt + STAGES - 1 < n_kt) {
       int fill = stage + STAGES - 1;
       if (fill >= STAGES) fill -= STAGES;
-      issue_tile(kt + STAGES - 1, fill);   // into the stage tile kt-1 occupied
+      issue_tile(kt_lo + kt + STAGES - 1, fill);   // into the stage tile kt-1 occupied
     }
     // four K steps per tile, each with its own fragment registers (no register is rewritten while
     // an MFMA that reads it may still be starting); the reads of step ks+1 are in flight during the
@@ -224,6 +244,63 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
     if (++stage == STAGES) stage = 0;
   }
 
+  SC_DMA_STAMP(3);
+  // ---- split K: leave the partial sums; the last workgroup of the tile adds them up ----------------------
+  if constexpr (SPLITK) {
+    if (splits > 1) {
+      // Partial sums travel through device-scope relaxed atomic stores and loads of 8 bytes: those
+      // write through to, and read from, the point where the XCDs' L2 caches agree, so no cache-wide
+      // write-back / invalidate fence is needed (a device-scope fence flushes a whole L2: tens of
+      // microseconds per launch here).  Order: stores acknowledged (vmcnt 0) -> workgroup barrier ->
+      // arrival counter; the last arrival reads after it has seen every other arrival.
+      constexpr int PER_WAVE = MI * NI * 8;     // 8-byte chunks per lane
+      typedef unsigned long long u64;
+      u64* part = reinterpret_cast<u64*>(p.partial) + ((int64_t)tile * splits * (kThreads / 64)) * PER_WAVE * 64;
+      u64* mine = part + ((int64_t)split * (kThreads / 64) + wave) * PER_WAVE * 64 + lane;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const u64 v = (u64)__float_as_uint(acc[mi][ni][2 * q]) | ((u64)__float_as_uint(acc[mi][ni][2 * q + 1]) << 32);
+            __hip_atomic_store(mine + ((mi * NI + ni) * 8 + q) * 64, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      SC_DMA_STAMP(4);
+      __syncthreads();
+      int32_t* s_flag = s_rows + BM;             // one word behind the row list
+      if (t == 0) {
+        const int old = __hip_atomic_fetch_add(p.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // everybody has arrived: leave the counter at zero for the next launch
+        if (old == splits - 1) __hip_atomic_store(p.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = old;
+      }
+      __syncthreads();
+      if (*s_flag != splits - 1) return;          // not the last one: done; the last one also writes the tile's zeros
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+      for (int sp = 0; sp < splits; ++sp) {      // fixed order: the sum does not depend on who came last
+        const u64* src = part + ((int64_t)sp * (kThreads / 64) + wave) * PER_WAVE * 64 + lane;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              const u64 v = __hip_atomic_load(src + ((mi * NI + ni) * 8 + q) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              acc[mi][ni][2 * q] += __uint_as_float((unsigned)v);
+              acc[mi][ni][2 * q + 1] += __uint_as_float((unsigned)(v >> 32));
+            }
+      }
+    }
+  }
+
+  SC_DMA_STAMP(5);
   // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) --------------------
   if (p.zero_fill) {
     const int lo = tile_m == 0 ? 0 : s_rows[0];
@@ -263,12 +340,13 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
       store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, 1, p.c_out, p.ho_wo, 0, 0, 0);
     }
   }
+  SC_DMA_STAMP(6);
 }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool SPLITK = false>
 hipError_t igemm_dma_launch(const ConvParams& p, hipStream_t stream) {
   constexpr size_t lds = igemm_dma_lds_bytes<BM, BN, STAGES>();
-  auto kern = igemm_dma_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES>;
+  auto kern = igemm_dma_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES, SPLITK>;
   static bool attr_set = false;
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -276,10 +354,14 @@ hipError_t igemm_dma_launch(const ConvParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int nwg = p.m_tiles * p.n_tiles;
+  const int nwg = p.m_tiles * p.n_tiles * (SPLITK ? p.splits : 1);
   const int grid = ((nwg + 7) / 8) * 8;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, p);
   return hipGetLastError();
 }
+
+// bytes of float partial sums one output tile and one split need
+template <int BM, int BN>
+constexpr size_t igemm_partial_bytes() { return (size_t)BM * BN * sizeof(float); }
 
 }  // namespace sc

@@ -275,6 +275,14 @@ hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
   KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
                 igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>,                          \
-                igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>, igemm_lds_bytes<BM, BN>() }
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>, nullptr, igemm_lds_bytes<BM, BN>() }
+
+// the same plus the split-K form of the direct-to-LDS kernel with a ring of SK_STAGES tiles
+#define SC_KERNEL_ENTRY_SPLITK(DT, BM, BN, WM_, WN_, DEPTH, STAGES, SK_STAGES)           \
+  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
+                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>,                          \
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>,                               \
+                igemm_dma_launch<DT, BM, BN, WM_, WN_, SK_STAGES, true>, igemm_lds_bytes<BM, BN>() }
 
 }  // namespace sc

@@ -213,6 +213,10 @@ __global__ void add_relu_kernel(const T* __restrict__ a, const T* __restrict__ b
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
 
+// float partial sums of a split-K launch at most (one BM x BN block per workgroup)
+constexpr size_t kSplitKPartialBytes = (size_t)16 << 20;
+constexpr int kSplitKMost = 64;   // splits per output tile at most
+
 struct Geometry {
   int32_t ho, wo;
   int64_t m;
@@ -221,7 +225,8 @@ struct Geometry {
   int64_t x_elems, y_elems, mask_len;
   int32_t nseg;
   // workspace carve (byte offsets)
-  size_t off_rows, off_counts, off_kept, off_zeros, off_mask, off_wp, off_ktab, off_band, off_band_rows, total;
+  size_t off_rows, off_counts, off_kept, off_zeros, off_mask, off_wp, off_ktab, off_band, off_band_rows, off_counters, off_partial, total;
+  bool splitk_ok;          // the layer may run the split-K kernel (workspace reserved for it)
 };
 
 static int out_extent(int in, int k, int stride, int pad, int dil) {
@@ -278,6 +283,15 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
   g->off_band = off;   off = align_up(off + ((size_t)d->n * g->ho + 1) * 4, 256);
   g->off_band_rows = off; off = align_up(off + (size_t)g->m * 4, 256);
+  // split-K (16-bit operands, direct-to-LDS gather, 128-channel tiles, deep K): arrival counters for
+  // every output tile (64 x 64 is the smallest split-K tile) and the float partial sums
+  g->splitk_ok = d->dtype != SC_F32 && g->vec_gather && g->vec_out && d->c_out >= 128 && g->k_tiles >= 16;
+  g->off_counters = g->off_partial = off;
+  if (g->splitk_ok) {
+    const size_t tiles = (size_t)((g->m + 63) / 64) * ((d->c_out + 63) / 64);
+    g->off_counters = off; off = align_up(off + tiles * 4, 256);
+    g->off_partial = off;  off = align_up(off + kSplitKPartialBytes, 256);
+  }
   g->total = off;
   return SC_OK;
 }
@@ -425,8 +439,10 @@ struct sc_plan {
   const KernelEntry* table;
   int table_count;
   int tile_sparse, tile_dense;     // chosen indices into table
+  int tile_splitk;                 // index of the 64 x 128 entry, the tile of automatic split-K launches (-1: none)
   int forced[2];                   // -1 = automatic, >= 0 generic tile index, kForceBand = band kernel
   int gather_pipeline;             // 0 = automatic, 1 = through registers, 2 = straight into LDS
+  int split_k;                     // 0 = automatic, 1 = never, n >= 2 = n splits wherever the kernel applies
 };
 constexpr int kForceBand = -2;
 
@@ -451,6 +467,42 @@ static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_ou
   for (int i = 0; i < count; ++i)
     if (tab[i].bm == bm && tab[i].bn == bn) return i;
   return 0;
+}
+
+// Split K?  Layers deep in a network have few rows and a long K: large output tiles cannot fill
+// 256 CUs, and with small tiles every workgroup walks the whole K, one L2 round trip after the other.
+// Dividing K among workgroups shortens that walk and still gives every CU work.
+struct TilePick { int ti, splits; };
+
+static int most_splits(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
+  const Geometry& g = pl->geo;
+  if (!g.splitk_ok || !ke.splitk || pl->split_k == 1 || pl->gather_pipeline == 1) return 1;
+  const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
+  const int64_t by_buffer = (int64_t)(kSplitKPartialBytes / ((size_t)ke.bm * ke.bn * sizeof(float))) / std::max<int64_t>(tiles, 1);
+  return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(by_buffer, g.k_tiles / 4), kSplitKMost));
+}
+
+static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
+  TilePick tp;
+  if (pl->forced[which] >= 0) {          // tuning: the forced tile, split as requested
+    tp.ti = pl->forced[which];
+    tp.splits = pl->split_k >= 2 ? std::min(pl->split_k, most_splits(pl, pl->table[tp.ti], rows)) : 1;
+    return tp;
+  }
+  tp.ti = which ? pl->tile_dense : pl->tile_sparse;
+  tp.splits = 1;
+  if (pl->tile_splitk >= 0) {
+    const KernelEntry& ke = pl->table[pl->tile_splitk];
+    const int most = most_splits(pl, ke, rows);
+    const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
+    // Measured on MI355X (ResNet18 / detector shapes): every tile shape moves its K tiles at about the
+    // same bytes per clock per CU, so splitting pays only where the 64 x 128 tiles leave half of the
+    // CUs idle and K is long enough to hide the partial-sum round trip: two splits there, none elsewhere.
+    int want = pl->split_k >= 2 ? pl->split_k : (tiles <= 128 && pl->geo.k_tiles >= 32 ? 2 : 1);
+    want = std::min(want, most);
+    if (want >= 2) { tp.ti = pl->tile_splitk; tp.splits = want; }
+  }
+  return tp;
 }
 
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
@@ -523,7 +575,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     SC_HIP(pl->band_table->fn[shape][b.ni_idx][mi_idx](q, b.lds, stream));
     return SC_OK;
   }
-  int ti = pl->forced[which] >= 0 ? pl->forced[which] : (dense ? pl->tile_dense : pl->tile_sparse);
+  const TilePick tp = pick_tile(pl, which, rows);
+  const int ti = tp.ti, splits = tp.splits;
   const KernelEntry& ke = pl->table[ti];
   ConvParams p;
   std::memset(&p, 0, sizeof(p));
@@ -553,12 +606,21 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.zero_fill = zero_fill ? 1 : 0;
   p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
   p.vec_out = g.vec_out ? 1 : 0;
+#ifdef SC_TIMING
+  p.dbg = g_dbg;
+#endif
   p.m_tiles = (int32_t)((rows + ke.bm - 1) / ke.bm);
   p.n_tiles = (d.c_out + ke.bn - 1) / ke.bn;
   // shallow K (pointwise layers): the workgroup lives for one or two K tiles, so residency, not
   // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
   LaunchFn fn = !g.vec_gather ? ke.elem
                 : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
+  if (splits > 1) {
+    p.splits = splits;
+    p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);
+    p.counters = reinterpret_cast<int32_t*>(pl->ws + g.off_counters);
+    fn = ke.splitk;
+  }
   SC_HIP(fn(p, stream));
   return SC_OK;
 }
@@ -611,6 +673,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   const int eb = elem_bytes(d.dtype);
 
   SC_HIP(hipMemsetAsync(ws + g.off_zeros, 0, 256, stream));
+  if (g.splitk_ok)   // arrival counters start at zero; every launch leaves them at zero again
+    SC_HIP(hipMemsetAsync(ws + g.off_counters, 0, g.off_partial - g.off_counters, stream));
   // a private copy of the mask (the zero fill of every run reads it)
   SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
 
@@ -698,6 +762,11 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather);
   pl->forced[0] = pl->forced[1] = -1;
   pl->gather_pipeline = 0;
+  pl->split_k = 0;
+  pl->tile_splitk = -1;
+  for (int i = 0; i < pl->table_count; ++i)
+    if (pl->table[i].splitk && pl->table[i].bm == 64 && pl->table[i].bn == 128) pl->tile_splitk = i;
+  if (pl->tile_splitk < 0) pl->geo.splitk_ok = false;
   pl->band = bp;
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
@@ -742,12 +811,13 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     if (workgroups) *workgroups = plan->band.pp ? plan->band.pp_grid : (int64_t)plan->band.n_bands * plan->band.n_tiles;
     return SC_OK;
   }
-  int ti = plan->forced[which] >= 0 ? plan->forced[which] : (which ? plan->tile_dense : plan->tile_sparse);
-  const KernelEntry& ke = plan->table[ti];
   int64_t rows = which ? plan->geo.m : plan->kept;
+  const TilePick tp = pick_tile(plan, which, rows);
+  const int splits = tp.splits;
+  const KernelEntry& ke = plan->table[tp.ti];
   if (tile_m) *tile_m = ke.bm;
   if (tile_n) *tile_n = ke.bn;
-  if (workgroups) *workgroups = ((rows + ke.bm - 1) / ke.bm) * ((plan->desc.c_out + ke.bn - 1) / ke.bn);
+  if (workgroups) *workgroups = ((rows + ke.bm - 1) / ke.bm) * ((plan->desc.c_out + ke.bn - 1) / ke.bn) * splits;
   return SC_OK;
 }
 
@@ -756,6 +826,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream)))
     return plan->band.stream ? "band_stream" : plan->band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
+  if (pick_tile(plan, which, which ? g.m : plan->kept).splits > 1) return "tile_split_k";
   if (!g.vec_gather) return "tile_elements";
   return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
 }
@@ -777,6 +848,7 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value) {
   if (!plan) return SC_ERR_NULL;
   if (option == SC_OPT_GATHER_PIPELINE && value >= 0 && value <= 2) { plan->gather_pipeline = value; return SC_OK; }
+  if (option == SC_OPT_SPLIT_K && value >= 0 && value <= kSplitKMost) { plan->split_k = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }
 

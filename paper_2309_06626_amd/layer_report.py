@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Per-layer report over the five benchmark configurations on one MI355X.
 
-    python -m paper_2309_06626_amd.layer_report [--configs 1,2,3,4,5] [--steps 200] [--json out.jsonl]
+    python -m paper_2309_06626_amd.layer_report [--configs 1,2,3,4,5] [--steps 200] [--json out.jsonl] [--library-conv]
 
 For every convolution: kernel chosen for the sparse and the dense run, time per launch, algorithmic
 TFLOP/s of the kept rows (2*kept*K*Cout / t) and its share of the MFMA peak, algorithmic GB/s and
@@ -9,8 +9,10 @@ its share of the HBM peak, and the speed-up over the dense run of the same kerne
 reported at s in {0, 0.25, 0.5, 0.7} in zero-fill mode and, for s > 0, in scatter-only mode.
 Configs 3 and 5 add the time of the whole chain (conv launches plus the pooling / residual glue),
 launched call by call and replayed as a HIP graph.
-Layers are timed one by one on synthetic inputs of their own shape (warm buffers, back-to-back
-launches on one stream).
+Layers are timed one by one on synthetic inputs of their own shape, back-to-back launches on one
+stream, in two cache regimes: warm (the same buffers every launch: working sets of tens of MB stay
+in the 256 MB memory-side cache, as they do between the layers of a network) and cold (the launches
+rotate through copies of the activations and outputs totalling 768 MB, so operands come from HBM).
 """
 from __future__ import annotations
 
@@ -32,14 +34,45 @@ def kernel_name(plan, which):
     return f"{B.sparse_conv_plan_kernel(plan, which)} {shape} ({wgs} wg)"
 
 
-def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
+def library_conv_us(spec, steps):
+    """Context only: torch.nn.functional.conv2d (MIOpen) on the same shape, channels-last, bias included,
+    no activation -- shows that the dense run the speed-ups are quoted against is not a weak baseline."""
+    import torch
+    import torch.nn.functional as F
+
+    from paper_2309_06626_amd import binding as B
+
+    dt = B.TORCH_DTYPE[spec.dtype]
+    x = torch.randn(spec.n, spec.c_in, spec.h, spec.w, device="cuda:0", dtype=dt).relu_().contiguous(
+        memory_format=torch.channels_last)
+    w = torch.randn(spec.c_out, spec.c_in, spec.kh, spec.kw, device="cuda:0", dtype=dt).contiguous(
+        memory_format=torch.channels_last)
+    b = torch.randn(spec.c_out, device="cuda:0", dtype=dt)
+
+    def run():
+        return F.conv2d(x, w, b, stride=(spec.stride_h, spec.stride_w), padding=(spec.pad_h, spec.pad_w),
+                        dilation=(spec.dil_h, spec.dil_w))
+
+    for _ in range(max(steps // 10, 5)):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / steps
+
+
+def measure_layer(spec, base_seed, steps, out_mode, x_host=None, library=False):
     import torch
 
     import workloads as W
     from paper_2309_06626_amd import binding as B
     from paper_2309_06626_amd import runtime as R
     from paper_2309_06626_amd.metrics import (HBM_PEAK_GBS, MFMA_PEAK_TFLOPS, algorithmic_bytes, algorithmic_flops,
-                                              time_launches)
+                                              buffer_sets_for_cold_runs, time_launches, time_rotating)
 
     ci = W.make_conv_inputs(spec, base_seed, x=x_host)
     layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, out_mode=out_mode)
@@ -49,6 +82,14 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
     warm = max(steps // 10, 5)
     _, ts = time_launches(B.prepared_run(layer.plan, x, layer.bias, y), steps, warm)
     _, td = time_launches(B.prepared_run(layer.plan, x, layer.bias, y, dense=True), steps, warm)
+    # cold regime: rotate through copies of the activations and outputs that together exceed the caches
+    nsets = buffer_sets_for_cold_runs(x.numel() * x.element_size() + y.numel() * y.element_size())
+    xs = [x] + [x.clone() for _ in range(nsets - 1)]
+    ys = [y] + [torch.zeros_like(y) for _ in range(nsets - 1)]
+    cold_steps = max(steps // 4, 2 * nsets)
+    tsc = time_rotating([B.prepared_run(layer.plan, a, layer.bias, b) for a, b in zip(xs, ys)], cold_steps, nsets)
+    tdc = time_rotating([B.prepared_run(layer.plan, a, layer.bias, b, dense=True) for a, b in zip(xs, ys)], cold_steps, nsets)
+    del xs, ys
     scatter = out_mode == B.SC_OUT_SCATTER_ONLY
     fl = algorithmic_flops(spec, ci.keep)
     by = algorithmic_bytes(spec, ci.keep, scatter_only=scatter)
@@ -58,12 +99,16 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None):
         "kernel_sparse": kernel_name(layer.plan, 0),
         "kernel_dense": kernel_name(layer.plan, 1),
         "sparse_us": ts * 1e6, "dense_us": td * 1e6, "speedup_vs_dense": td / ts,
+        "sparse_us_cold": tsc * 1e6, "dense_us_cold": tdc * 1e6, "speedup_vs_dense_cold": tdc / tsc,
+        "gbs_cold": by / tsc / 1e9, "hbm_frac_cold": by / tsc / 1e9 / HBM_PEAK_GBS, "cold_buffer_sets": nsets,
         "tflops": fl / ts / 1e12, "mfma_frac": fl / ts / 1e12 / MFMA_PEAK_TFLOPS[spec.dtype],
         "dense_tflops": algorithmic_flops(spec, spec.m) / td / 1e12,
         "gbs": by / ts / 1e9, "hbm_frac": by / ts / 1e9 / HBM_PEAK_GBS,
         "arithmetic_intensity": fl / by,
     }
     del layer, x, y
+    torch.cuda.empty_cache()
+    rec["library_dense_us"] = library_conv_us(spec, max(steps // 4, 20)) if library else None
     torch.cuda.empty_cache()
     return rec
 
@@ -109,6 +154,8 @@ def main():
     ap.add_argument("--configs", default="1,2,3,4,5")
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--json", default="")
+    ap.add_argument("--library-conv", action="store_true",
+                    help="also time torch.nn.functional.conv2d (MIOpen, dense) on every shape, as context")
     args = ap.parse_args()
 
     import torch
@@ -131,33 +178,36 @@ def main():
         print(f"| {cfg} | {rec['layer']} | {rec['m']}x{rec['k']}x{rec['c_out']} | {rec['sparsity']:.2f} {rec['out_mode'][:7]} | "
               f"{rec['kernel_sparse']} | {rec['sparse_us']:.2f} | {rec['dense_us']:.2f} | {rec['speedup_vs_dense']:.2f} | "
               f"{rec['tflops']:.1f} | {100 * rec['mfma_frac']:.1f} | {rec['gbs']:.0f} | {100 * rec['hbm_frac']:.1f} | "
-              f"{rec['arithmetic_intensity']:.0f} |", flush=True)
+              f"{rec['arithmetic_intensity']:.0f} | {rec['sparse_us_cold']:.2f} | {rec['dense_us_cold']:.2f} | "
+              f"{rec['speedup_vs_dense_cold']:.2f} | {100 * rec['hbm_frac_cold']:.1f} | "
+              + (f"{rec['library_dense_us']:.1f} |" if rec["library_dense_us"] is not None else "- |"), flush=True)
 
-    print("| cfg | layer | M x K x Cout | s, out mode | sparse kernel | sparse us | dense us | speed-up | TFLOP/s | % MFMA | GB/s | % HBM | FLOP/B |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print("| cfg | layer | M x K x Cout | s, out mode | sparse kernel | sparse us | dense us | speed-up | TFLOP/s | % MFMA | GB/s | % HBM | FLOP/B "
+          "| cold: sparse us | cold: dense us | cold: speed-up | cold: % HBM | torch conv2d us (context) |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
     if 1 in want:
-        emit(1, measure_layer(W.config1(), W.base_seed(1), args.steps, B.SC_OUT_ZERO_FILL))
+        emit(1, measure_layer(W.config1(), W.base_seed(1), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
     if 2 in want:
         for s in W.C2_SPARSITIES:
-            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_ZERO_FILL))
+            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
         for s in W.C2_SPARSITIES[1:]:
-            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_SCATTER_ONLY))
+            emit(2, measure_layer(W.config2(s), W.base_seed(2), args.steps, B.SC_OUT_SCATTER_ONLY, library=args.library_conv))
     chains = {}
     if 3 in want:
         ops = W.config3()
         for spec in W.conv_specs(ops):
-            emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL))
+            emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
         cs = max(args.steps // 10, 5)
         chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), cs)
         chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3), cs)
         chains["config 3, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(3), cs, dense=True)
     if 4 in want:
         for spec in W.config4():
-            emit(4, measure_layer(spec, W.base_seed(4), args.steps, B.SC_OUT_ZERO_FILL))
+            emit(4, measure_layer(spec, W.base_seed(4), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
     if 5 in want:
         ops = W.config5()
         for spec in W.conv_specs(ops):
-            emit(5, measure_layer(spec, W.base_seed(5), args.steps, B.SC_OUT_ZERO_FILL))
+            emit(5, measure_layer(spec, W.base_seed(5), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
         cs = max(args.steps // 10, 5)
         chains["config 5 (detector stack, batch 16, s=0.3)"] = chain_time(ops, W.base_seed(5), cs)
         chains["config 5, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(5), cs, dense=True)

@@ -55,3 +55,27 @@ def time_launches(fn, steps: int, warmup: int):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return wall / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def time_rotating(fns, steps: int, warmup: int):
+    """Event seconds per launch when the launches cycle through `fns` -- the same operation on different
+    buffer sets whose total size exceeds the caches, so every launch finds its operands in HBM only."""
+    import torch
+
+    n = len(fns)
+    for i in range(warmup):
+        fns[i % n]()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fns[i % n]()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / steps
+
+
+def buffer_sets_for_cold_runs(bytes_per_set: int, total_bytes: int = 768 << 20, most: int = 64) -> int:
+    """Number of (input, output) buffer sets to rotate through so that the sets total more than the
+    256 MB memory-side cache plus the L2s by a wide margin."""
+    return max(2, min(most, -(-total_bytes // max(bytes_per_set, 1))))

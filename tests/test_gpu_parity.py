@@ -153,6 +153,66 @@ def test_alternating_band_kernel_is_the_automatic_choice_for_long_band_lists():
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 
 
+SPLITK_CASES = [
+    dict(n=2, cin=128, h=14, w=14, cout=128),                         # 18 K tiles, 2 x 1 output tiles
+    dict(n=1, cin=128, h=20, w=17, cout=256, sp=0.3),                 # two channel tiles, ragged row tile
+    dict(n=2, cin=256, h=9, w=9, cout=160, sp=0.6),                   # ragged channel tile, 36 K tiles
+    dict(n=1, cin=512, h=7, w=7, cout=512, sp=0.5),                   # the deepest ResNet18 shape: 72 K tiles
+    dict(n=2, cin=128, h=15, w=15, cout=128, k=3, s=2, p=1, sp=0.4),  # stride 2
+    dict(n=4, cin=1024, h=8, w=8, cout=128, k=1, p=0, sp=0.5),        # pointwise with a long K
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("splits", [2, 3, 7])
+@pytest.mark.parametrize("case", range(len(SPLITK_CASES)))
+def test_split_k_kernel(case, splits, dtype):
+    spec = spec_of(dtype=dtype, **SPLITK_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 980 + case), split_k=splits)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
+    tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+    tiles = -(-layer.info["kept"] // 64) * -(-spec.c_out // 128)
+    assert (tm, tn) == (64, 128) and wgs % tiles == 0 and 2 <= wgs // tiles <= splits
+
+
+@pytest.mark.parametrize("tile", [(128, 128), (64, 128), (128, 64), (64, 64)])
+def test_split_k_every_tile_shape(tile):
+    spec = spec_of(2, 256, 12, 12, 160, dtype="bf16", sp=0.4)        # 36 K tiles, ragged rows and channels
+    layer = check_layer(W.make_conv_inputs(spec, 989), tiles=tile, split_k=5)
+    tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+    assert (tm, tn) == tile and wgs == 5 * -(-layer.info["kept"] // tile[0]) * -(-spec.c_out // tile[1])
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
+
+
+def test_split_k_is_automatic_for_short_deep_layers_and_can_be_switched_off():
+    spec = spec_of(64, 512, 7, 7, 512, dtype="bf16", sp=0.5)        # the deepest ResNet18 layers at batch 64
+    ci = W.make_conv_inputs(spec, 990)
+    layer = check_layer(ci, sample_rows=128)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
+    assert B.sparse_conv_plan_kernel(layer.plan, 1) == "tile_lds_direct"    # its dense run has enough tiles
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, 1)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    many = spec_of(64, 128, 28, 28, 128, dtype="bf16", sp=0.0)
+    layer = R.ConvLayer(many, *_wbm(many, 3))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+
+
+def test_split_k_repeated_launches_leave_the_counters_clean():
+    # the arrival counters are reset by the workgroup that finishes a tile: many launches in a row,
+    # sparse and dense interleaved, must all give the first launch's bits
+    spec = spec_of(2, 256, 10, 10, 256, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 991)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, 3)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
+    x = R.to_device(ci.x, spec.dtype)
+    first_s = R.bits_of(layer.sparse(x)).copy()
+    first_d = R.bits_of(layer.dense(x)).copy()
+    for _ in range(20):
+        assert np.array_equal(R.bits_of(layer.sparse(x)), first_s)
+        assert np.array_equal(R.bits_of(layer.dense(x)), first_d)
+
+
 STREAM_CASES = [
     dict(n=2, cin=64, h=14, w=14, cout=128),                         # 128 channels: one channel tile
     dict(n=1, cin=128, h=12, w=10, cout=256, sp=0.3),                # two channel tiles, two K tiles per tap
