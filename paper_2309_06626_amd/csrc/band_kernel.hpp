@@ -178,10 +178,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                      (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
   };
-#ifndef SC_EXPERIMENT_SKIP_FILTERS
   for (int qb = wave * 64; qb < nb; qb += kThreads) dma16(gb + swz(qb + lane), s_b + qb);
-#endif
-#ifndef SC_EXPERIMENT_SKIP_INPUT
   {
     const int q_end = qx0 + nx;
     for (int qb = (qx0 & ~63) + wave * 64; qb < q_end; qb += kThreads) {
@@ -189,7 +186,6 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
       if (g >= 0 && g < nx) dma16(gx + g, s_x + qb);
     }
   }
-#endif
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   if (t < 64) {
     const v4i z = {0, 0, 0, 0};
@@ -198,7 +194,9 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   if (t < BN) s_bias[t] = bias_v;
 
   SC_STAMP(1);
-  SC_STAMP(2);
+#ifdef SC_TIMING
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + 2] = wall0;
+#endif
   __syncthreads();   // slabs staged
   SC_STAMP(3);
   // the zero stores are issued now and drain while the matrix cores work; nothing waits for them
@@ -360,7 +358,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   }
   SC_STAMP(4);
 #ifdef SC_TIMING
-  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + 7] = wall_clock64() - wall0;
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + 7] = wall_clock64();
 #endif
 }
 

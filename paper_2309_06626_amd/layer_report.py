@@ -42,6 +42,7 @@ def library_conv_us(spec, steps):
 
     from paper_2309_06626_amd import binding as B
 
+    torch.backends.cudnn.benchmark = True    # let the library search its algorithms: the fairest context figure
     dt = B.TORCH_DTYPE[spec.dtype]
     x = torch.randn(spec.n, spec.c_in, spec.h, spec.w, device="cuda:0", dtype=dt).relu_().contiguous(
         memory_format=torch.channels_last)
