@@ -39,6 +39,8 @@ struct ConvParams {
   int32_t mask_spatial;    // mask has ho_wo entries shared by the batch
   int32_t vec_out;         // y rows are channel-contiguous and 16-byte groups are aligned
   int32_t m_tiles, n_tiles;
+  // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
+  uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
   // split-K launches only: the K tiles of an output tile are divided among `splits` workgroups
   int32_t splits;
   float* partial;          // [m_tiles * n_tiles][splits][BM * BN] float partial sums
@@ -47,6 +49,10 @@ struct ConvParams {
   long long* dbg;          // development builds only: per-workgroup phase time stamps
 #endif
 };
+
+__device__ __forceinline__ int fast_div(int n, uint32_t mul, uint32_t shift) {
+  return (int)(uint32_t)(((uint64_t)(uint32_t)n * mul) >> shift);
+}
 
 enum Dtype { kF32 = 0, kF16 = 1, kBF16 = 2 };
 

@@ -59,7 +59,9 @@ template <int N, int CNT> __device__ __forceinline__ void wait_frags(v4i (&f)[CN
 #endif
 
 template <int BM, int BN, int STAGES>
-constexpr size_t igemm_dma_lds_bytes() { return (size_t)STAGES * (BM + BN) * kRowBytes + (BM + 4) * sizeof(int32_t); }
+constexpr size_t igemm_dma_lds_bytes() {
+  return (size_t)STAGES * (BM + BN) * kRowBytes + (BM + 4) * sizeof(int32_t) + BN * sizeof(float);
+}
 
 // SPLITK: grid = output tiles x p.splits; workgroup (tile, split) contracts its share of the K tiles
 // and leaves float partial sums in p.partial; the workgroup that arrives last at the tile's counter
@@ -81,7 +83,8 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
   static_assert(STAGES >= 2 && (STAGES - 2) * LPT <= 63, "vmcnt is a 6-bit counter");
 
   extern __shared__ __align__(16) unsigned char smem[];
-  int32_t* s_rows = reinterpret_cast<int32_t*>(smem + STAGES * STAGE_BYTES);   // [BM]
+  int32_t* s_rows = reinterpret_cast<int32_t*>(smem + STAGES * STAGE_BYTES);   // [BM], then one flag word
+  float* s_bias = reinterpret_cast<float*>(s_rows + BM + 4);                   // [BN]
   SC_DMA_STAMP(0);
 
   const int splits = SPLITK ? p.splits : 1;
@@ -118,14 +121,25 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
     const int icc = min(m0 + lrow + 32 * j, p.rows - 1);     // clamped: the loads stay unconditional
     a_row[j] = p.row_idx ? p.row_idx[icc] : icc;
   }
+  // Everything the end of the kernel needs from global memory is requested here, in the same round
+  // trip, so that the epilogue and the zero fill start without one of their own: the bias slice and
+  // the first and last dense row this workgroup owns (Alg. 2, mask == 0 branch: it writes the zeros
+  // of the dense rows from its first kept row up to the next tile's first kept row).
+  float bias_v = 0.0f;
+  if (t < BN && p.bias && n0 + t < p.c_out) bias_v = p.bias[n0 + t];
+  int z_lo = 0, z_hi = p.m_total;
+  if (p.zero_fill) {
+    if (tile_m != 0) z_lo = p.row_idx[m0];
+    if (m0 + BM < p.rows) z_hi = p.row_idx[m0 + BM];
+  }
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const bool present = m0 + lrow + 32 * j < p.rows;
     const int rr = present ? a_row[j] : -1;
     s_rows[lrow + 32 * j] = rr;
     const int rc = present ? rr : 0;
-    const int n = rc / p.ho_wo, rem = rc - n * p.ho_wo;
-    const int oy = rem / p.wo, ox = rem - oy * p.wo;
+    const int n = fast_div(rc, p.div_howo_mul, p.div_howo_shift), rem = rc - n * p.ho_wo;
+    const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
     a_iy0[j] = present ? oy * p.sh - p.ph : -(1 << 30);      // no tap of an absent row is in range
     a_ix0[j] = ox * p.sw - p.pw;
     a_base[j] = (int32_t)(n * p.xs_n + (int64_t)(oy * p.sh - p.ph) * p.xs_h + (int64_t)a_ix0[j] * p.xs_w);
@@ -139,6 +153,19 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
     g_ci = k0 - tap * p.c_in;
     g_ky = tap / p.kw;
     g_kx = tap - g_ky * p.kw;
+  }
+  // mask bytes of the first zero-fill passes: requested before any K tile (they are older than the
+  // transfers, so no wait in the K loop is delayed by them) and first looked at after the K loop
+  constexpr int CPR = BN * EB / 16;        // 16-byte groups per output row slice
+  constexpr int RPI = kThreads / CPR;      // dense rows per fill pass of the workgroup
+  constexpr int ZB = 4;                    // passes whose mask bytes are fetched up front
+  const int zc = t % CPR, zr = t / CPR;
+  unsigned mk[ZB];
+#pragma unroll
+  for (int u = 0; u < ZB; ++u) {           // unconditional, clamped: dense runs read a few bytes they ignore
+    int r = min(z_lo + zr + u * RPI, p.m_total - 1);
+    if (p.mask_spatial) r -= fast_div(r, p.div_howo_mul, p.div_howo_shift) * p.ho_wo;
+    mk[u] = p.mask[r];
   }
   __syncthreads();   // s_rows written (read again in the epilogue); nothing is in flight yet
 
@@ -302,27 +329,31 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 
   SC_DMA_STAMP(5);
   // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) --------------------
+  if (t < BN) s_bias[t] = bias_v;
+  // LDS-only barrier (the bias slice): no global-memory wait, the zero stores below just drain
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
   if (p.zero_fill) {
-    const int lo = tile_m == 0 ? 0 : s_rows[0];
-    const int hi = (m0 + BM >= p.rows) ? p.m_total : p.row_idx[m0 + BM];
-    constexpr int CPR = BN * EB / 16;
-    constexpr int RPI = kThreads / CPR;
     const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
-    const int zc = t % CPR, zr = t / CPR;
     if (zc < valid) {
       unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
       const v4i z = {0, 0, 0, 0};
-      for (int r0 = lo + zr; r0 < hi; r0 += 4 * RPI) {
-        unsigned char mk[4];
+#pragma unroll
+      for (int u = 0; u < ZB; ++u) {
+        const int r = z_lo + zr + u * RPI;
+        if (r < z_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+      }
+      for (int r0 = z_lo + zr + ZB * RPI; r0 < z_hi; r0 += 4 * RPI) {   // tiles that own more rows
+        unsigned char m4[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          const int r = min(r0 + u * RPI, hi - 1);
-          mk[u] = p.mask[p.mask_spatial ? r % p.ho_wo : r];
+          int r = min(r0 + u * RPI, z_hi - 1);
+          if (p.mask_spatial) r -= fast_div(r, p.div_howo_mul, p.div_howo_shift) * p.ho_wo;
+          m4[u] = p.mask[r];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = r0 + u * RPI;
-          if (r < hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+          if (r < z_hi && m4[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
         }
       }
     }
@@ -337,7 +368,8 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
-      store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, 1, p.c_out, p.ho_wo, 0, 0, 0);
+      store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1, p.c_out,
+                           p.ho_wo, 0, 0, 0);
     }
   }
   SC_DMA_STAMP(6);

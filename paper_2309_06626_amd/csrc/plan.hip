@@ -505,6 +505,15 @@ static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
   return tp;
 }
 
+// Division of 0 <= n < 2^31 by d >= 1 as (n * mul) >> shift in 64-bit arithmetic: with l = ceil(log2 d)
+// and shift = 31 + l, mul = floor(2^shift / d) + 1 fits 32 bits and the quotient is exact.
+static void magic_div(uint32_t d, uint32_t* mul, uint32_t* shift) {
+  uint32_t l = 0;
+  while (((uint64_t)1 << l) < d) ++l;
+  *shift = 31 + l;
+  *mul = (uint32_t)((((uint64_t)1 << *shift) / d) + 1);
+}
+
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
                              hipStream_t stream) {
   const sc_conv_desc& d = pl->desc;
@@ -591,6 +600,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.rows = (int32_t)rows;
   p.m_total = (int32_t)g.m;
   p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
+  magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+  magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
   p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
   p.c_in = d.c_in; p.kh = d.kh; p.kw = d.kw; p.dil_h = d.dil_h; p.dil_w = d.dil_w;
   p.c_out = d.c_out;
