@@ -132,8 +132,8 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_stream", "tile_split_k", "tile_lds_direct", "tile_registers" or
- * "tile_elements".
+ * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_lds_direct",
+ * "tile_registers" or "tile_elements".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
 
@@ -157,7 +157,10 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
  * tile wherever the split-K kernel applies (16-bit NHWC layers with >= 128 output channels and a
  * deep K); n is at most 64 and is clamped so that the partial sums fit their 16 MiB buffer and every
  * split has at least four K tiles.  Partial sums are added in a fixed order: results do not depend on scheduling. */
-enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1 };
+/* SC_OPT_ROW_PANEL: 0 = automatic, 1 = never, 2 = always where it applies.  The row-panel kernel
+ * (16-bit NHWC layers with K <= 2 K tiles, i.e. pointwise layers with up to 128 input channels, and
+ * at most 1024 output channels) gathers 128 kept rows once and walks all channel tiles with them. */
+enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2 };
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
 
 void sparse_conv_plan_destroy(sc_plan* plan);

@@ -252,6 +252,7 @@ def sparse_conv_plan_set_tiles(plan: Plan, which: int, tile_m: int, tile_n: int)
 
 SC_OPT_GATHER_PIPELINE = 0
 SC_OPT_SPLIT_K = 1
+SC_OPT_ROW_PANEL = 2
 
 
 def sparse_conv_plan_set_option(plan: Plan, option: int, value: int):

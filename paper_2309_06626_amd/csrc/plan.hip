@@ -14,6 +14,7 @@
 #include "bandpp_kernel.hpp"
 #include "bandstream_kernel.hpp"
 #include "conv_params.hpp"
+#include "igemm_panel_kernel.hpp"
 
 namespace sc {
 
@@ -439,10 +440,12 @@ struct sc_plan {
   const KernelEntry* table;
   int table_count;
   int tile_sparse, tile_dense;     // chosen indices into table
+  LaunchFn panel;                  // row-panel kernel of the plan's dtype (null: none)
   int tile_splitk;                 // index of the 64 x 128 entry, the tile of automatic split-K launches (-1: none)
   int forced[2];                   // -1 = automatic, >= 0 generic tile index, kForceBand = band kernel
   int gather_pipeline;             // 0 = automatic, 1 = through registers, 2 = straight into LDS
   int split_k;                     // 0 = automatic, 1 = never, n >= 2 = n splits wherever the kernel applies
+  int row_panel;                   // 0 = automatic, 1 = never, 2 = wherever the kernel applies
 };
 constexpr int kForceBand = -2;
 
@@ -473,6 +476,17 @@ static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_ou
 // 256 CUs, and with small tiles every workgroup walks the whole K, one L2 round trip after the other.
 // Dividing K among workgroups shortens that walk and still gives every CU work.
 struct TilePick { int ti, splits; };
+
+// Row-panel kernel: short K (pointwise layers), several 64-channel tiles, enough rows to fill the
+// CUs with 128-row panels.  There the tiled kernels are bound by the instructions every
+// (row tile, channel tile) workgroup repeats; the panel kernel pays them once per row tile.
+static bool use_panel(const sc_plan* pl, int which, int64_t rows) {
+  const Geometry& g = pl->geo;
+  const sc_conv_desc& d = pl->desc;
+  const bool applies = pl->panel && pl->forced[which] < 0 && pl->gather_pipeline != 1 && pl->row_panel != 1 &&
+                       g.vec_gather && g.vec_out && g.k_tiles <= kPanelMaxKTiles && d.c_out <= 1024;
+  return applies && (pl->row_panel == 2 || (d.c_out >= 128 && rows >= 128 * 256));
+}
 
 static int most_splits(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
   const Geometry& g = pl->geo;
@@ -587,6 +601,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const TilePick tp = pick_tile(pl, which, rows);
   const int ti = tp.ti, splits = tp.splits;
   const KernelEntry& ke = pl->table[ti];
+  const bool panel = use_panel(pl, which, rows);
   ConvParams p;
   std::memset(&p, 0, sizeof(p));
   p.x = x;
@@ -631,6 +646,11 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);
     p.counters = reinterpret_cast<int32_t*>(pl->ws + g.off_counters);
     fn = ke.splitk;
+  }
+  if (panel) {
+    p.m_tiles = (int32_t)((rows + kPanelBM - 1) / kPanelBM);
+    p.n_tiles = (d.c_out + kPanelBN - 1) / kPanelBN;
+    fn = pl->panel;
   }
   SC_HIP(fn(p, stream));
   return SC_OK;
@@ -774,6 +794,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->forced[0] = pl->forced[1] = -1;
   pl->gather_pipeline = 0;
   pl->split_k = 0;
+  pl->row_panel = 0;
   pl->tile_splitk = -1;
   for (int i = 0; i < pl->table_count; ++i)
     if (pl->table[i].splitk && pl->table[i].bm == 64 && pl->table[i].bn == 128) pl->tile_splitk = i;
@@ -782,6 +803,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
   pl->pp_table = d.dtype == SC_BF16 ? bandpp_bf16() : d.dtype == SC_F16 ? bandpp_f16() : nullptr;
+  pl->panel = d.dtype == SC_BF16 ? panel_bf16() : d.dtype == SC_F16 ? panel_f16() : nullptr;
   (void)eb;
   *out = pl;
   return SC_OK;
@@ -823,6 +845,12 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     return SC_OK;
   }
   int64_t rows = which ? plan->geo.m : plan->kept;
+  if (use_panel(plan, which, rows)) {
+    if (tile_m) *tile_m = kPanelBM;
+    if (tile_n) *tile_n = kPanelBN;
+    if (workgroups) *workgroups = (rows + kPanelBM - 1) / kPanelBM;
+    return SC_OK;
+  }
   const TilePick tp = pick_tile(plan, which, rows);
   const int splits = tp.splits;
   const KernelEntry& ke = plan->table[tp.ti];
@@ -837,6 +865,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream)))
     return plan->band.stream ? "band_stream" : plan->band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
+  if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
   if (pick_tile(plan, which, which ? g.m : plan->kept).splits > 1) return "tile_split_k";
   if (!g.vec_gather) return "tile_elements";
   return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
@@ -859,6 +888,7 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value) {
   if (!plan) return SC_ERR_NULL;
   if (option == SC_OPT_GATHER_PIPELINE && value >= 0 && value <= 2) { plan->gather_pipeline = value; return SC_OK; }
+  if (option == SC_OPT_ROW_PANEL && value >= 0 && value <= 2) { plan->row_panel = value; return SC_OK; }
   if (option == SC_OPT_SPLIT_K && value >= 0 && value <= kSplitKMost) { plan->split_k = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }

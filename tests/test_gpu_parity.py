@@ -213,6 +213,41 @@ def test_split_k_repeated_launches_leave_the_counters_clean():
         assert np.array_equal(R.bits_of(layer.dense(x)), first_d)
 
 
+PANEL_CASES = [
+    dict(n=2, cin=96, h=15, w=15, cout=576, k=1, p=0),                   # two K tiles, nine channel tiles, ragged row tile
+    dict(n=3, cin=32, h=14, w=13, cout=192, k=1, p=0, sp=0.3),           # one K tile (half used), three channel tiles
+    dict(n=2, cin=128, h=12, w=12, cout=160, k=1, p=0, sp=0.6),          # ragged last channel tile
+    dict(n=4, cin=64, h=17, w=17, cout=128, k=1, p=0, s=2, sp=0.5),      # strided pointwise (downsample)
+    dict(n=1, cin=16, h=40, w=24, cout=48, k=1, p=0, sp=0.9),            # few kept rows, long zero-fill ranges
+    dict(n=2, cin=8, h=11, w=11, cout=64, k=3, p=1, sp=0.5),             # a 3x3 window with K = 72
+    dict(n=2, cin=64, h=10, w=10, cout=1024, k=1, p=0, sp=0.0),          # widest bias slice, every row kept
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("case", range(len(PANEL_CASES)))
+def test_row_panel_kernel(case, mask_mode, dtype):
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **PANEL_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 960 + case), row_panel=2)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_panel"
+    assert B.sparse_conv_plan_kernel(layer.plan, 1) == "tile_row_panel"
+    assert B.sparse_conv_plan_tiles(layer.plan, 0) == (128, 64, -(-layer.info["kept"] // 128))
+
+
+def test_row_panel_kernel_scatter_only_and_switch():
+    spec = spec_of(2, 96, 16, 16, 192, k=1, p=0, dtype="bf16", sp=0.5)
+    layer = check_layer(W.make_conv_inputs(spec, 969), out_mode=B.SC_OUT_SCATTER_ONLY, row_panel=2)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_panel"
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_ROW_PANEL, 0)      # too few rows for the automatic choice
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    big = spec_of(64, 96, 56, 56, 576, k=1, p=0, dtype="bf16", sp=0.5)
+    layer = R.ConvLayer(big, *_wbm(big, 3))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_panel"
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_ROW_PANEL, 1)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+
+
 STREAM_CASES = [
     dict(n=2, cin=64, h=14, w=14, cout=128),                         # 128 channels: one channel tile
     dict(n=1, cin=128, h=12, w=10, cout=256, sp=0.3),                # two channel tiles, two K tiles per tap
