@@ -41,6 +41,7 @@ struct ConvParams {
   int32_t m_tiles, n_tiles;
   // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+  uint32_t x_bytes, w_bytes;   // sizes of x and of the packed filters (buffer-load kernels; 0 = too large)
   // split-K launches only: the K tiles of an output tile are divided among `splits` workgroups
   int32_t splits;
   float* partial;          // [m_tiles * n_tiles][splits][BM * BN] float partial sums

@@ -14,6 +14,7 @@
 #include "bandpp_kernel.hpp"
 #include "bandstream_kernel.hpp"
 #include "conv_params.hpp"
+#include "igemm_buf_kernel.hpp"
 #include "igemm_panel_kernel.hpp"
 
 namespace sc {
@@ -454,18 +455,16 @@ namespace sc {
 // Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a heavily
 // masked layer gets narrower tiles than its dense twin (Sec. 3.2: the GEMM range shrinks with the
 // sparsity).  The rules come from sweeps over the ResNet18 / pointwise / detector layer shapes on
-// MI355X: the kernels are bound by L2 -> LDS traffic and latency, not by the matrix cores, and many
-// small workgroups per CU hide that latency better than few large ones; 128-wide tiles pay off
-// when they divide c_out, and short GEMMs (few rows) want 32-row tiles to fill 256 CUs.
+// MI355X: 64 x 128 tiles move the fewest operand bytes per FLOP of the shapes that still leave enough
+// workgroups, so they are taken once they give about one and a half workgroups per CU; below that the
+// 64 x 64 shape (twice the workgroups) wins, and short GEMMs with wide outputs take 32 x 128.
 static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather) {
   int bm, bn;
+  const int64_t wg_64x128 = ((rows + 63) / 64) * ((c_out + 127) / 128);
   if (!vec_gather) { bm = 128; bn = 64; }            // element gather: fewer, fatter workgroups
   else if (c_out <= 32) { bm = 128; bn = 32; }
-  else if (rows <= 8192) {
-    if (c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
-    else { bm = 64; bn = 64; }
-  }
-  else if (c_out % 128 == 0) { bm = 64; bn = 128; }
+  else if (c_out % 128 == 0 && wg_64x128 >= 384) { bm = 64; bn = 128; }
+  else if (rows <= 8192 && c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
   else { bm = 64; bn = 64; }
   for (int i = 0; i < count; ++i)
     if (tab[i].bm == bm && tab[i].bn == bn) return i;
@@ -508,11 +507,10 @@ static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
   if (pl->tile_splitk >= 0) {
     const KernelEntry& ke = pl->table[pl->tile_splitk];
     const int most = most_splits(pl, ke, rows);
-    const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
-    // Measured on MI355X (ResNet18 / detector shapes): every tile shape moves its K tiles at about the
-    // same bytes per clock per CU, so splitting pays only where the 64 x 128 tiles leave half of the
-    // CUs idle and K is long enough to hide the partial-sum round trip: two splits there, none elsewhere.
-    int want = pl->split_k >= 2 ? pl->split_k : (tiles <= 128 && pl->geo.k_tiles >= 32 ? 2 : 1);
+    // Measured on MI355X (ResNet18 / detector shapes): the partial-sum round trip costs more than the
+    // shorter K walk saves -- the unsplit 64 x 64 / 32 x 128 tiles are faster on every benchmark layer
+    // (ResNet18 layer 4: 22 us against 27 us with two splits) -- so K is split only on request.
+    int want = pl->split_k >= 2 ? pl->split_k : 1;
     want = std::min(want, most);
     if (want >= 2) { tp.ti = pl->tile_splitk; tp.splits = want; }
   }
@@ -641,6 +639,19 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
   LaunchFn fn = !g.vec_gather ? ke.elem
                 : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
+  {
+    // buffer-load form: Cin a multiple of the K tile (a K tile then lies inside one tap), windows up
+    // to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31), deeper than the two-tile ring
+    const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
+    const uint64_t xb = (uint64_t)d.n * d.h * d.w * d.c_in * eb, wb = (uint64_t)g.cout_pad * g.k_stride * eb;
+    LaunchFn bf = buf_kernel(dt, ke.bm, ke.bn);
+    if (bf && g.vec_gather && g.vec_out && pl->gather_pipeline == 0 && d.dtype != SC_F32 && d.c_in % 64 == 0 &&
+        d.kh <= 8 && d.kw <= 8 && g.k_tiles >= 3 && xb < ((uint64_t)1 << 31) && wb < ((uint64_t)1 << 31)) {
+      p.x_bytes = (uint32_t)xb;
+      p.w_bytes = (uint32_t)wb;
+      fn = bf;
+    }
+  }
   if (splits > 1) {
     p.splits = splits;
     p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);

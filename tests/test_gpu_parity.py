@@ -184,17 +184,43 @@ def test_split_k_every_tile_shape(tile):
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
 
 
-def test_split_k_is_automatic_for_short_deep_layers_and_can_be_switched_off():
+def test_split_k_runs_only_on_request():
     spec = spec_of(64, 512, 7, 7, 512, dtype="bf16", sp=0.5)        # the deepest ResNet18 layers at batch 64
     ci = W.make_conv_inputs(spec, 990)
     layer = check_layer(ci, sample_rows=128)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, 2)
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
-    assert B.sparse_conv_plan_kernel(layer.plan, 1) == "tile_lds_direct"    # its dense run has enough tiles
+    assert B.sparse_conv_plan_tiles(layer.plan, 0) == (64, 128, 2 * 25 * 4)
     B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, 1)
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
-    many = spec_of(64, 128, 28, 28, 128, dtype="bf16", sp=0.0)
-    layer = R.ConvLayer(many, *_wbm(many, 3))
+
+
+BUFFER_CASES = [
+    # Cin a multiple of 64 and at least three K tiles: the buffer-load form of the tiled kernel
+    dict(n=2, cin=64, h=13, w=11, cout=96, k=3, p=1),                        # padded taps on every side
+    dict(n=1, cin=128, h=9, w=14, cout=64, k=3, s=2, p=1, sp=0.4),           # stride 2
+    dict(n=2, cin=64, h=12, w=12, cout=48, k=3, p=2, d=2, sp=0.6),           # dilation 2
+    dict(n=2, cin=64, h=10, w=9, cout=80, k=5, p=2, sp=0.5),                 # 5x5 window: 25 taps
+    dict(n=1, cin=64, h=16, w=7, cout=64, k=3, kw=1, p=1, pw=0, sp=0.5),     # 3x1 window
+    dict(n=3, cin=256, h=6, w=6, cout=160, k=1, p=0, sp=0.5),                # pointwise, four K tiles, ragged channels
+    dict(n=2, cin=192, h=8, w=8, cout=32, k=1, p=0, s=2, sp=0.4),            # strided pointwise, three K tiles
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (64, 128), (64, 64), (128, 32), (32, 128)])
+@pytest.mark.parametrize("case", range(len(BUFFER_CASES)))
+def test_buffer_load_tiled_kernel(case, tile, dtype):
+    spec = spec_of(dtype=dtype, **BUFFER_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 1000 + case), tiles=tile)
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    # the global_load_lds form of the same tile must agree with it (same K order: bitwise)
+    ci = W.make_conv_inputs(spec, 1000 + case)
+    x = R.to_device(ci.x, spec.dtype)
+    a = R.bits_of(layer.sparse(x)).copy()
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_GATHER_PIPELINE, 2)
+    assert np.array_equal(R.bits_of(layer.sparse(x)), a)
 
 
 def test_split_k_repeated_launches_leave_the_counters_clean():
