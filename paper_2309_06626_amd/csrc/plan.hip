@@ -202,6 +202,55 @@ __global__ void maxpool_nhwc_kernel(const T* __restrict__ x, T* __restrict__ y, 
   y[idx] = (T)best;
 }
 
+// 16-bit types, channel count a multiple of 8: a thread owns 8 consecutive channels of one output
+// position (16-byte loads and stores; the scalar kernel above moves 2 bytes per thread and access)
+template <typename T>
+__global__ void maxpool_nhwc_vec8_kernel(const T* __restrict__ x, T* __restrict__ y, int n, int h, int w, int c, int k,
+                                         int s, int p, int ho, int wo) {
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  const int cg = c >> 3;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t total = (int64_t)n * ho * wo * cg;
+  if (idx >= total) return;
+  int g = (int)(idx % cg);
+  int64_t pos = idx / cg;
+  int ox = (int)(pos % wo);
+  int oy = (int)((pos / wo) % ho);
+  int b = (int)(pos / ((int64_t)wo * ho));
+  float best[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+  for (int ky = 0; ky < k; ++ky) {
+    int iy = oy * s - p + ky;
+    if (iy < 0 || iy >= h) continue;
+    for (int kx = 0; kx < k; ++kx) {
+      int ix = ox * s - p + kx;
+      if (ix < 0 || ix >= w) continue;
+      const vec8 v = *reinterpret_cast<const vec8*>(x + (((int64_t)b * h + iy) * w + ix) * c + g * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], (float)v[e]);
+    }
+  }
+  vec8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (T)best[e];
+  *reinterpret_cast<vec8*>(y + pos * c + g * 8) = o;
+}
+
+template <typename T>
+__global__ void add_relu_vec8_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t groups) {
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < groups; i += stride) {
+    const vec8 va = reinterpret_cast<const vec8*>(a)[i], vb = reinterpret_cast<const vec8*>(b)[i];
+    vec8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (T)fmaxf((float)va[e] + (float)vb[e], 0.0f);
+    reinterpret_cast<vec8*>(y)[i] = o;
+  }
+}
+
 template <typename T>
 __global__ void add_relu_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t count) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -458,12 +507,12 @@ namespace sc {
 // MI355X: 64 x 128 tiles move the fewest operand bytes per FLOP of the shapes that still leave enough
 // workgroups, so they are taken once they give about one and a half workgroups per CU; below that the
 // 64 x 64 shape (twice the workgroups) wins, and short GEMMs with wide outputs take 32 x 128.
-static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather) {
+static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather, int k_tiles) {
   int bm, bn;
   const int64_t wg_64x128 = ((rows + 63) / 64) * ((c_out + 127) / 128);
   if (!vec_gather) { bm = 128; bn = 64; }            // element gather: fewer, fatter workgroups
   else if (c_out <= 32) { bm = 128; bn = 32; }
-  else if (c_out % 128 == 0 && wg_64x128 >= 384) { bm = 64; bn = 128; }
+  else if (c_out % 128 == 0 && wg_64x128 >= (k_tiles >= 32 ? 256 : 384)) { bm = 64; bn = 128; }   // long K: one per CU is enough
   else if (rows <= 8192 && c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
   else { bm = 64; bn = 64; }
   for (int i = 0; i < count; ++i)
@@ -800,8 +849,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->table = d.dtype == SC_BF16 ? kernels_bf16(&pl->table_count)
               : d.dtype == SC_F16 ? kernels_f16(&pl->table_count)
                                   : kernels_f32(&pl->table_count);
-  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather);
-  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather);
+  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather, g.k_tiles);
+  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather, g.k_tiles);
   pl->forced[0] = pl->forced[1] = -1;
   pl->gather_pipeline = 0;
   pl->split_k = 0;
@@ -937,7 +986,16 @@ sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32
   if (total >= ((int64_t)1 << 31) * 256) return SC_ERR_BAD_SHAPE;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  if (dtype == SC_F32)
+  const bool vec8 = dtype != SC_F32 && c % 8 == 0 && (((uintptr_t)x_dev | (uintptr_t)y_dev) & 15) == 0;
+  if (vec8) {
+    dim3 vgrid((unsigned)((total / 8 + 255) / 256));
+    if (dtype == SC_F16)
+      hipLaunchKernelGGL(maxpool_nhwc_vec8_kernel<_Float16>, vgrid, block, 0, stream, (const _Float16*)x_dev,
+                         (_Float16*)y_dev, n, h, w, c, k, s, p, ho, wo);
+    else
+      hipLaunchKernelGGL(maxpool_nhwc_vec8_kernel<__bf16>, vgrid, block, 0, stream, (const __bf16*)x_dev,
+                         (__bf16*)y_dev, n, h, w, c, k, s, p, ho, wo);
+  } else if (dtype == SC_F32)
     hipLaunchKernelGGL(maxpool_nhwc_kernel<float>, grid, block, 0, stream, (const float*)x_dev, (float*)y_dev, n, h,
                        w, c, k, s, p, ho, wo);
   else if (dtype == SC_F16)
@@ -958,7 +1016,17 @@ sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t
   if (count == 0) return SC_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   dim3 grid((unsigned)std::min<int64_t>((count + 255) / 256, 65536)), block(256);
-  if (dtype == SC_F32)
+  const bool vec8 = dtype != SC_F32 && count % 8 == 0 &&
+                    (((uintptr_t)a_dev | (uintptr_t)b_dev | (uintptr_t)y_dev) & 15) == 0;
+  if (vec8) {
+    dim3 vgrid((unsigned)std::min<int64_t>((count / 8 + 255) / 256, 65536));
+    if (dtype == SC_F16)
+      hipLaunchKernelGGL(add_relu_vec8_kernel<_Float16>, vgrid, block, 0, stream, (const _Float16*)a_dev,
+                         (const _Float16*)b_dev, (_Float16*)y_dev, count / 8);
+    else
+      hipLaunchKernelGGL(add_relu_vec8_kernel<__bf16>, vgrid, block, 0, stream, (const __bf16*)a_dev,
+                         (const __bf16*)b_dev, (__bf16*)y_dev, count / 8);
+  } else if (dtype == SC_F32)
     hipLaunchKernelGGL(add_relu_kernel<float>, grid, block, 0, stream, (const float*)a_dev, (const float*)b_dev,
                        (float*)y_dev, count);
   else if (dtype == SC_F16)

@@ -394,8 +394,9 @@ def test_config4_pointwise(idx):
 
 def test_glue_ops_match_oracle():
     rng = np.random.default_rng(8)
-    for dtype in ("bf16", "f16", "f32"):
-        x = W.quantize(rng.standard_normal((3, 13, 10, 24)).astype(np.float32), dtype)
+    # 24 channels: eight per thread for the 16-bit types; 5 channels: the element-wise kernels
+    for dtype, shape in [(d, sh) for d in ("bf16", "f16", "f32") for sh in ((3, 13, 10, 24), (2, 9, 11, 5))]:
+        x = W.quantize(rng.standard_normal(shape).astype(np.float32), dtype)
         y = B.sc_maxpool2d_nhwc(R.to_device(x, dtype), 3, 2, 1)
         assert np.array_equal(R.to_host_f32(y), oracle.maxpool2d_nhwc(x, 3, 2, 1))
         b = W.quantize(rng.standard_normal(x.shape).astype(np.float32), dtype)
