@@ -3,6 +3,17 @@
 
 namespace sc {
 
+// ring of two tiles for layers with at most two K tiles (less LDS, more workgroups per CU)
+template <int DT>
+static LaunchFn pick_shallow(int bm, int bn) {
+  if (bm == 128 && bn == 64) return igemm_buf_launch<DT, 128, 64, 2, 2, 2>;
+  if (bm == 64 && bn == 128) return igemm_buf_launch<DT, 64, 128, 2, 2, 2>;
+  if (bm == 64 && bn == 64) return igemm_buf_launch<DT, 64, 64, 2, 2, 2>;
+  if (bm == 128 && bn == 32) return igemm_buf_launch<DT, 128, 32, 4, 1, 2>;
+  if (bm == 32 && bn == 128) return igemm_buf_launch<DT, 32, 128, 1, 4, 2>;
+  return nullptr;
+}
+
 template <int DT>
 static LaunchFn pick(int bm, int bn) {
   if (bm == 128 && bn == 128) return igemm_buf_launch<DT, 128, 128, 2, 2, 3>;
@@ -14,9 +25,9 @@ static LaunchFn pick(int bm, int bn) {
   return nullptr;
 }
 
-LaunchFn buf_kernel(int dtype, int bm, int bn) {
-  if (dtype == kBF16) return pick<kBF16>(bm, bn);
-  if (dtype == kF16) return pick<kF16>(bm, bn);
+LaunchFn buf_kernel(int dtype, int bm, int bn, bool shallow) {
+  if (dtype == kBF16) return shallow ? pick_shallow<kBF16>(bm, bn) : pick<kBF16>(bm, bn);
+  if (dtype == kF16) return shallow ? pick_shallow<kF16>(bm, bn) : pick<kF16>(bm, bn);
   return nullptr;
 }
 

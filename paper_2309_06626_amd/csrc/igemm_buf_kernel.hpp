@@ -293,7 +293,7 @@ hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// the buffer-load form of tile bm x bn for a 16-bit dtype, or null
-LaunchFn buf_kernel(int dtype, int bm, int bn);
+// the buffer-load form of tile bm x bn for a 16-bit dtype (shallow: ring of two K tiles), or null
+LaunchFn buf_kernel(int dtype, int bm, int bn, bool shallow);
 
 }  // namespace sc

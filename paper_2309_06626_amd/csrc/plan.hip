@@ -690,12 +690,12 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
                 : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
   {
     // buffer-load form: Cin a multiple of the K tile (a K tile then lies inside one tap), windows up
-    // to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31), deeper than the two-tile ring
+    // to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31)
     const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
     const uint64_t xb = (uint64_t)d.n * d.h * d.w * d.c_in * eb, wb = (uint64_t)g.cout_pad * g.k_stride * eb;
-    LaunchFn bf = buf_kernel(dt, ke.bm, ke.bn);
+    LaunchFn bf = buf_kernel(dt, ke.bm, ke.bn, g.k_tiles <= 2);
     if (bf && g.vec_gather && g.vec_out && pl->gather_pipeline == 0 && d.dtype != SC_F32 && d.c_in % 64 == 0 &&
-        d.kh <= 8 && d.kw <= 8 && g.k_tiles >= 3 && xb < ((uint64_t)1 << 31) && wb < ((uint64_t)1 << 31)) {
+        d.kh <= 8 && d.kw <= 8 && xb < ((uint64_t)1 << 31) && wb < ((uint64_t)1 << 31)) {
       p.x_bytes = (uint32_t)xb;
       p.w_bytes = (uint32_t)wb;
       fn = bf;
