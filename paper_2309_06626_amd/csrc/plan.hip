@@ -633,9 +633,12 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
       SC_HIP(pl->stream_table->fn[b.ni == 4 ? 1 : 0][mi - 1](q, b.lds, stream));
       return SC_OK;
     }
-    // rows per wavefront decide how many 32-row MFMA blocks share one filter fragment
-    const double per_wave = (double)rows / b.n_bands / 4.0;
-    const int mi_idx = per_wave > 32.0 ? 1 : 0;
+    // 32-row (MI = 1) or 64-row (MI = 2) MFMA blocks, dealt to the four wavefronts round robin: take
+    // the shape that leaves the busiest wavefront fewer 32-row units; at a tie the 64-row block, whose
+    // two row blocks share every filter fragment read from LDS
+    const double cnt = (double)rows / b.n_bands;
+    const double units1 = std::ceil(std::ceil(cnt / 32.0) / 4.0), units2 = 2.0 * std::ceil(std::ceil(cnt / 64.0) / 4.0);
+    const int mi_idx = units1 < units2 ? 0 : 1;
     if (b.pp) {
       SC_HIP(pl->pp_table->fn[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
       return SC_OK;
