@@ -133,7 +133,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
  * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_lds_direct",
- * "tile_registers" or "tile_elements".
+ * "tile_registers", "tile_row_segments" or "tile_elements".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparse_conv.so")
-SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "igemm_panel.hip", "igemm_buf.hip"]
+SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "igemm_panel.hip", "igemm_buf.hip", "igemm_rowseg.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-value",
@@ -31,7 +31,7 @@ def _compile(src: str, extra_flags=(), obj_dir: str = OBJ) -> str:
     return obj
 
 
-def build_library(jobs: int = 7, extra_flags=(), out: str = LIB, obj_dir: str = OBJ) -> str:
+def build_library(jobs: int = 8, extra_flags=(), out: str = LIB, obj_dir: str = OBJ) -> str:
     """Compile every HIP source and link the shared library.  Always recompiles."""
     os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(SOURCES)))) as ex:

@@ -41,6 +41,7 @@ struct ConvParams {
   int32_t m_tiles, n_tiles;
   // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+  int32_t seg_gpk, seg_gpk_inv, seg_tail;   // row-segment gather: 16-byte groups per window row, entries of the last one inside the window
   uint32_t x_bytes, w_bytes;   // sizes of x and of the packed filters (buffer-load kernels; 0 = too large)
   // split-K launches only: the K tiles of an output tile are divided among `splits` workgroups
   int32_t splits;
@@ -74,6 +75,9 @@ struct KernelEntry {
   LaunchFn splitk; // direct-to-LDS gather, deep ring, K divided among several workgroups (null: no such shape)
   size_t lds_bytes;
 };
+
+// the row-segment-gather form of tile bm x bn for a 16-bit dtype, or null (igemm_rowseg.hip)
+LaunchFn rowseg_kernel(int dtype, int bm, int bn);
 
 // per-dtype kernel tables (defined in igemm_<dtype>.hip)
 const KernelEntry* kernels_bf16(int* count);

@@ -30,8 +30,12 @@ namespace sc {
 template <int BM, int BN>
 constexpr size_t igemm_lds_bytes() { return 2 * (size_t)(BM + BN) * kRowBytes + BM * sizeof(int32_t); }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, int DEPTH>
+// GATHER: 0 = element by element (any layout), 1 = 16-byte channel groups (NHWC, Cin*eb % 16 == 0),
+// 2 = window-row segments of a zero-margined NHWC copy of the input (small Cin, 16-bit types).
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int GATHER, int DEPTH>
 __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
+  constexpr bool VEC = GATHER == 1;
+  constexpr bool ROWSEG = GATHER == 2;
   using E = Elem<DT>;
   using T = typename E::T;
   constexpr int V = E::V;
@@ -76,8 +80,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     if (ic < p.rows) rr = p.row_idx ? p.row_idx[ic] : ic;
     s_rows[lrow + 32 * j] = rr;   // eight threads write the same value; read again in the epilogue
     if (rr >= 0) {
-      int n = rr / p.ho_wo, rem = rr - n * p.ho_wo;
-      int oy = rem / p.wo, ox = rem - oy * p.wo;
+      int n = fast_div(rr, p.div_howo_mul, p.div_howo_shift), rem = rr - n * p.ho_wo;
+      int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
       a_iy0[j] = oy * p.sh - p.ph;
       a_ix0[j] = ox * p.sw - p.pw;
       a_base[j] = (int32_t)(n * p.xs_n + (int64_t)a_iy0[j] * p.xs_h + (int64_t)a_ix0[j] * p.xs_w);
@@ -100,10 +104,39 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     g_kx = tap - g_ky * p.kw;
   }
 
+  // row-segment gather: dword masks that clear the entries of a window row's last 16-byte group which
+  // lie beyond the window (their filter entries are zero, but a non-finite neighbour must not leak in)
+  int seg_mask[4] = {-1, -1, -1, -1};
+  if constexpr (ROWSEG) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      seg_mask[i] = p.seg_tail >= 2 * i + 2 ? -1 : p.seg_tail == 2 * i + 1 ? 0xffff : 0;
+  }
+
   v4i ra[DEPTH][A_LOADS], rb[DEPTH][B_LOADS];
 
   auto load_tile = [&](int kt, v4i (&a)[A_LOADS], v4i (&b)[B_LOADS]) {
-    if constexpr (VEC) {
+    if constexpr (ROWSEG) {
+      // group g of K = (window row ky, 16-byte group gx of that row); the input copy has zero margins,
+      // so every tap of every present row is in bounds
+      const int g = kt * 8 + c16;
+      const int ky = (g * p.seg_gpk_inv) >> 16, gx = g - ky * p.seg_gpk;   // g / gpk for g < 4096, gpk <= 8
+      const bool row_ok = ky < p.kh;
+      const int off = ky * p.dil_h * p.xs_h + gx * 8;
+      const bool last = gx == p.seg_gpk - 1;
+#pragma unroll
+      for (int j = 0; j < A_LOADS; ++j) {
+        v4i v = {0, 0, 0, 0};
+        if (row_ok && a_iy0[j] >= 0) {
+          __builtin_memcpy(&v, x + (a_base[j] + off), 16);   // element-aligned source
+          if (last) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] &= seg_mask[i];
+          }
+        }
+        a[j] = v;
+      }
+    } else if constexpr (VEC) {
       const int dy = g_ky * p.dil_h, dx = g_kx * p.dil_w;
       const int off = dy * p.xs_h + dx * p.xs_w + g_ci;
       const bool tap_ok = g_ky < p.kh;
@@ -155,15 +188,27 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     const int lo = tile_m == 0 ? 0 : s_rows[0];
     const int hi = (m0 + BM >= p.rows) ? p.m_total : p.row_idx[m0 + BM];
     if (p.vec_out) {
-      constexpr int CPR = BN * EB / 16;  // 16-byte groups per row slice
+      // thread (zr, zc) covers 16-byte group zc of rows lo + zr + u*RPI; mask bytes four passes at a time
+      constexpr int CPR = BN * EB / 16;   // 16-byte groups per row slice
+      constexpr int RPI = kThreads / CPR;
       const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
-      const int total = (hi - lo) * CPR;
-      for (int idx = t; idx < total; idx += kThreads) {
-        int r = lo + idx / CPR, c = idx % CPR;
-        int mr = p.mask_spatial ? r % p.ho_wo : r;
-        if (c < valid && p.mask[mr] == 0) {
-          v4i z = {0, 0, 0, 0};
-          sc_store16(reinterpret_cast<v4i*>(reinterpret_cast<unsigned char*>(y) + ((int64_t)r * p.c_out + n0) * EB + c * 16), z);
+      const int zc = t % CPR, zr = t / CPR;
+      if (zc < valid) {
+        unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
+        const v4i z = {0, 0, 0, 0};
+        for (int r0 = lo + zr; r0 < hi; r0 += 4 * RPI) {
+          unsigned char mk[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            int r = min(r0 + u * RPI, hi - 1);
+            if (p.mask_spatial) r -= fast_div(r, p.div_howo_mul, p.div_howo_shift) * p.ho_wo;
+            mk[u] = p.mask[r];
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int r = r0 + u * RPI;
+            if (r < hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+          }
         }
       }
     } else {
@@ -254,10 +299,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
   }
 }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, int DEPTH>
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int GATHER, int DEPTH>
 hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
   constexpr size_t lds = igemm_lds_bytes<BM, BN>();
-  auto kern = igemm_kernel<DT, BM, BN, WAVES_M, WAVES_N, VEC, DEPTH>;
+  auto kern = igemm_kernel<DT, BM, BN, WAVES_M, WAVES_N, GATHER, DEPTH>;
   static bool attr_set = false;
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -272,15 +317,15 @@ hipError_t igemm_launch(const ConvParams& p, hipStream_t stream) {
 }
 
 #define SC_KERNEL_ENTRY(DT, BM, BN, WM_, WN_, DEPTH, STAGES)                              \
-  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
-                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
+  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, 1, DEPTH>,                 \
+                igemm_launch<DT, BM, BN, WM_, WN_, 0, 1>,                            \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>,                          \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>, nullptr, igemm_lds_bytes<BM, BN>() }
 
 // the same plus the split-K form of the direct-to-LDS kernel with a ring of SK_STAGES tiles
 #define SC_KERNEL_ENTRY_SPLITK(DT, BM, BN, WM_, WN_, DEPTH, STAGES, SK_STAGES)           \
-  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, true, DEPTH>,                 \
-                igemm_launch<DT, BM, BN, WM_, WN_, false, 1>,                            \
+  KernelEntry { BM, BN, igemm_launch<DT, BM, BN, WM_, WN_, 1, DEPTH>,                 \
+                igemm_launch<DT, BM, BN, WM_, WN_, 0, 1>,                            \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, STAGES>,                          \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, 2>,                               \
                 igemm_dma_launch<DT, BM, BN, WM_, WN_, SK_STAGES, true>, igemm_lds_bytes<BM, BN>() }

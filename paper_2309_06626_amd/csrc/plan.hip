@@ -86,16 +86,24 @@ __global__ __launch_bounds__(256) void mask_scatter_kernel(const uint8_t* __rest
 // group of 32 output channels the rows are permuted so that MFMA output row 8j + 4h + i holds
 // channel 16h + 4j + i: a lane of the result then owns 16 consecutive channels.
 // ------------------------------------------------------------------------------------------------
+// epad > 0 selects the row-segment K order of the small-channel gather: K' = (ky, e) with e = kx*c_in + ci
+// padded to epad entries per window row (the padding holds zeros).
 template <typename T>
 __global__ void pack_filters_kernel(const T* __restrict__ w, T* __restrict__ wp, int c_out, int c_in, int kh, int kw,
-                                    int k, int k_pad, int cout_pad, int nchw) {
+                                    int k, int k_pad, int cout_pad, int nchw, int epad) {
   int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)cout_pad * k_pad) return;
   int prow = (int)(idx / k_pad), kk = (int)(idx % k_pad);
   int rho = prow & 31;
   int co = (prow & ~31) + 16 * ((rho >> 2) & 1) + 4 * (rho >> 3) + (rho & 3);
   T v = (T)0.0f;
-  if (co < c_out && kk < k) {
+  bool real = co < c_out && kk < k;
+  if (epad > 0 && real) {
+    int ky = kk / epad, e = kk % epad;
+    real = e < kw * c_in;
+    kk = ky * kw * c_in + e;   // position in the plain (ky, kx, ci) order
+  }
+  if (real) {
     int tap = kk / c_in, ci = kk % c_in;
     int ky = tap / kw, kx = tap % kw;
     int64_t src = nchw ? (((int64_t)co * c_in + ci) * kh + ky) * kw + kx
@@ -122,6 +130,25 @@ __global__ void build_ktab_kernel(KEntry* __restrict__ tab, int entries, int vec
     e.dydx = 0x7fff;  // row offset no image reaches: the padded K entries read as zero
   }
   tab[g] = e;
+}
+
+// Small-channel gather: copy x [N][H][W][C] into the interior of the zero-margined buffer
+// [N][Hp][Wp][C] (margins are zeroed once at plan time), 16 bytes per thread; rows of W*C elements are
+// a multiple of 8 elements here.
+template <typename T>
+__global__ void pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp, int n, int h, int row_elems, int hp,
+                                 int prow_elems, int top, int left_elems) {
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  const int gpr = row_elems >> 3;
+  int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  int64_t total = (int64_t)n * h * gpr;
+  if (idx >= total) return;
+  int g = (int)(idx % gpr);
+  int64_t r = idx / gpr;
+  int iy = (int)(r % h), b = (int)(r / h);
+  const vec8 v = *reinterpret_cast<const vec8*>(x + r * row_elems + g * 8);
+  T* dst = xp + ((int64_t)b * hp + iy + top) * prow_elems + left_elems + g * 8;
+  __builtin_memcpy(dst, &v, 16);   // destination is only element-aligned
 }
 
 __global__ void fill_zero_kernel(uint4* __restrict__ dst, int64_t n16, unsigned char* tail, int ntail) {
@@ -278,6 +305,12 @@ struct Geometry {
   // workspace carve (byte offsets)
   size_t off_rows, off_counts, off_kept, off_zeros, off_mask, off_wp, off_ktab, off_band, off_band_rows, off_counters, off_partial, total;
   bool splitk_ok;          // the layer may run the split-K kernel (workspace reserved for it)
+  // small-channel gather (NHWC, 16-bit, Cin*eb not a multiple of 16 bytes, e.g. the 3-channel stem): a
+  // window row of kw*Cin contiguous elements is fetched as ceil(kw*Cin/8) unaligned 16-byte groups
+  // from a zero-margined copy of the input, so no tap needs a bounds check
+  bool rowseg;
+  int32_t epad, hp, wp_cols;   // K entries per window row (padded to 8), padded input height and width
+  size_t off_xpad;
 };
 
 static int out_extent(int in, int k, int stride, int pad, int dil) {
@@ -313,6 +346,23 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
     return SC_ERR_BAD_SHAPE;
   const int eb = elem_bytes(d->dtype);
   g->vec = 16 / eb;
+  g->rowseg = false;
+  g->epad = g->hp = g->wp_cols = 0;
+  if (d->layout == SC_NHWC && d->dtype != SC_F32 && d->c_in % g->vec != 0 && d->dil_w == 1 && d->kw * d->c_in <= 64 &&
+      (d->w * d->c_in) % 8 == 0) {
+    const int epad = (d->kw * d->c_in + 7) / 8 * 8;
+    const int over = (epad - d->kw * d->c_in + d->c_in - 1) / d->c_in;      // pixels the last group reads past the window
+    const int max_iy = (g->ho - 1) * d->stride_h - d->pad_h + (d->kh - 1) * d->dil_h;
+    const int max_ix = (g->wo - 1) * d->stride_w - d->pad_w + d->kw - 1 + over;
+    const int64_t hp = d->pad_h + std::max<int64_t>(d->h, max_iy + 1), wpc = d->pad_w + std::max<int64_t>(d->w, max_ix + 1);
+    if ((int64_t)d->n * hp * wpc * d->c_in + 64 < lim - (1 << 20)) {
+      g->rowseg = true;
+      g->epad = epad;
+      g->hp = (int32_t)hp;
+      g->wp_cols = (int32_t)wpc;
+      k = (int64_t)d->kh * epad;
+    }
+  }
   g->k = (int32_t)k;
   const int bk = 8 * g->vec;
   g->k_pad = (int32_t)((k + bk - 1) / bk * bk);
@@ -334,6 +384,8 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->off_ktab = off;   off = align_up(off + (size_t)g->k_pad * sizeof(KEntry), 256);
   g->off_band = off;   off = align_up(off + ((size_t)d->n * g->ho + 1) * 4, 256);
   g->off_band_rows = off; off = align_up(off + (size_t)g->m * 4, 256);
+  g->off_xpad = off;
+  if (g->rowseg) off = align_up(off + ((size_t)d->n * g->hp * g->wp_cols * d->c_in + 64) * eb, 256);
   // split-K (16-bit operands, direct-to-LDS gather, 128-channel tiles, deep K): arrival counters for
   // every output tile (64 x 64 is the smallest split-K tile) and the float partial sums
   g->splitk_ok = d->dtype != SC_F32 && g->vec_gather && g->vec_out && d->c_out >= 128 && g->k_tiles >= 16;
@@ -507,10 +559,12 @@ namespace sc {
 // MI355X: 64 x 128 tiles move the fewest operand bytes per FLOP of the shapes that still leave enough
 // workgroups, so they are taken once they give about one and a half workgroups per CU; below that the
 // 64 x 64 shape (twice the workgroups) wins, and short GEMMs with wide outputs take 32 x 128.
-static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather, int k_tiles) {
+static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather, int k_tiles,
+                       bool rowseg) {
   int bm, bn;
   const int64_t wg_64x128 = ((rows + 63) / 64) * ((c_out + 127) / 128);
-  if (!vec_gather) { bm = 128; bn = 64; }            // element gather: fewer, fatter workgroups
+  if (rowseg) { bm = 64; bn = c_out <= 32 ? 32 : 64; if (c_out <= 32) bm = 128; }   // window-row gather (stems): measured best
+  else if (!vec_gather) { bm = 128; bn = 64; }       // element gather: fewer, fatter workgroups
   else if (c_out <= 32) { bm = 128; bn = 32; }
   else if (c_out % 128 == 0 && wg_64x128 >= (k_tiles >= 32 ? 256 : 384)) { bm = 64; bn = 128; }   // long K: one per CU is enough
   else if (rows <= 8192 && c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
@@ -691,6 +745,27 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
   LaunchFn fn = !g.vec_gather ? ke.elem
                 : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
+  if (g.rowseg) {
+    // small-channel gather: refresh the interior of the zero-margined input copy, then gather window rows
+    // from it (no padding in the copy's coordinates: the margins are the padding)
+    const int dt = d.dtype == SC_BF16 ? kBF16 : kF16;
+    LaunchFn rs = rowseg_kernel(dt, ke.bm, ke.bn);
+    if (!rs) return SC_ERR_UNSUPPORTED;
+    const int row_elems = d.w * d.c_in, prow_elems = g.wp_cols * d.c_in;
+    const int64_t groups = (int64_t)d.n * d.h * (row_elems / 8);
+    _Float16* xp = reinterpret_cast<_Float16*>(pl->ws + g.off_xpad);   // 16-bit patterns are moved verbatim
+    hipLaunchKernelGGL(pad_input_kernel<_Float16>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<const _Float16*>(x), xp, d.n, d.h, row_elems, g.hp, prow_elems, d.pad_h,
+                       d.pad_w * d.c_in);
+    SC_HIP(hipGetLastError());
+    p.x = xp;
+    p.h = g.hp; p.w = g.wp_cols; p.ph = 0; p.pw = 0;
+    p.xs_n = (int64_t)g.hp * prow_elems; p.xs_h = prow_elems; p.xs_w = d.c_in;
+    p.seg_gpk = g.epad / 8;
+    p.seg_gpk_inv = 65536 / p.seg_gpk + 1;   // (g * inv) >> 16 == g / gpk for g < 4096
+    p.seg_tail = d.kw * d.c_in - (p.seg_gpk - 1) * 8;
+    fn = rs;
+  }
   {
     // buffer-load form: Cin a multiple of the K tile (a K tile then lies inside one tap), windows up
     // to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31)
@@ -767,6 +842,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   const int eb = elem_bytes(d.dtype);
 
   SC_HIP(hipMemsetAsync(ws + g.off_zeros, 0, 256, stream));
+  if (g.rowseg)      // margins of the padded input copy stay zero; every run rewrites the interior
+    SC_HIP(hipMemsetAsync(ws + g.off_xpad, 0, ((size_t)d.n * g.hp * g.wp_cols * d.c_in + 64) * eb, stream));
   if (g.splitk_ok)   // arrival counters start at zero; every launch leaves them at zero again
     SC_HIP(hipMemsetAsync(ws + g.off_counters, 0, g.off_partial - g.off_counters, stream));
   // a private copy of the mask (the zero fill of every run reads it)
@@ -792,10 +869,10 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     const int nchw = d.layout == SC_NCHW;
     if (d.dtype == SC_F32)
       hipLaunchKernelGGL(pack_filters_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)w_dev,
-                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw);
+                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
     else  // 16-bit patterns are moved verbatim
       hipLaunchKernelGGL(pack_filters_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, (const _Float16*)w_dev,
-                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw);
+                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
     SC_HIP(hipGetLastError());
   }
 
@@ -852,8 +929,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->table = d.dtype == SC_BF16 ? kernels_bf16(&pl->table_count)
               : d.dtype == SC_F16 ? kernels_f16(&pl->table_count)
                                   : kernels_f32(&pl->table_count);
-  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather, g.k_tiles);
-  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather, g.k_tiles);
+  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather, g.k_tiles, g.rowseg);
+  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather, g.k_tiles, g.rowseg);
   pl->forced[0] = pl->forced[1] = -1;
   pl->gather_pipeline = 0;
   pl->split_k = 0;
@@ -930,6 +1007,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
   if (pick_tile(plan, which, which ? g.m : plan->kept).splits > 1) return "tile_split_k";
+  if (g.rowseg) return "tile_row_segments";
   if (!g.vec_gather) return "tile_elements";
   return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
 }

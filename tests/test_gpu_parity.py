@@ -278,6 +278,45 @@ def test_row_panel_kernel_scatter_only_and_switch():
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
 
 
+ROWSEG_CASES = [
+    # NHWC, Cin * 2 bytes not a multiple of 16, W * Cin a multiple of 8: window-row segments from a padded copy
+    dict(n=2, cin=3, h=37, w=40, cout=64, k=7, s=2, p=3),                    # stem-like: 21 entries per window row
+    dict(n=2, cin=4, h=15, w=18, cout=32, k=3, p=1, sp=0.3),                 # 12 entries per row, half a group of tail
+    dict(n=3, cin=1, h=19, w=32, cout=16, k=5, p=2, sp=0.6),                 # one channel: 5 entries per row
+    dict(n=1, cin=2, h=21, w=20, cout=24, k=3, p=2, d=2, dw=1, pw=1, sp=0.5),   # vertical dilation, scalar stores
+    dict(n=2, cin=3, h=16, w=24, cout=48, k=3, s=1, p=1, sp=0.4),            # 9 entries per row: two groups
+    dict(n=2, cin=6, h=12, w=12, cout=64, k=3, kw=5, p=1, pw=2, sp=0.5),     # 30 entries per row: four groups
+    dict(n=1, cin=3, h=14, w=16, cout=64, k=3, p=0, sp=0.0),                 # no padding, every row kept
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("case", range(len(ROWSEG_CASES)))
+def test_row_segment_gather(case, mask_mode, dtype):
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **ROWSEG_CASES[case])
+    layer = check_layer(W.make_conv_inputs(spec, 1020 + case))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_segments"
+    for tile in ((64, 64), (128, 32)):
+        check_layer(W.make_conv_inputs(spec, 1020 + case), tiles=tile)
+
+
+def test_row_segment_gather_ignores_non_finite_neighbours():
+    # the last 16-byte group of a window row reaches past the window: an infinity there must not
+    # turn the (zero-weight) product into NaN
+    spec = spec_of(1, 3, 8, 16, 16, k=3, p=1, dtype="bf16", sp=0.0, relu=False)
+    ci = W.make_conv_inputs(spec, 1030)
+    x = ci.x.copy()
+    x[0, 4, 9, :] = np.inf                      # poisons only the windows that contain pixel (4, 9)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_segments"
+    y = R.to_host_f32(layer.sparse(R.to_device(x, "bf16")))
+    touched = np.zeros((8, 16), bool)
+    touched[3:6, 8:11] = True
+    assert np.isfinite(y[0][~touched]).all()
+    assert not np.isfinite(y[0][touched]).all()
+
+
 STREAM_CASES = [
     dict(n=2, cin=64, h=14, w=14, cout=128),                         # 128 channels: one channel tile
     dict(n=1, cin=128, h=12, w=10, cout=256, sp=0.3),                # two channel tiles, two K tiles per tap
