@@ -169,6 +169,30 @@ const char* sc_status_string(sc_status s);
 int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread */
 
 /*
+ * Mask generator of the training pipeline (Alg. 1, function getMask; Sec. 3.1): the mask of one layer
+ * from a 2-D random score at the resolution of the network input.  Call it once per layer resolution
+ * with the same score: the masks of all layers then show the same pattern (the propagation of Sec. 3.1).
+ *   score_dev   float[in_h * in_w], row-major, device.  The random numbers are the caller's.
+ *               Not-a-number scores are not supported.
+ *   ho, wo      resolution of the layer's output map, 1 <= ho <= in_h, 1 <= wo <= in_w.  The score is
+ *               average-pooled with window = stride = (in_h / ho, in_w / wo) (integer division); when
+ *               the pooled map is larger than ho x wo its top-left corner is used.
+ *   sparsity    in [0, 1]: ho*wo - floor((1 - sparsity) * ho*wo + 0.5) pixels are dropped, those with
+ *               the lowest pooled score; equal scores are dropped in ascending pixel index.  Pixels are
+ *               compared by the double-precision sum of their window, added in row-major order.
+ *   mask_dev    uint8[ho * wo], device: 1 = keep, 0 = drop (the SC_MASK_SPATIAL mask of sparse_conv_plan).
+ *   workspace_dev  at least sparse_mask_workspace_bytes(ho, wo) bytes, 8-byte aligned, device; scratch,
+ *               owned by the caller, free for reuse once the stream has passed the call.
+ * Enqueues two kernels on `hip_stream` and returns; no allocation, no synchronisation.
+ * Errors: SC_ERR_NULL, SC_ERR_BAD_SHAPE (extents, sparsity outside [0, 1], more than 2^26 pixels),
+ * SC_ERR_WORKSPACE, SC_ERR_ALIGN, SC_ERR_HIP.
+ */
+sc_status sparse_mask_workspace_bytes(int32_t ho, int32_t wo, size_t* bytes);
+sc_status sparse_mask_generate(const float* score_dev, int32_t in_h, int32_t in_w, int32_t ho, int32_t wo,
+                               float sparsity, uint8_t* mask_dev, void* workspace_dev, size_t workspace_bytes,
+                               void* hip_stream);
+
+/*
  * Glue operators of the test networks (ResNet-style stacks), NHWC device tensors of `dtype`.
  * They are not part of the paper's method; they only connect conv layers in network runs.
  *   sc_maxpool2d_nhwc: window k, stride s, zero-free padding p (padded taps never win).

@@ -88,6 +88,10 @@ def lib() -> ctypes.CDLL:
         L.sc_maxpool2d_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.sc_add_relu.restype = ctypes.c_int
         L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
+        L.sparse_mask_workspace_bytes.restype = ctypes.c_int
+        L.sparse_mask_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        L.sparse_mask_generate.restype = ctypes.c_int
+        L.sparse_mask_generate.argtypes = [vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -310,3 +314,27 @@ def sc_add_relu(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = No
     _check(lib().sc_add_relu(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), _CODE_OF_TORCH[a.dtype],
                              a.numel(), _stream_handle(stream)), "sc_add_relu")
     return y
+
+
+def sparse_mask_workspace_bytes(ho: int, wo: int) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().sparse_mask_workspace_bytes(ho, wo, ctypes.byref(out)), "sparse_mask_workspace_bytes")
+    return int(out.value)
+
+
+def sparse_mask_generate(score: torch.Tensor, ho: int, wo: int, sparsity: float, mask: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Mask [ho, wo] (uint8, 1 = keep) of one layer from the input-resolution score [in_h, in_w] (float32)."""
+    if score.dim() != 2 or score.dtype != torch.float32:
+        raise ValueError("score must be a 2-D float32 tensor")
+    in_h, in_w = score.shape
+    if mask is None:
+        mask = torch.empty((ho, wo), dtype=torch.uint8, device=score.device)
+    if mask.numel() != ho * wo or mask.dtype != torch.uint8:
+        raise ValueError("mask must hold ho*wo bytes")
+    if workspace is None:
+        workspace = torch.empty(max(sparse_mask_workspace_bytes(ho, wo), 8), dtype=torch.uint8, device=score.device)
+    _check(lib().sparse_mask_generate(_dev_ptr(score, "score"), in_h, in_w, ho, wo, float(sparsity),
+                                      _dev_ptr(mask, "mask"), _dev_ptr(workspace, "workspace"), workspace.numel(),
+                                      _stream_handle(stream)), "sparse_mask_generate")
+    return mask

@@ -30,6 +30,9 @@ static inline bool hip_failed(hipError_t e) {
 }
 #define SC_HIP(expr) do { if (hip_failed((expr))) return SC_ERR_HIP; } while (0)
 
+// the other translation units of the library report their HIP failures through this
+void note_hip_error(int32_t code) { g_last_hip = code; }
+
 // ------------------------------------------------------------------------------------------------
 // Mask -> ascending list of kept rows (Alg. 2, indirection init: positions are visited in
 // ascending order and appended only where the mask is set).  Two passes, no inter-workgroup

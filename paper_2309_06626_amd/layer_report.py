@@ -150,6 +150,26 @@ def chain_time(ops, base_seed, steps, dense=False):
     return eager, timed(graph.replay)
 
 
+def mask_generator_times(steps):
+    """us per call of the mask generator (two launches) for the layer resolutions of the two networks."""
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd.metrics import time_launches
+
+    rows = []
+    for res, layer_res, s in ((224, (112, 56, 28, 14, 7), 0.5), (640, (320, 80, 40, 20), 0.3)):
+        score = torch.from_numpy(W.gen_score(res, res, seed=res)).to("cuda:0")
+        for r in layer_res:
+            mask = torch.empty((r, r), dtype=torch.uint8, device="cuda:0")
+            ws = torch.empty(B.sparse_mask_workspace_bytes(r, r), dtype=torch.uint8, device="cuda:0")
+            _, t = time_launches(lambda: B.sparse_mask_generate(score, r, r, s, mask=mask, workspace=ws), steps, 10)
+            rows.append({"score": f"{res}x{res}", "layer": f"{r}x{r}", "sparsity": s, "us": t * 1e6,
+                         "kept": int(mask.sum().item())})
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="1,2,3,4,5")
@@ -157,6 +177,7 @@ def main():
     ap.add_argument("--json", default="")
     ap.add_argument("--library-conv", action="store_true",
                     help="also time torch.nn.functional.conv2d (MIOpen, dense) on every shape, as context")
+    ap.add_argument("--masks", action="store_true", help="also time the mask generator (Alg. 1, getMask)")
     args = ap.parse_args()
 
     import torch
@@ -218,11 +239,21 @@ def main():
         print("|---|---|---|")
         for k, v in chains.items():
             print(f"| {k} | {v[0]:.1f} | {v[1]:.1f} |")
+    mask_rows = []
+    if args.masks:
+        mask_rows = mask_generator_times(max(args.steps // 4, 20))
+        print()
+        print("| mask generator: score | layer map | s | kept pixels | us per mask (pooling + ranking, two launches) |")
+        print("|---|---|---|---|---|")
+        for r in mask_rows:
+            print(f"| {r['score']} | {r['layer']} | {r['sparsity']:.2f} | {r['kept']} | {r['us']:.1f} |")
     if args.json:
         with open(args.json, "w") as f:
             for r in records:
                 f.write(json.dumps(r) + "\n")
             f.write(json.dumps({"chains_us": chains}) + "\n")
+            if mask_rows:
+                f.write(json.dumps({"mask_generator": mask_rows}) + "\n")
 
 
 if __name__ == "__main__":

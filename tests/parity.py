@@ -126,3 +126,17 @@ def check_layer(ci: W.ConvInputs, tiles=None, out_mode=B.SC_OUT_ZERO_FILL, check
         # sparse kept rows against the dense run of the same kernels
         assert_close(g[kept], gd[kept], np.abs(gd[kept]).astype(np.float64) + 1e-3, 2 * tol, f"{spec.name} sparse~dense")
     return layer
+
+
+def compare_network(ops, dev, ref, params, tol):
+    for op in ops:
+        g, r = R.to_host_f32(dev[op.out]), ref[op.out]
+        assert g.shape == r.shape
+        nr = np.linalg.norm(r.astype(np.float64))
+        err = np.linalg.norm(g.astype(np.float64) - r.astype(np.float64)) / max(nr, 1e-30)
+        assert err <= tol, f"{op.out}: normwise {err:.3e}"
+        assert np.abs(g - r).max() <= tol * max(np.abs(r).max(), 1e-30), op.out
+        if op.kind == "conv":
+            mask = params[op.spec.name][2]
+            bits = rows_view(op.spec, R.bits_of(dev[op.out]))
+            assert (bits[mask == 0] == 0).all(), f"{op.out}: dropped rows must be zero"

@@ -15,13 +15,14 @@ def declared_symbols():
     text = open(os.path.join(ROOT, "include", "sparse_conv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text)
-    return sorted(set(n for n in names if n.startswith(("sparse_conv", "dense_conv", "sc_"))))
+    return sorted(set(n for n in names if n.startswith(("sparse_conv", "sparse_mask", "dense_conv", "sc_"))))
 
 
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     names = declared_symbols()
-    assert {"sparse_conv_plan", "sparse_conv_run", "dense_conv_run", "sparse_conv_workspace_bytes"} <= set(names)
+    assert {"sparse_conv_plan", "sparse_conv_run", "dense_conv_run", "sparse_conv_workspace_bytes",
+            "sparse_mask_generate", "sparse_mask_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(L, n), n
 
@@ -99,3 +100,25 @@ def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(FileNotFoundError):
         B.lib()
+
+
+def test_mask_generator_rejects_bad_arguments_before_any_gpu_work():
+    L = B.lib()
+    size = ctypes.c_size_t(123)
+    assert L.sparse_mask_workspace_bytes(7, 5, ctypes.byref(size)) == B.SC_OK and size.value == 7 * 5 * 8
+    assert L.sparse_mask_workspace_bytes(7, 5, None) == B.SC_ERR_NULL
+    assert L.sparse_mask_workspace_bytes(0, 5, ctypes.byref(size)) == B.SC_ERR_BAD_SHAPE and size.value == 0
+    assert L.sparse_mask_workspace_bytes(1 << 14, 1 << 14, ctypes.byref(size)) == B.SC_ERR_BAD_SHAPE
+    fake = 0x1000   # never dereferenced: every check below fails on the host
+    gen = L.sparse_mask_generate
+    assert gen(None, 8, 8, 4, 4, 0.5, fake, fake, 1 << 20, None) == B.SC_ERR_NULL
+    assert gen(fake, 8, 8, 4, 4, 0.5, None, fake, 1 << 20, None) == B.SC_ERR_NULL
+    assert gen(fake, 8, 8, 4, 4, 0.5, fake, None, 1 << 20, None) == B.SC_ERR_NULL
+    assert gen(fake, 8, 8, 9, 4, 0.5, fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE      # layer larger than the input
+    assert gen(fake, 8, 8, 4, 0, 0.5, fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
+    assert gen(fake, 0, 8, 4, 4, 0.5, fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
+    assert gen(fake, 8, 8, 4, 4, -0.1, fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
+    assert gen(fake, 8, 8, 4, 4, 1.5, fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
+    assert gen(fake, 8, 8, 4, 4, float("nan"), fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
+    assert gen(fake, 8, 8, 4, 4, 0.5, fake, fake, 4 * 4 * 8 - 1, None) == B.SC_ERR_WORKSPACE
+    assert gen(fake, 8, 8, 4, 4, 0.5, fake, fake + 4, 1 << 20, None) == B.SC_ERR_ALIGN

@@ -1,0 +1,106 @@
+"""Mask generator (Alg. 1, getMask) on the GPU against its CPU oracle, through the C ABI: masks are
+bytes, so every comparison is bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2309_06626_amd.binding as B
+import paper_2309_06626_amd.runtime as R
+import workloads as W
+from oracle import mask_oracle as MO
+from oracle import oracle
+from parity import TOL, compare_network
+
+pytestmark = pytest.mark.gpu
+
+
+def f32(s):
+    """The sparsity as the C ABI receives it (a float)."""
+    return float(np.float32(s))
+
+
+def gpu_mask(score, ho, wo, s):
+    dev = torch.from_numpy(score).to("cuda:0")
+    mask = torch.full((ho, wo), 7, dtype=torch.uint8, device="cuda:0")      # poison: every byte must be written
+    B.sparse_mask_generate(dev, ho, wo, s, mask=mask)
+    torch.cuda.synchronize()
+    return mask.cpu().numpy()
+
+
+@pytest.mark.parametrize("h,w,ho,wo", [
+    (224, 224, 112, 112), (224, 224, 56, 56), (224, 224, 28, 28), (224, 224, 14, 14), (224, 224, 7, 7),
+    (64, 64, 64, 64), (33, 47, 16, 15), (9, 9, 4, 4), (15, 10, 7, 3), (5, 3, 1, 1), (1, 1, 1, 1), (640, 640, 80, 80),
+])
+@pytest.mark.parametrize("s", [0.25, 0.5, 0.7])
+def test_masks_match_the_oracle(h, w, ho, wo, s):
+    score = W.gen_score(h, w, seed=h * 1000 + ho)
+    want = MO.layer_mask(score, ho, wo, f32(s))
+    got = gpu_mask(score, ho, wo, s)
+    assert got.shape == want.shape and np.array_equal(got, want)
+    assert int(got.sum()) == MO.kept_pixels(f32(s), ho * wo)
+
+
+@pytest.mark.parametrize("s", [0.0, 1.0, 0.001, 0.999])
+def test_extreme_sparsities(s):
+    score = W.gen_score(48, 48, seed=3)
+    for ho in (48, 12):
+        assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+
+
+@pytest.mark.parametrize("levels", [1, 2, 3, 40])
+def test_ties_are_dropped_in_index_order(levels):
+    """Few distinct score values: the selected key is shared by many pixels, which go by index."""
+    rng = np.random.default_rng(levels)
+    score = rng.integers(0, levels, size=(96, 80)).astype(np.float32)
+    for (ho, wo), s in [((96, 80), 0.5), ((96, 80), 0.31), ((48, 40), 0.5), ((12, 10), 0.7)]:
+        assert np.array_equal(gpu_mask(score, ho, wo, s), MO.layer_mask(score, ho, wo, f32(s)))
+
+
+def test_negative_scores_zero_signs_and_infinities():
+    rng = np.random.default_rng(8)
+    score = rng.standard_normal((40, 40)).astype(np.float32)
+    score[rng.random((40, 40)) < 0.2] = 0.0
+    score[rng.random((40, 40)) < 0.1] = -0.0
+    score[3, 3], score[20, 7] = np.inf, -np.inf
+    for ho, s in [(40, 0.5), (40, 0.25), (20, 0.5), (10, 0.6)]:
+        assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+
+
+def test_large_map_with_narrow_score_range():
+    """All sums share their leading digits, so the first radix passes cannot shrink the candidate set."""
+    rng = np.random.default_rng(12)
+    score = (1.0 + rng.random((320, 320), dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+    for ho, s in [(320, 0.5), (160, 0.3)]:
+        assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+
+
+def test_resnet_stack_with_propagated_masks():
+    """Alg. 1 end to end on the inference side: one score, one mask per layer resolution from the GPU
+    generator, fed as 2-D masks to every convolution of the ResNet18 stack; the oracle does the same
+    with its own masks."""
+    ops = W.with_spatial_masks(W.config3(batch=2))
+    bs = W.base_seed(3)
+    res = W.network_input_shape(ops)[1]
+    score = W.gen_score(res, res, seed=bs + 77)
+    score_dev = torch.from_numpy(score).to("cuda:0")
+    params = {}
+    masks_dev = {}
+    for spec in W.conv_specs(ops):
+        ci = W.make_conv_inputs(spec, bs, x=np.zeros(1, np.float32))
+        want = MO.layer_mask(score, spec.ho, spec.wo, f32(spec.sparsity)).reshape(-1)
+        got = B.sparse_mask_generate(score_dev, spec.ho, spec.wo, spec.sparsity)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy().reshape(-1), want), spec.name
+        params[spec.name] = (ci.w, ci.bias, want)
+        masks_dev[spec.name] = got
+    # layers at one resolution share one mask (the propagation property)
+    assert np.array_equal(params["l1b0_conv1"][2], params["l1b1_conv2"][2])
+    dtype = "bf16"
+    host = {"input": W.gen_activations(W.network_input_shape(ops), bs, dtype)}
+    layers = {s.name: R.ConvLayer(s, params[s.name][0], params[s.name][1], masks_dev[s.name].cpu().numpy().reshape(-1))
+              for s in W.conv_specs(ops)}
+    dev = R.run_network(ops, {k: R.to_device(v, dtype) for k, v in host.items()}, layers)
+    torch.cuda.synchronize()
+    ref = oracle.run_network(ops, host, lambda spec: params[spec.name])
+    row_params = {k: (v[0], v[1], np.tile(v[2], 2)) for k, v in params.items()}     # per-row masks for the zero check
+    compare_network(ops, dev, ref, row_params, TOL["bf16"])

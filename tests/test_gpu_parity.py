@@ -9,7 +9,7 @@ import workloads as W
 from oracle import oracle
 from paper_2309_06626_amd import binding as B
 from paper_2309_06626_amd import runtime as R
-from parity import TOL, assert_close, check_layer, rows_view
+from parity import TOL, assert_close, check_layer, compare_network, rows_view
 
 pytestmark = pytest.mark.gpu
 
@@ -469,36 +469,22 @@ def _run_network_both(ops, bs, batch_note=""):
     return dev, ref, params
 
 
-def _compare_network(ops, dev, ref, params, tol):
-    for op in ops:
-        g, r = R.to_host_f32(dev[op.out]), ref[op.out]
-        assert g.shape == r.shape
-        nr = np.linalg.norm(r.astype(np.float64))
-        err = np.linalg.norm(g.astype(np.float64) - r.astype(np.float64)) / max(nr, 1e-30)
-        assert err <= tol, f"{op.out}: normwise {err:.3e}"
-        assert np.abs(g - r).max() <= tol * max(np.abs(r).max(), 1e-30), op.out
-        if op.kind == "conv":
-            mask = params[op.spec.name][2]
-            bits = rows_view(op.spec, R.bits_of(dev[op.out]))
-            assert (bits[mask == 0] == 0).all(), f"{op.out}: dropped rows must be zero"
-
-
 def test_config3_resnet18_stack_small_batch():
     ops = W.config3(batch=4)
     dev, ref, params = _run_network_both(ops, W.base_seed(3))
-    _compare_network(ops, dev, ref, params, TOL["bf16"])
+    compare_network(ops, dev, ref, params, TOL["bf16"])
 
 
 def test_config3_resnet18_stack_dense_downsample_variant():
     ops = W.config3(batch=2, sparse_downsample=False)
     dev, ref, params = _run_network_both(ops, W.base_seed(3))
-    _compare_network(ops, dev, ref, params, TOL["bf16"])
+    compare_network(ops, dev, ref, params, TOL["bf16"])
 
 
 def test_config5_detector_stack():
     ops = W.config5(batch=16)
     dev, ref, params = _run_network_both(ops, W.base_seed(5))
-    _compare_network(ops, dev, ref, params, TOL["bf16"])
+    compare_network(ops, dev, ref, params, TOL["bf16"])
 
 
 def test_fixed_buffer_runner_and_graph_replay_match_the_eager_chain():

@@ -197,6 +197,11 @@ def gen_mask(length: int, keep: int, seed: int) -> np.ndarray:
     return mask
 
 
+def gen_score(h: int, w: int, seed: int) -> np.ndarray:
+    """The random 2-D score of the mask generator (Alg. 1), uniform in [0, 1), at the input resolution."""
+    return np.random.default_rng(seed).random((h, w), dtype=np.float32)
+
+
 @dataclass
 class ConvInputs:
     spec: ConvSpec
@@ -344,6 +349,11 @@ def config5(batch: int = 16, sparsity: float = 0.3, dtype: str = "bf16") -> List
     conv("neck_128_64_80", "synthetic:n3", "n3", 128, 64, 80, 1, 1)
     conv("neck_256_256_40", "synthetic:n4", "n4", 256, 256, 40, 1, 1)
     return ops
+
+
+def with_spatial_masks(ops: List[NetOp]) -> List[NetOp]:
+    """The same graph with one 2-D mask per conv layer shared by the batch (the paper's mask shape)."""
+    return [replace(o, spec=o.spec.with_(mask_mode="spatial")) if o.kind == "conv" else o for o in ops]
 
 
 def network_input_shape(ops: List[NetOp]):
