@@ -154,6 +154,47 @@ def masked_conv2d_rows(spec, x, w, bias, mask, rows, want_absum: bool = False):
     return (y, absum) if want_absum else y
 
 
+def row_mask(spec, mask: np.ndarray) -> np.ndarray:
+    """One mask byte per lowered row (a 2-D mask is shared by every image of the batch)."""
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).ravel()
+    assert mask.size == spec.mask_len
+    return mask if spec.mask_mode == "row" else np.tile(mask, spec.n)
+
+
+def to_compact(t_dense: np.ndarray, mask_rows: np.ndarray) -> np.ndarray:
+    """The kept rows of a dense NHWC map [N,H,W,C], ascending, as a matrix [kept, C]: what the GEMM
+    of Sec. 3.2 stage (ii) leaves before the zeros are re-inserted."""
+    m = mask_rows.size
+    c = t_dense.size // m
+    return np.ascontiguousarray(t_dense.reshape(m, c)[mask_rows == 1])
+
+
+def from_compact(t_compact: np.ndarray, mask_rows: np.ndarray, shape) -> np.ndarray:
+    """Alg. 2 post-processing: the compact rows placed at their dense positions, +0.0 elsewhere."""
+    m = mask_rows.size
+    t_compact = np.asarray(t_compact)
+    out = np.zeros((m, t_compact.shape[1]), dtype=t_compact.dtype)
+    out[mask_rows == 1] = t_compact
+    return out.reshape(shape)
+
+
+def masked_conv2d_compact(spec, x, w, bias, mask, x_compact: bool = False, y_compact: bool = False):
+    """The masked convolution with compact operands (NHWC only).
+
+    x_compact: ``x`` is [kept, Cin], the kept rows of the layer's input map -- only a 1x1 stride-1
+    unpadded layer can take it (its window is the pixel itself, so the dropped pixels of the input are
+    never read by a kept output row).  y_compact: the result is [kept, Cout] instead of the dense map.
+    Both are defined through the dense-layout convolution: expand, convolve, take the kept rows.
+    """
+    assert spec.layout == "nhwc"
+    rm = row_mask(spec, mask)
+    if x_compact:
+        assert (spec.kh, spec.kw, spec.stride_h, spec.stride_w, spec.pad_h, spec.pad_w) == (1, 1, 1, 1, 0, 0)
+        x = from_compact(_f32(x), rm, spec.x_shape())
+    y = masked_conv2d(spec, x, w, bias, mask)
+    return to_compact(y, rm) if y_compact else y
+
+
 def round_storage(a: np.ndarray, dtype: str) -> np.ndarray:
     """Round float32 values to the storage type of a layer output (nearest even), widened back."""
     a = np.array(a, dtype=np.float32, order="C", copy=True)

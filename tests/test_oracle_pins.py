@@ -152,6 +152,63 @@ def test_matches_paper_pipeline_bruteforce(g, layout, mask_mode):
     np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
 
 
+def paper_stage_two(spec, x, w, b, mask):
+    """Stage (ii) of Sec. 3.2 alone: the GEMM over the kept rows of the explicit lowering matrix."""
+    a = lowered_matrix(spec, x)
+    bmat = w.reshape(spec.c_out, spec.k).astype(np.float64).T
+    rm = row_mask(spec, mask)
+    compact = a[rm == 1] @ bmat
+    if b is not None:
+        compact = compact + b.astype(np.float64)[None, :]
+    return np.maximum(compact, 0.0) if spec.relu else compact
+
+
+@pytest.mark.parametrize("g", GEOMS)
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+def test_compact_output_is_the_gemm_result_before_expansion(g, mask_mode):
+    spec = make_spec(g, "nhwc", bias=True, relu=True, s=0.35, mask_mode=mask_mode)
+    x, w, b, mask = rand_inputs(spec, 29)
+    got = oracle.masked_conv2d_compact(spec, x, w, b, mask, y_compact=True)
+    ref = paper_stage_two(spec, x, w, b, mask)
+    assert got.shape == ref.shape == (int(row_mask(spec, mask).sum()), spec.c_out)
+    np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
+
+
+def test_expansion_of_compact_rows_is_the_backward_walk_of_alg2():
+    rng = np.random.default_rng(31)
+    rm = W.gen_mask(40, 23, 3)
+    compact = rng.standard_normal((23, 5)).astype(np.float32)
+    out = np.full((40, 5), np.nan, dtype=np.float32)
+    out[:23] = compact
+    idx = 22
+    for r in range(39, -1, -1):                   # Alg. 2: from the last pixel to the first, in place
+        if rm[r] == 0:
+            out[r] = 0.0
+        else:
+            out[r] = out[idx]
+            idx -= 1
+    got = oracle.from_compact(compact, rm, (40, 5))
+    assert np.array_equal(got.view(np.uint32), out.view(np.uint32))
+    assert np.array_equal(oracle.to_compact(got, rm), compact)
+
+
+def test_pointwise_layer_on_compact_input_is_a_plain_matrix_product():
+    """A 1x1 stride-1 layer reads only the pixel itself: on the kept rows it is X_kept @ W^T + b."""
+    spec = make_spec(GEOMS[2], "nhwc", bias=True, relu=False, s=0.4)
+    x, w, b, mask = rand_inputs(spec, 37)
+    rm = row_mask(spec, mask)
+    x[...] = np.where(rm.reshape(spec.n, spec.h, spec.w, 1) == 1, x, 0.0)      # the producer left zeros there
+    xc = oracle.to_compact(x, rm)
+    ref = xc.astype(np.float64) @ w.reshape(spec.c_out, spec.c_in).astype(np.float64).T + b.astype(np.float64)
+    got = oracle.masked_conv2d_compact(spec, xc, w, b, mask, x_compact=True, y_compact=True)
+    np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
+    dense = oracle.masked_conv2d_compact(spec, xc, w, b, mask, x_compact=True)
+    assert np.array_equal(dense, oracle.masked_conv2d(spec, x, w, b, mask))
+    # garbage at the dropped pixels of a dense input does not reach the kept rows either
+    x2 = np.where(rm.reshape(spec.n, spec.h, spec.w, 1) == 1, x, np.float32(1e6))
+    assert np.array_equal(oracle.masked_conv2d(spec, x2, w, b, mask), dense)
+
+
 def test_spatial_mask_is_row_mask_tiled():
     spec = make_spec(GEOMS[3], s=0.5, mask_mode="spatial")
     x, w, b, mask = rand_inputs(spec, 3)
