@@ -114,6 +114,24 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
 sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
                           void* hip_stream);
 
+/*
+ * The masked convolution with compact operands (NHWC layers): between two layers that share one mask
+ * -- propagated masks are the same for every layer of one resolution, Sec. 3.1 -- the zeros of stage
+ * (iii) of Sec. 3.2 and the gather of stage (i) cancel, so a pointwise consumer can take the GEMM
+ * result of its producer as it is.
+ *   y_rows = SC_ROWS_COMPACT: y_dev is [kept][Cout]; row i is the result of lowered row row_idx[i]
+ *            (ascending, see sparse_conv_plan_info).  Nothing else is written: no zeros, no scatter.
+ *   x_rows = SC_ROWS_COMPACT: x_dev is [kept][Cin]; row i is input pixel row_idx[i] of THIS layer's
+ *            mask.  Only for 1x1 windows with stride 1 and no padding (the window is the pixel itself,
+ *            so a kept row never reads a dropped pixel); SC_ERR_UNSUPPORTED otherwise, also for NCHW
+ *            plans and for formats other than the two below.
+ *   SC_ROWS_DENSE for both is sparse_conv_run.  The out_mode of the plan applies to dense outputs only.
+ * Pointer and alignment rules as for sparse_conv_run; no allocation, no synchronisation.
+ */
+typedef enum { SC_ROWS_DENSE = 0, SC_ROWS_COMPACT = 1 } sc_rows_format;
+sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
+                               void* y_dev, int32_t y_rows, void* hip_stream);
+
 /* The same kernels with the identity row map: the ordinary dense convolution (the paper's
  * baseline; its GEMM is unchanged, App. A).  Ignores the mask. */
 sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,

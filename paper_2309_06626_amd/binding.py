@@ -65,6 +65,8 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_plan.argtypes = [pd, vp, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
         L.sparse_conv_run.restype = ctypes.c_int
         L.sparse_conv_run.argtypes = [vp, vp, vp, vp, vp]
+        L.sparse_conv_run_rows.restype = ctypes.c_int
+        L.sparse_conv_run_rows.argtypes = [vp, vp, i32, vp, vp, i32, vp]
         L.dense_conv_run.restype = ctypes.c_int
         L.dense_conv_run.argtypes = [vp, vp, vp, vp, vp]
         L.sparse_conv_plan_info.restype = ctypes.c_int
@@ -184,18 +186,60 @@ def sparse_conv_plan(desc: sc_conv_desc, mask: torch.Tensor, w: torch.Tensor,
     return Plan(out.value, desc, workspace)
 
 
-def _run(fn, name, plan: Plan, x, bias, y, stream):
+def _check_operands(plan: Plan, x, bias, y, x_compact=False, y_compact=False):
+    """The library cannot see tensor sizes: a wrong one would be an out-of-bounds access on the GPU."""
+    d = plan.desc
     for t, what in ((x, "x"), (y, "y")):
-        if _CODE_OF_TORCH.get(t.dtype) != plan.desc.dtype:
+        if _CODE_OF_TORCH.get(t.dtype) != d.dtype:
             raise ValueError(f"{what} dtype does not match the plan")
-    if bias is not None and bias.dtype != torch.float32:
-        raise ValueError("bias must be float32")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != d.c_out):
+        raise ValueError("bias must be float32[c_out]")
+    info = sparse_conv_plan_info(plan)
+    want_x = info["kept"] * d.c_in if x_compact else d.n * d.h * d.w * d.c_in
+    want_y = (info["kept"] if y_compact else info["m"]) * d.c_out
+    if x.numel() != want_x:
+        raise ValueError(f"x holds {x.numel()} elements, the plan needs {want_x}")
+    if y.numel() != want_y:
+        raise ValueError(f"y holds {y.numel()} elements, the plan needs {want_y}")
+
+
+def _run(fn, name, plan: Plan, x, bias, y, stream):
+    _check_operands(plan, x, bias, y)
     _check(fn(plan.handle, _dev_ptr(x, "x"), _dev_ptr(bias, "bias"), _dev_ptr(y, "y"), _stream_handle(stream)), name)
     return y
 
 
 def sparse_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):
     return _run(lib().sparse_conv_run, "sparse_conv_run", plan, x, bias, y, stream)
+
+
+SC_ROWS_DENSE, SC_ROWS_COMPACT = 0, 1
+
+
+def sparse_conv_run_rows(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor,
+                         x_rows: int = SC_ROWS_DENSE, y_rows: int = SC_ROWS_DENSE, stream=None):
+    """sparse_conv_run with compact operands: x = [kept, Cin] and / or y = [kept, Cout]."""
+    _check_operands(plan, x, bias, y, x_rows == SC_ROWS_COMPACT, y_rows == SC_ROWS_COMPACT)
+    _check(lib().sparse_conv_run_rows(plan.handle, _dev_ptr(x, "x"), x_rows, _dev_ptr(bias, "bias"), _dev_ptr(y, "y"),
+                                      y_rows, _stream_handle(stream)), "sparse_conv_run_rows")
+    return y
+
+
+def prepared_run_rows(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor,
+                      x_rows: int = SC_ROWS_DENSE, y_rows: int = SC_ROWS_DENSE, stream=None):
+    """Like prepared_run, for sparse_conv_run_rows."""
+    sparse_conv_run_rows(plan, x, bias, y, x_rows, y_rows, stream)
+    fn, h, px, pb, py, st = lib().sparse_conv_run_rows, plan.handle, x.data_ptr(), \
+        (bias.data_ptr() if bias is not None else None), y.data_ptr(), _stream_handle(stream)
+    keep = (plan, x, bias, y)
+
+    def call(stream_handle=None):
+        rc = fn(h, px, x_rows, pb, py, y_rows, st if stream_handle is None else stream_handle)
+        if rc != SC_OK:
+            raise ScError(rc, "sparse_conv_run_rows")
+        return keep[3]
+
+    return call
 
 
 def dense_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):

@@ -38,6 +38,9 @@ struct ConvParams {
   int32_t zero_fill;       // write zeros at dropped rows
   int32_t mask_spatial;    // mask has ho_wo entries shared by the batch
   int32_t vec_out;         // y rows are channel-contiguous and 16-byte groups are aligned
+  // compact row formats (NHWC): x holds only the kept rows of the input map, row i = pixel row_idx[i]
+  // (pointwise stride-1 layers); y receives only the kept rows, row i = result of row_idx[i]
+  int32_t x_compact, y_compact;
   int32_t m_tiles, n_tiles;
   // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;

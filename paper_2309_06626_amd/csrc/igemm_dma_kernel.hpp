@@ -135,9 +135,10 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const bool present = m0 + lrow + 32 * j < p.rows;
-    const int rr = present ? a_row[j] : -1;
+    const int ic = m0 + lrow + 32 * j;                       // position in the compacted GEMM
+    const int rr = present ? (p.y_compact ? ic : a_row[j]) : -1;   // row the epilogue stores to
     s_rows[lrow + 32 * j] = rr;
-    const int rc = present ? rr : 0;
+    const int rc = present ? (p.x_compact ? ic : a_row[j]) : 0;    // row the window is read from
     const int n = fast_div(rc, p.div_howo_mul, p.div_howo_shift), rem = rc - n * p.ho_wo;
     const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
     a_iy0[j] = present ? oy * p.sh - p.ph : -(1 << 30);      // no tap of an absent row is in range

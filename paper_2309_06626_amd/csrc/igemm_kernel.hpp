@@ -78,7 +78,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     const int ic = m0 + lrow + 32 * j;
     int rr = -1;
     if (ic < p.rows) rr = p.row_idx ? p.row_idx[ic] : ic;
-    s_rows[lrow + 32 * j] = rr;   // eight threads write the same value; read again in the epilogue
+    s_rows[lrow + 32 * j] = (rr >= 0 && p.y_compact) ? ic : rr;   // row the epilogue stores to (eight threads write the same value)
+    if (rr >= 0 && p.x_compact) rr = ic;                          // row the window is read from
     if (rr >= 0) {
       int n = fast_div(rr, p.div_howo_mul, p.div_howo_shift), rem = rr - n * p.ho_wo;
       int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;

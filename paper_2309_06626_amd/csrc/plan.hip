@@ -351,8 +351,10 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->vec = 16 / eb;
   g->rowseg = false;
   g->epad = g->hp = g->wp_cols = 0;
+  // (window-row gather; not for pointwise layers, whose window row is one pixel and which may be handed
+  // the kept rows of their input only)
   if (d->layout == SC_NHWC && d->dtype != SC_F32 && d->c_in % g->vec != 0 && d->dil_w == 1 && d->kw * d->c_in <= 64 &&
-      (d->w * d->c_in) % 8 == 0) {
+      (d->w * d->c_in) % 8 == 0 && d->kh * d->kw > 1) {
     const int epad = (d->kw * d->c_in + 7) / 8 * 8;
     const int over = (epad - d->kw * d->c_in + d->c_in - 1) / d->c_in;      // pixels the last group reads past the window
     const int max_iy = (g->ho - 1) * d->stride_h - d->pad_h + (d->kh - 1) * d->dil_h;
@@ -633,17 +635,19 @@ static void magic_div(uint32_t d, uint32_t* mul, uint32_t* shift) {
 }
 
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
-                             hipStream_t stream) {
+                             hipStream_t stream, bool x_compact = false, bool y_compact = false) {
   const sc_conv_desc& d = pl->desc;
   const Geometry& g = pl->geo;
   const int which = dense ? 1 : 0;
   const int64_t rows = dense ? g.m : pl->kept;
-  const bool zero_fill = !dense && d.out_mode == SC_OUT_ZERO_FILL && pl->kept < g.m;
-  // a mask that keeps every row makes the row list the identity: skip the indirection
-  const bool identity = dense || pl->kept == g.m;
+  const bool zero_fill = !dense && !y_compact && d.out_mode == SC_OUT_ZERO_FILL && pl->kept < g.m;
+  // a mask that keeps every row makes the row list the identity: skip the indirection; so does a run
+  // whose input and output both hold the kept rows only (row i in, row i out)
+  const bool identity = dense || pl->kept == g.m || (x_compact && y_compact);
+  const bool compact = !identity && (x_compact || y_compact);
   const int eb = elem_bytes(d.dtype);
   if (rows == 0) {
-    if (d.out_mode == SC_OUT_ZERO_FILL) {
+    if (d.out_mode == SC_OUT_ZERO_FILL && !y_compact) {
       int64_t bytes = g.y_elems * eb;
       int64_t n16 = bytes / 16;
       int ntail = (int)(bytes - n16 * 16);
@@ -656,7 +660,9 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   }
   // the streaming variant measured no faster than the tiled kernel on the benchmark layers, so the
   // automatic choice takes it only on request
-  const bool use_band = pl->band.ok && (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !pl->band.stream));
+  // the band kernels address input and output by dense position: runs with a compact operand take a tiled kernel
+  const bool use_band = pl->band.ok && !x_compact && !y_compact &&
+                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !pl->band.stream));
   if (use_band) {
     const BandPlan& b = pl->band;
     BandParams q;
@@ -739,6 +745,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.zero_fill = zero_fill ? 1 : 0;
   p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
   p.vec_out = g.vec_out ? 1 : 0;
+  p.x_compact = compact && x_compact ? 1 : 0;
+  p.y_compact = compact && y_compact ? 1 : 0;
 #ifdef SC_TIMING
   p.dbg = g_dbg;
 #endif
@@ -748,6 +756,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
   LaunchFn fn = !g.vec_gather ? ke.elem
                 : (g.vec_out && pl->gather_pipeline != 1) ? (g.k_tiles <= 2 ? ke.dma2 : ke.dma) : ke.vec;
+  if (g.rowseg && x_compact) return SC_ERR_UNSUPPORTED;   // the zero-margined copy is built from a dense input
   if (g.rowseg) {
     // small-channel gather: refresh the interior of the zero-margined input copy, then gather window rows
     // from it (no padding in the copy's coordinates: the margins are the padding)
@@ -957,6 +966,20 @@ sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* b
   sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
   if (s != SC_OK) return s;
   return launch_conv(plan, false, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream));
+}
+
+sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
+                               void* y_dev, int32_t y_rows, void* hip_stream) {
+  sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (s != SC_OK) return s;
+  if ((x_rows != SC_ROWS_DENSE && x_rows != SC_ROWS_COMPACT) || (y_rows != SC_ROWS_DENSE && y_rows != SC_ROWS_COMPACT))
+    return SC_ERR_UNSUPPORTED;
+  const sc_conv_desc& d = plan->desc;
+  const bool xc = x_rows == SC_ROWS_COMPACT, yc = y_rows == SC_ROWS_COMPACT;
+  if ((xc || yc) && d.layout != SC_NHWC) return SC_ERR_UNSUPPORTED;
+  if (xc && !(d.kh == 1 && d.kw == 1 && d.stride_h == 1 && d.stride_w == 1 && d.pad_h == 0 && d.pad_w == 0))
+    return SC_ERR_UNSUPPORTED;   // only a window that is the pixel itself never reads a dropped pixel
+  return launch_conv(plan, false, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream), xc, yc);
 }
 
 sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
