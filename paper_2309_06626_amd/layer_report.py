@@ -150,6 +150,46 @@ def chain_time(ops, base_seed, steps, dense=False):
     return eager, timed(graph.replay)
 
 
+def compact_format_times(steps):
+    """us per launch of the pointwise benchmark layers (config 4, 56x56 and 28x28 maps) and of the
+    ResNet18 stage-1 layer with dense and with compact operands; the dense run of the same plan beside them."""
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd import runtime as R
+    from paper_2309_06626_amd.metrics import time_launches
+
+    specs = [s for s in W.config4() if s.h in (56, 28)] + [W.config2(0.5)]
+    rows = []
+    warm = max(steps // 10, 5)
+    for spec in specs:
+        ci = W.make_conv_inputs(spec, W.base_seed(4))
+        layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+        kept = layer.info["kept"]
+        dt = B.TORCH_DTYPE[spec.dtype]
+        x = R.to_device(ci.x, spec.dtype)
+        y = layer.new_output().zero_()
+        xc = torch.randn((kept, spec.c_in), device="cuda:0").clamp_(min=0).to(dt)
+        yc = torch.zeros((kept, spec.c_out), dtype=dt, device="cuda:0")
+        pointwise = spec.kh == 1 and spec.kw == 1
+        rec = {"layer": spec.name, "m": spec.m, "kept": kept, "k": spec.k, "c_out": spec.c_out}
+        D, C = B.SC_ROWS_DENSE, B.SC_ROWS_COMPACT
+        for key, xa, xf, ya, yf in (("dense_dense", x, D, y, D), ("dense_compact", x, D, yc, C),
+                                    ("compact_dense", xc, C, y, D), ("compact_compact", xc, C, yc, C)):
+            if xf == C and not pointwise:
+                rec[key + "_us"] = None
+                continue
+            _, t = time_launches(B.prepared_run_rows(layer.plan, xa, layer.bias, ya, xf, yf), steps, warm)
+            rec[key + "_us"] = t * 1e6
+        _, t = time_launches(B.prepared_run(layer.plan, x, layer.bias, y, dense=True), steps, warm)
+        rec["dense_run_us"] = t * 1e6
+        rows.append(rec)
+        del layer, x, y, xc, yc
+        torch.cuda.empty_cache()
+    return rows
+
+
 def mask_generator_times(steps):
     """us per call of the mask generator (two launches) for the layer resolutions of the two networks."""
     import torch
@@ -178,6 +218,7 @@ def main():
     ap.add_argument("--library-conv", action="store_true",
                     help="also time torch.nn.functional.conv2d (MIOpen, dense) on every shape, as context")
     ap.add_argument("--masks", action="store_true", help="also time the mask generator (Alg. 1, getMask)")
+    ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
     args = ap.parse_args()
 
     import torch
@@ -239,6 +280,17 @@ def main():
         print("|---|---|---|")
         for k, v in chains.items():
             print(f"| {k} | {v[0]:.1f} | {v[1]:.1f} |")
+    compact_rows = []
+    if args.compact:
+        compact_rows = compact_format_times(args.steps)
+        fmt = lambda v: "-" if v is None else f"{v:.2f}"
+        print()
+        print("| layer (s = 0.5) | M x K x Cout | dense in, dense out (sparse_conv_run) us | dense in, compact out us | "
+              "compact in, dense out us | compact in, compact out us | dense_conv_run us |")
+        print("|---|---|---|---|---|---|---|")
+        for r in compact_rows:
+            print(f"| {r['layer']} | {r['m']}x{r['k']}x{r['c_out']} | {fmt(r['dense_dense_us'])} | {fmt(r['dense_compact_us'])} | "
+                  f"{fmt(r['compact_dense_us'])} | {fmt(r['compact_compact_us'])} | {fmt(r['dense_run_us'])} |")
     mask_rows = []
     if args.masks:
         mask_rows = mask_generator_times(max(args.steps // 4, 20))
@@ -254,6 +306,8 @@ def main():
             f.write(json.dumps({"chains_us": chains}) + "\n")
             if mask_rows:
                 f.write(json.dumps({"mask_generator": mask_rows}) + "\n")
+            if compact_rows:
+                f.write(json.dumps({"compact_formats": compact_rows}) + "\n")
 
 
 if __name__ == "__main__":
