@@ -195,6 +195,50 @@ def masked_conv2d_compact(spec, x, w, bias, mask, x_compact: bool = False, y_com
     return to_compact(y, rm) if y_compact else y
 
 
+def masked_depthwise_conv2d(spec, x, w, bias, mask, want_absum: bool = False):
+    """Masked depthwise convolution (groups == Cin == Cout, NHWC): channel c of the output is the
+    kh x kw cross-correlation of channel c of the input with filter w[c, :, :, 0]; the mask removes output
+    pixels exactly as in Sec. 3 (a dropped pixel is +0.0 in every channel, no bias, no activation).
+
+    The paper speaks of convolutional layers in general and times networks with depthwise layers; it
+    does not spell out this case -- the reading is the masking semantics of Sec. 3 applied unchanged.
+    Direct loop nest over output pixels and taps, double accumulation.
+    """
+    assert spec.layout == "nhwc" and spec.groups == spec.c_in == spec.c_out
+    x64 = np.asarray(x, dtype=np.float32).astype(np.float64)
+    w64 = np.asarray(w, dtype=np.float32).astype(np.float64).reshape(spec.c_out, spec.kh, spec.kw)
+    assert x64.shape == tuple(spec.x_shape())
+    b64 = np.asarray(bias, dtype=np.float32).astype(np.float64) if spec.has_bias else None
+    rm = row_mask(spec, mask).reshape(spec.n, spec.ho, spec.wo)
+    y = np.zeros(spec.y_shape(), dtype=np.float64)
+    absum = np.zeros(spec.y_shape(), dtype=np.float64)
+    for oy in range(spec.ho):
+        for ox in range(spec.wo):
+            acc = np.zeros((spec.n, spec.c_out), dtype=np.float64)
+            mag = np.zeros((spec.n, spec.c_out), dtype=np.float64)
+            for ky in range(spec.kh):
+                iy = oy * spec.stride_h - spec.pad_h + ky * spec.dil_h
+                if iy < 0 or iy >= spec.h:
+                    continue
+                for kx in range(spec.kw):
+                    ix = ox * spec.stride_w - spec.pad_w + kx * spec.dil_w
+                    if ix < 0 or ix >= spec.w:
+                        continue
+                    term = x64[:, iy, ix, :] * w64[None, :, ky, kx]
+                    acc = acc + term
+                    mag = mag + np.abs(term)
+            if b64 is not None:
+                acc = acc + b64[None, :]
+                mag = mag + np.abs(b64)[None, :]
+            if spec.relu:
+                acc = np.maximum(acc, 0.0)
+            keep = rm[:, oy, ox][:, None] == 1
+            y[:, oy, ox, :] = np.where(keep, acc, 0.0)
+            absum[:, oy, ox, :] = np.where(keep, mag, 0.0)
+    y = y.astype(np.float32)
+    return (y, absum) if want_absum else y
+
+
 def round_storage(a: np.ndarray, dtype: str) -> np.ndarray:
     """Round float32 values to the storage type of a layer output (nearest even), widened back."""
     a = np.array(a, dtype=np.float32, order="C", copy=True)

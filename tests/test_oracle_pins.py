@@ -471,3 +471,75 @@ def test_small_resnet_chain_matches_library_pipeline():
     ref = tt[last].permute(0, 2, 3, 1).numpy()
     np.testing.assert_allclose(t[last], ref, rtol=2e-4, atol=2e-5)
     assert t[last].shape == (1, 1, 1, 512)
+
+
+# ---------------------------------------------------------------------------------------
+# depthwise layers (groups == Cin == Cout)
+# ---------------------------------------------------------------------------------------
+DW_GEOMS = [
+    # n, c, h, w, kh, kw, sh, sw, ph, pw, dh, dw
+    (2, 5, 7, 9, 3, 3, 1, 1, 1, 1, 1, 1),
+    (1, 8, 10, 6, 3, 3, 2, 2, 1, 1, 1, 1),
+    (3, 3, 6, 6, 5, 5, 1, 1, 2, 2, 1, 1),
+    (1, 4, 9, 8, 3, 2, 1, 2, 0, 1, 2, 1),
+    (2, 6, 5, 5, 1, 1, 1, 1, 0, 0, 1, 1),
+]
+
+
+def dw_spec(g, bias=True, relu=False, s=0.4, mask_mode="row"):
+    n, c, h, w, kh, kw, sh, sw, ph, pw, dh, dw = g
+    return W.ConvSpec("dw", n=n, c_in=c, h=h, w=w, c_out=c, kh=kh, kw=kw, stride_h=sh, stride_w=sw, pad_h=ph,
+                      pad_w=pw, dil_h=dh, dil_w=dw, dtype="f32", has_bias=bias, relu=relu, sparsity=s,
+                      mask_mode=mask_mode, groups=c)
+
+
+@pytest.mark.parametrize("g", DW_GEOMS)
+@pytest.mark.parametrize("bias,relu", [(False, False), (True, True)])
+def test_depthwise_matches_library_grouped_conv2d(g, bias, relu):
+    spec = dw_spec(g, bias, relu, s=0.0)
+    x, w, b, mask = rand_inputs(spec, 41)
+    assert w.shape == (spec.c_out, spec.kh, spec.kw, 1) and mask.all()
+    xt = torch.from_numpy(x).double().permute(0, 3, 1, 2)
+    wt = torch.from_numpy(w).double().permute(0, 3, 1, 2)
+    ref = F.conv2d(xt, wt, torch.from_numpy(b).double() if bias else None, (spec.stride_h, spec.stride_w),
+                   (spec.pad_h, spec.pad_w), (spec.dil_h, spec.dil_w), groups=spec.c_in)
+    if relu:
+        ref = torch.relu(ref)
+    ref = ref.permute(0, 2, 3, 1).numpy()
+    got = oracle.masked_depthwise_conv2d(spec, x, w, b, mask)
+    np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
+    # any mask: the dense result times the mask, exact zeros at dropped pixels
+    spec_s = spec.with_(sparsity=0.4)
+    mask = W.gen_mask(spec_s.mask_len, W.n_keep(0.4, spec_s.mask_len), 5)
+    got = oracle.masked_depthwise_conv2d(spec_s, x, w, b, mask).reshape(spec.m, spec.c_out)
+    np.testing.assert_allclose(got, ref.reshape(spec.m, spec.c_out) * mask[:, None], rtol=3e-7, atol=1e-7)
+    assert (got[mask == 0].view(np.uint32) == 0).all()
+
+
+@pytest.mark.parametrize("g", DW_GEOMS)
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+def test_depthwise_is_the_full_convolution_with_block_diagonal_filters(g, mask_mode):
+    """A depthwise layer is an ordinary one whose filter for output channel c is zero on every other
+    input channel; the ordinary oracle (pinned above) must give the same numbers."""
+    spec = dw_spec(g, True, True, s=0.35, mask_mode=mask_mode)
+    x, w, b, mask = rand_inputs(spec, 43)
+    full = np.zeros((spec.c_out, spec.kh, spec.kw, spec.c_in), dtype=np.float32)
+    for c in range(spec.c_out):
+        full[c, :, :, c] = w[c, :, :, 0]
+    ref, ref_abs = oracle.masked_conv2d(spec.with_(groups=1), x, full, b, mask, want_absum=True)
+    got, got_abs = oracle.masked_depthwise_conv2d(spec, x, w, b, mask, want_absum=True)
+    np.testing.assert_allclose(got, ref, rtol=3e-7, atol=1e-7)
+    np.testing.assert_allclose(got_abs, ref_abs, rtol=1e-12, atol=1e-12)
+
+
+def test_depthwise_single_tap_filters_shift_each_channel_separately():
+    spec = dw_spec((1, 3, 6, 6, 3, 3, 1, 1, 1, 1, 1, 1), bias=False, relu=False, s=0.0)
+    x = np.random.default_rng(47).standard_normal(spec.x_shape()).astype(np.float32)
+    w = np.zeros(spec.w_shape(), np.float32)
+    w[0, 1, 1, 0] = 1.0      # channel 0: centre tap, identity
+    w[1, 0, 1, 0] = 2.0      # channel 1: the pixel above, doubled
+    w[2, 1, 2, 0] = -1.0     # channel 2: the pixel to the right, negated
+    y = oracle.masked_depthwise_conv2d(spec, x, w, None, np.ones(spec.mask_len, np.uint8))
+    assert np.array_equal(y[..., 0], x[..., 0])
+    assert np.array_equal(y[0, 1:, :, 1], 2.0 * x[0, :-1, :, 1]) and (y[0, 0, :, 1] == 0).all()
+    assert np.array_equal(y[0, :, :-1, 2], -x[0, :, 1:, 2]) and (y[0, :, -1, 2] == 0).all()

@@ -114,6 +114,7 @@ class ConvSpec:
     sparsity: float = 0.5
     mask_mode: str = "row"  # "row": uint8[N*Ho*Wo]; "spatial": uint8[Ho*Wo] shared by the batch
     layer_index: int = 0
+    groups: int = 1  # 1, or c_in == c_out == groups: depthwise (every channel has its own kh x kw filter)
 
     @property
     def ho(self) -> int:
@@ -129,7 +130,7 @@ class ConvSpec:
 
     @property
     def k(self) -> int:
-        return self.kh * self.kw * self.c_in
+        return self.kh * self.kw * (self.c_in // self.groups)
 
     @property
     def mask_len(self) -> int:
@@ -140,8 +141,8 @@ class ConvSpec:
 
     def w_shape(self):
         if self.layout == "nhwc":
-            return (self.c_out, self.kh, self.kw, self.c_in)
-        return (self.c_out, self.c_in, self.kh, self.kw)
+            return (self.c_out, self.kh, self.kw, self.c_in // self.groups)
+        return (self.c_out, self.c_in // self.groups, self.kh, self.kw)
 
     def y_shape(self):
         if self.layout == "nhwc":
@@ -175,7 +176,7 @@ def gen_activations(shape, seed: int, dtype: str) -> np.ndarray:
 
 def gen_weights(spec: ConvSpec, seed: int) -> np.ndarray:
     rng = np.random.default_rng(seed)
-    std = math.sqrt(2.0 / (spec.c_in * spec.kh * spec.kw))
+    std = math.sqrt(2.0 / (spec.c_in // spec.groups * spec.kh * spec.kw))
     w = rng.standard_normal(size=spec.w_shape(), dtype=np.float32) * np.float32(std)
     return quantize(w, spec.dtype)
 
