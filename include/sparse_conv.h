@@ -45,7 +45,7 @@ typedef enum {
   SC_OK = 0,
   SC_ERR_NULL = 1,        /* a required pointer is NULL */
   SC_ERR_BAD_SHAPE = 2,   /* non-positive extent, empty output, or a tensor too large for 32-bit element offsets */
-  SC_ERR_UNSUPPORTED = 3, /* groups != 1, unknown dtype/layout/mode */
+  SC_ERR_UNSUPPORTED = 3, /* groups other than 1 or depthwise, unknown dtype/layout/mode/format */
   SC_ERR_MASK_COUNT = 4,  /* popcount(mask) differs from the count the sparsity ratio demands */
   SC_ERR_WORKSPACE = 5,   /* workspace smaller than sparse_conv_workspace_bytes() */
   SC_ERR_ALIGN = 6,       /* a device pointer is not aligned to 16 bytes */
@@ -69,7 +69,9 @@ typedef enum { SC_OUT_ZERO_FILL = 0, SC_OUT_SCATTER_ONLY = 1 } sc_out_mode;
 typedef struct {
   int32_t n, c_in, h, w, c_out;
   int32_t kh, kw, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
-  int32_t groups;      /* must be 1 */
+  int32_t groups;      /* 1; or c_in == c_out == groups with SC_NHWC: depthwise, every channel filtered by its
+                          own kh x kw window (filters [C][kh][kw][1]); the mask removes output pixels as for
+                          ordinary layers (Sec. 3), compact formats work alike */
   int32_t dtype;       /* sc_dtype of x, w, y */
   int32_t layout;      /* sc_layout of x, w, y */
   int32_t has_bias;    /* 0/1 */
@@ -151,7 +153,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
  * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_lds_direct",
- * "tile_registers", "tile_row_segments" or "tile_elements".
+ * "tile_registers", "tile_row_segments", "tile_elements" or "depthwise".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
 

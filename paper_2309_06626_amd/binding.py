@@ -108,7 +108,7 @@ def make_desc(n, c_in, h, w, c_out, kh=3, kw=3, stride_h=1, stride_w=1, pad_h=1,
 def desc_from_spec(spec, out_mode=SC_OUT_ZERO_FILL, check_count=True) -> sc_conv_desc:
     """Descriptor of a workloads.ConvSpec."""
     return make_desc(spec.n, spec.c_in, spec.h, spec.w, spec.c_out, spec.kh, spec.kw, spec.stride_h, spec.stride_w,
-                     spec.pad_h, spec.pad_w, spec.dil_h, spec.dil_w, 1, DTYPE_CODE[spec.dtype],
+                     spec.pad_h, spec.pad_w, spec.dil_h, spec.dil_w, getattr(spec, "groups", 1), DTYPE_CODE[spec.dtype],
                      SC_NCHW if spec.layout == "nchw" else SC_NHWC, spec.has_bias, spec.relu,
                      SC_MASK_SPATIAL if spec.mask_mode == "spatial" else SC_MASK_ROW, out_mode,
                      spec.sparsity if check_count else -1.0)
@@ -175,7 +175,14 @@ def sparse_conv_plan(desc: sc_conv_desc, mask: torch.Tensor, w: torch.Tensor,
         raise ValueError("mask must be uint8")
     if _CODE_OF_TORCH.get(w.dtype) != desc.dtype:
         raise ValueError("filter dtype does not match the descriptor")
-    nbytes = sparse_conv_workspace_bytes(desc)
+    nbytes = sparse_conv_workspace_bytes(desc)    # also validates the descriptor
+    ho, wo, m = sparse_conv_output_shape(desc)
+    want_mask = m if desc.mask_mode == SC_MASK_ROW else ho * wo
+    want_w = desc.c_out * desc.kh * desc.kw * (desc.c_in // desc.groups)
+    if mask.numel() != want_mask:
+        raise ValueError(f"mask holds {mask.numel()} bytes, the layer needs {want_mask}")
+    if w.numel() != want_w:
+        raise ValueError(f"filters hold {w.numel()} elements, the layer needs {want_w}")
     if workspace is None:
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=mask.device)
     out = ctypes.c_void_p()

@@ -55,6 +55,21 @@ struct ConvParams {
 #endif
 };
 
+// depthwise layers (groups == Cin == Cout, NHWC)
+struct DepthwiseParams {
+  const void* x;
+  const void* wp;          // filters repacked to [kh*kw][C]
+  const float* bias;       // may be null
+  void* y;
+  const int32_t* row_idx;  // items are kept rows (scatter-only and compact output); null: items are dense rows
+  const uint8_t* mask;     // non-null: items are dense rows and a lane whose pixel is dropped stores zeros
+  int64_t items;
+  int32_t c, h, w, ho_wo, wo;
+  int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
+  int32_t relu, mask_spatial, x_compact, y_compact;
+  uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+};
+
 __device__ __forceinline__ int fast_div(int n, uint32_t mul, uint32_t shift) {
   return (int)(uint32_t)(((uint64_t)(uint32_t)n * mul) >> shift);
 }
@@ -86,5 +101,9 @@ LaunchFn rowseg_kernel(int dtype, int bm, int bn);
 const KernelEntry* kernels_bf16(int* count);
 const KernelEntry* kernels_f16(int* count);
 const KernelEntry* kernels_f32(int* count);
+
+// depthwise.hip
+hipError_t depthwise_launch(int dtype, const DepthwiseParams& p, hipStream_t stream);
+hipError_t depthwise_pack(int dtype, const void* w, void* wp, int c, int taps, hipStream_t stream);
 
 }  // namespace sc

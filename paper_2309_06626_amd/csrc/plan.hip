@@ -311,6 +311,7 @@ struct Geometry {
   // small-channel gather (NHWC, 16-bit, Cin*eb not a multiple of 16 bytes, e.g. the 3-channel stem): a
   // window row of kw*Cin contiguous elements is fetched as ceil(kw*Cin/8) unaligned 16-byte groups
   // from a zero-margined copy of the input, so no tap needs a bounds check
+  bool depthwise;          // groups == Cin == Cout: its own kernel, no lowering
   bool rowseg;
   int32_t epad, hp, wp_cols;   // K entries per window row (padded to 8), padded input height and width
   size_t off_xpad;
@@ -324,7 +325,9 @@ static int out_extent(int in, int k, int stride, int pad, int dil) {
 
 static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   if (!d) return SC_ERR_NULL;
-  if (d->groups != 1) return SC_ERR_UNSUPPORTED;
+  // one group (the paper's lowering) or one channel per group (depthwise, NHWC)
+  const bool depthwise = d->groups != 1;
+  if (depthwise && !(d->groups == d->c_in && d->c_in == d->c_out && d->layout == SC_NHWC)) return SC_ERR_UNSUPPORTED;
   if (d->dtype != SC_F32 && d->dtype != SC_F16 && d->dtype != SC_BF16) return SC_ERR_UNSUPPORTED;
   if (d->layout != SC_NHWC && d->layout != SC_NCHW) return SC_ERR_UNSUPPORTED;
   if (d->mask_mode != SC_MASK_ROW && d->mask_mode != SC_MASK_SPATIAL) return SC_ERR_UNSUPPORTED;
@@ -344,7 +347,8 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->m = (int64_t)d->n * g->ho * g->wo;
   g->x_elems = (int64_t)d->n * d->h * d->w * d->c_in;
   g->y_elems = g->m * d->c_out;
-  int64_t k = (int64_t)d->kh * d->kw * d->c_in;
+  int64_t k = (int64_t)d->kh * d->kw * (depthwise ? 1 : d->c_in);
+  g->depthwise = depthwise;
   if (g->m >= lim || g->x_elems >= lim - (1 << 20) || g->y_elems >= lim || k >= (1 << 24) || d->c_out >= (1 << 24))
     return SC_ERR_BAD_SHAPE;
   const int eb = elem_bytes(d->dtype);
@@ -354,7 +358,7 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   // (window-row gather; not for pointwise layers, whose window row is one pixel and which may be handed
   // the kept rows of their input only)
   if (d->layout == SC_NHWC && d->dtype != SC_F32 && d->c_in % g->vec != 0 && d->dil_w == 1 && d->kw * d->c_in <= 64 &&
-      (d->w * d->c_in) % 8 == 0 && d->kh * d->kw > 1) {
+      (d->w * d->c_in) % 8 == 0 && d->kh * d->kw > 1 && !depthwise) {
     const int epad = (d->kw * d->c_in + 7) / 8 * 8;
     const int over = (epad - d->kw * d->c_in + d->c_in - 1) / d->c_in;      // pixels the last group reads past the window
     const int max_iy = (g->ho - 1) * d->stride_h - d->pad_h + (d->kh - 1) * d->dil_h;
@@ -393,7 +397,7 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   if (g->rowseg) off = align_up(off + ((size_t)d->n * g->hp * g->wp_cols * d->c_in + 64) * eb, 256);
   // split-K (16-bit operands, direct-to-LDS gather, 128-channel tiles, deep K): arrival counters for
   // every output tile (64 x 64 is the smallest split-K tile) and the float partial sums
-  g->splitk_ok = d->dtype != SC_F32 && g->vec_gather && g->vec_out && d->c_out >= 128 && g->k_tiles >= 16;
+  g->splitk_ok = d->dtype != SC_F32 && g->vec_gather && g->vec_out && d->c_out >= 128 && g->k_tiles >= 16 && !depthwise;
   g->off_counters = g->off_partial = off;
   if (g->splitk_ok) {
     const size_t tiles = (size_t)((g->m + 63) / 64) * ((d->c_out + 63) / 64);
@@ -423,6 +427,7 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
   BandPlan bp;
   std::memset(&bp, 0, sizeof(bp));
   const int eb = elem_bytes(d.dtype);
+  if (g.depthwise) return bp;
   if (d.layout != SC_NHWC || !g.vec_gather || !g.vec_out) return bp;
   if ((d.c_in / g.vec) % 2 != 0) return bp;      // a K step of two 16-byte groups must stay inside one tap
   if (d.kh * d.kw == 1) return bp;               // no window overlap to exploit: gather kept rows directly
@@ -660,6 +665,29 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   }
   // the streaming variant measured no faster than the tiled kernel on the benchmark layers, so the
   // automatic choice takes it only on request
+  if (g.depthwise) {
+    DepthwiseParams q;
+    std::memset(&q, 0, sizeof(q));
+    q.x = x;
+    q.wp = pl->ws + g.off_wp;
+    q.bias = d.has_bias ? bias : nullptr;
+    q.y = y;
+    // zero-fill runs walk the dense rows and look at the mask; the others walk the kept rows
+    q.row_idx = (identity || zero_fill) ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+    q.mask = zero_fill ? pl->ws + g.off_mask : nullptr;
+    q.items = zero_fill ? g.m : rows;
+    q.c = d.c_in; q.h = d.h; q.w = d.w; q.ho_wo = g.ho * g.wo; q.wo = g.wo;
+    q.kh = d.kh; q.kw = d.kw; q.sh = d.stride_h; q.sw = d.stride_w; q.ph = d.pad_h; q.pw = d.pad_w;
+    q.dil_h = d.dil_h; q.dil_w = d.dil_w;
+    q.relu = d.relu;
+    q.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
+    q.x_compact = compact && x_compact ? 1 : 0;
+    q.y_compact = compact && y_compact ? 1 : 0;
+    magic_div((uint32_t)q.ho_wo, &q.div_howo_mul, &q.div_howo_shift);
+    magic_div((uint32_t)q.wo, &q.div_wo_mul, &q.div_wo_shift);
+    SC_HIP(depthwise_launch(d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32, q, stream));
+    return SC_OK;
+  }
   // the band kernels address input and output by dense position: runs with a compact operand take a tiled kernel
   const bool use_band = pl->band.ok && !x_compact && !y_compact &&
                         (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !pl->band.stream));
@@ -875,7 +903,10 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   SC_HIP(hipGetLastError());
 
   // filters
-  {
+  if (g.depthwise) {
+    const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
+    SC_HIP(depthwise_pack(dt, w_dev, ws + g.off_wp, d.c_in, d.kh * d.kw, stream));
+  } else {
     int64_t total = (int64_t)g.cout_pad * g.k_stride;
     int grid = (int)((total + 255) / 256);
     const int nchw = d.layout == SC_NCHW;
@@ -889,7 +920,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   }
 
   // gather table
-  {
+  if (!g.depthwise) {
     const int vec = g.vec_gather ? g.vec : 1;
     const int entries = g.k_pad / vec;
     int xs_h, xs_w, xs_c;
@@ -1004,6 +1035,15 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups) {
   if (!plan) return SC_ERR_NULL;
   if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
+  if (plan->geo.depthwise) {   // one lane per pixel and 16-byte channel group, 256 lanes per workgroup
+    const int eb = elem_bytes(plan->desc.dtype);
+    const int v = plan->desc.c_in % (16 / eb) == 0 ? 16 / eb : 1;
+    const bool walk_dense = which == 1 || plan->desc.out_mode == SC_OUT_ZERO_FILL;
+    if (tile_m) *tile_m = 1;
+    if (tile_n) *tile_n = v;
+    if (workgroups) *workgroups = ((walk_dense ? plan->geo.m : plan->kept) * (plan->desc.c_in / v) + 255) / 256;
+    return SC_OK;
+  }
   if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream))) {
     if (tile_m) *tile_m = -plan->band.bh;
     if (tile_n) *tile_n = 32 * plan->band.ni;
@@ -1028,6 +1068,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1)) return nullptr;
+  if (plan->geo.depthwise) return "depthwise";
   if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream)))
     return plan->band.stream ? "band_stream" : plan->band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
@@ -1042,6 +1083,7 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
   if (!plan) return SC_ERR_NULL;
   if (which != 0 && which != 1) return SC_ERR_UNSUPPORTED;
   if (tile_m == 0 && tile_n == 0) { plan->forced[which] = -1; return SC_OK; }
+  if (plan->geo.depthwise) return SC_ERR_UNSUPPORTED;   // one kernel, no tiles to choose
   if (tile_m < 0) {
     if (!plan->band.ok) return SC_ERR_UNSUPPORTED;
     plan->forced[which] = kForceBand;
@@ -1067,7 +1109,7 @@ const char* sc_status_string(sc_status s) {
     case SC_OK: return "ok";
     case SC_ERR_NULL: return "a required pointer is NULL";
     case SC_ERR_BAD_SHAPE: return "bad shape (non-positive extent, empty output or tensor too large)";
-    case SC_ERR_UNSUPPORTED: return "unsupported (groups != 1 or unknown dtype/layout/mode/tile)";
+    case SC_ERR_UNSUPPORTED: return "unsupported (groups other than 1 or depthwise NHWC, or unknown dtype/layout/mode/tile/format)";
     case SC_ERR_MASK_COUNT: return "mask popcount differs from the count the sparsity ratio demands";
     case SC_ERR_WORKSPACE: return "workspace too small";
     case SC_ERR_ALIGN: return "device pointer not sufficiently aligned";

@@ -122,3 +122,13 @@ def test_mask_generator_rejects_bad_arguments_before_any_gpu_work():
     assert gen(fake, 8, 8, 4, 4, float("nan"), fake, fake, 1 << 20, None) == B.SC_ERR_BAD_SHAPE
     assert gen(fake, 8, 8, 4, 4, 0.5, fake, fake, 4 * 4 * 8 - 1, None) == B.SC_ERR_WORKSPACE
     assert gen(fake, 8, 8, 4, 4, 0.5, fake, fake + 4, 1 << 20, None) == B.SC_ERR_ALIGN
+
+
+def test_grouped_layers_other_than_depthwise_are_refused():
+    L = B.lib()
+    size = ctypes.c_size_t()
+    for kw in (dict(c_in=16, c_out=16, groups=4), dict(c_in=16, c_out=32, groups=16), dict(c_in=16, c_out=16, groups=16, layout=B.SC_NCHW)):
+        d = B.make_desc(1, kw["c_in"], 8, 8, kw["c_out"], groups=kw["groups"], layout=kw.get("layout", B.SC_NHWC))
+        assert L.sparse_conv_workspace_bytes(ctypes.byref(d), ctypes.byref(size)) == B.SC_ERR_UNSUPPORTED
+    d = B.make_desc(1, 16, 8, 8, 16, groups=16)
+    assert L.sparse_conv_workspace_bytes(ctypes.byref(d), ctypes.byref(size)) == B.SC_OK
