@@ -68,7 +68,20 @@ struct DepthwiseParams {
   int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
   int32_t relu, mask_spatial, x_compact, y_compact;
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+  // LDS-tiled kernel (3x3 windows)
+  const int32_t* rank;     // [M]: position of a kept row in the row list (compact output); else null
+  int32_t n, ho;           // images, output rows
+  int32_t zero_fill;       // dropped pixels of a dense-layout output receive zeros (else they are left alone)
 };
+
+// Division of 0 <= n < 2^31 by d >= 1 as (n * mul) >> shift in 64-bit arithmetic: with l = ceil(log2 d)
+// and shift = 31 + l, mul = floor(2^shift / d) + 1 fits 32 bits and the quotient is exact.
+inline void magic_div(uint32_t d, uint32_t* mul, uint32_t* shift) {
+  uint32_t l = 0;
+  while (((uint64_t)1 << l) < d) ++l;
+  *shift = 31 + l;
+  *mul = (uint32_t)((((uint64_t)1 << *shift) / d) + 1);
+}
 
 __device__ __forceinline__ int fast_div(int n, uint32_t mul, uint32_t shift) {
   return (int)(uint32_t)(((uint64_t)(uint32_t)n * mul) >> shift);
@@ -105,5 +118,6 @@ const KernelEntry* kernels_f32(int* count);
 // depthwise.hip
 hipError_t depthwise_launch(int dtype, const DepthwiseParams& p, hipStream_t stream);
 hipError_t depthwise_pack(int dtype, const void* w, void* wp, int c, int taps, hipStream_t stream);
+hipError_t depthwise_rank(const int32_t* row_idx, const int32_t* kept_dev, int32_t* rank, int64_t m, hipStream_t stream);
 
 }  // namespace sc

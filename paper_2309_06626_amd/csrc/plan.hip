@@ -630,14 +630,6 @@ static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
   return tp;
 }
 
-// Division of 0 <= n < 2^31 by d >= 1 as (n * mul) >> shift in 64-bit arithmetic: with l = ceil(log2 d)
-// and shift = 31 + l, mul = floor(2^shift / d) + 1 fits 32 bits and the quotient is exact.
-static void magic_div(uint32_t d, uint32_t* mul, uint32_t* shift) {
-  uint32_t l = 0;
-  while (((uint64_t)1 << l) < d) ++l;
-  *shift = 31 + l;
-  *mul = (uint32_t)((((uint64_t)1 << *shift) / d) + 1);
-}
 
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
                              hipStream_t stream, bool x_compact = false, bool y_compact = false) {
@@ -674,8 +666,11 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.y = y;
     // zero-fill runs walk the dense rows and look at the mask; the others walk the kept rows
     q.row_idx = (identity || zero_fill) ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
-    q.mask = zero_fill ? pl->ws + g.off_mask : nullptr;
-    q.items = zero_fill ? g.m : rows;
+    q.mask = identity ? nullptr : pl->ws + g.off_mask;
+    q.items = q.row_idx ? rows : g.m;
+    q.zero_fill = zero_fill ? 1 : 0;
+    q.rank = (compact && y_compact) ? reinterpret_cast<const int32_t*>(pl->ws + g.off_band_rows) : nullptr;
+    q.n = d.n; q.ho = g.ho;
     q.c = d.c_in; q.h = d.h; q.w = d.w; q.ho_wo = g.ho * g.wo; q.wo = g.wo;
     q.kh = d.kh; q.kw = d.kw; q.sh = d.stride_h; q.sw = d.stride_w; q.ph = d.pad_h; q.pw = d.pad_w;
     q.dil_h = d.dil_h; q.dil_w = d.dil_w;
@@ -906,6 +901,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   if (g.depthwise) {
     const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
     SC_HIP(depthwise_pack(dt, w_dev, ws + g.off_wp, d.c_in, d.kh * d.kw, stream));
+    // position of every kept row in the row list (compact output of the LDS-tiled kernel)
+    SC_HIP(depthwise_rank(rows, kept_dev, reinterpret_cast<int32_t*>(ws + g.off_band_rows), g.m, stream));
   } else {
     int64_t total = (int64_t)g.cout_pad * g.k_stride;
     int grid = (int)((total + 255) / 256);

@@ -190,6 +190,39 @@ def compact_format_times(steps):
     return rows
 
 
+def depthwise_times(steps):
+    """Depthwise 3x3 layers (MobileNetV2-style body, batch 64, s = 0.5): us per launch for the dense-layout
+    run, the compact-output run and the dense run, with the HBM share of the algorithmic bytes."""
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd import runtime as R
+    from paper_2309_06626_amd.metrics import HBM_PEAK_GBS, algorithmic_bytes, time_launches
+
+    rows = []
+    warm = max(steps // 10, 5)
+    for spec in W.depthwise_layers():
+        ci = W.make_conv_inputs(spec, W.base_seed(6))
+        layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+        kept = layer.info["kept"]
+        x = R.to_device(ci.x, spec.dtype)
+        y = layer.new_output().zero_()
+        yc = torch.zeros((kept, spec.c_out), dtype=B.TORCH_DTYPE[spec.dtype], device="cuda:0")
+        _, ts = time_launches(B.prepared_run(layer.plan, x, layer.bias, y), steps, warm)
+        _, tc = time_launches(B.prepared_run_rows(layer.plan, x, layer.bias, yc, B.SC_ROWS_DENSE, B.SC_ROWS_COMPACT), steps, warm)
+        _, td = time_launches(B.prepared_run(layer.plan, x, layer.bias, y, dense=True), steps, warm)
+        by, byc, byd = (algorithmic_bytes(spec, kept), algorithmic_bytes(spec, kept, scatter_only=True),
+                        algorithmic_bytes(spec, spec.m))
+        rows.append({"layer": spec.name, "m": spec.m, "c": spec.c_out, "kept": kept,
+                     "sparse_us": ts * 1e6, "compact_out_us": tc * 1e6, "dense_us": td * 1e6,
+                     "sparse_hbm_frac": by / ts / 1e9 / HBM_PEAK_GBS, "compact_hbm_frac": byc / tc / 1e9 / HBM_PEAK_GBS,
+                     "dense_hbm_frac": byd / td / 1e9 / HBM_PEAK_GBS})
+        del layer, x, y, yc
+        torch.cuda.empty_cache()
+    return rows
+
+
 def mask_generator_times(steps):
     """us per call of the mask generator (two launches) for the layer resolutions of the two networks."""
     import torch
@@ -219,6 +252,7 @@ def main():
                     help="also time torch.nn.functional.conv2d (MIOpen, dense) on every shape, as context")
     ap.add_argument("--masks", action="store_true", help="also time the mask generator (Alg. 1, getMask)")
     ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
+    ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
     args = ap.parse_args()
 
     import torch
@@ -291,6 +325,17 @@ def main():
         for r in compact_rows:
             print(f"| {r['layer']} | {r['m']}x{r['k']}x{r['c_out']} | {fmt(r['dense_dense_us'])} | {fmt(r['dense_compact_us'])} | "
                   f"{fmt(r['compact_dense_us'])} | {fmt(r['compact_compact_us'])} | {fmt(r['dense_run_us'])} |")
+    dw_rows = []
+    if args.depthwise:
+        dw_rows = depthwise_times(args.steps)
+        print()
+        print("| depthwise 3x3 layer (batch 64, s = 0.5) | M x C | sparse us (zero fill) | % HBM | compact out us | % HBM | dense us | % HBM | "
+              "speed-up zero fill | speed-up compact out |")
+        print("|---|---|---|---|---|---|---|---|---|---|")
+        for r in dw_rows:
+            print(f"| {r['layer']} | {r['m']}x{r['c']} | {r['sparse_us']:.2f} | {100 * r['sparse_hbm_frac']:.1f} | "
+                  f"{r['compact_out_us']:.2f} | {100 * r['compact_hbm_frac']:.1f} | {r['dense_us']:.2f} | "
+                  f"{100 * r['dense_hbm_frac']:.1f} | {r['dense_us'] / r['sparse_us']:.2f} | {r['dense_us'] / r['compact_out_us']:.2f} |")
     mask_rows = []
     if args.masks:
         mask_rows = mask_generator_times(max(args.steps // 4, 20))
@@ -308,6 +353,8 @@ def main():
                 f.write(json.dumps({"mask_generator": mask_rows}) + "\n")
             if compact_rows:
                 f.write(json.dumps({"compact_formats": compact_rows}) + "\n")
+            if dw_rows:
+                f.write(json.dumps({"depthwise": dw_rows}) + "\n")
 
 
 if __name__ == "__main__":

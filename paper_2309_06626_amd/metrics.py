@@ -31,6 +31,7 @@ def algorithmic_bytes(spec, keep: int, scatter_only: bool = False) -> float:
     scatter-only mode), the mask bytes and the row list."""
     eb = elem_bytes(spec.dtype)
     out_rows = keep if scatter_only else spec.m
+    # spec.k counts the window entries per output channel (kh*kw for a depthwise layer)
     return (input_coverage(spec, keep) * spec.n * spec.h * spec.w * spec.c_in * eb + spec.k * spec.c_out * eb
             + out_rows * spec.c_out * eb + spec.m + 4 * keep)
 

@@ -134,3 +134,27 @@ def test_mobilenet_style_block_with_one_mask_stays_compact_between_pointwise_lay
     nr = np.linalg.norm(ref.astype(np.float64))
     assert np.linalg.norm(g.astype(np.float64) - ref) / nr <= TOL[dtype]
     assert np.abs(g - ref).max() <= TOL[dtype] * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_a_non_finite_input_value_reaches_only_the_windows_that_contain_it(dtype, stride):
+    """The 16-bit kernels pair window rows with rows outside the window (times a zero filter entry): an
+    infinity there must not leak into the result as 0 * inf."""
+    spec = dw_spec(1, 16, 12, 12, s=stride, dtype=dtype, sparsity=0.0, relu=False)
+    ci = W.make_conv_inputs(spec, 457)
+    x = ci.x.copy()
+    x[0, 5, 6, :] = np.inf
+    x[0, 8, 2, 3] = -np.inf
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    y = layer.new_output(fill_nan=True)
+    layer.sparse(R.to_device(x, dtype), y)
+    torch.cuda.synchronize()
+    got = R.to_host_f32(y)
+    with np.errstate(invalid="ignore", over="ignore"):
+        ref = oracle.masked_depthwise_conv2d(spec, x, ci.w, ci.bias, ci.mask)
+    finite = np.isfinite(ref)
+    assert np.array_equal(np.isfinite(got), finite)
+    assert finite.sum() < ref.size and not finite.all()
+    clean = oracle.masked_depthwise_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask)
+    assert np.abs(got[finite] - clean[finite]).max() <= TOL[dtype] * np.abs(clean).max()

@@ -263,6 +263,17 @@ def config4(batch: int = 64, sparsity: float = 0.5) -> List[ConvSpec]:
     return out
 
 
+def depthwise_layers(batch: int = 64, sparsity: float = 0.5, dtype: str = "bf16") -> List[ConvSpec]:
+    """Depthwise 3x3 layers of a MobileNetV2-style body at 224x224 input (channels, map, stride): the
+    second workload the build widens into -- the paper times such networks end to end (Sec. 4) but
+    lists no layer shapes, so these are the standard ones of that architecture."""
+    shapes = [(32, 112, 1), (96, 112, 2), (144, 56, 1), (144, 56, 2), (192, 28, 1), (192, 28, 2), (384, 14, 1),
+              (576, 14, 1), (576, 14, 2), (960, 7, 1)]
+    return [ConvSpec(f"dw_{c}_{hw}_s{st}", n=batch, c_in=c, h=hw, w=hw, c_out=c, kh=3, kw=3, stride_h=st, stride_w=st,
+                     pad_h=1, pad_w=1, dtype=dtype, relu=True, sparsity=sparsity, layer_index=i, groups=c)
+            for i, (c, hw, st) in enumerate(shapes)]
+
+
 @dataclass(frozen=True)
 class NetOp:
     """One node of a small inference graph.
