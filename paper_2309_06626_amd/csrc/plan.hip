@@ -380,7 +380,7 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->k_stride = (g->k_tiles & 1) ? g->k_pad : g->k_pad + bk;
   g->cout_pad = (d->c_out + 255) / 256 * 256;
   g->vec_gather = d->layout == SC_NHWC && d->c_in % g->vec == 0;
-  g->vec_out = d->layout == SC_NHWC && d->c_out % 16 == 0;
+  g->vec_out = d->layout == SC_NHWC && d->c_out % g->vec == 0;   // output rows are whole 16-byte groups
   g->mask_len = d->mask_mode == SC_MASK_ROW ? g->m : (int64_t)g->ho * g->wo;
   g->nseg = (int32_t)((g->m + kSeg - 1) / kSeg);
   size_t off = 0;

@@ -252,6 +252,8 @@ def main():
                     help="also time torch.nn.functional.conv2d (MIOpen, dense) on every shape, as context")
     ap.add_argument("--masks", action="store_true", help="also time the mask generator (Alg. 1, getMask)")
     ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
+    ap.add_argument("--pruned", action="store_true",
+                    help="also time a channel-pruned ResNet18 stack (51/102/205/410 channels, s = 0.3), as it is and padded to 8")
     ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
     args = ap.parse_args()
 
@@ -308,6 +310,14 @@ def main():
         cs = max(args.steps // 10, 5)
         chains["config 5 (detector stack, batch 16, s=0.3)"] = chain_time(ops, W.base_seed(5), cs)
         chains["config 5, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(5), cs, dense=True)
+    if args.pruned:
+        cs = max(args.steps // 10, 5)
+        ops = W.pruned_resnet18()
+        chains["pruned ResNet18 stack (batch 64, s=0.3), channels padded to multiples of 8 (56/104/208/416)"] = \
+            chain_time(W.pad_channels(ops), W.base_seed(3), cs)
+        chains["the same, every conv through dense_conv_run"] = chain_time(W.pad_channels(ops), W.base_seed(3), cs, dense=True)
+        chains["pruned ResNet18 stack with its own channel counts (51/102/205/410: element gather)"] = \
+            chain_time(ops, W.base_seed(3), cs)
     if chains:
         print()
         print("| whole chain (conv launches + pooling / residual glue, fixed buffers) | us per pass, call by call | us per pass, HIP graph replay |")

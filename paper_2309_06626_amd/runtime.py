@@ -59,6 +59,19 @@ class ConvLayer:
         return B.dense_conv_run(self.plan, x, self.bias, y)
 
 
+def pad_conv_params(spec, padded_spec, w: np.ndarray, bias: Optional[np.ndarray]):
+    """Filters and bias of `spec` laid out for `padded_spec` (more input / output channels, NHWC): the
+    additional filters, filter entries and bias entries are zero."""
+    assert spec.layout == "nhwc" and spec.groups == 1
+    wp = np.zeros(padded_spec.w_shape(), dtype=np.float32)
+    wp[: spec.c_out, :, :, : spec.c_in] = w
+    bp = None
+    if spec.has_bias:
+        bp = np.zeros(padded_spec.c_out, dtype=np.float32)
+        bp[: spec.c_out] = bias
+    return wp, bp
+
+
 def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer]) -> Dict[str, torch.Tensor]:
     """Interpret a workload op list on the device (conv = sparse_conv_run, plus the glue ops)."""
     t = dict(tensors)

@@ -525,3 +525,32 @@ def test_config3_full_batch_sampled_rows():
         ci = W.make_conv_inputs(spec, W.base_seed(3))
         check_layer(ci, sample_rows=256)
         torch.cuda.empty_cache()
+
+
+def test_pruned_resnet18_with_padded_channels_matches_the_unpadded_oracle():
+    """Channel counts that are no multiple of 8 (a structurally pruned model): the stack runs with every
+    tensor padded to 16-byte channel groups -- zero filters, so the extra channels stay exactly zero --
+    and must reproduce the oracle's run of the original shapes."""
+    ops = W.pruned_resnet18(batch=2, sparsity=0.3)
+    pops = W.pad_channels(ops)
+    assert [s.c_out for s in W.conv_specs(ops)][:2] == [51, 51] and W.conv_specs(pops)[1].c_in == 56
+    bs = W.base_seed(3)
+    params, layers = {}, {}
+    for spec, pspec in zip(W.conv_specs(ops), W.conv_specs(pops)):
+        ci = W.make_conv_inputs(spec, bs, x=np.zeros(1, np.float32))
+        params[spec.name] = (ci.w, ci.bias, ci.mask)
+        wp, bp = R.pad_conv_params(spec, pspec, ci.w, ci.bias)
+        layers[spec.name] = R.ConvLayer(pspec, wp, bp, ci.mask)
+        assert "elements" not in B.sparse_conv_plan_kernel(layers[spec.name].plan, 0) or spec.name == "stem"
+    dtype = "bf16"
+    host = {"input": W.gen_activations(W.network_input_shape(ops), bs, dtype)}
+    dev = R.run_network(pops, {k: R.to_device(v, dtype) for k, v in host.items()}, layers)
+    torch.cuda.synchronize()
+    ref = oracle.run_network(ops, host, lambda spec: params[spec.name])
+    trimmed = {}
+    for op in ops:
+        c = ref[op.out].shape[-1]
+        full = dev[op.out]
+        assert (R.bits_of(full)[..., c:] == 0).all(), f"{op.out}: padding channels must stay zero"
+        trimmed[op.out] = full[..., :c].contiguous()
+    compare_network(ops, trimmed, ref, params, TOL["bf16"])

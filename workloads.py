@@ -290,7 +290,8 @@ class NetOp:
     spec: Optional[ConvSpec] = None
 
 
-def _resnet18_ops(batch: int, res: int, dtype: str, sparsity: float, sparse_downsample: bool) -> List[NetOp]:
+def _resnet18_ops(batch: int, res: int, dtype: str, sparsity: float, sparse_downsample: bool,
+                  widths=(64, 128, 256, 512)) -> List[NetOp]:
     ops: List[NetOp] = []
     li = 0
 
@@ -302,11 +303,11 @@ def _resnet18_ops(batch: int, res: int, dtype: str, sparsity: float, sparse_down
         ops.append(NetOp("conv", out, src, spec=spec))
         return spec
 
-    st = conv("stem", "input", "stem", 3, 64, res, 7, 2, 3, True, sparsity)
+    st = conv("stem", "input", "stem", 3, widths[0], res, 7, 2, 3, True, sparsity)
     ops.append(NetOp("maxpool", "pool", "stem"))
     hw = (st.ho + 2 - 3) // 2 + 1
-    cur, ch = "pool", 64
-    for stage, co in enumerate((64, 128, 256, 512), start=1):
+    cur, ch = "pool", widths[0]
+    for stage, co in enumerate(widths, start=1):
         for blk in range(2):
             stride = 2 if (stage > 1 and blk == 0) else 1
             tag = f"l{stage}b{blk}"
@@ -330,6 +331,31 @@ def config3(batch: int = 64, res: int = 224, sparsity: float = 0.5, sparse_downs
     reproduces that, the default masks every conv as the benchmark description asks.
     """
     return _resnet18_ops(batch, res, dtype, sparsity, sparse_downsample)
+
+
+def pruned_resnet18(batch: int = 64, res: int = 224, sparsity: float = 0.3, keep: float = 0.8,
+                    dtype: str = "bf16") -> List[NetOp]:
+    """ResNet18 stack after structured channel pruning: every stage keeps the fraction `keep` of its
+    channels (51 / 102 / 205 / 410 at 0.8), counts that are no multiple of 8.  Stands in for the pruned
+    models of the paper's App. B.3 (structured weight pruning combined with activation sparsity at
+    5-30 %), whose channel counts the paper does not list."""
+    widths = tuple(int(round(c * keep)) for c in (64, 128, 256, 512))
+    return _resnet18_ops(batch, res, dtype, sparsity, True, widths)
+
+
+def pad_channels(ops: List[NetOp], multiple: int = 8) -> List[NetOp]:
+    """The same graph with every channel count rounded up to `multiple` (the network input keeps its own):
+    how a converter lays out a pruned model for 16-byte channel groups.  The extra filters and filter
+    entries are zero, so the extra channels of every tensor stay zero."""
+    up = lambda c: -(-c // multiple) * multiple
+    out = []
+    for o in ops:
+        if o.kind != "conv":
+            out.append(o)
+            continue
+        c_in = o.spec.c_in if o.src == "input" else up(o.spec.c_in)
+        out.append(replace(o, spec=o.spec.with_(c_in=c_in, c_out=up(o.spec.c_out))))
+    return out
 
 
 def config5(batch: int = 16, sparsity: float = 0.3, dtype: str = "bf16") -> List[NetOp]:
