@@ -337,7 +337,7 @@ def pruned_resnet18(batch: int = 64, res: int = 224, sparsity: float = 0.3, keep
                     dtype: str = "bf16") -> List[NetOp]:
     """ResNet18 stack after structured channel pruning: every stage keeps the fraction `keep` of its
     channels (51 / 102 / 205 / 410 at 0.8), counts that are no multiple of 8.  Stands in for the pruned
-    models of the paper's App. B.3 (structured weight pruning combined with activation sparsity at
+    models of the paper's Sec. 4.5 and the table of App. B.3 (structured weight pruning combined with activation sparsity at
     5-30 %), whose channel counts the paper does not list."""
     widths = tuple(int(round(c * keep)) for c in (64, 128, 256, 512))
     return _resnet18_ops(batch, res, dtype, sparsity, True, widths)
