@@ -106,6 +106,19 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
                            void* workspace_dev, size_t workspace_bytes, void* hip_stream, sc_plan** out);
 
 /*
+ * Training-side refresh of a plan (Alg. 1: getMask draws a new mask whenever updateMask says so, and the
+ * weights change with every optimiser step).  Same layer, same workspace, no new plan:
+ *   sparse_conv_plan_set_mask     the indirection init of Alg. 2 again for a new mask (compaction, band
+ *                                 tables); the kept-row count is checked against the descriptor's sparsity as
+ *                                 in sparse_conv_plan.  Synchronises `hip_stream`.  After an error the plan must
+ *                                 not be run until a later call has succeeded (its tables describe the rejected mask).
+ *   sparse_conv_plan_set_filters  repacks the filters (same layout and dtype as at plan time); enqueues only.
+ * Runs that are still in flight on another stream must have finished before either call.
+ */
+sc_status sparse_conv_plan_set_mask(sc_plan* plan, const uint8_t* mask_dev, void* hip_stream);
+sc_status sparse_conv_plan_set_filters(sc_plan* plan, const void* w_dev, void* hip_stream);
+
+/*
  * Masked convolution (Sec. 3.2 stages i-iii fused into one launch): gather the kept rows'
  * receptive fields, contract with the filters on the matrix cores, add bias / apply ReLU,
  * and store each result at its dense position; dropped positions receive zeros (or are

@@ -63,6 +63,10 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_workspace_bytes.argtypes = [pd, ctypes.POINTER(ctypes.c_size_t)]
         L.sparse_conv_plan.restype = ctypes.c_int
         L.sparse_conv_plan.argtypes = [pd, vp, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+        L.sparse_conv_plan_set_mask.restype = ctypes.c_int
+        L.sparse_conv_plan_set_mask.argtypes = [vp, vp, vp]
+        L.sparse_conv_plan_set_filters.restype = ctypes.c_int
+        L.sparse_conv_plan_set_filters.argtypes = [vp, vp, vp]
         L.sparse_conv_run.restype = ctypes.c_int
         L.sparse_conv_run.argtypes = [vp, vp, vp, vp, vp]
         L.sparse_conv_run_rows.restype = ctypes.c_int
@@ -208,6 +212,26 @@ def _check_operands(plan: Plan, x, bias, y, x_compact=False, y_compact=False):
         raise ValueError(f"x holds {x.numel()} elements, the plan needs {want_x}")
     if y.numel() != want_y:
         raise ValueError(f"y holds {y.numel()} elements, the plan needs {want_y}")
+
+
+def sparse_conv_plan_set_mask(plan: Plan, mask: torch.Tensor, stream=None):
+    """A new mask for an existing plan (re-runs the compaction; synchronises the stream)."""
+    d = plan.desc
+    info = sparse_conv_plan_info(plan)
+    want = info["m"] if d.mask_mode == SC_MASK_ROW else info["ho"] * info["wo"]
+    if mask.dtype != torch.uint8 or mask.numel() != want:
+        raise ValueError(f"mask must hold {want} bytes")
+    _check(lib().sparse_conv_plan_set_mask(plan.handle, _dev_ptr(mask, "mask"), _stream_handle(stream)),
+           "sparse_conv_plan_set_mask")
+
+
+def sparse_conv_plan_set_filters(plan: Plan, w: torch.Tensor, stream=None):
+    """New filter values for an existing plan (same layout and dtype)."""
+    d = plan.desc
+    if _CODE_OF_TORCH.get(w.dtype) != d.dtype or w.numel() != d.c_out * d.kh * d.kw * (d.c_in // d.groups):
+        raise ValueError("filters do not match the plan")
+    _check(lib().sparse_conv_plan_set_filters(plan.handle, _dev_ptr(w, "w"), _stream_handle(stream)),
+           "sparse_conv_plan_set_filters")
 
 
 def _run(fn, name, plan: Plan, x, bias, y, stream):

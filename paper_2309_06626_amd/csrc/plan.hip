@@ -837,6 +837,98 @@ static sc_status check_run_args(const sc_plan* plan, const void* x, const float*
   return SC_OK;
 }
 
+// Everything of a plan that depends on the filters: the packed filter matrix (and, once, the gather table).
+static sc_status pack_filters(const sc_conv_desc& d, const Geometry& g, unsigned char* ws, const void* w_dev,
+                              hipStream_t stream) {
+  if (g.depthwise) {
+    const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
+    SC_HIP(depthwise_pack(dt, w_dev, ws + g.off_wp, d.c_in, d.kh * d.kw, stream));
+    return SC_OK;
+  }
+  {
+    int64_t total = (int64_t)g.cout_pad * g.k_stride;
+    int grid = (int)((total + 255) / 256);
+    const int nchw = d.layout == SC_NCHW;
+    if (d.dtype == SC_F32)
+      hipLaunchKernelGGL(pack_filters_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)w_dev,
+                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
+    else  // 16-bit patterns are moved verbatim
+      hipLaunchKernelGGL(pack_filters_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, (const _Float16*)w_dev,
+                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
+    SC_HIP(hipGetLastError());
+  }
+  // gather table (depends on the geometry only; rebuilt with the filters for simplicity, it is tiny)
+  {
+    const int vec = g.vec_gather ? g.vec : 1;
+    const int entries = g.k_pad / vec;
+    int xs_h, xs_w, xs_c;
+    if (d.layout == SC_NHWC) { xs_h = d.w * d.c_in; xs_w = d.c_in; xs_c = 1; }
+    else { xs_h = d.w; xs_w = 1; xs_c = d.h * d.w; }
+    hipLaunchKernelGGL(build_ktab_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<KEntry*>(ws + g.off_ktab), entries, vec, g.k, d.c_in, d.kw, d.dil_h, d.dil_w,
+                       xs_h, xs_w, xs_c);
+    SC_HIP(hipGetLastError());
+  }
+  return SC_OK;
+}
+
+// Everything of a plan that depends on the mask (Alg. 2, indirection init): the private mask copy, the
+// ascending list of kept rows and its length, the band tables, the rank table of depthwise layers.
+// Synchronises the stream (the kept count decides the launch shapes) and checks the count against the
+// descriptor's sparsity.
+static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsigned char* ws, const uint8_t* mask_dev,
+                                  hipStream_t stream, BandPlan* bp_io, int32_t* kept_out) {
+  BandPlan& bp = *bp_io;
+  // a private copy of the mask (the zero fill of every run reads it)
+  SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
+
+  // compaction
+  const int period = d.mask_mode == SC_MASK_SPATIAL ? g.ho * g.wo : 0;
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + g.off_counts);
+  int32_t* rows = reinterpret_cast<int32_t*>(ws + g.off_rows);
+  int32_t* kept_dev = reinterpret_cast<int32_t*>(ws + g.off_kept);
+  const int cgrid = (g.nseg + 3) / 4;
+  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
+                     g.nseg, counts);
+  SC_HIP(hipGetLastError());
+  hipLaunchKernelGGL(mask_scatter_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
+                     g.nseg, counts, rows, kept_dev);
+  SC_HIP(hipGetLastError());
+  if (g.depthwise)   // position of every kept row in the row list (compact output of the LDS-tiled kernels)
+    SC_HIP(depthwise_rank(rows, kept_dev, reinterpret_cast<int32_t*>(ws + g.off_band_rows), g.m, stream));
+
+  if (bp.ok) {
+    hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
+                       reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
+    SC_HIP(hipGetLastError());
+    if (bp.stream) {
+      // kept_dev + 1 holds the per-band maximum
+      SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
+      hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
+                         reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
+      SC_HIP(hipGetLastError());
+    }
+    hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
+                       reinterpret_cast<const int32_t*>(ws + g.off_band),
+                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, g.ho, g.wo);
+    SC_HIP(hipGetLastError());
+  }
+
+  int32_t host_vals[2] = {-1, 0};   // kept count, most kept rows in one band
+  SC_HIP(hipMemcpyAsync(host_vals, kept_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  SC_HIP(hipStreamSynchronize(stream));
+  *kept_out = host_vals[0];
+  bp.max_kept = host_vals[1];
+
+  if (d.sparsity >= 0.0f) {
+    // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up)
+    int64_t want = (int64_t)std::floor((1.0 - (double)d.sparsity) * (double)g.mask_len + 0.5);
+    int64_t have = d.mask_mode == SC_MASK_ROW ? host_vals[0] : host_vals[0] / d.n;
+    if (want != have) return SC_ERR_MASK_COUNT;
+  }
+  return SC_OK;
+}
+
 }  // namespace sc
 
 extern "C" {
@@ -881,84 +973,12 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     SC_HIP(hipMemsetAsync(ws + g.off_xpad, 0, ((size_t)d.n * g.hp * g.wp_cols * d.c_in + 64) * eb, stream));
   if (g.splitk_ok)   // arrival counters start at zero; every launch leaves them at zero again
     SC_HIP(hipMemsetAsync(ws + g.off_counters, 0, g.off_partial - g.off_counters, stream));
-  // a private copy of the mask (the zero fill of every run reads it)
-  SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
-
-  // compaction
-  const int period = d.mask_mode == SC_MASK_SPATIAL ? g.ho * g.wo : 0;
-  int32_t* counts = reinterpret_cast<int32_t*>(ws + g.off_counts);
-  int32_t* rows = reinterpret_cast<int32_t*>(ws + g.off_rows);
-  int32_t* kept_dev = reinterpret_cast<int32_t*>(ws + g.off_kept);
-  const int cgrid = (g.nseg + 3) / 4;
-  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
-                     g.nseg, counts);
-  SC_HIP(hipGetLastError());
-  hipLaunchKernelGGL(mask_scatter_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
-                     g.nseg, counts, rows, kept_dev);
-  SC_HIP(hipGetLastError());
-
-  // filters
-  if (g.depthwise) {
-    const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
-    SC_HIP(depthwise_pack(dt, w_dev, ws + g.off_wp, d.c_in, d.kh * d.kw, stream));
-    // position of every kept row in the row list (compact output of the LDS-tiled kernel)
-    SC_HIP(depthwise_rank(rows, kept_dev, reinterpret_cast<int32_t*>(ws + g.off_band_rows), g.m, stream));
-  } else {
-    int64_t total = (int64_t)g.cout_pad * g.k_stride;
-    int grid = (int)((total + 255) / 256);
-    const int nchw = d.layout == SC_NCHW;
-    if (d.dtype == SC_F32)
-      hipLaunchKernelGGL(pack_filters_kernel<float>, dim3(grid), dim3(256), 0, stream, (const float*)w_dev,
-                         (float*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
-    else  // 16-bit patterns are moved verbatim
-      hipLaunchKernelGGL(pack_filters_kernel<_Float16>, dim3(grid), dim3(256), 0, stream, (const _Float16*)w_dev,
-                         (_Float16*)(ws + g.off_wp), d.c_out, d.c_in, d.kh, d.kw, g.k, g.k_stride, g.cout_pad, nchw, g.rowseg ? g.epad : 0);
-    SC_HIP(hipGetLastError());
-  }
-
-  // gather table
-  if (!g.depthwise) {
-    const int vec = g.vec_gather ? g.vec : 1;
-    const int entries = g.k_pad / vec;
-    int xs_h, xs_w, xs_c;
-    if (d.layout == SC_NHWC) { xs_h = d.w * d.c_in; xs_w = d.c_in; xs_c = 1; }
-    else { xs_h = d.w; xs_w = 1; xs_c = d.h * d.w; }
-    hipLaunchKernelGGL(build_ktab_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream,
-                       reinterpret_cast<KEntry*>(ws + g.off_ktab), entries, vec, g.k, d.c_in, d.kw, d.dil_h, d.dil_w,
-                       xs_h, xs_w, xs_c);
-    SC_HIP(hipGetLastError());
-  }
-
   BandPlan bp = plan_band(d, g);
-  if (bp.ok) {
-    hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
-                       reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
-    SC_HIP(hipGetLastError());
-    if (bp.stream) {
-      // kept_dev + 1 holds the per-band maximum
-      SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
-      hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
-                         reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
-      SC_HIP(hipGetLastError());
-    }
-    hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
-                       reinterpret_cast<const int32_t*>(ws + g.off_band),
-                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, g.ho, g.wo);
-    SC_HIP(hipGetLastError());
-  }
-
-  int32_t host_vals[2] = {-1, 0};   // kept count, most kept rows in one band
-  SC_HIP(hipMemcpyAsync(host_vals, kept_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-  SC_HIP(hipStreamSynchronize(stream));
-  const int32_t kept_host = host_vals[0];
-  bp.max_kept = host_vals[1];
-
-  if (d.sparsity >= 0.0f) {
-    // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up)
-    int64_t want = (int64_t)std::floor((1.0 - (double)d.sparsity) * (double)g.mask_len + 0.5);
-    int64_t have = d.mask_mode == SC_MASK_ROW ? kept_host : kept_host / d.n;
-    if (want != have) return SC_ERR_MASK_COUNT;
-  }
+  int32_t kept_host = 0;
+  s = pack_filters(d, g, ws, w_dev, stream);
+  if (s != SC_OK) return s;
+  s = build_row_tables(d, g, ws, mask_dev, stream, &bp, &kept_host);   // synchronises the stream
+  if (s != SC_OK) return s;
 
   sc_plan* pl = new (std::nothrow) sc_plan;
   if (!pl) return SC_ERR_NULL;
@@ -987,6 +1007,26 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   (void)eb;
   *out = pl;
   return SC_OK;
+}
+
+sc_status sparse_conv_plan_set_mask(sc_plan* plan, const uint8_t* mask_dev, void* hip_stream) {
+  if (!plan || !mask_dev) return SC_ERR_NULL;
+  const sc_conv_desc& d = plan->desc;
+  const Geometry& g = plan->geo;
+  BandPlan bp = plan->band;
+  int32_t kept_host = 0;
+  sc_status s = build_row_tables(d, g, plan->ws, mask_dev, static_cast<hipStream_t>(hip_stream), &bp, &kept_host);
+  if (s != SC_OK) return s;
+  plan->kept = kept_host;
+  plan->band = bp;
+  plan->tile_sparse = choose_tile(plan->table, plan->table_count, plan->kept, d.c_out, g.vec_gather, g.k_tiles, g.rowseg);
+  return SC_OK;
+}
+
+sc_status sparse_conv_plan_set_filters(sc_plan* plan, const void* w_dev, void* hip_stream) {
+  if (!plan || !w_dev) return SC_ERR_NULL;
+  if ((uintptr_t)w_dev & 15) return SC_ERR_ALIGN;
+  return pack_filters(plan->desc, plan->geo, plan->ws, w_dev, static_cast<hipStream_t>(hip_stream));
 }
 
 sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,

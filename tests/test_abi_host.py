@@ -132,3 +132,10 @@ def test_grouped_layers_other_than_depthwise_are_refused():
         assert L.sparse_conv_workspace_bytes(ctypes.byref(d), ctypes.byref(size)) == B.SC_ERR_UNSUPPORTED
     d = B.make_desc(1, 16, 8, 8, 16, groups=16)
     assert L.sparse_conv_workspace_bytes(ctypes.byref(d), ctypes.byref(size)) == B.SC_OK
+
+
+def test_plan_refresh_calls_reject_null_arguments():
+    L = B.lib()
+    fake = 0x1000
+    assert L.sparse_conv_plan_set_mask(None, fake, None) == B.SC_ERR_NULL
+    assert L.sparse_conv_plan_set_filters(None, fake, None) == B.SC_ERR_NULL

@@ -104,3 +104,43 @@ def test_resnet_stack_with_propagated_masks():
     ref = oracle.run_network(ops, host, lambda spec: params[spec.name])
     row_params = {k: (v[0], v[1], np.tile(v[2], 2)) for k, v in params.items()}     # per-row masks for the zero check
     compare_network(ops, dev, ref, row_params, TOL["bf16"])
+
+
+def test_training_style_steps_refresh_mask_and_filters_of_one_plan():
+    """Alg. 1, main loop: every step draws a new score, getMask turns it into the layer's mask, the optimiser
+    has changed the weights, and the same plan runs the masked forward pass with both."""
+    spec = W.ConvSpec("train", n=3, c_in=32, h=28, w=28, c_out=64, dtype="bf16", sparsity=0.5, mask_mode="spatial")
+    ci = W.make_conv_inputs(spec, 601)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    x = R.to_device(ci.x, spec.dtype)
+    rng = np.random.default_rng(607)
+    seen = []
+    for step in range(4):
+        score = W.gen_score(224, 224, seed=700 + step)
+        mask_dev = B.sparse_mask_generate(torch.from_numpy(score).to("cuda:0"), spec.ho, spec.wo, spec.sparsity)
+        w_step = W.quantize(ci.w + np.float32(0.01) * rng.standard_normal(ci.w.shape).astype(np.float32), spec.dtype)
+        B.sparse_conv_plan_set_mask(layer.plan, mask_dev)
+        B.sparse_conv_plan_set_filters(layer.plan, R.to_device(w_step, spec.dtype))
+        mask = MO.layer_mask(score, spec.ho, spec.wo, f32(spec.sparsity)).reshape(-1)
+        assert np.array_equal(mask_dev.cpu().numpy().reshape(-1), mask)
+        seen.append(mask)
+        rm = np.tile(mask, spec.n)
+        assert np.array_equal(B.plan_row_idx(layer.plan).cpu().numpy(), oracle.compact_rows(rm))
+        y = layer.new_output(fill_nan=True)
+        layer.sparse(x, y)
+        torch.cuda.synchronize()
+        ref, absum = oracle.masked_conv2d(spec, ci.x, w_step, ci.bias, mask, want_absum=True)
+        from parity import assert_close, rows_view
+        g, bits = rows_view(spec, R.to_host_f32(y)), rows_view(spec, R.bits_of(y))
+        assert (bits[rm == 0] == 0).all()
+        assert_close(g[rm == 1], rows_view(spec, ref)[rm == 1], rows_view(spec, absum)[rm == 1], TOL["bf16"], f"step {step}")
+    assert not np.array_equal(seen[0], seen[1])      # the masks really changed between steps
+    # a mask with the wrong count is refused; a good one afterwards puts the plan back to work
+    bad = torch.ones(spec.ho * spec.wo, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(B.ScError):
+        B.sparse_conv_plan_set_mask(layer.plan, bad)
+    B.sparse_conv_plan_set_mask(layer.plan, torch.from_numpy(seen[0]).to("cuda:0"))
+    y = layer.new_output(fill_nan=True)
+    layer.sparse(x, y)
+    torch.cuda.synchronize()
+    assert (rows_view(spec, R.bits_of(y))[np.tile(seen[0], spec.n) == 0] == 0).all()
