@@ -165,6 +165,60 @@ int oc_masked_conv2d(const int32_t* p, const float* x, const float* w, const flo
   return 0;
 }
 
+/* Backward pass of the masked convolution (Alg. 1: backward(model) follows maskedForward(model, mask)).
+ * The forward pass is y[r,co] = mask[r] ? act(sum_k A[r,k] w[co,k] + bias[co]) : 0 with A the lowered
+ * activations (Sec. 3), so with the upstream gradient dy and
+ *     g[r,co] = dy[r,co]   if mask[r] == 1 and (no ReLU or y[r,co] > 0),   0 otherwise
+ * the chain rule gives
+ *     db[co]   = sum_r g[r,co]
+ *     dw[co,k] = sum_r g[r,co] * A[r,k]                (a contraction over the kept rows only)
+ *     dx[pixel] = sum over the windows (r, tap) that contain the pixel of sum_co g[r,co] * w[co,tap,ci]
+ * The ReLU gate is read from the forward output y the caller passes (the stored values, so that both
+ * sides of a comparison gate on the same numbers).  Plain loop nest, double accumulation, one thread.
+ * dx and dw have the layouts of x and w; dx_abs / dw_abs (optional) receive the sums of the absolute
+ * values of the terms, the scale against which rounding error is judged.  Returns 0, -1, -2 like the
+ * forward function. */
+int oc_masked_conv2d_backward(const int32_t* p, const float* x, const float* w, const float* y, const float* dy,
+                              const uint8_t* mask, double* dx, double* dw, double* db, double* dx_abs,
+                              double* dw_abs) {
+  geom g;
+  if (make_geom(p, &g)) return -1;
+  int64_t mlen = g.mask_spatial ? (int64_t)g.ho * g.wo : (int64_t)g.n * g.ho * g.wo;
+  for (int64_t i = 0; i < mlen; ++i) if (mask[i] > 1) return -2;
+  const int64_t nx = (int64_t)g.n * g.cin * g.h * g.w, nw = (int64_t)g.cout * g.cin * g.kh * g.kw;
+  for (int64_t i = 0; i < nx; ++i) { dx[i] = 0.0; if (dx_abs) dx_abs[i] = 0.0; }
+  for (int64_t i = 0; i < nw; ++i) { dw[i] = 0.0; if (dw_abs) dw_abs[i] = 0.0; }
+  for (int co = 0; co < g.cout; ++co) db[co] = 0.0;
+  for (int n = 0; n < g.n; ++n)
+    for (int oy = 0; oy < g.ho; ++oy)
+      for (int ox = 0; ox < g.wo; ++ox) {
+        if (!mask_at(&g, mask, n, oy, ox)) continue;            /* a dropped row has no gradient */
+        for (int co = 0; co < g.cout; ++co) {
+          int64_t yo = n * g.ys_n + co * g.ys_c + oy * g.ys_h + ox * g.ys_w;
+          if (g.relu && !(y[yo] > 0.0f)) continue;               /* ReLU gate */
+          double gv = (double)dy[yo];
+          db[co] += gv;
+          for (int ky = 0; ky < g.kh; ++ky) {
+            int iy = oy * g.sh - g.ph + ky * g.dh;
+            if (iy < 0 || iy >= g.h) continue;
+            for (int kx = 0; kx < g.kw; ++kx) {
+              int ix = ox * g.sw - g.pw + kx * g.dw;
+              if (ix < 0 || ix >= g.w) continue;
+              for (int ci = 0; ci < g.cin; ++ci) {
+                int64_t xo = n * g.xs_n + ci * g.xs_c + iy * g.xs_h + ix * g.xs_w;
+                int64_t wo = co * g.ws_o + ci * g.ws_i + ky * g.ws_ky + kx * g.ws_kx;
+                dw[wo] += gv * (double)x[xo];
+                dx[xo] += gv * (double)w[wo];
+                if (dw_abs) dw_abs[wo] += fabs(gv * (double)x[xo]);
+                if (dx_abs) dx_abs[xo] += fabs(gv * (double)w[wo]);
+              }
+            }
+          }
+        }
+      }
+  return 0;
+}
+
 /* Selected output positions only (row r = (n*Ho + oy)*Wo + ox); y_rows is [nrows][Cout]
  * regardless of layout.  Used to spot-check layers too large to evaluate in full. */
 int oc_masked_conv2d_rows(const int32_t* p, const float* x, const float* w, const float* bias,

@@ -54,6 +54,8 @@ def _load():
         lib.oc_masked_conv2d.argtypes = [i32p, f32p, f32p, f32p, u8p, f32p, f64p]
         lib.oc_masked_conv2d_rows.restype = ctypes.c_int
         lib.oc_masked_conv2d_rows.argtypes = [i32p, f32p, f32p, f32p, u8p, i64p, ctypes.c_int64, f32p, f64p]
+        lib.oc_masked_conv2d_backward.restype = ctypes.c_int
+        lib.oc_masked_conv2d_backward.argtypes = [i32p, f32p, f32p, f32p, f32p, u8p, f64p, f64p, f64p, f64p, f64p]
         lib.oc_round_bf16.restype = None
         lib.oc_round_bf16.argtypes = [f32p, ctypes.c_int64]
         lib.oc_round_f16.restype = None
@@ -152,6 +154,29 @@ def masked_conv2d_rows(spec, x, w, bias, mask, rows, want_absum: bool = False):
     if rc != 0:
         raise ValueError(f"oracle rejected the problem (code {rc})")
     return (y, absum) if want_absum else y
+
+
+def masked_conv2d_backward(spec, x, w, y, dy, mask, want_abs: bool = False):
+    """Gradients of the masked convolution w.r.t. input, filters and bias (float64): ``(dx, dw, db)``, or
+    ``(dx, dw, db, dx_abs, dw_abs)`` with the sums of absolute terms.  ``y`` is the forward output whose
+    sign gates the ReLU; ``dy`` the upstream gradient (both in the output layout)."""
+    lib = _load()
+    x, w, y, dy = _f32(x), _f32(w), _f32(y), _f32(dy)
+    assert x.shape == tuple(spec.x_shape()) and w.shape == tuple(spec.w_shape()) and spec.groups == 1
+    assert y.shape == tuple(spec.y_shape()) and dy.shape == tuple(spec.y_shape())
+    mask = np.ascontiguousarray(mask, dtype=np.uint8).ravel()
+    assert mask.size == spec.mask_len
+    dx, dw, db = np.empty(x.shape, np.float64), np.empty(w.shape, np.float64), np.empty(spec.c_out, np.float64)
+    dxa = np.empty(x.shape, np.float64) if want_abs else None
+    dwa = np.empty(w.shape, np.float64) if want_abs else None
+    p = _params(spec)
+    rc = lib.oc_masked_conv2d_backward(_ptr(p, ctypes.c_int32), _ptr(x, ctypes.c_float), _ptr(w, ctypes.c_float),
+                                       _ptr(y, ctypes.c_float), _ptr(dy, ctypes.c_float), _ptr(mask, ctypes.c_uint8),
+                                       _ptr(dx, ctypes.c_double), _ptr(dw, ctypes.c_double), _ptr(db, ctypes.c_double),
+                                       _ptr(dxa, ctypes.c_double), _ptr(dwa, ctypes.c_double))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the problem (code {rc})")
+    return (dx, dw, db, dxa, dwa) if want_abs else (dx, dw, db)
 
 
 def row_mask(spec, mask: np.ndarray) -> np.ndarray:

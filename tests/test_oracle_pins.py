@@ -543,3 +543,98 @@ def test_depthwise_single_tap_filters_shift_each_channel_separately():
     assert np.array_equal(y[..., 0], x[..., 0])
     assert np.array_equal(y[0, 1:, :, 1], 2.0 * x[0, :-1, :, 1]) and (y[0, 0, :, 1] == 0).all()
     assert np.array_equal(y[0, :, :-1, 2], -x[0, :, 1:, 2]) and (y[0, :, -1, 2] == 0).all()
+
+
+# ---------------------------------------------------------------------------------------
+# backward pass of the masked convolution (Alg. 1: backward after maskedForward)
+# ---------------------------------------------------------------------------------------
+def torch_masked_grads(spec, x, w, b, mask, dy):
+    """Library autograd, float64: gradients of sum(dy * mask * act(conv2d(x, w) + b))."""
+    xt = torch.from_numpy(x).double()
+    wt = torch.from_numpy(w).double()
+    if spec.layout == "nhwc":
+        xt, wt = xt.permute(0, 3, 1, 2), wt.permute(0, 3, 1, 2)
+    xt = xt.contiguous().requires_grad_(True)
+    wt = wt.contiguous().requires_grad_(True)
+    bt = torch.from_numpy(b).double().requires_grad_(True) if b is not None else None
+    y = F.conv2d(xt, wt, bt, (spec.stride_h, spec.stride_w), (spec.pad_h, spec.pad_w), (spec.dil_h, spec.dil_w))
+    if spec.relu:
+        y = torch.relu(y)
+    m = torch.from_numpy(row_mask(spec, mask).astype(np.float64)).reshape(spec.n, 1, spec.ho, spec.wo)
+    y = y * m
+    dyt = torch.from_numpy(dy).double()
+    if spec.layout == "nhwc":
+        dyt = dyt.permute(0, 3, 1, 2)
+    (y * dyt).sum().backward()
+    gx, gw = xt.grad, wt.grad
+    if spec.layout == "nhwc":
+        gx, gw = gx.permute(0, 2, 3, 1), gw.permute(0, 2, 3, 1)
+    return gx.numpy(), gw.numpy(), (bt.grad.numpy() if bt is not None else None)
+
+
+@pytest.mark.parametrize("g", GEOMS)
+@pytest.mark.parametrize("layout", ["nhwc", "nchw"])
+@pytest.mark.parametrize("relu", [False, True])
+def test_backward_matches_library_autograd(g, layout, relu):
+    spec = make_spec(g, layout, bias=True, relu=relu, s=0.35)
+    x, w, b, mask = rand_inputs(spec, 53)
+    dy = np.random.default_rng(59).standard_normal(spec.y_shape()).astype(np.float32)
+    y = oracle.masked_conv2d(spec, x, w, b, mask)
+    dx, dw, db = oracle.masked_conv2d_backward(spec, x, w, y, dy, mask)
+    rx, rw, rb = torch_masked_grads(spec, x, w, b, mask, dy)
+    np.testing.assert_allclose(dx, rx, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(dw, rw, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(db, rb, rtol=1e-9, atol=1e-9)
+
+
+def test_backward_is_the_transposed_pipeline_on_the_kept_rows():
+    """With the explicit lowering matrix A: dW = G_kept^T A_kept (fewer rows, as in the forward GEMM),
+    dA_kept = G_kept W, and dx gathers dA back through the windows."""
+    spec = make_spec(GEOMS[1], "nhwc", bias=True, relu=True, s=0.4)
+    x, w, b, mask = rand_inputs(spec, 61)
+    dy = np.random.default_rng(67).standard_normal(spec.y_shape()).astype(np.float32)
+    y = oracle.masked_conv2d(spec, x, w, b, mask)
+    a = lowered_matrix(spec, x)
+    rm = row_mask(spec, mask)
+    gmat = dy.reshape(spec.m, spec.c_out).astype(np.float64) * (y.reshape(spec.m, spec.c_out) > 0)
+    gk, ak = gmat[rm == 1], a[rm == 1]
+    dw_ref = (gk.T @ ak).reshape(spec.w_shape())
+    da = np.zeros_like(a)
+    da[rm == 1] = gk @ w.reshape(spec.c_out, spec.k).astype(np.float64)
+    dx_ref = np.zeros(spec.x_shape(), np.float64)
+    da = da.reshape(spec.m, spec.kh, spec.kw, spec.c_in)
+    for n, oy, ox in itertools.product(range(spec.n), range(spec.ho), range(spec.wo)):
+        r = (n * spec.ho + oy) * spec.wo + ox
+        for ky, kx in itertools.product(range(spec.kh), range(spec.kw)):
+            iy, ix = oy * spec.stride_h - spec.pad_h + ky * spec.dil_h, ox * spec.stride_w - spec.pad_w + kx * spec.dil_w
+            if 0 <= iy < spec.h and 0 <= ix < spec.w:
+                dx_ref[n, iy, ix, :] += da[r, ky, kx, :]
+    dx, dw, db = oracle.masked_conv2d_backward(spec, x, w, y, dy, mask)
+    np.testing.assert_allclose(dw, dw_ref, rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(dx, dx_ref, rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(db, gk.sum(axis=0), rtol=1e-10, atol=1e-10)
+
+
+def test_backward_agrees_with_finite_differences_and_ignores_dropped_rows():
+    spec = make_spec(GEOMS[0], "nhwc", bias=True, relu=False, s=0.4)
+    x, w, b, mask = rand_inputs(spec, 71)
+    dy = np.random.default_rng(73).standard_normal(spec.y_shape()).astype(np.float32)
+    y = oracle.masked_conv2d(spec, x, w, b, mask)
+    dx, dw, db = oracle.masked_conv2d_backward(spec, x, w, y, dy, mask)
+    loss = lambda xx, ww: float((oracle.masked_conv2d(spec, xx, ww, b, mask).astype(np.float64) * dy).sum())
+    eps = 1e-2      # the layer is linear without the ReLU: a central difference is exact up to rounding
+    for idx in [(0, 2, 3, 1), (0, 0, 0, 0), (0, 4, 4, 2)]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += eps
+        xm[idx] -= eps
+        assert abs((loss(xp, w) - loss(xm, w)) / (2 * eps) - dx[idx]) < 1e-3
+    for idx in [(1, 0, 2, 1), (0, 1, 1, 0)]:
+        wp, wm = w.copy(), w.copy()
+        wp[idx] += eps
+        wm[idx] -= eps
+        assert abs((loss(x, wp) - loss(x, wm)) / (2 * eps) - dw[idx]) < 1e-3
+    # the upstream gradient of a dropped row changes nothing
+    dy2 = dy.copy().reshape(spec.m, spec.c_out)
+    dy2[mask == 0] = 1e6
+    dx2, dw2, db2 = oracle.masked_conv2d_backward(spec, x, w, y, dy2.reshape(spec.y_shape()), mask)
+    assert np.array_equal(dx2, dx) and np.array_equal(dw2, dw) and np.array_equal(db2, db)
