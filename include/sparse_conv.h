@@ -157,6 +157,10 @@ sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bi
 sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, int32_t* ho, int32_t* wo,
                                 const int32_t** row_idx_dev);
 
+/* The plan's private copy of the mask (device memory inside the workspace; uint8[N*Ho*Wo] or [Ho*Wo] as
+ * the descriptor's mask_mode says).  NULL for a NULL plan. */
+const uint8_t* sparse_conv_plan_mask(const sc_plan* plan);
+
 /* Tile shape chosen for the sparse (which = 0) or dense (which = 1) launch: rows x couts per
  * workgroup, and the number of workgroups.  The library has two kernels: the tiled gather kernel
  * (tile_m > 0 kept rows per workgroup) and the band kernel, which stages a band of input rows of
@@ -200,6 +204,36 @@ void sparse_conv_plan_destroy(sc_plan* plan);
 
 const char* sc_status_string(sc_status s);
 int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on this thread */
+
+/*
+ * Backward pass of the masked convolution (Alg. 1: backward(model) follows maskedForward(model, mask)).
+ * With g[r, co] = dy[r, co] where mask[r] == 1 and (no ReLU or y[r, co] > 0), and 0 elsewhere:
+ *     db[co] = sum_r g[r, co]      dw[co, k] = sum_r g[r, co] * A[r, k]      dx = transposed convolution of g
+ * (A = lowered activations, Sec. 3).  The contraction for dw runs over the kept rows only, like the
+ * forward GEMM (Sec. 3.2).  NHWC layers with one group, bf16 or fp16, Cin and Cout multiples of 8;
+ * SC_ERR_UNSUPPORTED otherwise.
+ *   sparse_conv_backward_plan   `fwd` is the layer's forward plan (it supplies the mask and the row list and must
+ *                         outlive the backward plan; after sparse_conv_plan_set_mask the backward plan follows);
+ *                         `desc` the descriptor the forward plan was made from; w_dev the filters.  workspace_dev:
+ *                         at least sparse_conv_backward_workspace_bytes() bytes, 256-byte aligned, device, owned
+ *                         by the caller, used by every run (g map, partial sums, rotated filters).  Synchronises.
+ *   sparse_conv_backward_run    x_dev: the forward input; y_dev: the forward output (its sign gates the ReLU; may be
+ *                         NULL for layers without ReLU); dy_dev: upstream gradient, layout and dtype of y.
+ *                         dx_dev (layout and dtype of x), dw_dev (float [Cout][kh][kw][Cin]) and db_dev
+ *                         (float [Cout]) are each optional (NULL = not wanted).  dx needs stride 1 (then it is the
+ *                         ordinary convolution of g with the rotated filters and runs through the forward
+ *                         kernels): SC_ERR_UNSUPPORTED for strided layers.  Additions happen in a fixed order:
+ *                         results do not depend on scheduling.  Enqueues only; no allocation, no synchronisation.
+ *   sparse_conv_backward_set_filters   new filter values (after an optimiser step) for the input gradient.
+ */
+typedef struct sc_bwd_plan sc_bwd_plan;
+sc_status sparse_conv_backward_workspace_bytes(const sc_conv_desc* desc, size_t* bytes);
+sc_status sparse_conv_backward_plan(const sc_plan* fwd, const sc_conv_desc* desc, const void* w_dev, void* workspace_dev,
+                                    size_t workspace_bytes, void* hip_stream, sc_bwd_plan** out);
+sc_status sparse_conv_backward_set_filters(sc_bwd_plan* plan, const void* w_dev, void* hip_stream);
+sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, const void* y_dev, const void* dy_dev,
+                                   void* dx_dev, float* dw_dev, float* db_dev, void* hip_stream);
+void sparse_conv_backward_destroy(sc_bwd_plan* plan);
 
 /*
  * Mask generator of the training pipeline (Alg. 1, function getMask; Sec. 3.1): the mask of one layer

@@ -94,6 +94,18 @@ def lib() -> ctypes.CDLL:
         L.sc_maxpool2d_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.sc_add_relu.restype = ctypes.c_int
         L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
+        L.sparse_conv_plan_mask.restype = vp
+        L.sparse_conv_plan_mask.argtypes = [vp]
+        L.sparse_conv_backward_workspace_bytes.restype = ctypes.c_int
+        L.sparse_conv_backward_workspace_bytes.argtypes = [pd, ctypes.POINTER(ctypes.c_size_t)]
+        L.sparse_conv_backward_plan.restype = ctypes.c_int
+        L.sparse_conv_backward_plan.argtypes = [vp, pd, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+        L.sparse_conv_backward_set_filters.restype = ctypes.c_int
+        L.sparse_conv_backward_set_filters.argtypes = [vp, vp, vp]
+        L.sparse_conv_backward_run.restype = ctypes.c_int
+        L.sparse_conv_backward_run.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
+        L.sparse_conv_backward_destroy.restype = None
+        L.sparse_conv_backward_destroy.argtypes = [vp]
         L.sparse_mask_workspace_bytes.restype = ctypes.c_int
         L.sparse_mask_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.sparse_mask_generate.restype = ctypes.c_int
@@ -413,3 +425,69 @@ def sparse_mask_generate(score: torch.Tensor, ho: int, wo: int, sparsity: float,
                                       _dev_ptr(mask, "mask"), _dev_ptr(workspace, "workspace"), workspace.numel(),
                                       _stream_handle(stream)), "sparse_mask_generate")
     return mask
+
+
+class BackwardPlan:
+    """Owner of an sc_bwd_plan handle, its workspace and the forward plan it follows."""
+
+    def __init__(self, handle: int, fwd: Plan, workspace: torch.Tensor):
+        self.handle, self.fwd, self.workspace = handle, fwd, workspace
+
+    def close(self):
+        if self.handle:
+            lib().sparse_conv_backward_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def sparse_conv_backward_workspace_bytes(desc: sc_conv_desc) -> int:
+    out = ctypes.c_size_t()
+    _check(lib().sparse_conv_backward_workspace_bytes(ctypes.byref(desc), ctypes.byref(out)),
+           "sparse_conv_backward_workspace_bytes")
+    return int(out.value)
+
+
+def sparse_conv_backward_plan(fwd: Plan, w: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None) -> BackwardPlan:
+    d = fwd.desc
+    if _CODE_OF_TORCH.get(w.dtype) != d.dtype or w.numel() != d.c_out * d.kh * d.kw * (d.c_in // d.groups):
+        raise ValueError("filters do not match the plan")
+    nbytes = sparse_conv_backward_workspace_bytes(d)
+    if workspace is None:
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=w.device)
+    out = ctypes.c_void_p()
+    _check(lib().sparse_conv_backward_plan(fwd.handle, ctypes.byref(d), _dev_ptr(w, "w"), _dev_ptr(workspace, "workspace"),
+                                           workspace.numel(), _stream_handle(stream), ctypes.byref(out)),
+           "sparse_conv_backward_plan")
+    return BackwardPlan(out.value, fwd, workspace)
+
+
+def sparse_conv_backward_set_filters(plan: BackwardPlan, w: torch.Tensor, stream=None):
+    d = plan.fwd.desc
+    if _CODE_OF_TORCH.get(w.dtype) != d.dtype or w.numel() != d.c_out * d.kh * d.kw * (d.c_in // d.groups):
+        raise ValueError("filters do not match the plan")
+    _check(lib().sparse_conv_backward_set_filters(plan.handle, _dev_ptr(w, "w"), _stream_handle(stream)),
+           "sparse_conv_backward_set_filters")
+
+
+def sparse_conv_backward_run(plan: BackwardPlan, x: Optional[torch.Tensor], y: Optional[torch.Tensor], dy: torch.Tensor,
+                             dx: Optional[torch.Tensor] = None, dw: Optional[torch.Tensor] = None,
+                             db: Optional[torch.Tensor] = None, stream=None):
+    """Gradients into the tensors given (each optional): dx like x, dw float32 [Cout, kh, kw, Cin], db float32 [Cout]."""
+    d = plan.fwd.desc
+    info = sparse_conv_plan_info(plan.fwd)
+    n_x, n_y = d.n * d.h * d.w * d.c_in, info["m"] * d.c_out
+    for t, what, want in ((x, "x", n_x), (dx, "dx", n_x), (y, "y", n_y), (dy, "dy", n_y)):
+        if t is not None and (_CODE_OF_TORCH.get(t.dtype) != d.dtype or t.numel() != want):
+            raise ValueError(f"{what} does not match the plan")
+    if dw is not None and (dw.dtype != torch.float32 or dw.numel() != d.c_out * d.kh * d.kw * d.c_in):
+        raise ValueError("dw must be float32 [Cout, kh, kw, Cin]")
+    if db is not None and (db.dtype != torch.float32 or db.numel() != d.c_out):
+        raise ValueError("db must be float32 [Cout]")
+    _check(lib().sparse_conv_backward_run(plan.handle, _dev_ptr(x, "x"), _dev_ptr(y, "y"), _dev_ptr(dy, "dy"),
+                                          _dev_ptr(dx, "dx"), _dev_ptr(dw, "dw"), _dev_ptr(db, "db"),
+                                          _stream_handle(stream)), "sparse_conv_backward_run")

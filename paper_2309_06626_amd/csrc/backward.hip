@@ -1,0 +1,482 @@
+// Backward pass of the masked convolution (Alg. 1: backward(model) follows maskedForward(model, mask)).
+//
+// Forward: y[r, co] = mask[r] ? act(sum_k A[r, k] w[co, k] + bias[co]) : 0, A = lowered activations (Sec. 3).
+// With the upstream gradient dy and  g[r, co] = dy[r, co] if mask[r] and (no ReLU or y[r, co] > 0), else 0:
+//     db[co]    = sum_r g[r, co]
+//     dw[co, k] = sum_r g[r, co] A[r, k]          -- a contraction over the kept rows only: it shrinks with
+//                                                     the sparsity exactly like the forward GEMM (Sec. 3.2)
+//     dx        = the transposed convolution of g  -- for stride 1 an ordinary convolution of the g map
+//                                                     with the filters rotated by 180 degrees and
+//                                                     transposed; it runs through the forward kernels
+// Kernels here: g map (elementwise), column sums (db), the filter-gradient GEMM on the matrix cores with
+// a deterministic two-pass reduction over row splits, and the filter rotation for the input gradient.
+#include "../../include/sparse_conv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "conv_params.hpp"
+#include "mma_common.hpp"
+
+namespace sc {
+
+void note_hip_error(int32_t code);   // defined with the other host code of the library
+
+// ---- g map: the gradient that actually flows through a row (zero rows for dropped positions) --------------
+template <typename T, int V>
+__global__ void grad_map_kernel(const T* __restrict__ y, const T* __restrict__ dy, const uint8_t* __restrict__ mask,
+                                T* __restrict__ g, int64_t groups_total, int groups_per_row, int relu, int period) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= groups_total) return;
+  const int64_t r = idx / groups_per_row;
+  const int64_t mr = period ? r % period : r;
+  struct alignas(sizeof(T) * V) Grp { T v[V]; };
+  Grp out;
+  if (mask[mr] == 0) {
+#pragma unroll
+    for (int j = 0; j < V; ++j) out.v[j] = (T)0.0f;
+  } else {
+    const Grp d = reinterpret_cast<const Grp*>(dy)[idx];
+    if (relu) {
+      const Grp f = reinterpret_cast<const Grp*>(y)[idx];
+#pragma unroll
+      for (int j = 0; j < V; ++j) out.v[j] = (float)f.v[j] > 0.0f ? d.v[j] : (T)0.0f;
+    } else {
+      out = d;
+    }
+  }
+  reinterpret_cast<Grp*>(g)[idx] = out;
+}
+
+// ---- db: column sums of the g map, two passes with a fixed order of additions --------------------------------
+constexpr int kSumRows = 512;   // rows per workgroup of the first pass
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ g, int64_t rows, int c, float* __restrict__ partial) {
+  const int64_t r0 = (int64_t)blockIdx.x * kSumRows, r1 = min(rows, r0 + kSumRows);
+  for (int col = threadIdx.x; col < c; col += 256) {
+    float acc = 0.0f;
+    for (int64_t r = r0; r < r1; ++r) acc += (float)g[r * c + col];
+    partial[(int64_t)blockIdx.x * c + col] = acc;
+  }
+}
+__global__ void colsum_final_kernel(const float* __restrict__ partial, int slabs, int c, float* __restrict__ out) {
+  const int col = blockIdx.x * 256 + threadIdx.x;
+  if (col >= c) return;
+  float acc = 0.0f;
+  for (int s = 0; s < slabs; ++s) acc += partial[(int64_t)s * c + col];
+  out[col] = acc;
+}
+
+// ---- filters for the input gradient: w'[ci][kh-1-ky][kw-1-kx][co] = w[co][ky][kx][ci] ---------------------------
+template <typename T>
+__global__ void rotate_filters_kernel(const T* __restrict__ w, T* __restrict__ wr, int c_out, int c_in, int kh, int kw) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = (int64_t)c_out * kh * kw * c_in;
+  if (idx >= total) return;
+  int64_t rest = idx;
+  const int co = (int)(rest % c_out); rest /= c_out;
+  const int kx = (int)(rest % kw); rest /= kw;
+  const int ky = (int)(rest % kh);
+  const int ci = (int)(rest / kh);
+  wr[idx] = w[(((int64_t)co * kh + (kh - 1 - ky)) * kw + (kw - 1 - kx)) * c_in + ci];
+}
+
+__global__ void fill_bytes_kernel(uint8_t* __restrict__ p, int64_t n, uint8_t v) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ---- filter gradient -----------------------------------------------------------------------------------------
+// dW[co][k] = sum over the kept rows i of g[row_i][co] * A[row_i][k]: a GEMM whose contraction runs over
+// rows.  Both operands are row-major (a row of g is Cout contiguous values, a window tap of a row is Cin
+// contiguous values), while an MFMA lane needs eight consecutive CONTRACTION entries of one column.  The
+// tiles are therefore staged row-major in LDS (coalesced 16-byte gathers, as in the forward kernels) and a
+// lane assembles its operand with eight 16-bit LDS reads down a column; rows of the LDS tiles are padded
+// by 16 bytes so that the two lane halves, eight rows apart, hit different banks.
+//   workgroup = 128 output channels x 128 window entries x one split of the kept rows; 2 x 2 wavefronts,
+//               each 64 x 64 (2 x 2 MFMA blocks of 32 x 32 x 16)
+//   stage     = 64 kept rows, double buffered: the next stage's gathers are in flight during the MFMAs
+//   result    = float partial sums per split; a second kernel adds the splits in order (deterministic)
+struct WgradParams {
+  const void* x;
+  const void* g;             // g map [M][Cout]
+  const int32_t* row_idx;    // kept rows, or null for the identity
+  float* out;                // [splits][Cout][K]
+  int32_t rows, rows_per_split, splits;
+  int32_t h, w, c_in, ho_wo, wo, c_out;
+  int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
+  int32_t k;                 // kh * kw * c_in
+  int32_t co_tiles, k_tiles;
+  uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+};
+
+constexpr int kWgBM = 128, kWgBN = 128, kWgRows = 64, kWgPitch = 128 + 8;   // pitch in 16-bit elements
+
+template <int DT>
+__global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
+  using E = Elem<DT>;
+  using T = typename E::T;
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned short* s_g = reinterpret_cast<unsigned short*>(smem);                       // [2][kWgRows][kWgPitch]
+  unsigned short* s_a = s_g + 2 * kWgRows * kWgPitch;                                  // [2][kWgRows][kWgPitch]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int fp = lane & 31, fh = lane >> 5;
+  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+  const int tiles = p.co_tiles * p.k_tiles;
+  const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
+  const int co0 = (tile / p.k_tiles) * kWgBM, k0 = (tile % p.k_tiles) * kWgBN;
+  const int i_begin = split * p.rows_per_split, i_end = min(p.rows, i_begin + p.rows_per_split);
+
+  // this lane's column group of the staged tiles: 16-byte group q of rows srow, srow + 16, srow + 32, srow + 48
+  const int q = t & 15, srow = t >> 4;
+  const int gcol = co0 + 8 * q;                       // first output channel of its g group
+  const bool g_ok = gcol < p.c_out;                   // (Cout is a multiple of 8)
+  const int kk = k0 + 8 * q;                          // first window entry of its A group
+  const bool a_ok = kk < p.k;                         // (Cin is a multiple of 8: a group lies inside one tap)
+  const int tap = a_ok ? kk / p.c_in : 0, ci = kk - tap * p.c_in;
+  const int ky = tap / p.kw, kx = tap - ky * p.kw;
+  const T* __restrict__ xg = static_cast<const T*>(p.x);
+  const T* __restrict__ gg = static_cast<const T*>(p.g);
+
+  v4i rg[4], ra[4];
+  auto request = [&](int i0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + srow + 16 * u;
+      rg[u] = v4i{0, 0, 0, 0};
+      ra[u] = v4i{0, 0, 0, 0};
+      if (i < i_end) {
+        const int r = p.row_idx ? p.row_idx[i] : i;
+        if (g_ok) rg[u] = *reinterpret_cast<const v4i*>(gg + (int64_t)r * p.c_out + gcol);
+        const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
+        const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
+        const int iy = oy * p.sh - p.ph + ky * p.dil_h, ix = ox * p.sw - p.pw + kx * p.dil_w;
+        if (a_ok && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w)
+          ra[u] = *reinterpret_cast<const v4i*>(xg + (((int64_t)n * p.h + iy) * p.w + ix) * p.c_in + ci);
+      }
+    }
+  };
+  auto deposit = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int off = (buf * kWgRows + srow + 16 * u) * kWgPitch + 8 * q;
+      *reinterpret_cast<v4i*>(s_g + off) = rg[u];
+      *reinterpret_cast<v4i*>(s_a + off) = ra[u];
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+
+  // eight values down column `col` of a staged tile, rows row0 .. row0 + 7, packed as an MFMA operand
+  auto column = [&](const unsigned short* tile, int row0, int col) -> v4i {
+    const unsigned short* s = tile + row0 * kWgPitch + col;
+    v4i f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      f[e] = (int)((unsigned)s[(2 * e) * kWgPitch] | ((unsigned)s[(2 * e + 1) * kWgPitch] << 16));
+    return f;
+  };
+
+  if (i_begin < i_end) {
+    request(i_begin);
+    deposit(0);
+  }
+  __syncthreads();
+  int buf = 0;
+  for (int i0 = i_begin; i0 < i_end; i0 += kWgRows) {
+    const bool more = i0 + kWgRows < i_end;
+    if (more) request(i0 + kWgRows);               // in flight during the MFMAs below
+    const unsigned short* tg = s_g + buf * kWgRows * kWgPitch;
+    const unsigned short* ta = s_a + buf * kWgRows * kWgPitch;
+#pragma unroll
+    for (int ks = 0; ks < kWgRows / 16; ++ks) {
+      v4i gf[2], af[2];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) gf[mi] = column(tg, 16 * ks + 8 * fh, wm0 + 32 * mi + fp);
+#pragma unroll
+      for (int ni = 0; ni < 2; ++ni) af[ni] = column(ta, 16 * ks + 8 * fh, wn0 + 32 * ni + fp);
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 2; ++ni) E::mma(acc[mi][ni], gf[mi], af[ni]);
+    }
+    if (more) deposit(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // MFMA result row 8j + 4h + i sits in register 4j + i of lane half h; column = lane % 32
+  float* __restrict__ out = p.out + (int64_t)split * p.c_out * p.k;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 2; ++ni) {
+      const int kcol = k0 + wn0 + 32 * ni + fp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = co0 + wm0 + 32 * mi + 8 * (v >> 2) + 4 * fh + (v & 3);
+        if (co < p.c_out && kcol < p.k) out[(int64_t)co * p.k + kcol] = acc[mi][ni][v];
+      }
+    }
+}
+
+__global__ void wgrad_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count, float* __restrict__ dw) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float acc = 0.0f;
+  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
+  dw[i] = acc;
+}
+
+constexpr size_t kWgradPartialBytes = (size_t)64 << 20;   // most workspace the row splits may take
+
+static int wgrad_splits(int64_t rows, int c_out, int k) {
+  const int64_t tiles = (int64_t)((c_out + kWgBM - 1) / kWgBM) * ((k + kWgBN - 1) / kWgBN);
+  int64_t want = (768 + tiles - 1) / tiles;                                        // about three workgroups per CU
+  want = std::min<int64_t>(want, (rows + 4 * kWgRows - 1) / (4 * kWgRows));        // at least four stages per split
+  want = std::min<int64_t>(want, (int64_t)(kWgradPartialBytes / ((size_t)c_out * k * 4)));
+  return (int)std::max<int64_t>(want, 1);
+}
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace sc
+
+struct sc_bwd_plan {
+  const sc_plan* fwd;
+  sc_conv_desc desc;
+  int32_t ho, wo;
+  int64_t m;
+  unsigned char* ws;
+  size_t off_g, off_ones, off_wrot, off_inner, off_partial, off_colsum;
+  sc_plan* inner;            // dense plan of the transposed convolution (null: no input gradient for this layer)
+};
+
+namespace sc {
+
+static sc_status backward_layout(const sc_conv_desc* d, int32_t* ho, int32_t* wo, int64_t* m, sc_conv_desc* inner,
+                                 bool* has_inner, size_t* off_g, size_t* off_ones, size_t* off_wrot, size_t* off_inner,
+                                 size_t* off_partial, size_t* off_colsum, size_t* total) {
+  if (!d) return SC_ERR_NULL;
+  sc_status s = sparse_conv_output_shape(d, ho, wo, m);
+  if (s != SC_OK) return s;
+  // the filter-gradient kernel gathers 16-byte channel groups of 16-bit values
+  if (d->groups != 1 || d->layout != SC_NHWC || (d->dtype != SC_BF16 && d->dtype != SC_F16) || d->c_in % 8 != 0 ||
+      d->c_out % 8 != 0)
+    return SC_ERR_UNSUPPORTED;
+  const size_t eb = 2;
+  const int64_t k = (int64_t)d->kh * d->kw * d->c_in;
+  // input gradient: stride 1 only (then it is an ordinary convolution of the g map)
+  const int pad_h = d->dil_h * (d->kh - 1) - d->pad_h, pad_w = d->dil_w * (d->kw - 1) - d->pad_w;
+  *has_inner = d->stride_h == 1 && d->stride_w == 1 && pad_h >= 0 && pad_w >= 0;
+  size_t off = 0;
+  *off_g = off;      off = align_up(off + (size_t)*m * d->c_out * eb, 256);
+  *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRows - 1) / kSumRows) * d->c_out * 4, 256);
+  *off_partial = off;
+  off = align_up(off + (size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4, 256);   // the dense row count bounds every mask
+  *off_ones = *off_wrot = *off_inner = off;
+  if (*has_inner) {
+    std::memset(inner, 0, sizeof(*inner));
+    inner->n = d->n; inner->c_in = d->c_out; inner->h = *ho; inner->w = *wo; inner->c_out = d->c_in;
+    inner->kh = d->kh; inner->kw = d->kw; inner->stride_h = 1; inner->stride_w = 1;
+    inner->pad_h = pad_h; inner->pad_w = pad_w; inner->dil_h = d->dil_h; inner->dil_w = d->dil_w;
+    inner->groups = 1; inner->dtype = d->dtype; inner->layout = SC_NHWC; inner->has_bias = 0; inner->relu = 0;
+    inner->mask_mode = SC_MASK_SPATIAL; inner->out_mode = SC_OUT_ZERO_FILL; inner->sparsity = -1.0f;
+    size_t inner_bytes = 0;
+    s = sparse_conv_workspace_bytes(inner, &inner_bytes);
+    if (s != SC_OK) return s;
+    *off_ones = off;  off = align_up(off + (size_t)d->h * d->w, 256);
+    *off_wrot = off;  off = align_up(off + (size_t)d->c_out * k * eb, 256);
+    *off_inner = off; off = align_up(off + inner_bytes, 256);
+  }
+  *total = off;
+  return SC_OK;
+}
+
+static sc_status rotate_filters(const sc_bwd_plan* bp, const void* w_dev, hipStream_t stream) {
+  const sc_conv_desc& d = bp->desc;
+  const int64_t total = (int64_t)d.c_out * d.kh * d.kw * d.c_in;
+  hipLaunchKernelGGL(rotate_filters_kernel<_Float16>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                     (const _Float16*)w_dev, (_Float16*)(bp->ws + bp->off_wrot), d.c_out, d.c_in, d.kh, d.kw);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { note_hip_error((int32_t)e); return SC_ERR_HIP; }
+  return SC_OK;
+}
+
+}  // namespace sc
+
+extern "C" {
+
+sc_status sparse_conv_backward_workspace_bytes(const sc_conv_desc* desc, size_t* bytes) {
+  if (!bytes) return SC_ERR_NULL;
+  *bytes = 0;
+  int32_t ho, wo; int64_t m; sc_conv_desc inner; bool has_inner;
+  size_t a, b, c, e, f, g, total;
+  sc_status s = sc::backward_layout(desc, &ho, &wo, &m, &inner, &has_inner, &a, &b, &c, &e, &f, &g, &total);
+  if (s != SC_OK) return s;
+  *bytes = total;
+  return SC_OK;
+}
+
+sc_status sparse_conv_backward_plan(const sc_plan* fwd, const sc_conv_desc* desc, const void* w_dev, void* workspace_dev,
+                                    size_t workspace_bytes, void* hip_stream, sc_bwd_plan** out) {
+  if (!out) return SC_ERR_NULL;
+  *out = nullptr;
+  if (!fwd || !desc || !w_dev || !workspace_dev) return SC_ERR_NULL;
+  sc_bwd_plan tmp;
+  std::memset(&tmp, 0, sizeof(tmp));
+  sc_conv_desc inner; bool has_inner; size_t total;
+  sc_status s = sc::backward_layout(desc, &tmp.ho, &tmp.wo, &tmp.m, &inner, &has_inner, &tmp.off_g, &tmp.off_ones,
+                                    &tmp.off_wrot, &tmp.off_inner, &tmp.off_partial, &tmp.off_colsum, &total);
+  if (s != SC_OK) return s;
+  // the descriptor must be the forward plan's
+  int64_t fm = 0, fkept = 0; int32_t fho = 0, fwo = 0;
+  s = sparse_conv_plan_info(fwd, &fm, &fkept, &fho, &fwo, nullptr);
+  if (s != SC_OK) return s;
+  if (fm != tmp.m || fho != tmp.ho || fwo != tmp.wo) return SC_ERR_BAD_SHAPE;
+  if (workspace_bytes < total) return SC_ERR_WORKSPACE;
+  if (((uintptr_t)workspace_dev & 255) || ((uintptr_t)w_dev & 15)) return SC_ERR_ALIGN;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  tmp.fwd = fwd;
+  tmp.desc = *desc;
+  tmp.ws = static_cast<unsigned char*>(workspace_dev);
+  if (has_inner) {
+    const int64_t ones = (int64_t)desc->h * desc->w;
+    hipLaunchKernelGGL(sc::fill_bytes_kernel, dim3((unsigned)((ones + 255) / 256)), dim3(256), 0, stream,
+                       tmp.ws + tmp.off_ones, ones, (uint8_t)1);
+    s = sc::rotate_filters(&tmp, w_dev, stream);
+    if (s != SC_OK) return s;
+    s = sparse_conv_plan(&inner, tmp.ws + tmp.off_ones, tmp.ws + tmp.off_wrot, tmp.ws + tmp.off_inner,
+                         total - tmp.off_inner, hip_stream, &tmp.inner);
+    if (s != SC_OK) return s;
+  }
+  sc_bwd_plan* bp = new (std::nothrow) sc_bwd_plan(tmp);
+  if (!bp) { sparse_conv_plan_destroy(tmp.inner); return SC_ERR_NULL; }
+  *out = bp;
+  return SC_OK;
+}
+
+sc_status sparse_conv_backward_set_filters(sc_bwd_plan* plan, const void* w_dev, void* hip_stream) {
+  if (!plan || !w_dev) return SC_ERR_NULL;
+  if ((uintptr_t)w_dev & 15) return SC_ERR_ALIGN;
+  if (!plan->inner) return SC_OK;            // only the input gradient uses the filters
+  sc_status s = sc::rotate_filters(plan, w_dev, static_cast<hipStream_t>(hip_stream));
+  if (s != SC_OK) return s;
+  return sparse_conv_plan_set_filters(plan->inner, plan->ws + plan->off_wrot, hip_stream);
+}
+
+sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, const void* y_dev, const void* dy_dev,
+                                   void* dx_dev, float* dw_dev, float* db_dev, void* hip_stream) {
+  if (!plan || !dy_dev) return SC_ERR_NULL;
+  const sc_conv_desc& d = plan->desc;
+  if (d.relu && !y_dev) return SC_ERR_NULL;
+  if (dw_dev && !x_dev) return SC_ERR_NULL;
+  if (((uintptr_t)dy_dev & 15) || ((uintptr_t)y_dev & 15) || ((uintptr_t)x_dev & 15) || ((uintptr_t)dx_dev & 15) ||
+      ((uintptr_t)dw_dev & 15) || ((uintptr_t)db_dev & 3))
+    return SC_ERR_ALIGN;
+  if (dx_dev && !plan->inner) return SC_ERR_UNSUPPORTED;     // strided layers: no input gradient
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  int64_t m = 0, kept = 0; const int32_t* rows_dev = nullptr;
+  sc_status s = sparse_conv_plan_info(plan->fwd, &m, &kept, nullptr, nullptr, &rows_dev);
+  if (s != SC_OK) return s;
+  const uint8_t* mask = sparse_conv_plan_mask(plan->fwd);
+  const int dt = d.dtype == SC_BF16 ? sc::kBF16 : sc::kF16;
+  const int period = d.mask_mode == SC_MASK_SPATIAL ? plan->ho * plan->wo : 0;
+  _Float16* g = reinterpret_cast<_Float16*>(plan->ws + plan->off_g);    // 16-bit patterns; compared as the real type below
+
+  // g map
+  {
+    const int gpr = d.c_out / 8;
+    const int64_t groups = m * gpr;
+    const unsigned grid = (unsigned)((groups + 255) / 256);
+    if (dt == sc::kBF16)
+      hipLaunchKernelGGL((sc::grad_map_kernel<__bf16, 8>), dim3(grid), dim3(256), 0, stream, (const __bf16*)y_dev,
+                         (const __bf16*)dy_dev, mask, (__bf16*)g, groups, gpr, d.relu, period);
+    else
+      hipLaunchKernelGGL((sc::grad_map_kernel<_Float16, 8>), dim3(grid), dim3(256), 0, stream, (const _Float16*)y_dev,
+                         (const _Float16*)dy_dev, mask, g, groups, gpr, d.relu, period);
+  }
+  // db
+  if (db_dev) {
+    const int slabs = (int)((m + sc::kSumRows - 1) / sc::kSumRows);
+    float* partial = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
+    if (dt == sc::kBF16)
+      hipLaunchKernelGGL(sc::colsum_partial_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)g, m, d.c_out, partial);
+    else
+      hipLaunchKernelGGL(sc::colsum_partial_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, g, m, d.c_out, partial);
+    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 255) / 256), dim3(256), 0, stream, partial, slabs, d.c_out, db_dev);
+  }
+  // dw
+  if (dw_dev) {
+    const int k = d.kh * d.kw * d.c_in;
+    const int64_t count = (int64_t)d.c_out * k;
+    if (kept == 0) {
+      hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+                         (const float*)nullptr, 0, count, dw_dev);
+    } else {
+      sc::WgradParams p;
+      std::memset(&p, 0, sizeof(p));
+      p.x = x_dev; p.g = g;
+      p.row_idx = kept == m ? nullptr : rows_dev;
+      p.splits = sc::wgrad_splits(kept, d.c_out, k);
+      p.rows = (int32_t)kept;
+      p.rows_per_split = (int32_t)(((kept + p.splits - 1) / p.splits + sc::kWgRows - 1) / sc::kWgRows * sc::kWgRows);
+      p.splits = (int32_t)((kept + p.rows_per_split - 1) / p.rows_per_split);
+      p.out = p.splits == 1 ? dw_dev : reinterpret_cast<float*>(plan->ws + plan->off_partial);
+      p.h = d.h; p.w = d.w; p.c_in = d.c_in; p.ho_wo = plan->ho * plan->wo; p.wo = plan->wo; p.c_out = d.c_out;
+      p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+      p.dil_h = d.dil_h; p.dil_w = d.dil_w;
+      p.k = k;
+      p.co_tiles = (d.c_out + sc::kWgBM - 1) / sc::kWgBM;
+      p.k_tiles = (k + sc::kWgBN - 1) / sc::kWgBN;
+      sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+      sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
+      const size_t lds = (size_t)4 * sc::kWgRows * sc::kWgPitch * 2;
+      static bool attr_set[2] = {false, false};
+      const unsigned grid = (unsigned)(p.co_tiles * p.k_tiles * p.splits);
+      if (dt == sc::kBF16) {
+        if (!attr_set[0]) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sc::wgrad_kernel<sc::kBF16>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+          if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+          attr_set[0] = true;
+        }
+        hipLaunchKernelGGL(sc::wgrad_kernel<sc::kBF16>, dim3(grid), dim3(256), lds, stream, p);
+      } else {
+        if (!attr_set[1]) {
+          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sc::wgrad_kernel<sc::kF16>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+          if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+          attr_set[1] = true;
+        }
+        hipLaunchKernelGGL(sc::wgrad_kernel<sc::kF16>, dim3(grid), dim3(256), lds, stream, p);
+      }
+      if (p.splits > 1)
+        hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+                           (const float*)p.out, p.splits, count, dw_dev);
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+  // dx: the g map through the forward kernels with the rotated filters
+  if (dx_dev) return dense_conv_run(plan->inner, g, nullptr, dx_dev, hip_stream);
+  return SC_OK;
+}
+
+void sparse_conv_backward_destroy(sc_bwd_plan* plan) {
+  if (!plan) return;
+  sparse_conv_plan_destroy(plan->inner);
+  delete plan;
+}
+
+}  // extern "C"

@@ -1068,6 +1068,10 @@ sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, 
   return SC_OK;
 }
 
+const uint8_t* sparse_conv_plan_mask(const sc_plan* plan) {
+  return plan ? plan->ws + plan->geo.off_mask : nullptr;
+}
+
 sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* tile_m, int32_t* tile_n,
                                  int64_t* workgroups) {
   if (!plan) return SC_ERR_NULL;
