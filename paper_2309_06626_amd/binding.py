@@ -491,3 +491,20 @@ def sparse_conv_backward_run(plan: BackwardPlan, x: Optional[torch.Tensor], y: O
     _check(lib().sparse_conv_backward_run(plan.handle, _dev_ptr(x, "x"), _dev_ptr(y, "y"), _dev_ptr(dy, "dy"),
                                           _dev_ptr(dx, "dx"), _dev_ptr(dw, "dw"), _dev_ptr(db, "db"),
                                           _stream_handle(stream)), "sparse_conv_backward_run")
+
+
+def prepared_backward_run(plan: BackwardPlan, x, y, dy, dx=None, dw=None, db=None, stream=None):
+    """Validate once, run once, and return a zero-argument callable that issues the same backward run again."""
+    sparse_conv_backward_run(plan, x, y, dy, dx, dw, db, stream)
+    fn, h, st = lib().sparse_conv_backward_run, plan.handle, _stream_handle(stream)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    args = (ptr(x), ptr(y), ptr(dy), ptr(dx), ptr(dw), ptr(db))
+    keep = (plan, x, y, dy, dx, dw, db)
+
+    def call(stream_handle=None):
+        rc = fn(h, *args, st if stream_handle is None else stream_handle)
+        if rc != SC_OK:
+            raise ScError(rc, "sparse_conv_backward_run")
+        return keep
+
+    return call

@@ -52,22 +52,68 @@ __global__ void grad_map_kernel(const T* __restrict__ y, const T* __restrict__ d
 }
 
 // ---- db: column sums of the g map, two passes with a fixed order of additions --------------------------------
-constexpr int kSumRows = 512;   // rows per workgroup of the first pass
+// First pass: a workgroup owns kSumRows rows; a lane owns one 16-byte group of channels and every
+// (256 / groups)-th row of the slab, then the row lanes of a group are added in lane order through LDS.
+constexpr int kSumRows = 512;   // most rows per workgroup of the first pass
+constexpr int kSumRowsLeast = 32;
+// rows per workgroup: about 1024 workgroups, between kSumRowsLeast and kSumRows rows each
+static inline int colsum_slab_rows(int64_t rows) {
+  const int64_t want = (rows + 1023) / 1024;
+  return (int)std::min<int64_t>(kSumRows, std::max<int64_t>(kSumRowsLeast, (want + 31) / 32 * 32));
+}
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ g, int64_t rows, int c, float* __restrict__ partial) {
-  const int64_t r0 = (int64_t)blockIdx.x * kSumRows, r1 = min(rows, r0 + kSumRows);
-  for (int col = threadIdx.x; col < c; col += 256) {
-    float acc = 0.0f;
-    for (int64_t r = r0; r < r1; ++r) acc += (float)g[r * c + col];
-    partial[(int64_t)blockIdx.x * c + col] = acc;
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ g, int64_t rows, int c, int slab_rows,
+                                                             float* __restrict__ partial) {
+  __shared__ float s_acc[256][9];                       // (padded: the final adds walk a column of it)
+  struct alignas(16) Grp { T v[8]; };
+  const int groups = c / 8;
+  const int64_t r0 = (int64_t)blockIdx.x * slab_rows, r1 = min(rows, r0 + slab_rows);
+  for (int gbase = 0; gbase < groups; gbase += 256) {   // (more than 2048 channels: several sweeps)
+    const int gcount = min(256, groups - gbase);
+    const int lanes_per_group = 256 / gcount;            // row lanes that share a channel group
+    const int gi = threadIdx.x % gcount, rl = threadIdx.x / gcount;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+    if (rl < lanes_per_group)
+      for (int64_t r = r0 + rl; r < r1; r += lanes_per_group) {
+        const Grp v = *reinterpret_cast<const Grp*>(g + r * c + (int64_t)(gbase + gi) * 8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (float)v.v[j];
+      }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s_acc[threadIdx.x][j] = acc[j];
+    __syncthreads();
+    if (threadIdx.x < gcount) {
+      float tot[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tot[j] = 0.0f;
+      for (int l = 0; l < lanes_per_group; ++l)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tot[j] += s_acc[l * gcount + threadIdx.x][j];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) partial[(int64_t)blockIdx.x * c + (int64_t)(gbase + threadIdx.x) * 8 + j] = tot[j];
+    }
+    __syncthreads();
   }
 }
-__global__ void colsum_final_kernel(const float* __restrict__ partial, int slabs, int c, float* __restrict__ out) {
-  const int col = blockIdx.x * 256 + threadIdx.x;
-  if (col >= c) return;
+// Second pass: 16 lanes per channel each add every 16th slab, then the 16 sub-sums are added in lane order.
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int slabs, int c,
+                                                           float* __restrict__ out) {
+  __shared__ float s_sub[16][17];
+  const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int col = blockIdx.x * 16 + e;
   float acc = 0.0f;
-  for (int s = 0; s < slabs; ++s) acc += partial[(int64_t)s * c + col];
-  out[col] = acc;
+  if (col < c)
+    for (int s = sl; s < slabs; s += 16) acc += partial[(int64_t)s * c + col];
+  s_sub[sl][e] = acc;
+  __syncthreads();
+  if (threadIdx.x < 16 && col < c) {
+    float tot = 0.0f;
+#pragma unroll
+    for (int l = 0; l < 16; ++l) tot += s_sub[l][threadIdx.x];
+    out[col] = tot;
+  }
 }
 
 // ---- filters for the input gradient: w'[ci][kh-1-ky][kw-1-kx][co] = w[co][ky][kx][ci] ---------------------------
@@ -142,15 +188,23 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   const T* __restrict__ xg = static_cast<const T*>(p.x);
   const T* __restrict__ gg = static_cast<const T*>(p.g);
 
+  // row numbers are fetched one stage ahead of the data they address, so a stage costs one round trip
   v4i rg[4], ra[4];
-  auto request = [&](int i0) {
+  int r_next[4];
+  auto request_rows = [&](int i0) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int i = i0 + srow + 16 * u;
+      r_next[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
+    }
+  };
+  auto request = [&](int i0) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
       rg[u] = v4i{0, 0, 0, 0};
       ra[u] = v4i{0, 0, 0, 0};
-      if (i < i_end) {
-        const int r = p.row_idx ? p.row_idx[i] : i;
+      const int r = r_next[u];
+      if (r >= 0) {
         if (g_ok) rg[u] = *reinterpret_cast<const v4i*>(gg + (int64_t)r * p.c_out + gcol);
         const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
         const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
@@ -188,14 +242,19 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   };
 
   if (i_begin < i_end) {
+    request_rows(i_begin);
     request(i_begin);
+    request_rows(i_begin + kWgRows);
     deposit(0);
   }
   __syncthreads();
   int buf = 0;
   for (int i0 = i_begin; i0 < i_end; i0 += kWgRows) {
     const bool more = i0 + kWgRows < i_end;
-    if (more) request(i0 + kWgRows);               // in flight during the MFMAs below
+    if (more) {
+      request(i0 + kWgRows);                       // in flight during the MFMAs below
+      request_rows(i0 + 2 * kWgRows);
+    }
     const unsigned short* tg = s_g + buf * kWgRows * kWgPitch;
     const unsigned short* ta = s_a + buf * kWgRows * kWgPitch;
 #pragma unroll
@@ -230,20 +289,39 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
     }
 }
 
-__global__ void wgrad_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count, float* __restrict__ dw) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= count) return;
-  float acc = 0.0f;
-  for (int s = 0; s < splits; ++s) acc += partial[(int64_t)s * count + i];
-  dw[i] = acc;
+// dw[i] = sum over the splits of partial[s][i].  A workgroup owns 64 consecutive elements (16 groups of
+// four); 16 lanes per group each add every 16th split (independent 16-byte loads in flight), then the 16
+// sub-sums are added in lane order: the order of additions is fixed.  (Cout * K is a multiple of 64.)
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
+                                                           float* __restrict__ dw) {
+  __shared__ v4f s_sub[16][17];
+  const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t i = ((int64_t)blockIdx.x * 16 + e) * 4;
+  v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (i < count)
+    for (int s = sl; s < splits; s += 16) {
+      const v4f v = *reinterpret_cast<const v4f*>(partial + (int64_t)s * count + i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += v[j];
+    }
+  s_sub[sl][e] = acc;
+  __syncthreads();
+  if (threadIdx.x < 16 && i < count) {
+    v4f tot = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int l = 0; l < 16; ++l)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tot[j] += s_sub[l][threadIdx.x][j];
+    *reinterpret_cast<v4f*>(dw + i) = tot;
+  }
 }
 
 constexpr size_t kWgradPartialBytes = (size_t)64 << 20;   // most workspace the row splits may take
 
 static int wgrad_splits(int64_t rows, int c_out, int k) {
   const int64_t tiles = (int64_t)((c_out + kWgBM - 1) / kWgBM) * ((k + kWgBN - 1) / kWgBN);
-  int64_t want = (768 + tiles - 1) / tiles;                                        // about three workgroups per CU
-  want = std::min<int64_t>(want, (rows + 4 * kWgRows - 1) / (4 * kWgRows));        // at least four stages per split
+  int64_t want = (512 + tiles - 1) / tiles;                                        // about two workgroups per CU
+  want = std::min<int64_t>(want, (rows + 8 * kWgRows - 1) / (8 * kWgRows));        // at least eight stages per split
   want = std::min<int64_t>(want, (int64_t)(kWgradPartialBytes / ((size_t)c_out * k * 4)));
   return (int)std::max<int64_t>(want, 1);
 }
@@ -281,7 +359,7 @@ static sc_status backward_layout(const sc_conv_desc* d, int32_t* ho, int32_t* wo
   *has_inner = d->stride_h == 1 && d->stride_w == 1 && pad_h >= 0 && pad_w >= 0;
   size_t off = 0;
   *off_g = off;      off = align_up(off + (size_t)*m * d->c_out * eb, 256);
-  *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRows - 1) / kSumRows) * d->c_out * 4, 256);
+  *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRowsLeast - 1) / kSumRowsLeast) * d->c_out * 4, 256);
   *off_partial = off;
   off = align_up(off + (size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4, 256);   // the dense row count bounds every mask
   *off_ones = *off_wrot = *off_inner = off;
@@ -408,20 +486,22 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   }
   // db
   if (db_dev) {
-    const int slabs = (int)((m + sc::kSumRows - 1) / sc::kSumRows);
+    const int slab_rows = sc::colsum_slab_rows(m);
+    const int slabs = (int)((m + slab_rows - 1) / slab_rows);
     float* partial = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
     if (dt == sc::kBF16)
-      hipLaunchKernelGGL(sc::colsum_partial_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)g, m, d.c_out, partial);
+      hipLaunchKernelGGL(sc::colsum_partial_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)g, m, d.c_out,
+                         slab_rows, partial);
     else
-      hipLaunchKernelGGL(sc::colsum_partial_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, g, m, d.c_out, partial);
-    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 255) / 256), dim3(256), 0, stream, partial, slabs, d.c_out, db_dev);
+      hipLaunchKernelGGL(sc::colsum_partial_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, g, m, d.c_out, slab_rows, partial);
+    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 15) / 16), dim3(256), 0, stream, partial, slabs, d.c_out, db_dev);
   }
   // dw
   if (dw_dev) {
     const int k = d.kh * d.kw * d.c_in;
     const int64_t count = (int64_t)d.c_out * k;
     if (kept == 0) {
-      hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+      hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
                          (const float*)nullptr, 0, count, dw_dev);
     } else {
       sc::WgradParams p;
@@ -462,7 +542,7 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
         hipLaunchKernelGGL(sc::wgrad_kernel<sc::kF16>, dim3(grid), dim3(256), lds, stream, p);
       }
       if (p.splits > 1)
-        hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream,
+        hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
                            (const float*)p.out, p.splits, count, dw_dev);
     }
   }

@@ -223,6 +223,46 @@ def depthwise_times(steps):
     return rows
 
 
+def backward_times(steps):
+    """Backward pass (Alg. 1) of a few benchmark layers: us per call for the filter + bias gradients, the
+    input gradient, and the forward run beside them; TFLOP/s of the filter-gradient contraction
+    (2 * kept * K * Cout, the same count as the forward GEMM)."""
+    import torch
+
+    import workloads as W
+    from paper_2309_06626_amd import binding as B
+    from paper_2309_06626_amd import runtime as R
+    from paper_2309_06626_amd.metrics import algorithmic_flops, time_launches
+
+    c3 = {s.name: s for s in W.conv_specs(W.config3())}
+    specs = [W.config2(0.5), W.config2(0.0), c3["l2b0_conv2"], c3["l3b0_conv2"], c3["l4b0_conv2"],
+             [s for s in W.config4() if s.name == "c4_pw_96_576_28"][0]]
+    rows = []
+    warm = max(steps // 10, 5)
+    for spec in specs:
+        ci = W.make_conv_inputs(spec, W.base_seed(2))
+        layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+        bwd = B.sparse_conv_backward_plan(layer.plan, layer.w)
+        x = R.to_device(ci.x, spec.dtype)
+        y = layer.new_output().zero_()
+        layer.sparse(x, y)
+        dy = torch.randn(spec.y_shape(), device="cuda:0").to(B.TORCH_DTYPE[spec.dtype])
+        dx = torch.empty_like(x)
+        dw = torch.empty(spec.w_shape(), dtype=torch.float32, device="cuda:0")
+        db = torch.empty(spec.c_out, dtype=torch.float32, device="cuda:0")
+        _, tf = time_launches(B.prepared_run(layer.plan, x, layer.bias, y), steps, warm)
+        _, tw = time_launches(B.prepared_backward_run(bwd, x, y, dy, None, dw, db), steps, warm)
+        _, tx = time_launches(B.prepared_backward_run(bwd, x, y, dy, dx, None, None), steps, warm)
+        _, tb = time_launches(B.prepared_backward_run(bwd, x, y, dy, dx, dw, db), steps, warm)
+        fl = algorithmic_flops(spec, layer.info["kept"])
+        rows.append({"layer": spec.name, "m": spec.m, "k": spec.k, "c_out": spec.c_out, "sparsity": spec.sparsity,
+                     "forward_us": tf * 1e6, "dw_db_us": tw * 1e6, "dx_us": tx * 1e6, "all_us": tb * 1e6,
+                     "dw_tflops": fl / tw / 1e12})
+        del layer, bwd, x, y, dy, dx, dw, db
+        torch.cuda.empty_cache()
+    return rows
+
+
 def mask_generator_times(steps):
     """us per call of the mask generator (two launches) for the layer resolutions of the two networks."""
     import torch
@@ -254,6 +294,7 @@ def main():
     ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
     ap.add_argument("--pruned", action="store_true",
                     help="also time a channel-pruned ResNet18 stack (51/102/205/410 channels, s = 0.3), as it is and padded to 8")
+    ap.add_argument("--backward", action="store_true", help="also time the backward pass of a few layers")
     ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
     args = ap.parse_args()
 
@@ -346,6 +387,16 @@ def main():
             print(f"| {r['layer']} | {r['m']}x{r['c']} | {r['sparse_us']:.2f} | {100 * r['sparse_hbm_frac']:.1f} | "
                   f"{r['compact_out_us']:.2f} | {100 * r['compact_hbm_frac']:.1f} | {r['dense_us']:.2f} | "
                   f"{100 * r['dense_hbm_frac']:.1f} | {r['dense_us'] / r['sparse_us']:.2f} | {r['dense_us'] / r['compact_out_us']:.2f} |")
+    bw_rows = []
+    if args.backward:
+        bw_rows = backward_times(max(args.steps // 2, 20))
+        print()
+        print("| backward pass: layer | M x K x Cout | s | forward us | dw + db us (g map, column sums, row-contraction GEMM, reduce) | "
+              "TFLOP/s of that GEMM | dx us (g map + convolution with rotated filters) | dx + dw + db us |")
+        print("|---|---|---|---|---|---|---|---|")
+        for r in bw_rows:
+            print(f"| {r['layer']} | {r['m']}x{r['k']}x{r['c_out']} | {r['sparsity']:.2f} | {r['forward_us']:.2f} | {r['dw_db_us']:.2f} | "
+                  f"{r['dw_tflops']:.1f} | {r['dx_us']:.2f} | {r['all_us']:.2f} |")
     mask_rows = []
     if args.masks:
         mask_rows = mask_generator_times(max(args.steps // 4, 20))
@@ -365,6 +416,8 @@ def main():
                 f.write(json.dumps({"compact_formats": compact_rows}) + "\n")
             if dw_rows:
                 f.write(json.dumps({"depthwise": dw_rows}) + "\n")
+            if bw_rows:
+                f.write(json.dumps({"backward": bw_rows}) + "\n")
 
 
 if __name__ == "__main__":
