@@ -8,7 +8,7 @@
 //     dx        = the transposed convolution of g  -- for stride 1 an ordinary convolution of the g map
 //                                                     with the filters rotated by 180 degrees and
 //                                                     transposed; it runs through the forward kernels
-// Kernels here: g map (elementwise), column sums (db), the filter-gradient GEMM on the matrix cores with
+// Kernels here: g map with its column sums (db), the filter-gradient GEMM on the matrix cores with
 // a deterministic two-pass reduction over row splits, and the filter rotation for the input gradient.
 #include "../../include/sparse_conv.h"
 
@@ -25,36 +25,12 @@ namespace sc {
 
 void note_hip_error(int32_t code);   // defined with the other host code of the library
 
-// ---- g map: the gradient that actually flows through a row (zero rows for dropped positions) --------------
-template <typename T, int V>
-__global__ void grad_map_kernel(const T* __restrict__ y, const T* __restrict__ dy, const uint8_t* __restrict__ mask,
-                                T* __restrict__ g, int64_t groups_total, int groups_per_row, int relu, int period) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (idx >= groups_total) return;
-  const int64_t r = idx / groups_per_row;
-  const int64_t mr = period ? r % period : r;
-  struct alignas(sizeof(T) * V) Grp { T v[V]; };
-  Grp out;
-  if (mask[mr] == 0) {
-#pragma unroll
-    for (int j = 0; j < V; ++j) out.v[j] = (T)0.0f;
-  } else {
-    const Grp d = reinterpret_cast<const Grp*>(dy)[idx];
-    if (relu) {
-      const Grp f = reinterpret_cast<const Grp*>(y)[idx];
-#pragma unroll
-      for (int j = 0; j < V; ++j) out.v[j] = (float)f.v[j] > 0.0f ? d.v[j] : (T)0.0f;
-    } else {
-      out = d;
-    }
-  }
-  reinterpret_cast<Grp*>(g)[idx] = out;
-}
-
-// ---- db: column sums of the g map, two passes with a fixed order of additions --------------------------------
-// First pass: a workgroup owns kSumRows rows; a lane owns one 16-byte group of channels and every
-// (256 / groups)-th row of the slab, then the row lanes of a group are added in lane order through LDS.
-constexpr int kSumRows = 512;   // most rows per workgroup of the first pass
+// ---- g map and db ------------------------------------------------------------------------------------------------
+// g = the gradient that actually flows through a row (zero rows for dropped positions); db = its column
+// sums, in two passes with a fixed order of additions.  First pass, fused with the g map: a workgroup owns
+// a slab of rows; a lane owns one 16-byte group of channels and every (256 / groups)-th row of the slab,
+// writes g for them and keeps their sum; the row lanes of a group are then added in lane order through LDS.
+constexpr int kSumRows = 512;   // most rows per workgroup
 constexpr int kSumRowsLeast = 32;
 // rows per workgroup: about 1024 workgroups, between kSumRowsLeast and kSumRows rows each
 static inline int colsum_slab_rows(int64_t rows) {
@@ -62,8 +38,10 @@ static inline int colsum_slab_rows(int64_t rows) {
   return (int)std::min<int64_t>(kSumRows, std::max<int64_t>(kSumRowsLeast, (want + 31) / 32 * 32));
 }
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict__ g, int64_t rows, int c, int slab_rows,
-                                                             float* __restrict__ partial) {
+__global__ __launch_bounds__(256) void grad_map_kernel(const T* __restrict__ y, const T* __restrict__ dy,
+                                                       const uint8_t* __restrict__ mask, T* __restrict__ g, int64_t rows,
+                                                       int c, int slab_rows, int relu, int period,
+                                                       float* __restrict__ partial) {
   __shared__ float s_acc[256][9];                       // (padded: the final adds walk a column of it)
   struct alignas(16) Grp { T v[8]; };
   const int groups = c / 8;
@@ -77,9 +55,21 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
     for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
     if (rl < lanes_per_group)
       for (int64_t r = r0 + rl; r < r1; r += lanes_per_group) {
-        const Grp v = *reinterpret_cast<const Grp*>(g + r * c + (int64_t)(gbase + gi) * 8);
+        const int64_t at = r * c + (int64_t)(gbase + gi) * 8;
+        Grp out;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] += (float)v.v[j];
+        for (int j = 0; j < 8; ++j) out.v[j] = (T)0.0f;
+        if (mask[period ? r % period : r] != 0) {
+          out = *reinterpret_cast<const Grp*>(dy + at);
+          if (relu) {
+            const Grp f = *reinterpret_cast<const Grp*>(y + at);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) out.v[j] = (float)f.v[j] > 0.0f ? out.v[j] : (T)0.0f;
+          }
+        }
+        *reinterpret_cast<Grp*>(g + at) = out;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += (float)out.v[j];
       }
 #pragma unroll
     for (int j = 0; j < 8; ++j) s_acc[threadIdx.x][j] = acc[j];
@@ -97,21 +87,21 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const T* __restrict
     __syncthreads();
   }
 }
-// Second pass: 16 lanes per channel each add every 16th slab, then the 16 sub-sums are added in lane order.
+// Second pass: a workgroup owns four channels; 64 lanes per channel each add every 64th slab, then the 64
+// sub-sums are added in lane order.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ partial, int slabs, int c,
                                                            float* __restrict__ out) {
-  __shared__ float s_sub[16][17];
-  const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
-  const int col = blockIdx.x * 16 + e;
+  __shared__ float s_sub[64][5];
+  const int e = threadIdx.x & 3, sl = threadIdx.x >> 2;
+  const int col = blockIdx.x * 4 + e;
   float acc = 0.0f;
   if (col < c)
-    for (int s = sl; s < slabs; s += 16) acc += partial[(int64_t)s * c + col];
+    for (int s = sl; s < slabs; s += 64) acc += partial[(int64_t)s * c + col];
   s_sub[sl][e] = acc;
   __syncthreads();
-  if (threadIdx.x < 16 && col < c) {
+  if (threadIdx.x < 4 && col < c) {
     float tot = 0.0f;
-#pragma unroll
-    for (int l = 0; l < 16; ++l) tot += s_sub[l][threadIdx.x];
+    for (int l = 0; l < 64; ++l) tot += s_sub[l][threadIdx.x];
     out[col] = tot;
   }
 }
@@ -159,29 +149,39 @@ struct WgradParams {
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
 };
 
-constexpr int kWgBM = 128, kWgBN = 128, kWgRows = 64, kWgPitch = 128 + 8;   // pitch in 16-bit elements
+constexpr int kWgRows = 64;      // kept rows per stage
 
-template <int DT>
+// BM output channels x BN window entries per workgroup, BM * BN = 128 * 128.  (A 64 x 256 shape for layers
+// with at most 64 output channels measured slower than 128 x 128 with half of its channel rows idle: the
+// kernel is bound by the instructions spent per staged row, not by the MFMAs.)
+template <int DT, int BM, int BN>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
+  constexpr int R = kWgRows;
+  constexpr int WAVES_N = BN / 64;
+  static_assert((BM / 64) * WAVES_N == 4, "four wavefronts of 64 x 64");
+  constexpr int PG = BM + 8, PA = BN + 8;              // LDS row pitches in 16-bit elements
+  constexpr int GQ = BM / 8, AQ = BN / 8;              // 16-byte groups per staged row
+  constexpr int NG = R * GQ / 256, NA = R * AQ / 256;  // groups a lane stages per tile
   extern __shared__ __align__(16) unsigned char smem[];
-  unsigned short* s_g = reinterpret_cast<unsigned short*>(smem);                       // [2][kWgRows][kWgPitch]
-  unsigned short* s_a = s_g + 2 * kWgRows * kWgPitch;                                  // [2][kWgRows][kWgPitch]
+  unsigned short* s_g = reinterpret_cast<unsigned short*>(smem);      // [2][R][PG]
+  unsigned short* s_a = s_g + 2 * R * PG;                             // [2][R][PA]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int fp = lane & 31, fh = lane >> 5;
-  const int wm0 = (wave >> 1) * 64, wn0 = (wave & 1) * 64;
+  const int wm0 = (wave / WAVES_N) * 64, wn0 = (wave % WAVES_N) * 64;
   const int tiles = p.co_tiles * p.k_tiles;
   const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
-  const int co0 = (tile / p.k_tiles) * kWgBM, k0 = (tile % p.k_tiles) * kWgBN;
+  const int co0 = (tile / p.k_tiles) * BM, k0 = (tile % p.k_tiles) * BN;
   const int i_begin = split * p.rows_per_split, i_end = min(p.rows, i_begin + p.rows_per_split);
 
-  // this lane's column group of the staged tiles: 16-byte group q of rows srow, srow + 16, srow + 32, srow + 48
-  const int q = t & 15, srow = t >> 4;
-  const int gcol = co0 + 8 * q;                       // first output channel of its g group
+  // this lane's column groups of the staged tiles (fixed for the whole kernel)
+  const int qg = t % GQ, srow_g = t / GQ;             // g tile: group qg of rows srow_g + u * (256 / GQ)
+  const int qa = t % AQ, srow_a = t / AQ;             // A tile: group qa of rows srow_a + u * (256 / AQ)
+  const int gcol = co0 + 8 * qg;                      // first output channel of its g group
   const bool g_ok = gcol < p.c_out;                   // (Cout is a multiple of 8)
-  const int kk = k0 + 8 * q;                          // first window entry of its A group
+  const int kk = k0 + 8 * qa;                         // first window entry of its A group
   const bool a_ok = kk < p.k;                         // (Cin is a multiple of 8: a group lies inside one tap)
   const int tap = a_ok ? kk / p.c_in : 0, ci = kk - tap * p.c_in;
   const int ky = tap / p.kw, kx = tap - ky * p.kw;
@@ -189,38 +189,46 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   const T* __restrict__ gg = static_cast<const T*>(p.g);
 
   // row numbers are fetched one stage ahead of the data they address, so a stage costs one round trip
-  v4i rg[4], ra[4];
-  int r_next[4];
+  v4i rg[NG], ra[NA];
+  int rn_g[NG], rn_a[NA];
   auto request_rows = [&](int i0) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = i0 + srow + 16 * u;
-      r_next[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
+    for (int u = 0; u < NG; ++u) {
+      const int i = i0 + srow_g + (256 / GQ) * u;
+      rn_g[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < NA; ++u) {
+      const int i = i0 + srow_a + (256 / AQ) * u;
+      rn_a[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
     }
   };
-  auto request = [&](int i0) {
+  auto request = [&]() {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < NG; ++u) {
       rg[u] = v4i{0, 0, 0, 0};
+      if (rn_g[u] >= 0 && g_ok) rg[u] = *reinterpret_cast<const v4i*>(gg + (int64_t)rn_g[u] * p.c_out + gcol);
+    }
+#pragma unroll
+    for (int u = 0; u < NA; ++u) {
       ra[u] = v4i{0, 0, 0, 0};
-      const int r = r_next[u];
-      if (r >= 0) {
-        if (g_ok) rg[u] = *reinterpret_cast<const v4i*>(gg + (int64_t)r * p.c_out + gcol);
+      const int r = rn_a[u];
+      if (r >= 0 && a_ok) {
         const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
         const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
         const int iy = oy * p.sh - p.ph + ky * p.dil_h, ix = ox * p.sw - p.pw + kx * p.dil_w;
-        if (a_ok && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w)
+        if ((unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w)
           ra[u] = *reinterpret_cast<const v4i*>(xg + (((int64_t)n * p.h + iy) * p.w + ix) * p.c_in + ci);
       }
     }
   };
   auto deposit = [&](int buf) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int off = (buf * kWgRows + srow + 16 * u) * kWgPitch + 8 * q;
-      *reinterpret_cast<v4i*>(s_g + off) = rg[u];
-      *reinterpret_cast<v4i*>(s_a + off) = ra[u];
-    }
+    for (int u = 0; u < NG; ++u)
+      *reinterpret_cast<v4i*>(s_g + (buf * R + srow_g + (256 / GQ) * u) * PG + 8 * qg) = rg[u];
+#pragma unroll
+    for (int u = 0; u < NA; ++u)
+      *reinterpret_cast<v4i*>(s_a + (buf * R + srow_a + (256 / AQ) * u) * PA + 8 * qa) = ra[u];
   };
 
   floatx16 acc[2][2];
@@ -231,39 +239,38 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-  // eight values down column `col` of a staged tile, rows row0 .. row0 + 7, packed as an MFMA operand
-  auto column = [&](const unsigned short* tile, int row0, int col) -> v4i {
-    const unsigned short* s = tile + row0 * kWgPitch + col;
+  // eight values down a column of a staged tile (rows row0 .. row0 + 7), packed as an MFMA operand
+  auto column = [&](const unsigned short* s, int pitch) -> v4i {
     v4i f;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-      f[e] = (int)((unsigned)s[(2 * e) * kWgPitch] | ((unsigned)s[(2 * e + 1) * kWgPitch] << 16));
+      f[e] = (int)((unsigned)s[(2 * e) * pitch] | ((unsigned)s[(2 * e + 1) * pitch] << 16));
     return f;
   };
 
   if (i_begin < i_end) {
     request_rows(i_begin);
-    request(i_begin);
-    request_rows(i_begin + kWgRows);
+    request();
+    request_rows(i_begin + R);
     deposit(0);
   }
   __syncthreads();
   int buf = 0;
-  for (int i0 = i_begin; i0 < i_end; i0 += kWgRows) {
-    const bool more = i0 + kWgRows < i_end;
+  for (int i0 = i_begin; i0 < i_end; i0 += R) {
+    const bool more = i0 + R < i_end;
     if (more) {
-      request(i0 + kWgRows);                       // in flight during the MFMAs below
-      request_rows(i0 + 2 * kWgRows);
+      request();                                   // in flight during the MFMAs below
+      request_rows(i0 + 2 * R);
     }
-    const unsigned short* tg = s_g + buf * kWgRows * kWgPitch;
-    const unsigned short* ta = s_a + buf * kWgRows * kWgPitch;
+    const unsigned short* tg = s_g + buf * R * PG;
+    const unsigned short* ta = s_a + buf * R * PA;
 #pragma unroll
-    for (int ks = 0; ks < kWgRows / 16; ++ks) {
+    for (int ks = 0; ks < R / 16; ++ks) {
       v4i gf[2], af[2];
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi) gf[mi] = column(tg, 16 * ks + 8 * fh, wm0 + 32 * mi + fp);
+      for (int mi = 0; mi < 2; ++mi) gf[mi] = column(tg + (16 * ks + 8 * fh) * PG + wm0 + 32 * mi + fp, PG);
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) af[ni] = column(ta, 16 * ks + 8 * fh, wn0 + 32 * ni + fp);
+      for (int ni = 0; ni < 2; ++ni) af[ni] = column(ta + (16 * ks + 8 * fh) * PA + wn0 + 32 * ni + fp, PA);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -287,6 +294,23 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
         if (co < p.c_out && kcol < p.k) out[(int64_t)co * p.k + kcol] = acc[mi][ni][v];
       }
     }
+}
+
+template <int DT, int BM, int BN>
+static hipError_t wgrad_launch(WgradParams p, hipStream_t stream) {
+  constexpr size_t lds = (size_t)2 * kWgRows * (BM + 8 + BN + 8) * 2;
+  p.co_tiles = (p.c_out + BM - 1) / BM;
+  p.k_tiles = (p.k + BN - 1) / BN;
+  const unsigned grid = (unsigned)(p.co_tiles * p.k_tiles * p.splits);
+  static bool attr_set = false;                       // (one flag per tile shape and type)
+  if (lds > 64 * 1024 && !attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<DT, BM, BN>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((wgrad_kernel<DT, BM, BN>), dim3(grid), dim3(256), lds, stream, p);
+  return hipGetLastError();
 }
 
 // dw[i] = sum over the splits of partial[s][i].  A workgroup owns 64 consecutive elements (16 groups of
@@ -319,8 +343,9 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 constexpr size_t kWgradPartialBytes = (size_t)64 << 20;   // most workspace the row splits may take
 
 static int wgrad_splits(int64_t rows, int c_out, int k) {
-  const int64_t tiles = (int64_t)((c_out + kWgBM - 1) / kWgBM) * ((k + kWgBN - 1) / kWgBN);
-  int64_t want = (512 + tiles - 1) / tiles;                                        // about two workgroups per CU
+  const int bm = 128, bn = 128;
+  const int64_t tiles = (int64_t)((c_out + bm - 1) / bm) * ((k + bn - 1) / bn);
+  int64_t want = (768 + tiles - 1) / tiles;                                        // about three workgroups per CU
   want = std::min<int64_t>(want, (rows + 8 * kWgRows - 1) / (8 * kWgRows));        // at least eight stages per split
   want = std::min<int64_t>(want, (int64_t)(kWgradPartialBytes / ((size_t)c_out * k * 4)));
   return (int)std::max<int64_t>(want, 1);
@@ -472,30 +497,19 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   const int period = d.mask_mode == SC_MASK_SPATIAL ? plan->ho * plan->wo : 0;
   _Float16* g = reinterpret_cast<_Float16*>(plan->ws + plan->off_g);    // 16-bit patterns; compared as the real type below
 
-  // g map
-  {
-    const int gpr = d.c_out / 8;
-    const int64_t groups = m * gpr;
-    const unsigned grid = (unsigned)((groups + 255) / 256);
-    if (dt == sc::kBF16)
-      hipLaunchKernelGGL((sc::grad_map_kernel<__bf16, 8>), dim3(grid), dim3(256), 0, stream, (const __bf16*)y_dev,
-                         (const __bf16*)dy_dev, mask, (__bf16*)g, groups, gpr, d.relu, period);
-    else
-      hipLaunchKernelGGL((sc::grad_map_kernel<_Float16, 8>), dim3(grid), dim3(256), 0, stream, (const _Float16*)y_dev,
-                         (const _Float16*)dy_dev, mask, g, groups, gpr, d.relu, period);
-  }
+  // g map, with the column sums of its slabs on the side
+  const int slab_rows = sc::colsum_slab_rows(m);
+  const int slabs = (int)((m + slab_rows - 1) / slab_rows);
+  float* colsum = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
+  if (dt == sc::kBF16)
+    hipLaunchKernelGGL(sc::grad_map_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)y_dev,
+                       (const __bf16*)dy_dev, mask, (__bf16*)g, m, d.c_out, slab_rows, d.relu, period, colsum);
+  else
+    hipLaunchKernelGGL(sc::grad_map_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, (const _Float16*)y_dev,
+                       (const _Float16*)dy_dev, mask, g, m, d.c_out, slab_rows, d.relu, period, colsum);
   // db
-  if (db_dev) {
-    const int slab_rows = sc::colsum_slab_rows(m);
-    const int slabs = (int)((m + slab_rows - 1) / slab_rows);
-    float* partial = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
-    if (dt == sc::kBF16)
-      hipLaunchKernelGGL(sc::colsum_partial_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)g, m, d.c_out,
-                         slab_rows, partial);
-    else
-      hipLaunchKernelGGL(sc::colsum_partial_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, g, m, d.c_out, slab_rows, partial);
-    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 15) / 16), dim3(256), 0, stream, partial, slabs, d.c_out, db_dev);
-  }
+  if (db_dev)
+    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 3) / 4), dim3(256), 0, stream, colsum, slabs, d.c_out, db_dev);
   // dw
   if (dw_dev) {
     const int k = d.kh * d.kw * d.c_in;
@@ -517,30 +531,11 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
       p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
       p.dil_h = d.dil_h; p.dil_w = d.dil_w;
       p.k = k;
-      p.co_tiles = (d.c_out + sc::kWgBM - 1) / sc::kWgBM;
-      p.k_tiles = (k + sc::kWgBN - 1) / sc::kWgBN;
       sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
       sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
-      const size_t lds = (size_t)4 * sc::kWgRows * sc::kWgPitch * 2;
-      static bool attr_set[2] = {false, false};
-      const unsigned grid = (unsigned)(p.co_tiles * p.k_tiles * p.splits);
-      if (dt == sc::kBF16) {
-        if (!attr_set[0]) {
-          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sc::wgrad_kernel<sc::kBF16>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-          if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
-          attr_set[0] = true;
-        }
-        hipLaunchKernelGGL(sc::wgrad_kernel<sc::kBF16>, dim3(grid), dim3(256), lds, stream, p);
-      } else {
-        if (!attr_set[1]) {
-          hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(sc::wgrad_kernel<sc::kF16>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-          if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
-          attr_set[1] = true;
-        }
-        hipLaunchKernelGGL(sc::wgrad_kernel<sc::kF16>, dim3(grid), dim3(256), lds, stream, p);
-      }
+      hipError_t e;
+      e = dt == sc::kBF16 ? sc::wgrad_launch<sc::kBF16, 128, 128>(p, stream) : sc::wgrad_launch<sc::kF16, 128, 128>(p, stream);
+      if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
       if (p.splits > 1)
         hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
                            (const float*)p.out, p.splits, count, dw_dev);
