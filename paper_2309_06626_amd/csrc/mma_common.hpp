@@ -66,16 +66,27 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
   for (int v = 0; v < 16; ++v) vals[v] = acc[v];
   if (vec_out) {
     // c_out is a multiple of the 16-byte group (8 channels of a 16-bit type, 4 floats), not necessarily
-    // of 16: the groups of this block that lie beyond c_out are neither loaded (bias) nor stored
+    // of 16: in a block that straddles c_out, the groups beyond it are neither loaded (bias) nor stored.
+    // Blocks that lie inside c_out -- all of them when c_out is a multiple of 16 -- take the plain path.
     constexpr int GC = 16 / EB;                 // channels per 16-byte group
-    const int groups_ok = min(16, c_out - c0) / GC;
+    const bool full = c0 + 16 <= c_out;
+    const int groups_ok = full ? 16 / GC : (c_out - c0) / GC;
     if (bias) {
+      if (full) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        if (4 * q < groups_ok * GC) {
+        for (int q = 0; q < 4; ++q) {
           v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
 #pragma unroll
           for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
+        }
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (4 * q < groups_ok * GC) {
+            v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
+          }
         }
       }
     }
@@ -89,9 +100,14 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
     v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * c_out + c0));
     v4i pk[16 * EB / 16];
     __builtin_memcpy(pk, outv, 16 * EB);
+    if (full) {
 #pragma unroll
-    for (int q = 0; q < 16 * EB / 16; ++q)
-      if (q < groups_ok) sc_store16(dst + q, pk[q]);
+      for (int q = 0; q < 16 * EB / 16; ++q) sc_store16(dst + q, pk[q]);
+    } else {
+#pragma unroll
+      for (int q = 0; q < 16 * EB / 16; ++q)
+        if (q < groups_ok) sc_store16(dst + q, pk[q]);
+    }
   } else {
     const int n = rr / ho_wo, rem = rr - n * ho_wo;
     T* dst = y + n * ys_n + (int64_t)rem * ys_p;
