@@ -220,9 +220,10 @@ int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on th
  *   sparse_conv_backward_run    x_dev: the forward input; y_dev: the forward output (its sign gates the ReLU; may be
  *                         NULL for layers without ReLU); dy_dev: upstream gradient, layout and dtype of y.
  *                         dx_dev (layout and dtype of x), dw_dev (float [Cout][kh][kw][Cin]) and db_dev
- *                         (float [Cout]) are each optional (NULL = not wanted).  dx needs stride 1 (then it is the
- *                         ordinary convolution of g with the rotated filters and runs through the forward
- *                         kernels): SC_ERR_UNSUPPORTED for strided layers.  Additions happen in a fixed order:
+ *                         (float [Cout]) are each optional (NULL = not wanted).  dx is the ordinary convolution of g (with
+ *                         zeros interleaved for strided layers) with the rotated filters and runs through the
+ *                         forward kernels; SC_ERR_UNSUPPORTED only when the layer's padding exceeds
+ *                         dil * (k - 1).  Additions happen in a fixed order:
  *                         results do not depend on scheduling.  Enqueues only; no allocation, no synchronisation.
  *   sparse_conv_backward_set_filters   new filter values (after an optimiser step) for the input gradient.
  */

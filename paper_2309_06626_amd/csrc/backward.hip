@@ -125,6 +125,21 @@ __global__ void fill_bytes_kernel(uint8_t* __restrict__ p, int64_t n, uint8_t v)
   if (i < n) p[i] = v;
 }
 
+// Strided layers: the transposed convolution is an ordinary stride-1 convolution of the g map with zeros
+// interleaved -- row (oy, ox) of g lands at (oy * sh, ox * sw) of a map of hu x wu pixels that is zero
+// everywhere else.  The zeros are written once (plan time) and stay: every run rewrites the same pixels.
+template <int V16>
+__global__ void upsample_rows_kernel(const v4i* __restrict__ g, v4i* __restrict__ gu, int64_t groups_total,
+                                     int groups_per_row, int ho_wo, int wo, int sh, int sw, int hu, int wu) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= groups_total) return;
+  const int64_t r = idx / groups_per_row;
+  const int q = (int)(idx - r * groups_per_row);
+  const int n = (int)(r / ho_wo), rem = (int)(r - (int64_t)n * ho_wo);
+  const int oy = rem / wo, ox = rem - oy * wo;
+  gu[(((int64_t)n * hu + (int64_t)oy * sh) * wu + (int64_t)ox * sw) * groups_per_row + q] = g[idx];
+}
+
 // ---- filter gradient -----------------------------------------------------------------------------------------
 // dW[co][k] = sum over the kept rows i of g[row_i][co] * A[row_i][k]: a GEMM whose contraction runs over
 // rows.  Both operands are row-major (a row of g is Cout contiguous values, a window tap of a row is Cin
@@ -361,16 +376,20 @@ struct sc_bwd_plan {
   int32_t ho, wo;
   int64_t m;
   unsigned char* ws;
-  size_t off_g, off_ones, off_wrot, off_inner, off_partial, off_colsum;
+  size_t off_g, off_ones, off_wrot, off_inner, off_partial, off_colsum, off_gup;
+  int32_t hu, wu;            // zero-interleaved g map of strided layers (0: stride 1, the g map itself is used)
   sc_plan* inner;            // dense plan of the transposed convolution (null: no input gradient for this layer)
 };
 
 namespace sc {
 
-static sc_status backward_layout(const sc_conv_desc* d, int32_t* ho, int32_t* wo, int64_t* m, sc_conv_desc* inner,
-                                 bool* has_inner, size_t* off_g, size_t* off_ones, size_t* off_wrot, size_t* off_inner,
-                                 size_t* off_partial, size_t* off_colsum, size_t* total) {
+static sc_status backward_layout(const sc_conv_desc* d, sc_bwd_plan* L, sc_conv_desc* inner, bool* has_inner,
+                                 size_t* total) {
   if (!d) return SC_ERR_NULL;
+  int32_t *ho = &L->ho, *wo = &L->wo, *hu = &L->hu, *wu = &L->wu;
+  int64_t* m = &L->m;
+  size_t *off_g = &L->off_g, *off_ones = &L->off_ones, *off_wrot = &L->off_wrot, *off_inner = &L->off_inner,
+         *off_partial = &L->off_partial, *off_colsum = &L->off_colsum, *off_gup = &L->off_gup;
   sc_status s = sparse_conv_output_shape(d, ho, wo, m);
   if (s != SC_OK) return s;
   // the filter-gradient kernel gathers 16-byte channel groups of 16-bit values
@@ -379,18 +398,25 @@ static sc_status backward_layout(const sc_conv_desc* d, int32_t* ho, int32_t* wo
     return SC_ERR_UNSUPPORTED;
   const size_t eb = 2;
   const int64_t k = (int64_t)d->kh * d->kw * d->c_in;
-  // input gradient: stride 1 only (then it is an ordinary convolution of the g map)
+  // input gradient: an ordinary stride-1 convolution of the g map (zero-interleaved for strided layers) with
+  // the rotated filters, padded by dil * (k - 1) - pad; the interleaved map gets as many extra zero rows /
+  // columns at the end as the forward pass left input rows / columns unused
   const int pad_h = d->dil_h * (d->kh - 1) - d->pad_h, pad_w = d->dil_w * (d->kw - 1) - d->pad_w;
-  *has_inner = d->stride_h == 1 && d->stride_w == 1 && pad_h >= 0 && pad_w >= 0;
+  *has_inner = pad_h >= 0 && pad_w >= 0;
+  const bool strided = d->stride_h != 1 || d->stride_w != 1;
+  const int eff_h = d->h + 2 * d->pad_h - d->dil_h * (d->kh - 1) - 1, eff_w = d->w + 2 * d->pad_w - d->dil_w * (d->kw - 1) - 1;
+  *hu = strided ? (*ho - 1) * d->stride_h + 1 + eff_h % d->stride_h : 0;
+  *wu = strided ? (*wo - 1) * d->stride_w + 1 + eff_w % d->stride_w : 0;
   size_t off = 0;
   *off_g = off;      off = align_up(off + (size_t)*m * d->c_out * eb, 256);
   *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRowsLeast - 1) / kSumRowsLeast) * d->c_out * 4, 256);
   *off_partial = off;
   off = align_up(off + (size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4, 256);   // the dense row count bounds every mask
-  *off_ones = *off_wrot = *off_inner = off;
+  *off_ones = *off_wrot = *off_inner = *off_gup = off;
   if (*has_inner) {
     std::memset(inner, 0, sizeof(*inner));
-    inner->n = d->n; inner->c_in = d->c_out; inner->h = *ho; inner->w = *wo; inner->c_out = d->c_in;
+    inner->n = d->n; inner->c_in = d->c_out; inner->h = strided ? *hu : *ho; inner->w = strided ? *wu : *wo;
+    inner->c_out = d->c_in;
     inner->kh = d->kh; inner->kw = d->kw; inner->stride_h = 1; inner->stride_w = 1;
     inner->pad_h = pad_h; inner->pad_w = pad_w; inner->dil_h = d->dil_h; inner->dil_w = d->dil_w;
     inner->groups = 1; inner->dtype = d->dtype; inner->layout = SC_NHWC; inner->has_bias = 0; inner->relu = 0;
@@ -398,9 +424,14 @@ static sc_status backward_layout(const sc_conv_desc* d, int32_t* ho, int32_t* wo
     size_t inner_bytes = 0;
     s = sparse_conv_workspace_bytes(inner, &inner_bytes);
     if (s != SC_OK) return s;
+    int32_t iho = 0, iwo = 0; int64_t im = 0;
+    s = sparse_conv_output_shape(inner, &iho, &iwo, &im);
+    if (s != SC_OK) return s;
+    if (iho != d->h || iwo != d->w) return SC_ERR_UNSUPPORTED;     // (cannot happen: the sizes above are made to fit)
     *off_ones = off;  off = align_up(off + (size_t)d->h * d->w, 256);
     *off_wrot = off;  off = align_up(off + (size_t)d->c_out * k * eb, 256);
     *off_inner = off; off = align_up(off + inner_bytes, 256);
+    if (strided) { *off_gup = off; off = align_up(off + (size_t)d->n * *hu * *wu * d->c_out * eb, 256); }
   }
   *total = off;
   return SC_OK;
@@ -423,9 +454,8 @@ extern "C" {
 sc_status sparse_conv_backward_workspace_bytes(const sc_conv_desc* desc, size_t* bytes) {
   if (!bytes) return SC_ERR_NULL;
   *bytes = 0;
-  int32_t ho, wo; int64_t m; sc_conv_desc inner; bool has_inner;
-  size_t a, b, c, e, f, g, total;
-  sc_status s = sc::backward_layout(desc, &ho, &wo, &m, &inner, &has_inner, &a, &b, &c, &e, &f, &g, &total);
+  sc_bwd_plan layout; sc_conv_desc inner; bool has_inner; size_t total;
+  sc_status s = sc::backward_layout(desc, &layout, &inner, &has_inner, &total);
   if (s != SC_OK) return s;
   *bytes = total;
   return SC_OK;
@@ -439,8 +469,7 @@ sc_status sparse_conv_backward_plan(const sc_plan* fwd, const sc_conv_desc* desc
   sc_bwd_plan tmp;
   std::memset(&tmp, 0, sizeof(tmp));
   sc_conv_desc inner; bool has_inner; size_t total;
-  sc_status s = sc::backward_layout(desc, &tmp.ho, &tmp.wo, &tmp.m, &inner, &has_inner, &tmp.off_g, &tmp.off_ones,
-                                    &tmp.off_wrot, &tmp.off_inner, &tmp.off_partial, &tmp.off_colsum, &total);
+  sc_status s = sc::backward_layout(desc, &tmp, &inner, &has_inner, &total);
   if (s != SC_OK) return s;
   // the descriptor must be the forward plan's
   int64_t fm = 0, fkept = 0; int32_t fho = 0, fwo = 0;
@@ -459,6 +488,10 @@ sc_status sparse_conv_backward_plan(const sc_plan* fwd, const sc_conv_desc* desc
                        tmp.ws + tmp.off_ones, ones, (uint8_t)1);
     s = sc::rotate_filters(&tmp, w_dev, stream);
     if (s != SC_OK) return s;
+    if (tmp.hu > 0) {   // the zeros between the rows of g: written once, never overwritten
+      hipError_t e = hipMemsetAsync(tmp.ws + tmp.off_gup, 0, (size_t)desc->n * tmp.hu * tmp.wu * desc->c_out * 2, stream);
+      if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+    }
     s = sparse_conv_plan(&inner, tmp.ws + tmp.off_ones, tmp.ws + tmp.off_wrot, tmp.ws + tmp.off_inner,
                          total - tmp.off_inner, hip_stream, &tmp.inner);
     if (s != SC_OK) return s;
@@ -487,7 +520,7 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   if (((uintptr_t)dy_dev & 15) || ((uintptr_t)y_dev & 15) || ((uintptr_t)x_dev & 15) || ((uintptr_t)dx_dev & 15) ||
       ((uintptr_t)dw_dev & 15) || ((uintptr_t)db_dev & 3))
     return SC_ERR_ALIGN;
-  if (dx_dev && !plan->inner) return SC_ERR_UNSUPPORTED;     // strided layers: no input gradient
+  if (dx_dev && !plan->inner) return SC_ERR_UNSUPPORTED;     // padding larger than the window reach: no input gradient
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   int64_t m = 0, kept = 0; const int32_t* rows_dev = nullptr;
   sc_status s = sparse_conv_plan_info(plan->fwd, &m, &kept, nullptr, nullptr, &rows_dev);
@@ -543,8 +576,22 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
-  // dx: the g map through the forward kernels with the rotated filters
-  if (dx_dev) return dense_conv_run(plan->inner, g, nullptr, dx_dev, hip_stream);
+  // dx: the g map (zero-interleaved for strided layers) through the forward kernels with the rotated filters
+  if (dx_dev) {
+    const void* src = g;
+    if (plan->hu > 0) {
+      const int gpr = d.c_out / 8;
+      const int64_t groups = m * gpr;
+      sc::v4i* gu = reinterpret_cast<sc::v4i*>(plan->ws + plan->off_gup);
+      hipLaunchKernelGGL(sc::upsample_rows_kernel<0>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
+                         reinterpret_cast<const sc::v4i*>(g), gu, groups, gpr, plan->ho * plan->wo, plan->wo, d.stride_h,
+                         d.stride_w, plan->hu, plan->wu);
+      hipError_t e2 = hipGetLastError();
+      if (e2 != hipSuccess) { sc::note_hip_error((int32_t)e2); return SC_ERR_HIP; }
+      src = gu;
+    }
+    return dense_conv_run(plan->inner, src, nullptr, dx_dev, hip_stream);
+  }
   return SC_OK;
 }
 

@@ -37,7 +37,7 @@ struct ConvParams {
   int32_t relu;
   int32_t zero_fill;       // write zeros at dropped rows
   int32_t mask_spatial;    // mask has ho_wo entries shared by the batch
-  int32_t vec_out;         // y rows are channel-contiguous and 16-byte groups are aligned
+  int32_t vec_out;         // 0: element stores; 1: y rows are whole 16-byte groups and c_out % 16 == 0; 2: whole groups only
   // compact row formats (NHWC): x holds only the kept rows of the input map, row i = pixel row_idx[i]
   // (pointwise stride-1 layers); y receives only the kept rows, row i = result of row_idx[i]
   int32_t x_compact, y_compact;

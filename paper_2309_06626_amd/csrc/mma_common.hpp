@@ -53,6 +53,10 @@ __device__ __forceinline__ void sc_store16(v4i* dst, v4i v) { *dst = v; }
 // Bias, ReLU, conversion and store of one 32x32 MFMA block for the lane's output position:
 // `acc` holds 16 consecutive output channels c0..c0+15 of dense row rr (Alg. 2, copy branch: the
 // result of a kept row goes to its dense slot).  bias[bias_at + v] belongs to channel c0 + v.
+// vec_out: 0 = element stores with strides; 1 = 16-byte stores, c_out a multiple of 16 (every block lies inside
+// c_out; the only mode the LDS-direct, band and row-panel kernels are launched with, as a literal, so their
+// epilogue stays as lean as it was); 2 = 16-byte stores, c_out a multiple of the 16-byte group only (the
+// register-staged tiled kernel).
 template <int DT>
 __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* __restrict__ y,
                                                  const float* __restrict__ bias, int bias_at, int relu, int vec_out,
@@ -64,29 +68,40 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
   float vals[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) vals[v] = acc[v];
-  if (vec_out) {
-    // c_out is a multiple of the 16-byte group (8 channels of a 16-bit type, 4 floats), not necessarily
-    // of 16: in a block that straddles c_out, the groups beyond it are neither loaded (bias) nor stored.
-    // Blocks that lie inside c_out -- all of them when c_out is a multiple of 16 -- take the plain path.
-    constexpr int GC = 16 / EB;                 // channels per 16-byte group
-    const bool full = c0 + 16 <= c_out;
-    const int groups_ok = full ? 16 / GC : (c_out - c0) / GC;
+  if (vec_out == 1) {
+    // every 16-channel block lies inside c_out (c_out is a multiple of 16): the plain path
     if (bias) {
-      if (full) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+      for (int q = 0; q < 4; ++q) {
+        v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
+      }
+    }
+    if (relu) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
+    }
+    T outv[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
+    v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * c_out + c0));
+    v4i pk[16 * EB / 16];
+    __builtin_memcpy(pk, outv, 16 * EB);
+#pragma unroll
+    for (int q = 0; q < 16 * EB / 16; ++q) sc_store16(dst + q, pk[q]);
+  } else if (vec_out == 2) {
+    // c_out is a multiple of the 16-byte group (8 channels of a 16-bit type, 4 floats) but not of 16: in
+    // the block that straddles c_out, the groups beyond it are neither loaded (bias) nor stored
+    constexpr int GC = 16 / EB;                 // channels per 16-byte group
+    const int groups_ok = min(16, c_out - c0) / GC;
+    if (bias) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (4 * q < groups_ok * GC) {
           v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
 #pragma unroll
           for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
-        }
-      } else {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (4 * q < groups_ok * GC) {
-            v4f b4 = *reinterpret_cast<const v4f*>(bias + bias_at + 4 * q);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) vals[4 * q + e] += b4[e];
-          }
         }
       }
     }
@@ -100,14 +115,9 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
     v4i* dst = reinterpret_cast<v4i*>(y + ((int64_t)rr * c_out + c0));
     v4i pk[16 * EB / 16];
     __builtin_memcpy(pk, outv, 16 * EB);
-    if (full) {
 #pragma unroll
-      for (int q = 0; q < 16 * EB / 16; ++q) sc_store16(dst + q, pk[q]);
-    } else {
-#pragma unroll
-      for (int q = 0; q < 16 * EB / 16; ++q)
-        if (q < groups_ok) sc_store16(dst + q, pk[q]);
-    }
+    for (int q = 0; q < 16 * EB / 16; ++q)
+      if (q < groups_ok) sc_store16(dst + q, pk[q]);
   } else {
     const int n = rr / ho_wo, rem = rr - n * ho_wo;
     T* dst = y + n * ys_n + (int64_t)rem * ys_p;

@@ -302,7 +302,7 @@ struct Geometry {
   int32_t ho, wo;
   int64_t m;
   int32_t k, k_pad, k_stride, k_tiles, vec, cout_pad;
-  bool vec_gather, vec_out;
+  bool vec_gather, vec_out, vec_out8;
   int64_t x_elems, y_elems, mask_len;
   int32_t nseg;
   // workspace carve (byte offsets)
@@ -380,7 +380,10 @@ static sc_status check_desc(const sc_conv_desc* d, Geometry* g) {
   g->k_stride = (g->k_tiles & 1) ? g->k_pad : g->k_pad + bk;
   g->cout_pad = (d->c_out + 255) / 256 * 256;
   g->vec_gather = d->layout == SC_NHWC && d->c_in % g->vec == 0;
-  g->vec_out = d->layout == SC_NHWC && d->c_out % g->vec == 0;   // output rows are whole 16-byte groups
+  g->vec_out = d->layout == SC_NHWC && d->c_out % 16 == 0;
+  // output rows that are whole 16-byte groups but no multiple of 16 channels (e.g. 40, 56, 104): vectorised
+  // stores in the register-staged tiled kernel only
+  g->vec_out8 = d->layout == SC_NHWC && !g->vec_out && d->c_out % g->vec == 0;
   g->mask_len = d->mask_mode == SC_MASK_ROW ? g->m : (int64_t)g->ho * g->wo;
   g->nseg = (int32_t)((g->m + kSeg - 1) / kSeg);
   size_t off = 0;
@@ -767,7 +770,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.relu = d.relu;
   p.zero_fill = zero_fill ? 1 : 0;
   p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
-  p.vec_out = g.vec_out ? 1 : 0;
+  p.vec_out = g.vec_out ? 1 : g.vec_out8 ? 2 : 0;
   p.x_compact = compact && x_compact ? 1 : 0;
   p.y_compact = compact && y_compact ? 1 : 0;
 #ifdef SC_TIMING

@@ -293,7 +293,7 @@ def main():
     ap.add_argument("--masks", action="store_true", help="also time the mask generator (Alg. 1, getMask)")
     ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
     ap.add_argument("--pruned", action="store_true",
-                    help="also time a channel-pruned ResNet18 stack (51/102/205/410 channels, s = 0.3), as it is and padded to 8")
+                    help="also time a channel-pruned ResNet18 stack (51/102/205/410 channels, s = 0.3), as it is and padded to 16 and to 8")
     ap.add_argument("--backward", action="store_true", help="also time the backward pass of a few layers")
     ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
     args = ap.parse_args()
@@ -354,9 +354,11 @@ def main():
     if args.pruned:
         cs = max(args.steps // 10, 5)
         ops = W.pruned_resnet18()
-        chains["pruned ResNet18 stack (batch 64, s=0.3), channels padded to multiples of 8 (56/104/208/416)"] = \
-            chain_time(W.pad_channels(ops), W.base_seed(3), cs)
-        chains["the same, every conv through dense_conv_run"] = chain_time(W.pad_channels(ops), W.base_seed(3), cs, dense=True)
+        chains["pruned ResNet18 stack (batch 64, s=0.3), channels padded to multiples of 16 (64/112/208/416)"] = \
+            chain_time(W.pad_channels(ops, 16), W.base_seed(3), cs)
+        chains["the same, every conv through dense_conv_run"] = chain_time(W.pad_channels(ops, 16), W.base_seed(3), cs, dense=True)
+        chains["pruned ResNet18 stack, channels padded to multiples of 8 (56/104/208/416: register-staged tiled kernel)"] = \
+            chain_time(W.pad_channels(ops, 8), W.base_seed(3), cs)
         chains["pruned ResNet18 stack with its own channel counts (51/102/205/410: element gather)"] = \
             chain_time(ops, W.base_seed(3), cs)
     if chains:

@@ -83,9 +83,21 @@ def test_many_rows_and_row_splits():
     run_backward(spec_of(16, 32, 28, 32, k=1, sparsity=0.25), 823)
 
 
-def test_strided_layers_have_filter_and_bias_gradients_only():
-    spec = spec_of(2, 32, 16, 64, s=2)
-    layer, bwd, ci = run_backward(spec, 827, want_dx=False)
+@pytest.mark.parametrize("shape", [
+    dict(n=2, c_in=32, hw=16, c_out=64, s=2),                   # the forward pass leaves the last input row unused
+    dict(n=2, c_in=32, hw=15, c_out=64, s=2),                   # every input row used
+    dict(n=1, c_in=64, hw=14, c_out=128, k=1, s=2),             # pointwise downsample
+    dict(n=1, c_in=16, hw=17, c_out=32, s=3, w=11),             # stride 3, non-square
+    dict(n=1, c_in=16, hw=18, c_out=16, k=5, s=2, d=2),         # dilated and strided
+])
+def test_strided_layers(shape):
+    """The input gradient of a strided layer: the g map with zeros interleaved, through the forward kernels."""
+    run_backward(spec_of(**shape), 827)
+
+
+def test_padding_beyond_the_window_reach_has_no_input_gradient_path():
+    spec = spec_of(1, 16, 8, 16, k=1, p=1)          # 1x1 window with padding 1: dil*(k-1) - pad < 0
+    layer, bwd, ci = run_backward(spec, 829, want_dx=False)
     dx = torch.empty(spec.x_shape(), dtype=torch.bfloat16, device="cuda:0")
     dy = torch.zeros(spec.y_shape(), dtype=torch.bfloat16, device="cuda:0")
     with pytest.raises(B.ScError) as err:

@@ -527,13 +527,14 @@ def test_config3_full_batch_sampled_rows():
         torch.cuda.empty_cache()
 
 
-def test_pruned_resnet18_with_padded_channels_matches_the_unpadded_oracle():
+@pytest.mark.parametrize("multiple", [8, 16])
+def test_pruned_resnet18_with_padded_channels_matches_the_unpadded_oracle(multiple):
     """Channel counts that are no multiple of 8 (a structurally pruned model): the stack runs with every
     tensor padded to 16-byte channel groups -- zero filters, so the extra channels stay exactly zero --
     and must reproduce the oracle's run of the original shapes."""
     ops = W.pruned_resnet18(batch=2, sparsity=0.3)
-    pops = W.pad_channels(ops)
-    assert [s.c_out for s in W.conv_specs(ops)][:2] == [51, 51] and W.conv_specs(pops)[1].c_in == 56
+    pops = W.pad_channels(ops, multiple)
+    assert [s.c_out for s in W.conv_specs(ops)][:2] == [51, 51] and W.conv_specs(pops)[1].c_in == (56 if multiple == 8 else 64)
     bs = W.base_seed(3)
     params, layers = {}, {}
     for spec, pspec in zip(W.conv_specs(ops), W.conv_specs(pops)):

@@ -343,9 +343,10 @@ def pruned_resnet18(batch: int = 64, res: int = 224, sparsity: float = 0.3, keep
     return _resnet18_ops(batch, res, dtype, sparsity, True, widths)
 
 
-def pad_channels(ops: List[NetOp], multiple: int = 8) -> List[NetOp]:
+def pad_channels(ops: List[NetOp], multiple: int = 16) -> List[NetOp]:
     """The same graph with every channel count rounded up to `multiple` (the network input keeps its own):
-    how a converter lays out a pruned model for 16-byte channel groups.  The extra filters and filter
+    how a converter lays out a pruned model for 16-byte channel groups (multiples of 8 channels suffice for
+    vectorised gathers and stores; multiples of 16 are what every kernel of the library accepts).  The extra filters and filter
     entries are zero, so the extra channels of every tensor stay zero."""
     up = lambda c: -(-c // multiple) * multiple
     out = []
