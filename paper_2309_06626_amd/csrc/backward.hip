@@ -144,9 +144,9 @@ __global__ void upsample_rows_kernel(const v4i* __restrict__ g, v4i* __restrict_
 // dW[co][k] = sum over the kept rows i of g[row_i][co] * A[row_i][k]: a GEMM whose contraction runs over
 // rows.  Both operands are row-major (a row of g is Cout contiguous values, a window tap of a row is Cin
 // contiguous values), while an MFMA lane needs eight consecutive CONTRACTION entries of one column.  The
-// tiles are therefore staged row-major in LDS (coalesced 16-byte gathers, as in the forward kernels) and a
-// lane assembles its operand with eight 16-bit LDS reads down a column; rows of the LDS tiles are padded
-// by 16 bytes so that the two lane halves, eight rows apart, hit different banks.
+// tiles are therefore staged row-major in LDS (coalesced 16-byte gathers, as in the forward kernels) and
+// read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16): two loads give a lane the eight
+// consecutive rows of its column.
 //   workgroup = 128 output channels x 128 window entries x one split of the kept rows; 2 x 2 wavefronts,
 //               each 64 x 64 (2 x 2 MFMA blocks of 32 x 32 x 16)
 //   stage     = 64 kept rows, double buffered: the next stage's gathers are in flight during the MFMAs
@@ -176,9 +176,12 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   constexpr int R = kWgRows;
   constexpr int WAVES_N = BN / 64;
   static_assert((BM / 64) * WAVES_N == 4, "four wavefronts of 64 x 64");
-  constexpr int PG = BM + 8, PA = BN + 8;              // LDS row pitches in 16-bit elements
+  // LDS row pitches in 16-bit elements: 64 bytes more than a multiple of 256, so that the 4 rows x 32 bytes
+  // x 2 column blocks that 32 lanes of a transposing read touch fall into 64 different banks
+  constexpr int PG = BM + 32, PA = BN + 32;
   constexpr int GQ = BM / 8, AQ = BN / 8;              // 16-byte groups per staged row
-  constexpr int NG = R * GQ / 256, NA = R * AQ / 256;  // groups a lane stages per tile
+  constexpr int NG = GQ / 4, NA = AQ / 4;              // groups a lane stages per tile
+  static_assert(R == 64, "one staged row per four lanes");
   extern __shared__ __align__(16) unsigned char smem[];
   unsigned short* s_g = reinterpret_cast<unsigned short*>(smem);      // [2][R][PG]
   unsigned short* s_a = s_g + 2 * R * PG;                             // [2][R][PA]
@@ -191,59 +194,63 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
   const int co0 = (tile / p.k_tiles) * BM, k0 = (tile % p.k_tiles) * BN;
   const int i_begin = split * p.rows_per_split, i_end = min(p.rows, i_begin + p.rows_per_split);
 
-  // this lane's column groups of the staged tiles (fixed for the whole kernel)
-  const int qg = t % GQ, srow_g = t / GQ;             // g tile: group qg of rows srow_g + u * (256 / GQ)
-  const int qa = t % AQ, srow_a = t / AQ;             // A tile: group qa of rows srow_a + u * (256 / AQ)
-  const int gcol = co0 + 8 * qg;                      // first output channel of its g group
-  const bool g_ok = gcol < p.c_out;                   // (Cout is a multiple of 8)
-  const int kk = k0 + 8 * qa;                         // first window entry of its A group
-  const bool a_ok = kk < p.k;                         // (Cin is a multiple of 8: a group lies inside one tap)
-  const int tap = a_ok ? kk / p.c_in : 0, ci = kk - tap * p.c_in;
-  const int ky = tap / p.kw, kx = tap - ky * p.kw;
+  // Staging: four lanes share one row of a stage; lane `sub` of the four takes the 16-byte groups
+  // sub, sub + 4, sub + 8, ... of that row in both tiles (adjacent lanes: adjacent groups, so a load
+  // instruction covers 64 contiguous bytes per row).  The row is decoded once per lane and stage; what
+  // depends on the group -- its window tap and channel -- is fixed for the whole kernel.
+  const int srow = t >> 2, sub = t & 3;
   const T* __restrict__ xg = static_cast<const T*>(p.x);
   const T* __restrict__ gg = static_cast<const T*>(p.g);
+  int g_col[NG];                                       // first output channel of group u, or -1 beyond Cout
+#pragma unroll
+  for (int u = 0; u < NG; ++u) {
+    const int c = co0 + 8 * (4 * u + sub);
+    g_col[u] = c < p.c_out ? c : -1;                   // (Cout is a multiple of 8)
+  }
+  int a_dy[NA], a_dx[NA], a_off[NA];                   // tap displacement and element offset of group u; a_off < 0 beyond K
+#pragma unroll
+  for (int u = 0; u < NA; ++u) {
+    const int kk = k0 + 8 * (4 * u + sub);             // (Cin is a multiple of 8: a group lies inside one tap)
+    const int tap = kk < p.k ? kk / p.c_in : 0, ci = kk - tap * p.c_in;
+    const int ky = tap / p.kw, kx = tap - ky * p.kw;
+    a_dy[u] = ky * p.dil_h;
+    a_dx[u] = kx * p.dil_w;
+    a_off[u] = kk < p.k ? (a_dy[u] * p.w + a_dx[u]) * p.c_in + ci : -1;
+  }
 
   // row numbers are fetched one stage ahead of the data they address, so a stage costs one round trip
   v4i rg[NG], ra[NA];
-  int rn_g[NG], rn_a[NA];
+  int r_next = -1;
   auto request_rows = [&](int i0) {
-#pragma unroll
-    for (int u = 0; u < NG; ++u) {
-      const int i = i0 + srow_g + (256 / GQ) * u;
-      rn_g[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
-    }
-#pragma unroll
-    for (int u = 0; u < NA; ++u) {
-      const int i = i0 + srow_a + (256 / AQ) * u;
-      rn_a[u] = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
-    }
+    const int i = i0 + srow;
+    r_next = i < i_end ? (p.row_idx ? p.row_idx[i] : i) : -1;
   };
   auto request = [&]() {
+    const int r = r_next;
 #pragma unroll
-    for (int u = 0; u < NG; ++u) {
-      rg[u] = v4i{0, 0, 0, 0};
-      if (rn_g[u] >= 0 && g_ok) rg[u] = *reinterpret_cast<const v4i*>(gg + (int64_t)rn_g[u] * p.c_out + gcol);
-    }
+    for (int u = 0; u < NG; ++u) rg[u] = v4i{0, 0, 0, 0};
 #pragma unroll
-    for (int u = 0; u < NA; ++u) {
-      ra[u] = v4i{0, 0, 0, 0};
-      const int r = rn_a[u];
-      if (r >= 0 && a_ok) {
-        const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
-        const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
-        const int iy = oy * p.sh - p.ph + ky * p.dil_h, ix = ox * p.sw - p.pw + kx * p.dil_w;
-        if ((unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w)
-          ra[u] = *reinterpret_cast<const v4i*>(xg + (((int64_t)n * p.h + iy) * p.w + ix) * p.c_in + ci);
-      }
+    for (int u = 0; u < NA; ++u) ra[u] = v4i{0, 0, 0, 0};
+    if (r >= 0) {
+      const T* grow = gg + (int64_t)r * p.c_out;
+#pragma unroll
+      for (int u = 0; u < NG; ++u)
+        if (g_col[u] >= 0) rg[u] = *reinterpret_cast<const v4i*>(grow + g_col[u]);
+      const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
+      const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
+      const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
+      const T* xrow = xg + (((int64_t)n * p.h + iy0) * p.w + ix0) * p.c_in;     // may point before the tensor: used with in-range taps only
+#pragma unroll
+      for (int u = 0; u < NA; ++u)
+        if (a_off[u] >= 0 && (unsigned)(iy0 + a_dy[u]) < (unsigned)p.h && (unsigned)(ix0 + a_dx[u]) < (unsigned)p.w)
+          ra[u] = *reinterpret_cast<const v4i*>(xrow + a_off[u]);
     }
   };
   auto deposit = [&](int buf) {
 #pragma unroll
-    for (int u = 0; u < NG; ++u)
-      *reinterpret_cast<v4i*>(s_g + (buf * R + srow_g + (256 / GQ) * u) * PG + 8 * qg) = rg[u];
+    for (int u = 0; u < NG; ++u) *reinterpret_cast<v4i*>(s_g + (buf * R + srow) * PG + 8 * (4 * u + sub)) = rg[u];
 #pragma unroll
-    for (int u = 0; u < NA; ++u)
-      *reinterpret_cast<v4i*>(s_a + (buf * R + srow_a + (256 / AQ) * u) * PA + 8 * qa) = ra[u];
+    for (int u = 0; u < NA; ++u) *reinterpret_cast<v4i*>(s_a + (buf * R + srow) * PA + 8 * (4 * u + sub)) = ra[u];
   };
 
   floatx16 acc[2][2];
@@ -254,13 +261,21 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-  // eight values down a column of a staged tile (rows row0 .. row0 + 7), packed as an MFMA operand
+  // An MFMA operand: eight consecutive rows of one column of a staged tile.  ds_read_b64_tr_b16 transposes
+  // within groups of 16 lanes -- result lane j, element t = source lane 4t + j/4, element j%4 (layout checked
+  // on the device) -- so with source lane s of a group addressing row s/4, columns 4*(s%4) .. +3 of a
+  // 4 x 16 block, result lane j holds rows 0..3 of column j of that block: two such reads (rows 0..3 and
+  // 4..7) are the operand, in the order the MFMA wants, with no further instructions.
+  typedef short tr_s16x4 __attribute__((ext_vector_type(4)));
+  typedef __attribute__((address_space(3))) tr_s16x4 lds_s16x4;
+  const int l16 = lane & 15;
+  const int tr_g = (8 * fh + (l16 >> 2)) * PG + 16 * ((lane & 31) >> 4) + 4 * (l16 & 3);   // element offsets
+  const int tr_a = (8 * fh + (l16 >> 2)) * PA + 16 * ((lane & 31) >> 4) + 4 * (l16 & 3);
   auto column = [&](const unsigned short* s, int pitch) -> v4i {
-    v4i f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      f[e] = (int)((unsigned)s[(2 * e) * pitch] | ((unsigned)s[(2 * e + 1) * pitch] << 16));
-    return f;
+    const tr_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(s));
+    const tr_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(s + 4 * pitch));
+    struct { tr_s16x4 a, b; } both = {lo, hi};
+    return __builtin_bit_cast(v4i, both);
   };
 
   if (i_begin < i_end) {
@@ -283,9 +298,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
     for (int ks = 0; ks < R / 16; ++ks) {
       v4i gf[2], af[2];
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi) gf[mi] = column(tg + (16 * ks + 8 * fh) * PG + wm0 + 32 * mi + fp, PG);
+      for (int mi = 0; mi < 2; ++mi) gf[mi] = column(tg + 16 * ks * PG + wm0 + 32 * mi + tr_g, PG);
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni) af[ni] = column(ta + (16 * ks + 8 * fh) * PA + wn0 + 32 * ni + fp, PA);
+      for (int ni = 0; ni < 2; ++ni) af[ni] = column(ta + 16 * ks * PA + wn0 + 32 * ni + tr_a, PA);
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
@@ -313,7 +328,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradParams p) {
 
 template <int DT, int BM, int BN>
 static hipError_t wgrad_launch(WgradParams p, hipStream_t stream) {
-  constexpr size_t lds = (size_t)2 * kWgRows * (BM + 8 + BN + 8) * 2;
+  constexpr size_t lds = (size_t)2 * kWgRows * (BM + 32 + BN + 32) * 2;
   p.co_tiles = (p.c_out + BM - 1) / BM;
   p.k_tiles = (p.k + BN - 1) / BN;
   const unsigned grid = (unsigned)(p.co_tiles * p.k_tiles * p.splits);
