@@ -261,15 +261,19 @@ sc_status sparse_mask_generate(const float* score_dev, int32_t in_h, int32_t in_
                                void* hip_stream);
 
 /*
- * Glue operators of the test networks (ResNet-style stacks), NHWC device tensors of `dtype`.
+ * Glue operators of the test networks (ResNet- and MobileNet-style stacks), NHWC device tensors of `dtype`.
  * They are not part of the paper's method; they only connect conv layers in network runs.
  *   sc_maxpool2d_nhwc: window k, stride s, zero-free padding p (padded taps never win).
- *   sc_add_relu:       y = max(a + b, 0), element-wise; y may alias a or b.
+ *   sc_add_relu:       y = max(a + b, 0), element-wise over `count` elements; y may alias a or b.
+ *   sc_add:            y = a + b, likewise (the linear shortcut of inverted-residual blocks).  Both work on
+ *                      compact [kept x C] matrices as well: an element-wise operator keeps the row format.
+ * Errors: SC_ERR_NULL, SC_ERR_UNSUPPORTED (dtype), SC_ERR_BAD_SHAPE (negative count), SC_ERR_HIP.
  */
 sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32_t n, int32_t h, int32_t w,
                             int32_t c, int32_t k, int32_t s, int32_t p, void* hip_stream);
 sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
                       void* hip_stream);
+sc_status sc_add(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -306,13 +306,17 @@ def run_network(ops, tensors: Dict[str, np.ndarray], layer_inputs) -> Dict[str, 
     for op in ops:
         if op.kind == "conv":
             w, b, m = layer_inputs(op.spec)
-            y = masked_conv2d(op.spec, t[op.src], w, b, m)
+            conv = masked_depthwise_conv2d if op.spec.groups > 1 else masked_conv2d
+            y = conv(op.spec, t[op.src], w, b, m)
             t[op.out] = round_storage(y, op.spec.dtype)
         elif op.kind == "maxpool":
             t[op.out] = maxpool2d_nhwc(t[op.src], 3, 2, 1)
         elif op.kind == "add_relu":
             dt = next(o.spec.dtype for o in ops if o.kind == "conv")
             t[op.out] = round_storage(add_relu(t[op.src], t[op.src2]), dt)
+        elif op.kind == "add":
+            dt = next(o.spec.dtype for o in ops if o.kind == "conv")
+            t[op.out] = round_storage((_f32(t[op.src]).astype(np.float64) + _f32(t[op.src2])).astype(np.float32), dt)
         else:
             raise ValueError(op.kind)
     return t

@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
         L.sc_maxpool2d_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.sc_add_relu.restype = ctypes.c_int
         L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
+        L.sc_add.restype = ctypes.c_int
+        L.sc_add.argtypes = [vp, vp, vp, i32, i64, vp]
         L.sparse_conv_plan_mask.restype = vp
         L.sparse_conv_plan_mask.argtypes = [vp]
         L.sparse_conv_backward_workspace_bytes.restype = ctypes.c_int
@@ -377,30 +379,45 @@ def prepared_maxpool(x: torch.Tensor, y: torch.Tensor, k: int = 3, s: int = 2, p
     return call
 
 
-def prepared_add_relu(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor, stream=None):
-    """Like prepared_run, for sc_add_relu into a caller-owned output."""
+def prepared_add(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor, relu: bool = False, stream=None):
+    """Like prepared_run, for sc_add (relu=False) or sc_add_relu into a caller-owned output."""
     if a.shape != b.shape or a.dtype != b.dtype or y.shape != a.shape or y.dtype != a.dtype:
         raise ValueError("operands differ in shape or dtype")
-    fn, pa, pb, py, code, n, st = lib().sc_add_relu, _dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), \
+    name = "sc_add_relu" if relu else "sc_add"
+    fn, pa, pb, py, code, n, st = getattr(lib(), name), _dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), \
         _CODE_OF_TORCH[a.dtype], a.numel(), _stream_handle(stream)
     keep = (a, b, y)
 
     def call(stream_handle=None):
-        _check(fn(pa, pb, py, code, n, st if stream_handle is None else stream_handle), "sc_add_relu")
+        _check(fn(pa, pb, py, code, n, st if stream_handle is None else stream_handle), name)
         return keep[2]
 
     call()
     return call
 
 
-def sc_add_relu(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+def prepared_add_relu(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor, stream=None):
+    return prepared_add(a, b, y, relu=True, stream=stream)
+
+
+def _add(name: str, a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor], stream) -> torch.Tensor:
     if a.shape != b.shape or a.dtype != b.dtype:
         raise ValueError("operands differ in shape or dtype")
     if y is None:
         y = torch.empty_like(a)
-    _check(lib().sc_add_relu(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), _CODE_OF_TORCH[a.dtype],
-                             a.numel(), _stream_handle(stream)), "sc_add_relu")
+    elif y.shape != a.shape or y.dtype != a.dtype:
+        raise ValueError("output differs from the operands in shape or dtype")
+    _check(getattr(lib(), name)(_dev_ptr(a, "a"), _dev_ptr(b, "b"), _dev_ptr(y, "y"), _CODE_OF_TORCH[a.dtype],
+                                a.numel(), _stream_handle(stream)), name)
     return y
+
+
+def sc_add_relu(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _add("sc_add_relu", a, b, y, stream)
+
+
+def sc_add(a: torch.Tensor, b: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    return _add("sc_add", a, b, y, stream)
 
 
 def sparse_mask_workspace_bytes(ho: int, wo: int) -> int:

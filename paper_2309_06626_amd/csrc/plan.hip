@@ -267,8 +267,8 @@ __global__ void maxpool_nhwc_vec8_kernel(const T* __restrict__ x, T* __restrict_
   *reinterpret_cast<vec8*>(y + pos * c + g * 8) = o;
 }
 
-template <typename T>
-__global__ void add_relu_vec8_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t groups) {
+template <typename T, bool RELU>
+__global__ void add_vec8_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t groups) {
   typedef T vec8 __attribute__((ext_vector_type(8)));
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -276,18 +276,21 @@ __global__ void add_relu_vec8_kernel(const T* __restrict__ a, const T* __restric
     const vec8 va = reinterpret_cast<const vec8*>(a)[i], vb = reinterpret_cast<const vec8*>(b)[i];
     vec8 o;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = (T)fmaxf((float)va[e] + (float)vb[e], 0.0f);
+    for (int e = 0; e < 8; ++e) {
+      const float v = (float)va[e] + (float)vb[e];
+      o[e] = (T)(RELU ? fmaxf(v, 0.0f) : v);
+    }
     reinterpret_cast<vec8*>(y)[i] = o;
   }
 }
 
-template <typename T>
-__global__ void add_relu_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t count) {
+template <typename T, bool RELU>
+__global__ void add_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t count) {
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) {
-    float v = (float)a[i] + (float)b[i];
-    y[i] = (T)fmaxf(v, 0.0f);
+    const float v = (float)a[i] + (float)b[i];
+    y[i] = (T)(RELU ? fmaxf(v, 0.0f) : v);
   }
 }
 
@@ -1201,8 +1204,11 @@ sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32
   return SC_OK;
 }
 
-sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
-                      void* hip_stream) {
+}  // extern "C"
+
+template <bool RELU>
+static sc_status add_launch(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
+                            void* hip_stream) {
   if (!a_dev || !b_dev || !y_dev) return SC_ERR_NULL;
   if (dtype != SC_F32 && dtype != SC_F16 && dtype != SC_BF16) return SC_ERR_UNSUPPORTED;
   if (count < 0) return SC_ERR_BAD_SHAPE;
@@ -1214,22 +1220,33 @@ sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t
   if (vec8) {
     dim3 vgrid((unsigned)std::min<int64_t>((count / 8 + 255) / 256, 65536));
     if (dtype == SC_F16)
-      hipLaunchKernelGGL(add_relu_vec8_kernel<_Float16>, vgrid, block, 0, stream, (const _Float16*)a_dev,
+      hipLaunchKernelGGL((add_vec8_kernel<_Float16, RELU>), vgrid, block, 0, stream, (const _Float16*)a_dev,
                          (const _Float16*)b_dev, (_Float16*)y_dev, count / 8);
     else
-      hipLaunchKernelGGL(add_relu_vec8_kernel<__bf16>, vgrid, block, 0, stream, (const __bf16*)a_dev,
+      hipLaunchKernelGGL((add_vec8_kernel<__bf16, RELU>), vgrid, block, 0, stream, (const __bf16*)a_dev,
                          (const __bf16*)b_dev, (__bf16*)y_dev, count / 8);
   } else if (dtype == SC_F32)
-    hipLaunchKernelGGL(add_relu_kernel<float>, grid, block, 0, stream, (const float*)a_dev, (const float*)b_dev,
+    hipLaunchKernelGGL((add_kernel<float, RELU>), grid, block, 0, stream, (const float*)a_dev, (const float*)b_dev,
                        (float*)y_dev, count);
   else if (dtype == SC_F16)
-    hipLaunchKernelGGL(add_relu_kernel<_Float16>, grid, block, 0, stream, (const _Float16*)a_dev,
+    hipLaunchKernelGGL((add_kernel<_Float16, RELU>), grid, block, 0, stream, (const _Float16*)a_dev,
                        (const _Float16*)b_dev, (_Float16*)y_dev, count);
   else
-    hipLaunchKernelGGL(add_relu_kernel<__bf16>, grid, block, 0, stream, (const __bf16*)a_dev, (const __bf16*)b_dev,
+    hipLaunchKernelGGL((add_kernel<__bf16, RELU>), grid, block, 0, stream, (const __bf16*)a_dev, (const __bf16*)b_dev,
                        (__bf16*)y_dev, count);
   SC_HIP(hipGetLastError());
   return SC_OK;
+}
+
+extern "C" {
+
+sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count,
+                      void* hip_stream) {
+  return add_launch<true>(a_dev, b_dev, y_dev, dtype, count, hip_stream);
+}
+
+sc_status sc_add(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count, void* hip_stream) {
+  return add_launch<false>(a_dev, b_dev, y_dev, dtype, count, hip_stream);
 }
 
 }  // extern "C"

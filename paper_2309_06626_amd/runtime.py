@@ -5,6 +5,7 @@ called, results are copied back.
 """
 from __future__ import annotations
 
+import hashlib
 from typing import Callable, Dict, List, Optional
 
 import numpy as np
@@ -40,6 +41,9 @@ class ConvLayer:
         self.w = to_device(w, spec.dtype, device)
         self.bias = torch.from_numpy(np.ascontiguousarray(bias, np.float32)).to(device) if spec.has_bias else None
         self.mask = torch.from_numpy(np.ascontiguousarray(mask, np.uint8)).to(device)
+        # identifies the set of kept rows: two layers with equal keys have the same row list
+        self.rows_key = (spec.n, spec.ho, spec.wo, spec.mask_mode,
+                         hashlib.sha1(np.ascontiguousarray(mask, np.uint8).tobytes()).hexdigest())
         self.desc = B.desc_from_spec(spec, out_mode=out_mode, check_count=check_count)
         self.plan = B.sparse_conv_plan(self.desc, self.mask, self.w)
         self.info = B.sparse_conv_plan_info(self.plan)
@@ -72,6 +76,61 @@ def pad_conv_params(spec, padded_spec, w: np.ndarray, bias: Optional[np.ndarray]
     return wp, bp
 
 
+def plan_row_formats(ops, layers: Dict[str, "ConvLayer"]) -> Dict[str, bool]:
+    """Which tensors of a graph can live as compact [kept x C] matrices (True) instead of dense maps.
+
+    Under mask propagation (Alg. 1, getMask) all layers of one resolution share a mask, so a masked conv may
+    hand its kept rows straight to a pointwise (1x1, stride 1, no padding) conv with the same mask, through
+    element-wise ops whose operands share that row list, without the scatter, zero fill and re-gather in
+    between.  A tensor stays dense when any consumer needs neighbours (larger windows, depthwise, pooling,
+    strides), when masks differ, and at the graph's outputs.  Host-side bookkeeping only."""
+    consumers: Dict[str, list] = {}
+    for op in ops:
+        for src in (op.src, op.src2):
+            if src:
+                consumers.setdefault(src, []).append(op)
+    key: Dict[str, object] = {}
+    compact: Dict[str, bool] = {}
+    for op in ops:
+        if op.kind == "conv":
+            key[op.out] = layers[op.spec.name].rows_key
+            compact[op.out] = op.spec.layout == "nhwc"
+        elif op.kind in ("add", "add_relu"):
+            same = key.get(op.src) is not None and key.get(op.src) == key.get(op.src2)
+            key[op.out] = key.get(op.src) if same else None
+            compact[op.out] = same
+        else:
+            key[op.out] = None
+            compact[op.out] = False
+
+    def accepts(op, name) -> bool:
+        """May `op` read tensor `name` in compact form?"""
+        if op.kind == "conv":
+            sp = op.spec
+            pointwise = (sp.kh == 1 and sp.kw == 1 and sp.stride_h == 1 and sp.stride_w == 1 and sp.pad_h == 0 and
+                         sp.pad_w == 0 and sp.groups == 1 and sp.layout == "nhwc")
+            return pointwise and layers[sp.name].rows_key == key[name]
+        if op.kind in ("add", "add_relu"):
+            return compact[op.out]
+        return False
+
+    changed = True
+    while changed:
+        changed = False
+        for op in ops:
+            out = op.out
+            if not compact[out]:
+                continue
+            users = consumers.get(out, [])
+            ok = bool(users) and all(accepts(u, out) for u in users)
+            if ok and op.kind in ("add", "add_relu"):
+                ok = compact.get(op.src, False) and compact.get(op.src2, False)
+            if not ok:
+                compact[out] = False
+                changed = True
+    return compact
+
+
 def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer]) -> Dict[str, torch.Tensor]:
     """Interpret a workload op list on the device (conv = sparse_conv_run, plus the glue ops)."""
     t = dict(tensors)
@@ -82,6 +141,8 @@ def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLay
             t[op.out] = B.sc_maxpool2d_nhwc(t[op.src], 3, 2, 1)
         elif op.kind == "add_relu":
             t[op.out] = B.sc_add_relu(t[op.src], t[op.src2])
+        elif op.kind == "add":
+            t[op.out] = B.sc_add(t[op.src], t[op.src2])
         else:
             raise ValueError(op.kind)
     return t
@@ -92,23 +153,36 @@ class NetworkRunner:
     launch is validated once, so a pass is a plain sequence of C-ABI calls (and can be recorded into
     a HIP graph: the library launches kernels only, no memsets, no allocations, no synchronisation)."""
 
-    def __init__(self, ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer], dense: bool = False):
+    def __init__(self, ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer], dense: bool = False,
+                 row_formats: Optional[Dict[str, bool]] = None):
+        """row_formats: the result of plan_row_formats, to keep those tensors compact (sparse runs only)."""
         self.tensors = dict(tensors)
         self.calls: List[Callable] = []
+        self.row_formats = {} if (dense or row_formats is None) else dict(row_formats)
+        fmt = lambda name: B.SC_ROWS_COMPACT if self.row_formats.get(name, False) else B.SC_ROWS_DENSE
         t = self.tensors
         for op in ops:
             if op.kind == "conv":
                 layer = layers[op.spec.name]
-                t[op.out] = layer.new_output()
-                self.calls.append(B.prepared_run(layer.plan, t[op.src], layer.bias, t[op.out], dense=dense))
+                xf, yf = fmt(op.src), fmt(op.out)
+                if xf == B.SC_ROWS_DENSE and yf == B.SC_ROWS_DENSE:
+                    t[op.out] = layer.new_output()
+                    self.calls.append(B.prepared_run(layer.plan, t[op.src], layer.bias, t[op.out], dense=dense))
+                    continue
+                if yf == B.SC_ROWS_COMPACT:
+                    t[op.out] = torch.empty((layer.info["kept"], op.spec.c_out), dtype=B.TORCH_DTYPE[op.spec.dtype],
+                                            device=layer.device)
+                else:
+                    t[op.out] = layer.new_output()
+                self.calls.append(B.prepared_run_rows(layer.plan, t[op.src], layer.bias, t[op.out], xf, yf))
             elif op.kind == "maxpool":
                 n, h, w, c = t[op.src].shape
                 t[op.out] = torch.empty((n, (h + 2 - 3) // 2 + 1, (w + 2 - 3) // 2 + 1, c), dtype=t[op.src].dtype,
                                         device=t[op.src].device)
                 self.calls.append(B.prepared_maxpool(t[op.src], t[op.out], 3, 2, 1))
-            elif op.kind == "add_relu":
+            elif op.kind in ("add", "add_relu"):
                 t[op.out] = torch.empty_like(t[op.src])
-                self.calls.append(B.prepared_add_relu(t[op.src], t[op.src2], t[op.out]))
+                self.calls.append(B.prepared_add(t[op.src], t[op.src2], t[op.out], relu=op.kind == "add_relu"))
             else:
                 raise ValueError(op.kind)
         self.graph = None

@@ -91,6 +91,9 @@ def test_null_and_alignment_errors_come_before_any_gpu_work():
     assert L.sparse_conv_plan_info(None, None, None, None, None, None) == B.SC_ERR_NULL
     assert L.sc_add_relu(None, 256, 256, B.SC_BF16, 10, None) == B.SC_ERR_NULL
     assert L.sc_add_relu(256, 256, 256, 7, 10, None) == B.SC_ERR_UNSUPPORTED
+    assert L.sc_add(256, None, 256, B.SC_BF16, 10, None) == B.SC_ERR_NULL
+    assert L.sc_add(256, 256, 256, 7, 10, None) == B.SC_ERR_UNSUPPORTED
+    assert L.sc_add(256, 256, 256, B.SC_F16, -1, None) == B.SC_ERR_BAD_SHAPE
     assert L.sc_maxpool2d_nhwc(256, 256, B.SC_BF16, 1, 4, 4, 8, 3, 2, 2, None) == B.SC_ERR_BAD_SHAPE
     L.sparse_conv_plan_destroy(None)  # harmless
 

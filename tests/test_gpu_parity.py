@@ -445,6 +445,9 @@ def test_glue_ops_match_oracle():
         b = W.quantize(rng.standard_normal(x.shape).astype(np.float32), dtype)
         z = B.sc_add_relu(R.to_device(x, dtype), R.to_device(b, dtype))
         assert np.array_equal(R.to_host_f32(z), oracle.round_storage(oracle.add_relu(x, b), dtype))
+        z = B.sc_add(R.to_device(x, dtype), R.to_device(b, dtype))
+        want = oracle.round_storage((x.astype(np.float64) + b).astype(np.float32), dtype)
+        assert np.array_equal(R.to_host_f32(z), want)
 
 
 def _run_network_both(ops, bs, batch_note=""):

@@ -473,6 +473,42 @@ def test_small_resnet_chain_matches_library_pipeline():
     assert t[last].shape == (1, 1, 1, 512)
 
 
+def test_small_mobilenet_chain_with_masks_matches_library_pipeline():
+    """Depthwise layers, linear shortcuts and 2-D masks in the network interpreter: the same graph through
+    the library's grouped conv2d in float64, with the dropped pixels of every conv cleared afterwards."""
+    ops = W.mobilenet_v2(batch=2, res=32, sparsity=0.5, dtype="f32")
+    bs = 77
+    x = W.gen_activations(W.network_input_shape(ops), bs, "f32")
+    params = {}
+
+    def layer_inputs(spec):
+        if spec.name not in params:
+            ci = W.make_conv_inputs(spec, bs, x=np.zeros(1, np.float32))
+            params[spec.name] = (ci.w, ci.bias, ci.mask)
+        return params[spec.name]
+
+    t = oracle.run_network(ops, {"input": x}, layer_inputs)
+    tt = {"input": torch.from_numpy(x).double().permute(0, 3, 1, 2)}
+    for op in ops:
+        if op.kind == "conv":
+            s = op.spec
+            w, b, m = layer_inputs(s)
+            y = F.conv2d(tt[op.src], torch.from_numpy(w).double().permute(0, 3, 1, 2), torch.from_numpy(b).double(),
+                         stride=s.stride_h, padding=s.pad_h, groups=s.groups)
+            y = torch.relu(y) if s.relu else y
+            tt[op.out] = y * torch.from_numpy(m.reshape(1, 1, s.ho, s.wo).astype(np.float64))
+        else:
+            assert op.kind == "add"
+            tt[op.out] = tt[op.src] + tt[op.src2]
+    checked = 0
+    for name in ("b0_out", "b2_out", "b6_d", "b13_e", "head"):
+        ref = tt[name].permute(0, 2, 3, 1).numpy()
+        np.testing.assert_allclose(t[name], ref, rtol=3e-4, atol=3e-5 * max(1.0, np.abs(ref).max()))
+        assert np.abs(ref).max() > 0
+        checked += 1
+    assert checked == 5 and t["head"].shape == (2, 1, 1, 1280)
+
+
 # ---------------------------------------------------------------------------------------
 # depthwise layers (groups == Cin == Cout)
 # ---------------------------------------------------------------------------------------

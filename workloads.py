@@ -278,7 +278,7 @@ def depthwise_layers(batch: int = 64, sparsity: float = 0.5, dtype: str = "bf16"
 class NetOp:
     """One node of a small inference graph.
 
-    kind: "conv" (spec set), "maxpool" (3x3 stride 2 pad 1), "add_relu" (out = max(a+b, 0)).
+    kind: "conv" (spec set), "maxpool" (3x3 stride 2 pad 1), "add_relu" (out = max(a+b, 0)), "add" (out = a+b).
     Tensors are named; "input" is the synthetic network input; a conv whose ``src``
     starts with "synthetic:" draws its own input from the generator.
     """
@@ -387,6 +387,46 @@ def config5(batch: int = 16, sparsity: float = 0.3, dtype: str = "bf16") -> List
     conv("neck_256_128_40", "synthetic:n2", "n2", 256, 128, 40, 1, 1)
     conv("neck_128_64_80", "synthetic:n3", "n3", 128, 64, 80, 1, 1)
     conv("neck_256_256_40", "synthetic:n4", "n4", 256, 256, 40, 1, 1)
+    return ops
+
+
+def mobilenet_v2(batch: int = 64, res: int = 224, sparsity: float = 0.5, dtype: str = "bf16") -> List[NetOp]:
+    """Convolution stack of a MobileNetV2-style network (width 1.0): 3x3 stem, one depthwise-separable block,
+    sixteen inverted-residual blocks (1x1 expansion by 6 -> depthwise 3x3 -> linear 1x1 projection, identity
+    shortcut where shape allows) and the 1x1 head; 52 convs.  BN folded into bias; ReLU stands in for the
+    architecture's clipped ReLU (the library has none / ReLU).  The paper times this family end to end
+    (Sec. 4) without listing shapes: these are the standard ones.  Every conv is masked with 2-D masks
+    (one per layer resolution under Alg. 1's propagation), so all layers of one resolution share a mask."""
+    ops: List[NetOp] = []
+    li = 0
+
+    def conv(name, src, out, ci, co, hw, k, s, relu, groups=1):
+        nonlocal li
+        spec = ConvSpec(name, n=batch, c_in=ci, h=hw, w=hw, c_out=co, kh=k, kw=k, stride_h=s, stride_w=s,
+                        pad_h=k // 2, pad_w=k // 2, dtype=dtype, relu=relu, sparsity=sparsity, layer_index=li,
+                        groups=groups, mask_mode="spatial")
+        li += 1
+        ops.append(NetOp("conv", out, src, spec=spec))
+        return spec
+
+    hw = conv("stem", "input", "stem", 3, 32, res, 3, 2, True).ho
+    conv("b0_dw", "stem", "b0_d", 32, 32, hw, 3, 1, True, groups=32)
+    conv("b0_project", "b0_d", "b0_out", 32, 16, hw, 1, 1, False)
+    cur, ch, blk = "b0_out", 16, 1
+    for expand, co, repeats, stride in [(6, 24, 2, 2), (6, 32, 3, 2), (6, 64, 4, 2), (6, 96, 3, 1), (6, 160, 3, 2),
+                                        (6, 320, 1, 1)]:
+        for r in range(repeats):
+            st = stride if r == 0 else 1
+            mid, tag = ch * expand, f"b{blk}"
+            conv(f"{tag}_expand", cur, f"{tag}_e", ch, mid, hw, 1, 1, True)
+            d = conv(f"{tag}_dw", f"{tag}_e", f"{tag}_d", mid, mid, hw, 3, st, True, groups=mid)
+            conv(f"{tag}_project", f"{tag}_d", f"{tag}_p", mid, co, d.ho, 1, 1, False)
+            out = f"{tag}_p"
+            if st == 1 and ch == co:
+                ops.append(NetOp("add", f"{tag}_out", f"{tag}_p", cur))
+                out = f"{tag}_out"
+            cur, ch, hw, blk = out, co, d.ho, blk + 1
+    conv("head", cur, "head", ch, 1280, hw, 1, 1, True)
     return ops
 
 
