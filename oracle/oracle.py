@@ -264,6 +264,25 @@ def masked_depthwise_conv2d(spec, x, w, bias, mask, want_absum: bool = False):
     return (y, absum) if want_absum else y
 
 
+def masked_depthwise_conv2d_compact(spec, x, w, bias, mask, x_mask=None, y_compact: bool = False):
+    """The masked depthwise convolution with compact operands (NHWC).
+
+    x_mask: when given, ``x`` is [kept_in, C] -- the rows that ``x_mask`` keeps of the layer's input map (one
+    byte per input pixel and image in row mode, one per input pixel in spatial mode: the mask of the layer
+    that produced the map).  The dropped input pixels are +0.0, which is what Alg. 2 writes there, so unlike
+    a 1x1 layer a window may read them.  y_compact: the result is [kept, C] instead of the dense map.
+    Both are defined through the dense-layout convolution: expand, convolve, take the kept rows."""
+    assert spec.layout == "nhwc"
+    if x_mask is not None:
+        xm = np.ascontiguousarray(x_mask, dtype=np.uint8).ravel()
+        pixels = spec.h * spec.w
+        assert xm.size == (spec.n * pixels if spec.mask_mode == "row" else pixels)
+        in_rows = xm if spec.mask_mode == "row" else np.tile(xm, spec.n)
+        x = from_compact(_f32(x), in_rows, spec.x_shape())
+    y = masked_depthwise_conv2d(spec, x, w, bias, mask)
+    return to_compact(y, row_mask(spec, mask)) if y_compact else y
+
+
 def round_storage(a: np.ndarray, dtype: str) -> np.ndarray:
     """Round float32 values to the storage type of a layer output (nearest even), widened back."""
     a = np.array(a, dtype=np.float32, order="C", copy=True)

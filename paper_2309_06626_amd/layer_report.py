@@ -114,24 +114,35 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None, library=False):
     return rec
 
 
-def chain_time(ops, base_seed, steps, dense=False):
-    """Whole network with fixed buffers: (us per pass launched call by call, us per pass as a HIP graph replay)."""
+def chain_time(ops, base_seed, steps, dense=False, propagated_masks=False, compact=False):
+    """Whole network with fixed buffers: (us per pass launched call by call, us per pass as a HIP graph replay).
+
+    propagated_masks: every layer's 2-D mask comes from one score through the mask generator (Alg. 1,
+    getMask), so layers of one resolution share it; compact: tensors between such layers stay compact."""
     import numpy as np
     import torch
 
     import workloads as W
+    from paper_2309_06626_amd import binding as B
     from paper_2309_06626_amd import runtime as R
 
     dtype = W.conv_specs(ops)[0].dtype
     layers = {}
+    if propagated_masks:
+        res = W.network_input_shape(ops)[1]
+        score = torch.from_numpy(W.gen_score(res, res, seed=base_seed + 77)).to("cuda:0")
     for s in W.conv_specs(ops):
         ci = W.make_conv_inputs(s, base_seed, x=np.zeros(1, np.float32))
-        layers[s.name] = R.ConvLayer(s, ci.w, ci.bias, ci.mask)
+        mask = ci.mask
+        if propagated_masks:
+            mask = B.sparse_mask_generate(score, s.ho, s.wo, s.sparsity).cpu().numpy().reshape(-1)
+        layers[s.name] = R.ConvLayer(s, ci.w, ci.bias, mask)
     tensors = {"input": R.to_device(W.gen_activations(W.network_input_shape(ops), base_seed, dtype), dtype)}
     for op in ops:
         if op.kind == "conv" and op.src.startswith("synthetic:"):
             tensors[op.src] = R.to_device(W.gen_activations(op.spec.x_shape(), base_seed + 500 + op.spec.layer_index, dtype), dtype)
-    net = R.NetworkRunner(ops, tensors, layers, dense=dense)
+    net = R.NetworkRunner(ops, tensors, layers, dense=dense,
+                          row_formats=R.plan_row_formats(ops, layers) if compact else None)
 
     def timed(fn):
         for _ in range(max(steps // 5, 3)):
@@ -294,6 +305,8 @@ def main():
     ap.add_argument("--compact", action="store_true", help="also time runs with compact row formats")
     ap.add_argument("--pruned", action="store_true",
                     help="also time a channel-pruned ResNet18 stack (51/102/205/410 channels, s = 0.3), as it is and padded to 16 and to 8")
+    ap.add_argument("--mobilenet", action="store_true",
+                    help="also time a MobileNetV2-style stack with propagated masks, with dense and with compact tensors")
     ap.add_argument("--backward", action="store_true", help="also time the backward pass of a few layers")
     ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
     args = ap.parse_args()
@@ -361,6 +374,16 @@ def main():
             chain_time(W.pad_channels(ops, 8), W.base_seed(3), cs)
         chains["pruned ResNet18 stack with its own channel counts (51/102/205/410: element gather)"] = \
             chain_time(ops, W.base_seed(3), cs)
+    if args.mobilenet:
+        cs = max(args.steps // 10, 5)
+        for sp in (0.5, 0.3):
+            ops = W.mobilenet_v2(sparsity=sp)
+            tag = f"MobileNetV2-style stack (52 convs, batch 64, s={sp}, masks propagated from one score)"
+            chains[tag + ", dense tensors"] = chain_time(ops, W.base_seed(6), cs, propagated_masks=True)
+            chains[tag + ", compact tensors between layers that share a mask"] = \
+                chain_time(ops, W.base_seed(6), cs, propagated_masks=True, compact=True)
+        chains["MobileNetV2-style stack, every conv through dense_conv_run"] = \
+            chain_time(ops, W.base_seed(6), cs, dense=True, propagated_masks=True)
     if chains:
         print()
         print("| whole chain (conv launches + pooling / residual glue, fixed buffers) | us per pass, call by call | us per pass, HIP graph replay |")

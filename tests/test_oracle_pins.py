@@ -530,6 +530,36 @@ def dw_spec(g, bias=True, relu=False, s=0.4, mask_mode="row"):
 
 
 @pytest.mark.parametrize("g", DW_GEOMS)
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+def test_depthwise_on_compact_input_reads_zeros_at_dropped_pixels(g, mask_mode):
+    """A compact input under the producer's mask is the dense map with +0.0 at the dropped pixels: the
+    library's grouped conv2d on that map, masked afterwards, must agree -- also when the two masks differ
+    (a strided layer reads a map of another resolution) and when both operands are compact."""
+    spec = dw_spec(g, True, True, s=0.4, mask_mode=mask_mode)
+    x, w, b, mask = rand_inputs(spec, 43)
+    rng = np.random.default_rng(44)
+    pixels = spec.h * spec.w
+    x_mask = (rng.random(spec.n * pixels if mask_mode == "row" else pixels) < 0.6).astype(np.uint8)
+    in_rows = x_mask if mask_mode == "row" else np.tile(x_mask, spec.n)
+    xc = np.ascontiguousarray(x.reshape(-1, spec.c_in)[in_rows == 1])
+    xz = x * in_rows.reshape(spec.n, spec.h, spec.w, 1)
+    y = F.conv2d(torch.from_numpy(xz).double().permute(0, 3, 1, 2), torch.from_numpy(w).double().permute(0, 3, 1, 2),
+                 torch.from_numpy(b).double(), stride=(spec.stride_h, spec.stride_w), padding=(spec.pad_h, spec.pad_w),
+                 dilation=(spec.dil_h, spec.dil_w), groups=spec.c_in)
+    rm = oracle.row_mask(spec, mask)
+    ref = (torch.relu(y).permute(0, 2, 3, 1).numpy().reshape(spec.m, spec.c_out)) * rm[:, None]
+    got = oracle.masked_depthwise_conv2d_compact(spec, xc, w, b, mask, x_mask=x_mask)
+    np.testing.assert_allclose(got.reshape(spec.m, spec.c_out), ref, rtol=1e-5, atol=1e-6)
+    assert (got.reshape(spec.m, spec.c_out)[rm == 0] == 0).all()
+    got_c = oracle.masked_depthwise_conv2d_compact(spec, xc, w, b, mask, x_mask=x_mask, y_compact=True)
+    np.testing.assert_allclose(got_c, ref[rm == 1], rtol=1e-5, atol=1e-6)
+    # the dropped input pixels really matter: with the full map the result differs
+    full = oracle.masked_depthwise_conv2d(spec, x, w, b, mask)
+    if spec.kh * spec.kw > 1:
+        assert not np.allclose(full.reshape(spec.m, spec.c_out), ref, rtol=1e-3, atol=1e-4)
+
+
+@pytest.mark.parametrize("g", DW_GEOMS)
 @pytest.mark.parametrize("bias,relu", [(False, False), (True, True)])
 def test_depthwise_matches_library_grouped_conv2d(g, bias, relu):
     spec = dw_spec(g, bias, relu, s=0.0)
