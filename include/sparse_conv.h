@@ -137,15 +137,28 @@ sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* b
  *   y_rows = SC_ROWS_COMPACT: y_dev is [kept][Cout]; row i is the result of lowered row row_idx[i]
  *            (ascending, see sparse_conv_plan_info).  Nothing else is written: no zeros, no scatter.
  *   x_rows = SC_ROWS_COMPACT: x_dev is [kept][Cin]; row i is input pixel row_idx[i] of THIS layer's
- *            mask.  Only for 1x1 windows with stride 1 and no padding (the window is the pixel itself,
- *            so a kept row never reads a dropped pixel); SC_ERR_UNSUPPORTED otherwise, also for NCHW
- *            plans and for formats other than the two below.
+ *            mask.  For 1x1 windows with stride 1 and no padding (the window is the pixel itself,
+ *            so a kept row never reads a dropped pixel).  A depthwise layer with larger windows takes a
+ *            compact input after sparse_conv_plan_set_input_mask (below): x_dev then holds the pixels that
+ *            the INPUT's mask keeps, and the dropped ones read as the +0.0 Alg. 2 would have written.
+ *            SC_ERR_UNSUPPORTED otherwise, also for NCHW plans and for formats other than the two below.
  *   SC_ROWS_DENSE for both is sparse_conv_run.  The out_mode of the plan applies to dense outputs only.
  * Pointer and alignment rules as for sparse_conv_run; no allocation, no synchronisation.
  */
 typedef enum { SC_ROWS_DENSE = 0, SC_ROWS_COMPACT = 1 } sc_rows_format;
 sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
                                void* y_dev, int32_t y_rows, void* hip_stream);
+
+/*
+ * Row list of a compact input for a depthwise layer with windows larger than one pixel (its producer's
+ * mask, which under Alg. 1's propagation differs from the layer's own when the layer is strided):
+ * mask_in_dev is uint8[N*H*W] (SC_MASK_ROW plans) or uint8[H*W] (SC_MASK_SPATIAL plans) over the INPUT
+ * pixels, 1 = present in x.  Builds, inside the workspace, the map from input pixel to row of x that the
+ * kernels consult for every tap; *kept_in (may be NULL) receives the number of rows x must hold.
+ * Synchronises `hip_stream`.  SC_ERR_UNSUPPORTED for other plans; may be called again for a new mask.
+ */
+sc_status sparse_conv_plan_set_input_mask(sc_plan* plan, const uint8_t* mask_in_dev, int64_t* kept_in,
+                                          void* hip_stream);
 
 /* The same kernels with the identity row map: the ordinary dense convolution (the paper's
  * baseline; its GEMM is unchanged, App. A).  Ignores the mask. */

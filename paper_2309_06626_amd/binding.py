@@ -94,6 +94,8 @@ def lib() -> ctypes.CDLL:
         L.sc_maxpool2d_nhwc.argtypes = [vp, vp] + [i32] * 8 + [vp]
         L.sc_add_relu.restype = ctypes.c_int
         L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
+        L.sparse_conv_plan_set_input_mask.restype = ctypes.c_int
+        L.sparse_conv_plan_set_input_mask.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
         L.sc_add.restype = ctypes.c_int
         L.sc_add.argtypes = [vp, vp, vp, i32, i64, vp]
         L.sparse_conv_plan_mask.restype = vp
@@ -220,7 +222,12 @@ def _check_operands(plan: Plan, x, bias, y, x_compact=False, y_compact=False):
     if bias is not None and (bias.dtype != torch.float32 or bias.numel() != d.c_out):
         raise ValueError("bias must be float32[c_out]")
     info = sparse_conv_plan_info(plan)
-    want_x = info["kept"] * d.c_in if x_compact else d.n * d.h * d.w * d.c_in
+    # a compact input holds this layer's kept pixels (1x1 windows) or, for a depthwise layer with windows, the
+    # pixels its input mask keeps (sparse_conv_plan_set_input_mask)
+    x_rows = getattr(plan, "x_kept", None) if (d.groups > 1 and d.kh * d.kw > 1) else info["kept"]
+    if x_compact and x_rows is None:
+        raise ValueError("a compact input of this layer needs sparse_conv_plan_set_input_mask first")
+    want_x = x_rows * d.c_in if x_compact else d.n * d.h * d.w * d.c_in
     want_y = (info["kept"] if y_compact else info["m"]) * d.c_out
     if x.numel() != want_x:
         raise ValueError(f"x holds {x.numel()} elements, the plan needs {want_x}")
@@ -377,6 +384,19 @@ def prepared_maxpool(x: torch.Tensor, y: torch.Tensor, k: int = 3, s: int = 2, p
 
     call()
     return call
+
+
+def sparse_conv_plan_set_input_mask(plan: "Plan", mask_in: torch.Tensor, stream=None) -> int:
+    """Row list of a compact input of a depthwise layer with windows; returns the rows x must hold."""
+    d = plan.desc
+    want = d.h * d.w * (d.n if d.mask_mode == SC_MASK_ROW else 1)
+    if mask_in.dtype != torch.uint8 or mask_in.numel() != want:
+        raise ValueError(f"input mask must be uint8 with {want} entries")
+    kept = ctypes.c_int64()
+    _check(lib().sparse_conv_plan_set_input_mask(plan.handle, _dev_ptr(mask_in, "mask_in"), ctypes.byref(kept),
+                                                 _stream_handle(stream)), "sparse_conv_plan_set_input_mask")
+    plan.x_kept = int(kept.value)
+    return plan.x_kept
 
 
 def prepared_add(a: torch.Tensor, b: torch.Tensor, y: torch.Tensor, relu: bool = False, stream=None):

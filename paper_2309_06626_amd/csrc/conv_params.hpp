@@ -72,6 +72,9 @@ struct DepthwiseParams {
   const int32_t* rank;     // [M]: position of a kept row in the row list (compact output); else null
   int32_t n, ho;           // images, output rows
   int32_t zero_fill;       // dropped pixels of a dense-layout output receive zeros (else they are left alone)
+  // compact input of a layer with windows: row of every input pixel in x, -1 for a pixel its producer dropped
+  // (such a pixel reads as +0.0); null: a compact input holds the layer's own kept pixels (1x1 windows)
+  const int32_t* x_rank;   // [N * H * W]
 };
 
 // Division of 0 <= n < 2^31 by d >= 1 as (n * mul) >> shift in 64-bit arithmetic: with l = ceil(log2 d)

@@ -61,10 +61,14 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DepthwiseParams p)
   }
   const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
   const int iy0 = oy * p.sh - p.ph, ix0 = ox * p.sw - p.pw;
-  // a compact input (1x1 windows only: the window is the pixel itself) holds pixel r in row `item`
-  const T* __restrict__ x = p.x_compact
+  // a compact input without a rank map (1x1 windows only: the window is the pixel itself) holds pixel r in
+  // row `item`; with a rank map every tap looks its pixel up
+  const bool ranked = p.x_compact && p.x_rank;
+  const T* __restrict__ x = ranked ? static_cast<const T*>(p.x) + c0
+                            : p.x_compact
                                 ? static_cast<const T*>(p.x) + (item - ((int64_t)iy0 * p.w + ix0)) * p.c + c0
                                 : static_cast<const T*>(p.x) + (int64_t)n * p.h * p.w * p.c + c0;
+  const int32_t* __restrict__ xr = ranked ? p.x_rank + (int64_t)n * p.h * p.w : nullptr;
   const T* __restrict__ wp = static_cast<const T*>(p.wp) + c0;
   float acc[V];
 #pragma unroll
@@ -75,7 +79,12 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const DepthwiseParams p)
     for (int kx = 0; kx < p.kw; ++kx) {
       const int ix = ix0 + kx * p.dil_w;
       if ((unsigned)ix >= (unsigned)p.w) continue;
-      const G xv = *reinterpret_cast<const G*>(x + ((int64_t)iy * p.w + ix) * p.c);
+      int64_t pix = (int64_t)iy * p.w + ix;
+      if (ranked) {
+        pix = xr[pix];
+        if (pix < 0) continue;            // dropped by the producer: +0.0
+      }
+      const G xv = *reinterpret_cast<const G*>(x + pix * p.c);
       const G wv = *reinterpret_cast<const G*>(wp + (int64_t)(ky * p.kw + kx) * p.c);
 #pragma unroll
       for (int j = 0; j < V; ++j) acc[j] += (float)xv.v[j] * (float)wv.v[j];
@@ -268,8 +277,10 @@ struct DwPairTile {
   uint32_t div_tilesx_mul, div_tilesx_shift, div_tilesy_mul, div_tilesy_shift;
 };
 
-template <typename T, int S>
-__global__ __launch_bounds__(256) void depthwise3x3_dot2_kernel(const DepthwiseParams p, const DwPairTile q) {
+// XC: the input is compact; p.x_rank maps every input pixel to its row (or -1).  The ranks of a tile's patch
+// are requested one tile before its data, so that the data requests never wait for them.
+template <typename T, int S, bool XC>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void depthwise3x3_dot2_kernel(const DepthwiseParams p, const DwPairTile q) {
   constexpr int V = 8;
   typedef unsigned u4 __attribute__((ext_vector_type(4)));
   extern __shared__ __align__(16) unsigned char smem[];
@@ -327,8 +338,26 @@ __global__ __launch_bounds__(256) void depthwise3x3_dot2_kernel(const DepthwiseP
     const int n = fast_div(t1, q.div_tilesy_mul, q.div_tilesy_shift), tile_y = t1 - n * q.tiles_y;
     return Tile{n, tile_y * q.ty, tile_x * q.tx};
   };
+  int ia[XC ? kDwStageMost : 1], ib[XC ? kDwStageMost : 1];     // rows of the patch pixels in a compact input
+  auto request_ranks = [&](const Tile& tl) {
+    if constexpr (XC) {
+      const int32_t* __restrict__ xr = p.x_rank + (int64_t)tl.n * p.h * p.w;
+      const int iy_first = tl.oy0 * S - p.ph, ix_first = tl.ox0 * S - p.pw;
+#pragma unroll
+      for (int u = 0; u < kDwStageMost; ++u) {
+        const int e = u * 256 + t;
+        const int pix = fast_div(e, q.div_cg_mul, q.div_cg_shift);
+        const int pr = fast_div(pix, q.div_inw_mul, q.div_inw_shift), px = pix - pr * q.in_w;
+        const int iy = iy_first + 2 * pr, ix = ix_first + px;
+        const bool ok = e < plane && (unsigned)ix < (unsigned)p.w;
+        ia[u] = ib[u] = -1;
+        if (ok && (unsigned)iy < (unsigned)p.h) ia[u] = xr[iy * p.w + ix];
+        if (ok && (unsigned)(iy + 1) < (unsigned)p.h) ib[u] = xr[(iy + 1) * p.w + ix];
+      }
+    }
+  };
   auto request = [&](const Tile& tl) {
-    const T* __restrict__ x = static_cast<const T*>(p.x) + (int64_t)tl.n * p.h * p.w * p.c;
+    const T* __restrict__ x = static_cast<const T*>(p.x) + (XC ? (int64_t)0 : (int64_t)tl.n * p.h * p.w * p.c);
     const int iy_first = tl.oy0 * S - p.ph, ix_first = tl.ox0 * S - p.pw;
 #pragma unroll
     for (int u = 0; u < kDwStageMost; ++u) {
@@ -338,10 +367,17 @@ __global__ __launch_bounds__(256) void depthwise3x3_dot2_kernel(const DepthwiseP
       const int iy = iy_first + 2 * pr, ix = ix_first + px;
       ra[u] = u4{0, 0, 0, 0};
       rb[u] = u4{0, 0, 0, 0};
-      const bool ok = e < plane && (unsigned)ix < (unsigned)p.w && g0 + gg < groups;
-      const T* src = x + ((int64_t)iy * p.w + ix) * p.c + (g0 + gg) * V;
-      if (ok && (unsigned)iy < (unsigned)p.h) ra[u] = *reinterpret_cast<const u4*>(src);
-      if (ok && (unsigned)(iy + 1) < (unsigned)p.h) rb[u] = *reinterpret_cast<const u4*>(src + (int64_t)p.w * p.c);
+      if constexpr (XC) {
+        // (ranks outside the patch, the image or the channel range were left at -1 or are masked here)
+        const bool ok = g0 + gg < groups;
+        if (ok && ia[u] >= 0) ra[u] = *reinterpret_cast<const u4*>(x + (int64_t)ia[u] * p.c + (g0 + gg) * V);
+        if (ok && ib[u] >= 0) rb[u] = *reinterpret_cast<const u4*>(x + (int64_t)ib[u] * p.c + (g0 + gg) * V);
+      } else {
+        const bool ok = e < plane && (unsigned)ix < (unsigned)p.w && g0 + gg < groups;
+        const T* src = x + ((int64_t)iy * p.w + ix) * p.c + (g0 + gg) * V;
+        if (ok && (unsigned)iy < (unsigned)p.h) ra[u] = *reinterpret_cast<const u4*>(src);
+        if (ok && (unsigned)(iy + 1) < (unsigned)p.h) rb[u] = *reinterpret_cast<const u4*>(src + (int64_t)p.w * p.c);
+      }
     }
     // mask byte of the tile pixel this lane looks after (a tile has at most 256 pixels): 1 = kept,
     // 2 = dropped, 0 = outside the map
@@ -457,7 +493,9 @@ __global__ __launch_bounds__(256) void depthwise3x3_dot2_kernel(const DepthwiseP
   int id = blockIdx.x;
   if (id >= q.tiles) return;
   Tile cur = tile_of(id);
+  request_ranks(cur);
   request(cur);
+  if (id + (int)gridDim.x < q.tiles) request_ranks(tile_of(id + gridDim.x));
   deposit();
   __syncthreads();
   for (;;) {
@@ -467,6 +505,7 @@ __global__ __launch_bounds__(256) void depthwise3x3_dot2_kernel(const DepthwiseP
     if (more) {
       nxt = tile_of(next_id);
       request(nxt);            // in flight while this tile is computed
+      if (next_id + (int)gridDim.x < q.tiles) request_ranks(tile_of(next_id + gridDim.x));
     }
     compute(cur);
     if (!more) break;
@@ -543,7 +582,7 @@ static hipError_t launch_tiles(const DepthwiseParams& p, hipStream_t stream) {
   return hipGetLastError();
 }
 
-template <typename T, int S>
+template <typename T, int S, bool XC>
 static hipError_t launch_pair_tiles(const DepthwiseParams& p, hipStream_t stream) {
   const int groups = p.c / 8;
   DwPairTile q;
@@ -576,7 +615,7 @@ static hipError_t launch_pair_tiles(const DepthwiseParams& p, hipStream_t stream
   // persistent workgroups: about three per compute unit (LDS and registers allow that many), split over the chunks
   constexpr int per_cu = 3;
   const int wgs = std::max(1, std::min(q.tiles, (256 * per_cu + chunks - 1) / chunks));
-  hipLaunchKernelGGL((depthwise3x3_dot2_kernel<T, S>), dim3((unsigned)wgs, (unsigned)chunks), dim3(256), lds, stream, p, q);
+  hipLaunchKernelGGL((depthwise3x3_dot2_kernel<T, S, XC>), dim3((unsigned)wgs, (unsigned)chunks), dim3(256), lds, stream, p, q);
   return hipGetLastError();
 }
 
@@ -584,13 +623,17 @@ template <typename T>
 static hipError_t launch_typed(const DepthwiseParams& p, hipStream_t stream) {
   constexpr int V = DwVec<T>::V;
   const bool vec = p.c % V == 0;
-  // the LDS-tiled kernel: 3x3 windows, no dilation, stride 1 or 2, dense-layout input
-  if (vec && p.kh == 3 && p.kw == 3 && p.dil_h == 1 && p.dil_w == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2) &&
-      !p.x_compact) {
-    if constexpr (sizeof(T) == 2)
-      return p.sh == 1 ? launch_pair_tiles<T, 1>(p, stream) : launch_pair_tiles<T, 2>(p, stream);
-    else
+  // the LDS-tiled kernels: 3x3 windows, no dilation, stride 1 or 2; a compact input (with its rank map) only
+  // in the 16-bit kernel
+  if (vec && p.kh == 3 && p.kw == 3 && p.dil_h == 1 && p.dil_w == 1 && p.sh == p.sw && (p.sh == 1 || p.sh == 2)) {
+    if constexpr (sizeof(T) == 2) {
+      if (p.x_compact && p.x_rank)
+        return p.sh == 1 ? launch_pair_tiles<T, 1, true>(p, stream) : launch_pair_tiles<T, 2, true>(p, stream);
+      if (!p.x_compact)
+        return p.sh == 1 ? launch_pair_tiles<T, 1, false>(p, stream) : launch_pair_tiles<T, 2, false>(p, stream);
+    } else if (!p.x_compact) {
       return p.sh == 1 ? launch_tiles<T, 1>(p, stream) : launch_tiles<T, 2>(p, stream);
+    }
   }
   const int64_t threads = p.items * (vec ? p.c / V : p.c);
   const unsigned grid = (unsigned)((threads + 255) / 256);

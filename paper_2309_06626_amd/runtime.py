@@ -76,14 +76,19 @@ def pad_conv_params(spec, padded_spec, w: np.ndarray, bias: Optional[np.ndarray]
     return wp, bp
 
 
+kCompactDepthwiseInput = 16 << 20     # input elements from which a depthwise layer reads its input in compact form
+
+
 def plan_row_formats(ops, layers: Dict[str, "ConvLayer"]) -> Dict[str, bool]:
     """Which tensors of a graph can live as compact [kept x C] matrices (True) instead of dense maps.
 
     Under mask propagation (Alg. 1, getMask) all layers of one resolution share a mask, so a masked conv may
     hand its kept rows straight to a pointwise (1x1, stride 1, no padding) conv with the same mask, through
     element-wise ops whose operands share that row list, without the scatter, zero fill and re-gather in
-    between.  A tensor stays dense when any consumer needs neighbours (larger windows, depthwise, pooling,
-    strides), when masks differ, and at the graph's outputs.  Host-side bookkeeping only."""
+    between.  A depthwise layer with windows also reads a compact map: it looks every tap up in the row list
+    of its input (the producer's mask, whatever its own).  A tensor stays dense when any consumer needs
+    neighbours through the lowering (larger windows with one group, pooling, strided 1x1 layers), when masks
+    differ, and at the graph's outputs.  Host-side bookkeeping only."""
     consumers: Dict[str, list] = {}
     for op in ops:
         for src in (op.src, op.src2):
@@ -107,8 +112,15 @@ def plan_row_formats(ops, layers: Dict[str, "ConvLayer"]) -> Dict[str, bool]:
         """May `op` read tensor `name` in compact form?"""
         if op.kind == "conv":
             sp = op.spec
+            if sp.layout != "nhwc":
+                return False
+            if sp.groups > 1 and sp.kh * sp.kw > 1:
+                # depthwise with windows: any known row list.  The rank look-ups cost the layer itself a little
+                # (one more dependent fetch per tile); what is saved is the producer's zero fill, which outweighs
+                # that only on large maps (measured on MI355X: from about 16 M input elements on)
+                return key[name] is not None and sp.n * sp.h * sp.w * sp.c_in >= kCompactDepthwiseInput
             pointwise = (sp.kh == 1 and sp.kw == 1 and sp.stride_h == 1 and sp.stride_w == 1 and sp.pad_h == 0 and
-                         sp.pad_w == 0 and sp.groups == 1 and sp.layout == "nhwc")
+                         sp.pad_w == 0 and sp.groups == 1)
             return pointwise and layers[sp.name].rows_key == key[name]
         if op.kind in ("add", "add_relu"):
             return compact[op.out]
@@ -161,10 +173,19 @@ class NetworkRunner:
         self.row_formats = {} if (dense or row_formats is None) else dict(row_formats)
         fmt = lambda name: B.SC_ROWS_COMPACT if self.row_formats.get(name, False) else B.SC_ROWS_DENSE
         t = self.tensors
+        rows_mask: Dict[str, torch.Tensor] = {}       # the mask whose kept rows a tensor holds when compact
+        for op in ops:
+            if op.kind != "conv":
+                if op.src in rows_mask:
+                    rows_mask[op.out] = rows_mask[op.src]
+            else:
+                rows_mask[op.out] = layers[op.spec.name].mask
         for op in ops:
             if op.kind == "conv":
                 layer = layers[op.spec.name]
                 xf, yf = fmt(op.src), fmt(op.out)
+                if xf == B.SC_ROWS_COMPACT and op.spec.groups > 1 and op.spec.kh * op.spec.kw > 1:
+                    B.sparse_conv_plan_set_input_mask(layer.plan, rows_mask[op.src])
                 if xf == B.SC_ROWS_DENSE and yf == B.SC_ROWS_DENSE:
                     t[op.out] = layer.new_output()
                     self.calls.append(B.prepared_run(layer.plan, t[op.src], layer.bias, t[op.out], dense=dense))

@@ -158,3 +158,109 @@ def test_a_non_finite_input_value_reaches_only_the_windows_that_contain_it(dtype
     assert finite.sum() < ref.size and not finite.all()
     clean = oracle.masked_depthwise_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask)
     assert np.abs(got[finite] - clean[finite]).max() <= TOL[dtype] * np.abs(clean).max()
+
+
+# ---------------------------------------------------------------------------------------------------------
+# compact input under the producer's mask (sparse_conv_plan_set_input_mask)
+# ---------------------------------------------------------------------------------------------------------
+def check_compact_input(spec, seed, in_sparsity=0.5):
+    ci = W.make_conv_inputs(spec, seed)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    pixels = spec.h * spec.w
+    length = spec.n * pixels if spec.mask_mode == "row" else pixels
+    x_mask = W.gen_mask(length, W.n_keep(in_sparsity, length), seed + 2)
+    in_rows = x_mask if spec.mask_mode == "row" else np.tile(x_mask, spec.n)
+    # a value the window must not see sits at every dropped pixel of the dense map the oracle expands to zeros
+    xc_host = np.ascontiguousarray(ci.x.reshape(-1, spec.c_in)[in_rows == 1])
+    n_in = xc_host.shape[0]
+    assert B.sparse_conv_plan_set_input_mask(layer.plan, torch.from_numpy(x_mask).to("cuda:0")) == n_in
+    tol = TOL[spec.dtype]
+    xz = ci.x * in_rows.reshape(spec.n, spec.h, spec.w, 1)
+    ref, absum = oracle.masked_depthwise_conv2d(spec, xz, ci.w, ci.bias, ci.mask, want_absum=True)
+    via_compact = oracle.masked_depthwise_conv2d_compact(spec, xc_host, ci.w, ci.bias, ci.mask, x_mask=x_mask)
+    assert np.array_equal(via_compact, ref)
+    ref, absum = rows_view(spec, ref), rows_view(spec, absum)
+    rm = row_mask(spec, ci.mask)
+    kept = rm == 1
+    dt = B.TORCH_DTYPE[spec.dtype]
+    xc = R.to_device(xc_host, spec.dtype) if n_in else torch.empty((0, spec.c_in), dtype=dt, device="cuda:0")
+    y = layer.new_output(fill_nan=True)
+    if n_in:
+        B.sparse_conv_run_rows(layer.plan, xc, layer.bias, y, B.SC_ROWS_COMPACT, B.SC_ROWS_DENSE)
+    else:   # (an empty tensor has no address: the library is called with a placeholder it never reads)
+        pad = torch.zeros((1, spec.c_in), dtype=dt, device="cuda:0")
+        B._check(B.lib().sparse_conv_run_rows(layer.plan.handle, pad.data_ptr(), B.SC_ROWS_COMPACT,
+                                              layer.bias.data_ptr() if layer.bias is not None else None, y.data_ptr(),
+                                              B.SC_ROWS_DENSE, None), "sparse_conv_run_rows")
+    torch.cuda.synchronize()
+    g, bits = rows_view(spec, R.to_host_f32(y)), rows_view(spec, R.bits_of(y))
+    assert (bits[~kept] == 0).all()
+    assert_close(g[kept], ref[kept], absum[kept], tol, "depthwise, compact input")
+    # the dense-layout run on the zero-filled map computes the same numbers
+    yz = layer.new_output(fill_nan=True)
+    layer.sparse(R.to_device(xz, spec.dtype), yz)
+    torch.cuda.synchronize()
+    if spec.dtype == "f32":     # (another kernel, another order of the nine products)
+        assert_close(rows_view(spec, R.to_host_f32(yz))[kept], g[kept], absum[kept], 2 * tol, "zero-filled map")
+    else:
+        assert np.array_equal(R.bits_of(yz), R.bits_of(y))
+    # compact in, compact out
+    n_kept = int(kept.sum())
+    if n_kept and n_in:
+        buf = torch.empty((n_kept + 1, spec.c_out), dtype=xc.dtype, device="cuda:0").fill_(float("nan"))
+        B.sparse_conv_run_rows(layer.plan, xc, layer.bias, buf[:n_kept], B.SC_ROWS_COMPACT, B.SC_ROWS_COMPACT)
+        torch.cuda.synchronize()
+        assert np.array_equal(R.bits_of(buf[:n_kept]), bits[kept])
+        assert np.isnan(R.to_host_f32(buf[n_kept:])).all()
+    return layer
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+@pytest.mark.parametrize("shape", [
+    dict(n=2, c=32, h=14, w=14),                       # one tile per image
+    dict(n=1, c=96, h=37, w=29, s=2),                  # stride 2: the input mask has another resolution; ragged tiles
+    dict(n=3, c=144, h=40, w=40),                      # several tiles per workgroup: ranks are fetched a tile ahead
+    dict(n=1, c=576, h=14, w=14),                      # several channel chunks
+    dict(n=1, c=7, h=8, w=10),                         # one channel per lane
+    dict(n=1, c=16, h=12, w=12, k=5),                  # 5x5 window: the general kernel
+    dict(n=1, c=8, h=13, w=13, d=2),                   # dilation 2
+])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+def test_depthwise_reads_a_compact_input_through_its_producers_mask(dtype, shape, mask_mode):
+    check_compact_input(dw_spec(dtype=dtype, sparsity=0.4, mask_mode=mask_mode, **shape), 431)
+
+
+@pytest.mark.parametrize("in_sparsity", [0.0, 0.9, 1.0])
+def test_compact_input_extremes(in_sparsity):
+    check_compact_input(dw_spec(2, 64, 18, 18, sparsity=0.5, mask_mode="spatial"), 433, in_sparsity=in_sparsity)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_compact_input_with_a_layer_mask_that_keeps_every_pixel(dtype):
+    check_compact_input(dw_spec(2, 24, 15, 15, s=2, sparsity=0.0, dtype=dtype, mask_mode="spatial"), 434)
+
+
+def test_many_tiles_per_workgroup_with_a_compact_input():
+    """A map large enough that every persistent workgroup walks several tiles."""
+    check_compact_input(dw_spec(8, 32, 112, 112, sparsity=0.5, mask_mode="spatial"), 435)
+    check_compact_input(dw_spec(8, 96, 112, 112, s=2, sparsity=0.5, mask_mode="spatial"), 436)
+
+
+def test_compact_input_needs_the_input_mask_first_and_only_depthwise_window_layers_take_one():
+    spec = dw_spec(1, 16, 10, 10)
+    ci = W.make_conv_inputs(spec, 437)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    x = R.to_device(ci.x, spec.dtype)
+    y = layer.new_output()
+    rc = B.lib().sparse_conv_run_rows(layer.plan.handle, x.data_ptr(), B.SC_ROWS_COMPACT, layer.bias.data_ptr(),
+                                      y.data_ptr(), B.SC_ROWS_DENSE, None)
+    assert rc == B.SC_ERR_UNSUPPORTED
+    with pytest.raises(ValueError):
+        B.sparse_conv_run_rows(layer.plan, x, layer.bias, y, B.SC_ROWS_COMPACT, B.SC_ROWS_DENSE)
+    # an ordinary 3x3 layer has no such map
+    spec2 = W.ConvSpec("c", n=1, c_in=16, h=10, w=10, c_out=16, dtype="bf16", sparsity=0.5)
+    ci2 = W.make_conv_inputs(spec2, 438)
+    layer2 = R.ConvLayer(spec2, ci2.w, ci2.bias, ci2.mask)
+    m = torch.ones(100, dtype=torch.uint8, device="cuda:0")
+    assert B.lib().sparse_conv_plan_set_input_mask(layer2.plan.handle, m.data_ptr(), None, None) == B.SC_ERR_UNSUPPORTED
+    assert B.lib().sparse_conv_plan_set_input_mask(layer.plan.handle, None, None, None) == B.SC_ERR_NULL

@@ -64,8 +64,11 @@ def compare(ops, dev, ref, params, layers, fmt, tol, what):
             assert (bits[mask == 0] == 0).all(), f"{what} {op.out}: dropped rows must be zero"
 
 
-@pytest.mark.parametrize("dtype,batch,res,sparsity", [("bf16", 2, 96, 0.5), ("f16", 1, 64, 0.3)])
-def test_inverted_residual_stack_dense_and_compact_formats(dtype, batch, res, sparsity):
+@pytest.mark.parametrize("dtype,batch,res,sparsity,dw_compact", [("bf16", 2, 96, 0.5, True), ("f16", 1, 64, 0.3, False),
+                                                                  ("f16", 2, 64, 0.5, True)])
+def test_inverted_residual_stack_dense_and_compact_formats(dtype, batch, res, sparsity, dw_compact, monkeypatch):
+    if dw_compact:    # (the maps are small here: lift the size rule so that the depthwise layers read compact inputs too)
+        monkeypatch.setattr(R, "kCompactDepthwiseInput", 0)
     ops, params, layers, host = build(dtype, batch, res, sparsity, seed=900)
     ref = oracle.run_network(ops, host, lambda spec: params[spec.name])
     tol = TOL[dtype]
@@ -76,7 +79,8 @@ def test_inverted_residual_stack_dense_and_compact_formats(dtype, batch, res, sp
     compare(ops, dev, ref, params, layers, {}, tol, "dense tensors")
     # compact tensors wherever the graph allows
     fmt = R.plan_row_formats(ops, layers)
-    assert sum(fmt.values()) == 44 and fmt["b2_out"] and fmt["b5_d"] and not fmt["b5_e"]
+    assert sum(fmt.values()) == (len(ops) - 1 if dw_compact else 44)
+    assert fmt["b2_out"] and fmt["b5_d"] and fmt["b5_e"] == dw_compact and not fmt["head"]
     runner = R.NetworkRunner(ops, x, layers, row_formats=fmt)
     for name, t in runner.tensors.items():
         if name != "input":
