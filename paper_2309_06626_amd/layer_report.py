@@ -223,13 +223,19 @@ def depthwise_times(steps):
         _, ts = time_launches(B.prepared_run(layer.plan, x, layer.bias, y), steps, warm)
         _, tc = time_launches(B.prepared_run_rows(layer.plan, x, layer.bias, yc, B.SC_ROWS_DENSE, B.SC_ROWS_COMPACT), steps, warm)
         _, td = time_launches(B.prepared_run(layer.plan, x, layer.bias, y, dense=True), steps, warm)
+        # compact input under a producer's mask of the same sparsity (input resolution), compact output
+        pixels = spec.n * spec.h * spec.w
+        in_mask = W.gen_mask(pixels, W.n_keep(spec.sparsity, pixels), W.base_seed(6) + 900 + spec.layer_index)
+        kept_in = B.sparse_conv_plan_set_input_mask(layer.plan, torch.from_numpy(in_mask).to("cuda:0"))
+        xc = torch.randn((kept_in, spec.c_in), device="cuda:0").clamp_(min=0).to(B.TORCH_DTYPE[spec.dtype])
+        _, tcc = time_launches(B.prepared_run_rows(layer.plan, xc, layer.bias, yc, B.SC_ROWS_COMPACT, B.SC_ROWS_COMPACT), steps, warm)
         by, byc, byd = (algorithmic_bytes(spec, kept), algorithmic_bytes(spec, kept, scatter_only=True),
                         algorithmic_bytes(spec, spec.m))
         rows.append({"layer": spec.name, "m": spec.m, "c": spec.c_out, "kept": kept,
-                     "sparse_us": ts * 1e6, "compact_out_us": tc * 1e6, "dense_us": td * 1e6,
+                     "sparse_us": ts * 1e6, "compact_out_us": tc * 1e6, "dense_us": td * 1e6, "compact_in_out_us": tcc * 1e6,
                      "sparse_hbm_frac": by / ts / 1e9 / HBM_PEAK_GBS, "compact_hbm_frac": byc / tc / 1e9 / HBM_PEAK_GBS,
                      "dense_hbm_frac": byd / td / 1e9 / HBM_PEAK_GBS})
-        del layer, x, y, yc
+        del layer, x, y, yc, xc
         torch.cuda.empty_cache()
     return rows
 
@@ -406,12 +412,13 @@ def main():
         dw_rows = depthwise_times(args.steps)
         print()
         print("| depthwise 3x3 layer (batch 64, s = 0.5) | M x C | sparse us (zero fill) | % HBM | compact out us | % HBM | dense us | % HBM | "
-              "speed-up zero fill | speed-up compact out |")
-        print("|---|---|---|---|---|---|---|---|---|---|")
+              "speed-up zero fill | speed-up compact out | compact in (producer's mask, s = 0.5) and out us |")
+        print("|---|---|---|---|---|---|---|---|---|---|---|")
         for r in dw_rows:
             print(f"| {r['layer']} | {r['m']}x{r['c']} | {r['sparse_us']:.2f} | {100 * r['sparse_hbm_frac']:.1f} | "
                   f"{r['compact_out_us']:.2f} | {100 * r['compact_hbm_frac']:.1f} | {r['dense_us']:.2f} | "
-                  f"{100 * r['dense_hbm_frac']:.1f} | {r['dense_us'] / r['sparse_us']:.2f} | {r['dense_us'] / r['compact_out_us']:.2f} |")
+                  f"{100 * r['dense_hbm_frac']:.1f} | {r['dense_us'] / r['sparse_us']:.2f} | {r['dense_us'] / r['compact_out_us']:.2f} | "
+                  f"{r['compact_in_out_us']:.2f} |")
     bw_rows = []
     if args.backward:
         bw_rows = backward_times(max(args.steps // 2, 20))
