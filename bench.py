@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the fused kernel on the benchmark workload, from the rocprofv3 --pmc
-# runs summarised in profiles/band_kernel_bf16_resnet18_stage1_s50.md:
-# FETCH_SIZE 6931.51 KiB x 1.999 (64 MiB copy calibration) + WRITE_SIZE 12544 KiB x 1.000.
-MEASURED_TRAFFIC_BYTES = int(6931.51 * 1024 * 1.999 + 12544 * 1024)
+# runs summarised in profiles/band_alternating_kernel_bf16_resnet18_stage1_s50.md:
+# FETCH_SIZE 6890.01 KiB x 1.999 (64 MiB copy calibration) + WRITE_SIZE 12544 KiB x 1.000.
+MEASURED_TRAFFIC_BYTES = int(6890.01 * 1024 * 1.999 + 12544 * 1024)
 
 
 def cpu_baseline(spec, ci, budget_s: float = 12.0):

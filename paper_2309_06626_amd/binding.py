@@ -175,6 +175,7 @@ class Plan:
         self.handle = handle
         self.desc = desc
         self.workspace = workspace  # keeps the device memory alive
+        self.x_kept = None          # rows of a compact input after sparse_conv_plan_set_input_mask
 
     def close(self):
         if self.handle:

@@ -332,7 +332,7 @@ static hipError_t wgrad_launch(WgradParams p, hipStream_t stream) {
   p.co_tiles = (p.c_out + BM - 1) / BM;
   p.k_tiles = (p.k + BN - 1) / BN;
   const unsigned grid = (unsigned)(p.co_tiles * p.k_tiles * p.splits);
-  static bool attr_set = false;                       // (one flag per tile shape and type)
+  static std::atomic<bool> attr_set{false};                       // (one flag per tile shape and type)
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_kernel<DT, BM, BN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

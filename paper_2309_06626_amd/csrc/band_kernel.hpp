@@ -34,6 +34,7 @@ struct BandParams {
   int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
   int32_t k_stride;          // elements between packed filter rows (odd multiple of the K tile)
   int32_t bh, bands_per_image, n_bands, n_tiles;
+  int32_t split;             // alternating-group kernel: every run of bh rows is two bands of half its pixels
   int32_t b_bytes;           // LDS bytes of the filter slab
   int32_t x_groups;          // 16-byte groups reserved for the input slab (a zeroed KiB follows)
   int32_t relu, zero_fill, mask_spatial;
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
 template <int DT, int NI, int MI, int KH, int KW, int CPP>
 hipError_t band_launch(const BandParams& p, size_t lds, hipStream_t stream) {
   auto kern = band_kernel<DT, NI, MI, KH, KW, CPP>;
-  static size_t attr_bytes = 0;
+  static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -55,6 +55,7 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
   const int n0 = (logical % p.n_tiles) * BN;
   const int lane_id = logical / p.n_tiles;
   const int steps = lane_id < p.n_bands ? (p.n_bands - lane_id + lanes - 1) / lanes : 0;
+  auto band_at = [&](int k) { return lane_id + k * lanes; };      // bands are dealt round robin
 
   const int t = threadIdx.x;
   const int grp = __builtin_amdgcn_readfirstlane(t >> 8);
@@ -97,10 +98,11 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
   auto geo = [&](int band) {
     Geo g;
     g.img = band / p.bands_per_image;
-    const int oy0 = (band - g.img * p.bands_per_image) * p.bh;
-    const int oy1 = min(oy0 + p.bh, p.ho);
-    g.r_lo = g.img * ho_wo + oy0 * p.wo;
-    g.r_hi = g.img * ho_wo + oy1 * p.wo;
+    int first, end;       // the band's pixels; with split bands the range may begin and end inside a row
+    band_pixel_range(band - g.img * p.bands_per_image, p.bh, p.split, p.ho, p.wo, &first, &end);
+    const int oy0 = first / p.wo, oy1 = (end - 1) / p.wo + 1;
+    g.r_lo = g.img * ho_wo + first;
+    g.r_hi = g.img * ho_wo + end;
     g.iy_base = oy0 * p.sh - p.ph;
     g.iy_lo = max(g.iy_base, 0);
     g.iy_hi = min((oy1 - 1) * p.sh - p.ph + (KH - 1) * p.dil_h + 1, p.h);
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
     v4i* slab_k = reinterpret_cast<v4i*>(s_x_bytes + (size_t)(k & 1) * x_bytes);
     if (grp == (k & 1)) {
       SC_PP_STAMP(k, 0);
-      if (k < steps) transfer(lane_id + k * lanes, slab_k);
+      if (k < steps) transfer(band_at(k), slab_k);
       SC_PP_STAMP(k, 1);
       // everything this group has in flight: the slab (and, at k = 0, the filters), and the stores
       // of the band it computed in the previous step
@@ -292,7 +294,7 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
       if (k == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this group's share of the filter slab
       SC_PP_STAMP(k, 4);
       if (k >= 1)
-        compute(lane_id + (k - 1) * lanes, reinterpret_cast<const v4i*>(s_x_bytes + (size_t)((k - 1) & 1) * x_bytes), k);
+        compute(band_at(k - 1), reinterpret_cast<const v4i*>(s_x_bytes + (size_t)((k - 1) & 1) * x_bytes), k);
       SC_PP_STAMP(k, 5);
     }
     // LDS is the only memory the two groups share: wait for this wavefront's LDS operations, then
@@ -308,7 +310,7 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
 template <int DT, int NI, int MI, int KH, int KW, int CPP>
 hipError_t bandpp_launch(const BandParams& p, size_t lds, int grid, hipStream_t stream) {
   auto kern = bandpp_kernel<DT, NI, MI, KH, KW, CPP>;
-  static size_t attr_bytes = 0;
+  static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

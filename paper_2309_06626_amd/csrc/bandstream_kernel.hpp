@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void bandstream_kernel(const BandParams p
 template <int DT, int NI, int MI>
 hipError_t bandstream_launch(const BandParams& p, size_t lds, hipStream_t stream) {
   auto kern = bandstream_kernel<DT, NI, MI>;
-  static size_t attr_bytes = 0;
+  static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

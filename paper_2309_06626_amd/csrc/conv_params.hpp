@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace sc {
 
 // One entry of the gather table: where a group of consecutive K entries of the lowered
@@ -76,6 +78,31 @@ struct DepthwiseParams {
   // (such a pixel reads as +0.0); null: a compact input holds the layer's own kept pixels (1x1 windows)
   const int32_t* x_rank;   // [N * H * W]
 };
+
+// Bands of output pixels of one image.  Without `split` band i holds the output rows [i*bh, (i+1)*bh) (the
+// last band of an image may be shorter).  With `split` every such run of bh rows is cut into two bands of
+// half its pixels each (the cut may fall inside a row): a way to give persistent workgroups two equal steps
+// where one band per workgroup is all there is (56 rows: 8 x 7 rows -> 16 bands of 196 pixels).
+__host__ __device__ inline void band_pixel_range(int band_in_image, int bh, int split, int ho, int wo, int* first,
+                                                 int* end) {
+  const int run = split ? band_in_image >> 1 : band_in_image;
+  const int p0 = run * bh * wo;
+  const int px = (ho - run * bh < bh ? ho - run * bh : bh) * wo;
+  if (!split) { *first = p0; *end = p0 + px; return; }
+  const int half = (px + 1) >> 1;
+  *first = (band_in_image & 1) ? p0 + half : p0;
+  *end = (band_in_image & 1) ? p0 + px : p0 + half;
+}
+__host__ __device__ inline int band_of_pixel(int pixel_in_image, int bh, int split, int ho, int wo) {
+  const int run = (pixel_in_image / wo) / bh;
+  if (!split) return run;
+  const int p0 = run * bh * wo;
+  const int px = (ho - run * bh < bh ? ho - run * bh : bh) * wo;
+  return 2 * run + (pixel_in_image - p0 >= ((px + 1) >> 1) ? 1 : 0);
+}
+__host__ __device__ inline int bands_in_image(int ho, int bh, int split) {
+  return (ho + bh - 1) / bh * (split ? 2 : 1);
+}
 
 // Division of 0 <= n < 2^31 by d >= 1 as (n * mul) >> shift in 64-bit arithmetic: with l = ceil(log2 d)
 // and shift = 31 + l, mul = floor(2^shift / d) + 1 fits 32 bits and the quotient is exact.

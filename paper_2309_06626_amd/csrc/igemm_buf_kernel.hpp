@@ -281,7 +281,7 @@ template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
 hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
   constexpr size_t lds = igemm_dma_lds_bytes<BM, BN, STAGES>();
   auto kern = igemm_buf_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES>;
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -269,7 +269,7 @@ template <int DT, int BM, int BN, int WAVES_M, int WAVES_N>
 hipError_t igemm_panel_launch(const ConvParams& p, hipStream_t stream) {
   const size_t lds = igemm_panel_lds_bytes<BM, BN>(p.k_tiles, p.c_out);
   auto kern = igemm_panel_kernel<DT, BM, BN, WAVES_M, WAVES_N>;
-  static size_t attr_bytes = 0;
+  static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

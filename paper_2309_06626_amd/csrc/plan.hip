@@ -187,8 +187,8 @@ __global__ void fill_zero_kernel(uint4* __restrict__ dst, int64_t n16, unsigned 
 
 // First compacted row of every band: lower bound of the band's first dense row in the kept-row list.
 __global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
-                                  int32_t* __restrict__ band_i0, int n_bands, int bands_per_image, int bh, int ho,
-                                  int wo) {
+                                  int32_t* __restrict__ band_i0, int n_bands, int bands_per_image, int bh, int split,
+                                  int ho, int wo) {
   int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b > n_bands) return;
   const int kept = *kept_dev;
@@ -196,8 +196,9 @@ __global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int
   if (b == n_bands) {
     target = 0x7fffffff;
   } else {
-    int img = b / bands_per_image, oy0 = (b - img * bands_per_image) * bh;
-    target = (img * ho + oy0) * wo;
+    int img = b / bands_per_image, first, end;
+    band_pixel_range(b - img * bands_per_image, bh, split, ho, wo, &first, &end);
+    target = img * ho * wo + first;
   }
   int lo = 0, hi = kept;
   while (lo < hi) {
@@ -217,15 +218,17 @@ __global__ void band_max_kernel(const int32_t* __restrict__ band_i0, int n_bands
 // r_lo(b) (the band's first dense row) on, so the band kernel finds them without knowing counts.
 __global__ void band_rows_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
                                  const int32_t* __restrict__ band_i0, int32_t* __restrict__ band_rows,
-                                 int bands_per_image, int bh, int ho, int wo) {
+                                 int bands_per_image, int bh, int split, int ho, int wo) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= *kept_dev) return;
   const int r = row_idx[i];
   const int ho_wo = ho * wo;
-  const int img = r / ho_wo, oy = (r - img * ho_wo) / wo;
-  const int bi = oy / bh;
+  const int img = r / ho_wo;
+  const int bi = band_of_pixel(r - img * ho_wo, bh, split, ho, wo);
   const int band = img * bands_per_image + bi;
-  band_rows[(img * ho + bi * bh) * wo + (i - band_i0[band])] = r;
+  int first, end;
+  band_pixel_range(bi, bh, split, ho, wo, &first, &end);
+  band_rows[img * ho_wo + first + (i - band_i0[band])] = r;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -453,6 +456,7 @@ struct BandPlan {
   int pp_grid;       // workgroups of that kernel
   int max_kept;      // most kept rows in one band (streaming kernel only)
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
+  int split;         // alternating-group kernel only: every run of bh rows is two bands of half its pixels
   size_t b_bytes, x_bytes, lds;
 };
 
@@ -460,7 +464,17 @@ constexpr size_t kLdsLimit = 160 * 1024;
 // behind the band kernel's slabs: a zeroed KiB and 128 bias floats
 constexpr size_t kBandExtraLds = 1024 + 128 * 4;
 
-static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
+// 32-row MFMA units the busiest of four wavefronts runs for a band with `cnt` rows, with 32-row (MI = 1) or
+// 64-row (MI = 2) blocks dealt round robin; `mi_idx` receives the better shape (at a tie the 64-row block, whose
+// two row blocks share every filter fragment read from LDS).
+static double band_units(double cnt, int* mi_idx) {
+  const double units1 = std::ceil(std::ceil(cnt / 32.0) / 4.0), units2 = 2.0 * std::ceil(std::ceil(cnt / 64.0) / 4.0);
+  if (mi_idx) *mi_idx = units1 < units2 ? 0 : 1;
+  return std::min(units1, units2);
+}
+
+// `rows`: the rows the run is expected to contract (the kept rows of a sparse run, M of a dense one).
+static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows) {
   BandPlan bp;
   std::memset(&bp, 0, sizeof(bp));
   const int eb = elem_bytes(d.dtype);
@@ -486,37 +500,57 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g) {
     pp.ni_idx = pp.ni - 1;
     pp.n_tiles = (d.c_out + 32 * pp.ni - 1) / (32 * pp.ni);
     pp.b_bytes = (size_t)32 * pp.ni * g.k_stride * eb;
+    // SPARSE_CONV_BAND_HEIGHT=<bh> or <bh>,split overrides the search (tuning and tests)
     const char* env = std::getenv("SPARSE_CONV_BAND_HEIGHT");
     const int forced_bh = env ? std::atoi(env) : 0;
+    const int forced_split = (env && std::strstr(env, ",split")) ? 1 : 0;
     const int lanes_max = std::max(1, 256 / pp.n_tiles);
     int best_steps = 0;
     double best = 1e300;
+    // whole runs of bh rows, and runs cut into two bands of half their pixels
     for (int bh = 1; bh <= g.ho; ++bh) {
-      int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
-      size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
-      if (pp.b_bytes + 2 * xbytes + kPPFixedLds > kLdsLimit) break;
-      if ((int64_t)bh * g.wo > kPPMaxRows) break;
-      int bpi = (g.ho + bh - 1) / bh;
-      int64_t nb = (int64_t)d.n * bpi;
-      int lanes = (int)std::min<int64_t>(nb, lanes_max);
-      int steps = (int)((nb + lanes - 1) / lanes);
-      // a step costs its band plus a fixed part (halo rows, barrier, transfer latency)
-      double cost = steps * (bh + 1.5);
-      if (forced_bh > 0 ? bh == forced_bh : cost <= best) {
-        best = cost;
-        best_steps = steps;
-        pp.ok = true;
-        pp.pp = true;
-        pp.bh = bh;
-        pp.bands_per_image = bpi;
-        pp.n_bands = (int)nb;
-        pp.x_bytes = xbytes;
-        pp.lds = pp.b_bytes + 2 * xbytes + kPPFixedLds;
-        pp.pp_grid = lanes * pp.n_tiles;
+      for (int split = 0; split <= 1; ++split) {
+        // rows of output a band touches: a half band of an odd run reaches into the middle row from either side
+        const int rows_out = split ? bh / 2 + 1 : bh;
+        if (split && bh < 2) continue;
+        int64_t ih = (int64_t)(rows_out - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
+        size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
+        if (pp.b_bytes + 2 * xbytes + kPPFixedLds > kLdsLimit) continue;
+        const int64_t band_px = split ? ((int64_t)bh * g.wo + 1) / 2 : (int64_t)bh * g.wo;
+        if (band_px > kPPMaxRows) continue;
+        int bpi = bands_in_image(g.ho, bh, split);
+        int64_t nb = (int64_t)d.n * bpi;
+        int lanes = (int)std::min<int64_t>(nb, lanes_max);
+        int steps = (int)((nb + lanes - 1) / lanes);
+        // a step costs its band plus a fixed part (halo rows, barrier, transfer latency)
+        double cost = steps * ((split ? 0.5 * bh : (double)bh) + 1.5);
+        const bool take = forced_bh > 0 ? (bh == forced_bh && split == forced_split) : cost <= best;
+        if (take) {
+          best = cost;
+          best_steps = steps;
+          pp.ok = true;
+          pp.pp = true;
+          pp.bh = bh;
+          pp.split = split;
+          pp.bands_per_image = bpi;
+          pp.n_bands = (int)nb;
+          pp.x_bytes = xbytes;
+          pp.lds = pp.b_bytes + 2 * xbytes + kPPFixedLds;
+          pp.pp_grid = lanes * pp.n_tiles;
+        }
       }
     }
     // two channel tiles would transfer every band twice: measured slower than the tiled kernel
     if (pp.ok && (want_pp || (best_steps >= 3 && pp.n_tiles == 1))) return pp;
+    // Exactly two equal steps per workgroup (split bands, as many runs of rows as workgroups): the second band's
+    // transfer hides behind the first one's MFMAs and stores, which is worth 4-8 % on the stage-1 ResNet layer at
+    // batch 32 -- unless halving the bands costs MFMA blocks (64-row blocks that a whole run fills well fall apart
+    // into more 32-row blocks: s = 0.25 there, 3 units per run against 2 + 2 per pair of halves).
+    if (pp.ok && pp.split && best_steps == 2 && pp.n_tiles == 1 && pp.n_bands == 2 * pp.pp_grid && !want_single) {
+      const double whole = band_units((double)rows / (pp.n_bands / 2), nullptr);
+      const double halves = 2.0 * band_units((double)rows / pp.n_bands, nullptr);
+      if (halves <= std::max(whole, 2.0)) return pp;
+    }
   }
   if (bp.b_bytes > 96 * 1024) {
     // Filters too large to stay resident: stream them (16-bit types, whole 128-byte K tiles per tap,
@@ -580,7 +614,8 @@ using namespace sc;
 struct sc_plan {
   sc_conv_desc desc;
   Geometry geo;
-  BandPlan band;
+  BandPlan band;                   // of the sparse run (the band tables in the workspace follow it)
+  BandPlan band_dense;             // of the dense run, which needs no tables: it may cut the bands differently
   const BandTable* band_table;
   const BandStreamTable* stream_table;
   const BandPPTable* pp_table;
@@ -727,10 +762,11 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     return SC_OK;
   }
   // the band kernels address input and output by dense position: runs with a compact operand take a tiled kernel
-  const bool use_band = pl->band.ok && !x_compact && !y_compact &&
-                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !pl->band.stream));
+  const BandPlan& band = dense ? pl->band_dense : pl->band;
+  const bool use_band = band.ok && !x_compact && !y_compact &&
+                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream));
   if (use_band) {
-    const BandPlan& b = pl->band;
+    const BandPlan& b = band;
     BandParams q;
     std::memset(&q, 0, sizeof(q));
     q.x = x;
@@ -745,7 +781,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.kh = d.kh; q.kw = d.kw; q.sh = d.stride_h; q.sw = d.stride_w; q.ph = d.pad_h; q.pw = d.pad_w;
     q.dil_h = d.dil_h; q.dil_w = d.dil_w;
     q.k_stride = g.k_stride;
-    q.bh = b.bh; q.bands_per_image = b.bands_per_image; q.n_bands = b.n_bands; q.n_tiles = b.n_tiles;
+    q.bh = b.bh; q.split = b.split; q.bands_per_image = b.bands_per_image; q.n_bands = b.n_bands; q.n_tiles = b.n_tiles;
     q.b_bytes = (int32_t)b.b_bytes;
     q.x_groups = (int32_t)(b.x_bytes / 16);
     q.relu = d.relu;
@@ -762,12 +798,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
       SC_HIP(pl->stream_table->fn[b.ni == 4 ? 1 : 0][mi - 1](q, b.lds, stream));
       return SC_OK;
     }
-    // 32-row (MI = 1) or 64-row (MI = 2) MFMA blocks, dealt to the four wavefronts round robin: take
-    // the shape that leaves the busiest wavefront fewer 32-row units; at a tie the 64-row block, whose
-    // two row blocks share every filter fragment read from LDS
-    const double cnt = (double)rows / b.n_bands;
-    const double units1 = std::ceil(std::ceil(cnt / 32.0) / 4.0), units2 = 2.0 * std::ceil(std::ceil(cnt / 64.0) / 4.0);
-    const int mi_idx = units1 < units2 ? 0 : 1;
+    // 32-row (MI = 1) or 64-row (MI = 2) MFMA blocks, dealt to the four wavefronts round robin: the
+    // shape that leaves the busiest wavefront fewer 32-row units
+    int mi_idx = 0;
+    band_units((double)rows / b.n_bands, &mi_idx);
     if (b.pp) {
       SC_HIP(pl->pp_table->fn[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
       return SC_OK;
@@ -942,7 +976,7 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
 
   if (bp.ok) {
     hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
-                       reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, g.ho, g.wo);
+                       reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);
     SC_HIP(hipGetLastError());
     if (bp.stream) {
       // kept_dev + 1 holds the per-band maximum
@@ -953,7 +987,7 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
     }
     hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<const int32_t*>(ws + g.off_band),
-                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, g.ho, g.wo);
+                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);
     SC_HIP(hipGetLastError());
   }
 
@@ -1016,7 +1050,9 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     SC_HIP(hipMemsetAsync(ws + g.off_xpad, 0, ((size_t)d.n * g.hp * g.wp_cols * d.c_in + 64) * eb, stream));
   if (g.splitk_ok)   // arrival counters start at zero; every launch leaves them at zero again
     SC_HIP(hipMemsetAsync(ws + g.off_counters, 0, g.off_partial - g.off_counters, stream));
-  BandPlan bp = plan_band(d, g);
+  // (the kept-row count is not known yet: the descriptor's sparsity says what to expect, half the rows if it is silent)
+  const int64_t rows_hint = d.sparsity >= 0.0f ? (int64_t)((1.0 - (double)d.sparsity) * (double)g.m + 0.5) : g.m / 2;
+  BandPlan bp = plan_band(d, g, rows_hint);
   int32_t kept_host = 0;
   s = pack_filters(d, g, ws, w_dev, stream);
   if (s != SC_OK) return s;
@@ -1044,6 +1080,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
     if (pl->table[i].splitk && pl->table[i].bm == 64 && pl->table[i].bn == 128) pl->tile_splitk = i;
   if (pl->tile_splitk < 0) pl->geo.splitk_ok = false;
   pl->band = bp;
+  pl->band_dense = plan_band(d, g, g.m);
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
   pl->pp_table = d.dtype == SC_BF16 ? bandpp_bf16() : d.dtype == SC_F16 ? bandpp_f16() : nullptr;
@@ -1158,10 +1195,11 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     if (workgroups) *workgroups = ((walk_dense ? plan->geo.m : plan->kept) * (plan->desc.c_in / v) + 255) / 256;
     return SC_OK;
   }
-  if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream))) {
-    if (tile_m) *tile_m = -plan->band.bh;
-    if (tile_n) *tile_n = 32 * plan->band.ni;
-    if (workgroups) *workgroups = plan->band.pp ? plan->band.pp_grid : (int64_t)plan->band.n_bands * plan->band.n_tiles;
+  const BandPlan& band = which ? plan->band_dense : plan->band;
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream))) {
+    if (tile_m) *tile_m = -band.bh;     // (rows per run; split bands hold half a run each)
+    if (tile_n) *tile_n = 32 * band.ni;
+    if (workgroups) *workgroups = band.pp ? band.pp_grid : (int64_t)band.n_bands * band.n_tiles;
     return SC_OK;
   }
   int64_t rows = which ? plan->geo.m : plan->kept;
@@ -1183,8 +1221,9 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1)) return nullptr;
   if (plan->geo.depthwise) return "depthwise";
-  if (plan->band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->band.stream)))
-    return plan->band.stream ? "band_stream" : plan->band.pp ? "band_alternating" : "band";
+  const BandPlan& band = which ? plan->band_dense : plan->band;
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream)))
+    return band.stream ? "band_stream" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
   if (pick_tile(plan, which, which ? g.m : plan->kept).splits > 1) return "tile_split_k";
@@ -1199,7 +1238,7 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
   if (tile_m == 0 && tile_n == 0) { plan->forced[which] = -1; return SC_OK; }
   if (plan->geo.depthwise) return SC_ERR_UNSUPPORTED;   // one kernel, no tiles to choose
   if (tile_m < 0) {
-    if (!plan->band.ok) return SC_ERR_UNSUPPORTED;
+    if (!(which ? plan->band_dense : plan->band).ok) return SC_ERR_UNSUPPORTED;
     plan->forced[which] = kForceBand;
     return SC_OK;
   }

@@ -144,6 +144,32 @@ def test_alternating_band_kernel_many_steps(bh, h, w, sp, monkeypatch):
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
 
 
+@pytest.mark.parametrize("bh,n,h,w,sp,s", [(7, 3, 23, 20, 0.5, 1), (5, 2, 17, 9, 0.4, 1), (4, 2, 10, 7, 0.6, 1), (3, 1, 3, 5, 0.5, 1),
+                                           (7, 40, 56, 16, 0.5, 1), (6, 2, 31, 11, 0.3, 2), (7, 2, 20, 20, 0.0, 1)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_alternating_band_kernel_with_split_bands(bh, n, h, w, sp, s, dtype, monkeypatch):
+    """Runs of bh output rows cut into two bands of half their pixels: the cut falls inside a row when bh * Wo is
+    odd or bh is; the last run of an image may be shorter; 40 images x 8 runs: more bands than workgroups."""
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", f"{bh},split")
+    spec = spec_of(n, 64, h, w, 64, dtype=dtype, sp=sp, s=s, mask_mode="spatial" if n == 3 else "row")
+    layer = check_layer(W.make_conv_inputs(spec, 960 + bh + h), tiles=(-1, 0), sample_rows=None if n * h * w < 4000 else 400)
+    tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+    runs = n * ((spec.ho + bh - 1) // bh)
+    assert (tm, tn) == (-bh, 64) and wgs == min(2 * runs, 256)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
+
+
+def test_split_bands_are_the_automatic_choice_when_every_workgroup_gets_one_run():
+    """The benchmark layer: 256 runs of 7 rows for 256 workgroups; sparse and dense runs decide separately."""
+    for sp, want in [(0.5, "band_alternating"), (0.7, "band_alternating"), (0.25, "band")]:
+        spec = spec_of(32, 64, 56, 56, 64, dtype="bf16", sp=sp)
+        layer = R.ConvLayer(spec, *_wbm(spec, 3))
+        assert B.sparse_conv_plan_kernel(layer.plan, 0) == want, sp
+        assert B.sparse_conv_plan_kernel(layer.plan, 1) == "band_alternating"
+        assert B.sparse_conv_plan_tiles(layer.plan, 1) == (-7, 64, 256)
+
+
 def test_alternating_band_kernel_is_the_automatic_choice_for_long_band_lists():
     big = spec_of(64, 64, 56, 56, 64, dtype="bf16", sp=0.5)
     layer = R.ConvLayer(big, *_wbm(big, 3))
