@@ -454,7 +454,7 @@ struct BandPlan {
   bool stream;       // filters streamed through an LDS ring instead of resident
   bool pp;           // persistent workgroups, two wavefront groups alternating between transfer and MFMA
   int pp_grid;       // workgroups of that kernel
-  int max_kept;      // most kept rows in one band (streaming kernel only)
+  int max_kept;      // most kept rows in one band
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
   int split;         // alternating-group kernel only: every run of bh rows is two bands of half its pixels
   size_t b_bytes, x_bytes, lds;
@@ -546,9 +546,14 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows
     // transfer hides behind the first one's MFMAs and stores, which is worth 4-8 % on the stage-1 ResNet layer at
     // batch 32 -- unless halving the bands costs MFMA blocks (64-row blocks that a whole run fills well fall apart
     // into more 32-row blocks: s = 0.25 there, 3 units per run against 2 + 2 per pair of halves).
+    // The slowest workgroup sets the kernel's time, so the counts are those of a band three standard deviations
+    // above the mean of a random mask (at s = 0.4 a half band keeps 118 rows on average, but more than the 128 of
+    // four blocks in some workgroup of nearly every launch).
     if (pp.ok && pp.split && best_steps == 2 && pp.n_tiles == 1 && pp.n_bands == 2 * pp.pp_grid && !want_single) {
-      const double whole = band_units((double)rows / (pp.n_bands / 2), nullptr);
-      const double halves = 2.0 * band_units((double)rows / pp.n_bands, nullptr);
+      const double drop = 1.0 - (double)rows / (double)g.m;
+      auto busiest = [&](double mean) { return mean + 3.0 * std::sqrt(std::max(mean * drop, 0.0)); };
+      const double whole = band_units(busiest((double)rows / (pp.n_bands / 2)), nullptr);
+      const double halves = 2.0 * band_units(busiest((double)rows / pp.n_bands), nullptr);
       if (halves <= std::max(whole, 2.0)) return pp;
     }
   }
@@ -801,7 +806,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     // 32-row (MI = 1) or 64-row (MI = 2) MFMA blocks, dealt to the four wavefronts round robin: the
     // shape that leaves the busiest wavefront fewer 32-row units
     int mi_idx = 0;
-    band_units((double)rows / b.n_bands, &mi_idx);
+    const int band_px = (std::min(b.bh, g.ho) * g.wo + (b.split ? 1 : 0)) / (b.split ? 2 : 1);
+    band_units(dense || identity ? (double)band_px : (double)b.max_kept, &mi_idx);
     if (b.pp) {
       SC_HIP(pl->pp_table->fn[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
       return SC_OK;
@@ -978,13 +984,12 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
     hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);
     SC_HIP(hipGetLastError());
-    if (bp.stream) {
-      // kept_dev + 1 holds the per-band maximum
-      SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
-      hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
-                         reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
-      SC_HIP(hipGetLastError());
-    }
+    // kept_dev + 1 holds the per-band maximum (it sizes the accumulator blocks of the streaming kernel and picks
+    // the MFMA block shape of the others: the fullest band is the one the launch waits for)
+    SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
+    hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
+                       reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
+    SC_HIP(hipGetLastError());
     hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<const int32_t*>(ws + g.off_band),
                        reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);

@@ -162,7 +162,7 @@ def test_alternating_band_kernel_with_split_bands(bh, n, h, w, sp, s, dtype, mon
 
 def test_split_bands_are_the_automatic_choice_when_every_workgroup_gets_one_run():
     """The benchmark layer: 256 runs of 7 rows for 256 workgroups; sparse and dense runs decide separately."""
-    for sp, want in [(0.5, "band_alternating"), (0.7, "band_alternating"), (0.25, "band")]:
+    for sp, want in [(0.5, "band_alternating"), (0.7, "band_alternating"), (0.4, "band"), (0.25, "band")]:
         spec = spec_of(32, 64, 56, 56, 64, dtype="bf16", sp=sp)
         layer = R.ConvLayer(spec, *_wbm(spec, 3))
         assert B.sparse_conv_plan_kernel(layer.plan, 0) == want, sp
