@@ -287,7 +287,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
   const int plane = q.pairs_h * q.in_w * q.cg;            // 16-byte words per plane
   u4* s_lo = reinterpret_cast<u4*>(smem);
   u4* s_hi = s_lo + plane;
-  unsigned char* s_keep = smem + (size_t)plane * 32;
+  unsigned char* s_keep = smem + (size_t)plane * 32;        // [256] mask byte of every tile pixel
+  int* s_rank = reinterpret_cast<int*>(s_keep + 256);       // [256] its row in a compact output
 
   const int t = threadIdx.x;
   const int groups = p.c / V;
@@ -332,6 +333,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
   // ---- staging: request a tile's patch and mask bytes; later interleave the rows two by two into LDS ------
   u4 ra[kDwStageMost], rb[kDwStageMost];
   unsigned keep_r = 0;
+  int rank_r = 0;
   struct Tile { int n, oy0, ox0; };
   auto tile_of = [&](int id) -> Tile {
     const int t1 = fast_div(id, q.div_tilesx_mul, q.div_tilesx_shift), tile_x = id - t1 * q.tiles_x;
@@ -381,12 +383,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
     }
     // mask byte of the tile pixel this lane looks after (a tile has at most 256 pixels): 1 = kept,
     // 2 = dropped, 0 = outside the map
+    // The row of the pixel in a compact output travels the same way: looked up at the store it would be a
+    // dependent global load in the compute loop, whose wait also waits for the next tile's patch.
     keep_r = 0;
+    rank_r = 0;
     if (t < tile_pixels) {
       const int ty = fast_div(t, q.div_tx_mul, q.div_tx_shift), tx = t - ty * q.tx;
       const int oy = tl.oy0 + ty, ox = tl.ox0 + tx;
-      if (oy < p.ho && ox < p.wo)
+      if (oy < p.ho && ox < p.wo) {
         keep_r = p.mask ? (p.mask[(p.mask_spatial ? 0 : tl.n * p.ho_wo) + oy * p.wo + ox] ? 1u : 2u) : 1u;
+        if (p.rank) rank_r = p.rank[tl.n * p.ho_wo + oy * p.wo + ox];   // (meaningful for kept pixels only)
+      }
     }
   };
   auto deposit = [&]() {
@@ -403,7 +410,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
         s_hi[e] = hi;
       }
     }
-    if (t < tile_pixels) s_keep[t] = (unsigned char)keep_r;
+    if (t < tile_pixels) {
+      s_keep[t] = (unsigned char)keep_r;
+      if (p.rank) s_rank[t] = rank_r;
+    }
   };
 
   auto pack_out = [&](const float (&a)[V]) -> u4 {
@@ -412,8 +422,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
     for (int j = 0; j < V; ++j) o.v[j] = (T)__builtin_fmaxf(a[j], floor_v);
     return __builtin_bit_cast(u4, o);
   };
-  auto put = [&](unsigned k, int r, u4 v) {
-    if (k == 1) *reinterpret_cast<u4*>(y + (p.rank ? (int64_t)p.rank[r] : (int64_t)r) * p.c) = v;
+  // pixel `pix` of the tile = dense row r
+  auto put = [&](unsigned k, int pix, int r, u4 v) {
+    if (k == 1) *reinterpret_cast<u4*>(y + (p.rank ? (int64_t)s_rank[pix] : (int64_t)r) * p.c) = v;
     else if (k == 2 && p.zero_fill) *reinterpret_cast<u4*>(y + (int64_t)r * p.c) = u4{0, 0, 0, 0};   // Alg. 2, mask == 0 branch
   };
 
@@ -455,8 +466,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
           o0 = pack_out(a0);
           o1 = pack_out(a1);
         }
-        put(k0, r0, o0);
-        put(k1, r0 + p.wo, o1);
+        put(k0, (2 * j) * q.tx + tx, r0, o0);
+        put(k1, (2 * j + 1) * q.tx + tx, r0 + p.wo, o1);
       }
     } else {
       const int items = q.ty * q.tx;
@@ -484,7 +495,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void d
           }
           o0 = pack_out(a0);
         }
-        put(k0, r0, o0);
+        put(k0, it, r0, o0);
       }
     }
   };
@@ -611,7 +622,7 @@ static hipError_t launch_pair_tiles(const DepthwiseParams& p, hipStream_t stream
   magic_div((uint32_t)q.tx, &q.div_tx_mul, &q.div_tx_shift);
   magic_div((uint32_t)q.tiles_x, &q.div_tilesx_mul, &q.div_tilesx_shift);
   magic_div((uint32_t)q.tiles_y, &q.div_tilesy_mul, &q.div_tilesy_shift);
-  const size_t lds = (size_t)q.pairs_h * pair_bytes + 256;
+  const size_t lds = (size_t)q.pairs_h * pair_bytes + 256 + 256 * sizeof(int);   // patch, mask bytes, compact rows
   // persistent workgroups: about three per compute unit (LDS and registers allow that many), split over the chunks
   constexpr int per_cu = 3;
   const int wgs = std::max(1, std::min(q.tiles, (256 * per_cu + chunks - 1) / chunks));
