@@ -220,6 +220,27 @@ def masked_conv2d_compact(spec, x, w, bias, mask, x_compact: bool = False, y_com
     return to_compact(y, rm) if y_compact else y
 
 
+def masked_conv2d_residual(spec, x, w, bias, mask, residual, post_relu: bool, x_compact: bool = False,
+                           y_compact: bool = False):
+    """The masked convolution followed by a shortcut sum, as one operator:
+
+        y = post( masked_conv2d(x) + residual ),   post = ReLU or identity
+
+    i.e. what a block computes when the sum (ResNet: ReLU after it; inverted-residual blocks: linear) follows the
+    layer directly.  A dropped row of the convolution is +0.0 (Alg. 2), so there y = post(residual): the sum is not
+    masked.  ``residual`` has the format of the result (dense map, or [kept, Cout] when y_compact).  Defined through
+    the dense-layout operators in double precision; the layer's own activation (spec.relu) acts before the sum."""
+    assert spec.layout == "nhwc"
+    rm = row_mask(spec, mask)
+    conv = masked_conv2d_compact(spec, x, w, bias, mask, x_compact=x_compact, y_compact=y_compact)
+    res = _f32(residual)
+    assert res.shape == conv.shape or res.size == conv.size
+    y = conv.astype(np.float64) + res.reshape(conv.shape).astype(np.float64)
+    if post_relu:
+        y = np.maximum(y, 0.0)
+    return y.astype(np.float32)
+
+
 def masked_depthwise_conv2d(spec, x, w, bias, mask, want_absum: bool = False):
     """Masked depthwise convolution (groups == Cin == Cout, NHWC): channel c of the output is the
     kh x kw cross-correlation of channel c of the input with filter w[c, :, :, 0]; the mask removes output

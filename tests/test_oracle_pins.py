@@ -473,6 +473,45 @@ def test_small_resnet_chain_matches_library_pipeline():
     assert t[last].shape == (1, 1, 1, 512)
 
 
+@pytest.mark.parametrize("post_relu", [False, True])
+@pytest.mark.parametrize("y_compact", [False, True])
+def test_convolution_with_shortcut_sum_matches_the_library_pipeline(post_relu, y_compact):
+    """conv2d by the library, masked, plus the shortcut, ReLU last: the dropped rows of the result hold
+    post(shortcut), not zero; a compact result holds the kept rows of that map."""
+    spec = W.ConvSpec("r", n=2, c_in=5, h=7, w=6, c_out=4, kh=3, kw=3, pad_h=1, pad_w=1, dtype="f32", relu=False,
+                      sparsity=0.4)
+    x, w, b, mask = rand_inputs(spec, 71)
+    rng = np.random.default_rng(72)
+    rm = oracle.row_mask(spec, mask)
+    res_dense = rng.standard_normal(spec.y_shape()).astype(np.float32)
+    conv = torch_conv(spec, x, w, b).reshape(spec.m, spec.c_out) * rm[:, None]
+    want = conv + res_dense.reshape(spec.m, spec.c_out)
+    if post_relu:
+        want = np.maximum(want, 0.0)
+    if y_compact:
+        res = np.ascontiguousarray(res_dense.reshape(spec.m, spec.c_out)[rm == 1])
+        got = oracle.masked_conv2d_residual(spec, x, w, b, mask, res, post_relu, y_compact=True)
+        np.testing.assert_allclose(got, want[rm == 1], rtol=1e-5, atol=1e-6)
+    else:
+        got = oracle.masked_conv2d_residual(spec, x, w, b, mask, res_dense, post_relu)
+        np.testing.assert_allclose(got.reshape(spec.m, spec.c_out), want, rtol=1e-5, atol=1e-6)
+        dropped = got.reshape(spec.m, spec.c_out)[rm == 0]
+        ref = res_dense.reshape(spec.m, spec.c_out)[rm == 0]
+        assert np.array_equal(dropped, np.maximum(ref, 0.0) if post_relu else ref)     # exactly the shortcut there
+        assert np.abs(dropped).max() > 0
+
+
+def test_shortcut_sum_is_the_sum_of_the_two_network_ops():
+    """One fused operator = conv op followed by the add / add_relu op of the network interpreter (before rounding)."""
+    spec = W.ConvSpec("r", n=1, c_in=8, h=6, w=6, c_out=8, kh=1, kw=1, pad_h=0, pad_w=0, dtype="f32", relu=True, sparsity=0.5)
+    x, w, b, mask = rand_inputs(spec, 73)
+    res = np.random.default_rng(74).standard_normal(spec.y_shape()).astype(np.float32)
+    conv = oracle.masked_conv2d(spec, x, w, b, mask)
+    np.testing.assert_allclose(oracle.masked_conv2d_residual(spec, x, w, b, mask, res, True), oracle.add_relu(conv, res),
+                               rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(oracle.masked_conv2d_residual(spec, x, w, b, mask, res, False), conv + res, rtol=1e-6, atol=1e-6)
+
+
 def test_small_mobilenet_chain_with_masks_matches_library_pipeline():
     """Depthwise layers, linear shortcuts and 2-D masks in the network interpreter: the same graph through
     the library's grouped conv2d in float64, with the dropped pixels of every conv cleared afterwards."""
