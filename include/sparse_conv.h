@@ -150,6 +150,25 @@ sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x
                                void* y_dev, int32_t y_rows, void* hip_stream);
 
 /*
+ * The masked convolution fused with the shortcut sum that follows it in a residual block:
+ *
+ *     y = post( act(conv(x) + bias) + residual )        post = ReLU if residual_relu != 0, else identity
+ *
+ * `act` is the plan's own activation.  Alg. 2 makes a dropped row of the convolution +0.0, so a dropped row of a
+ * dense-layout y receives post(residual) (in SC_OUT_SCATTER_ONLY mode it is left alone, as always).  residual_dev
+ * has the dtype and the row format of y (dense map, or [kept][Cout] with y_rows = SC_ROWS_COMPACT), is 16-byte
+ * aligned and must not overlap y.  The sum is formed in float before the one rounding to the layer dtype.
+ * Runs in the tiled kernels (never the band, row-panel or depthwise kernels, whatever the plan would pick for
+ * the plain run): SC_ERR_UNSUPPORTED for depthwise plans; x_rows / y_rows as in sparse_conv_run_rows.
+ * dense_conv_run_residual: the same with the identity row map (every row kept).
+ */
+sc_status sparse_conv_run_residual(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
+                                   const void* residual_dev, int32_t residual_relu, void* y_dev, int32_t y_rows,
+                                   void* hip_stream);
+sc_status dense_conv_run_residual(const sc_plan* plan, const void* x_dev, const float* bias_dev,
+                                  const void* residual_dev, int32_t residual_relu, void* y_dev, void* hip_stream);
+
+/*
  * Row list of a compact input for a depthwise layer with windows larger than one pixel (its producer's
  * mask, which under Alg. 1's propagation differs from the layer's own when the layer is strided):
  * mask_in_dev is uint8[N*H*W] (SC_MASK_ROW plans) or uint8[H*W] (SC_MASK_SPATIAL plans) over the INPUT

@@ -230,9 +230,10 @@ def masked_conv2d_residual(spec, x, w, bias, mask, residual, post_relu: bool, x_
     layer directly.  A dropped row of the convolution is +0.0 (Alg. 2), so there y = post(residual): the sum is not
     masked.  ``residual`` has the format of the result (dense map, or [kept, Cout] when y_compact).  Defined through
     the dense-layout operators in double precision; the layer's own activation (spec.relu) acts before the sum."""
-    assert spec.layout == "nhwc"
-    rm = row_mask(spec, mask)
-    conv = masked_conv2d_compact(spec, x, w, bias, mask, x_compact=x_compact, y_compact=y_compact)
+    if x_compact or y_compact:
+        conv = masked_conv2d_compact(spec, x, w, bias, mask, x_compact=x_compact, y_compact=y_compact)
+    else:
+        conv = masked_conv2d(spec, x, w, bias, mask)      # (any layout)
     res = _f32(residual)
     assert res.shape == conv.shape or res.size == conv.size
     y = conv.astype(np.float64) + res.reshape(conv.shape).astype(np.float64)

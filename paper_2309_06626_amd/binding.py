@@ -96,6 +96,10 @@ def lib() -> ctypes.CDLL:
         L.sc_add_relu.argtypes = [vp, vp, vp, i32, i64, vp]
         L.sparse_conv_plan_set_input_mask.restype = ctypes.c_int
         L.sparse_conv_plan_set_input_mask.argtypes = [vp, vp, ctypes.POINTER(i64), vp]
+        L.sparse_conv_run_residual.restype = ctypes.c_int
+        L.sparse_conv_run_residual.argtypes = [vp, vp, i32, vp, vp, i32, vp, i32, vp]
+        L.dense_conv_run_residual.restype = ctypes.c_int
+        L.dense_conv_run_residual.argtypes = [vp, vp, vp, vp, i32, vp, vp]
         L.sc_add.restype = ctypes.c_int
         L.sc_add.argtypes = [vp, vp, vp, i32, i64, vp]
         L.sparse_conv_plan_mask.restype = vp
@@ -291,6 +295,47 @@ def prepared_run_rows(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor],
         if rc != SC_OK:
             raise ScError(rc, "sparse_conv_run_rows")
         return keep[3]
+
+    return call
+
+
+def _check_residual(residual: torch.Tensor, y: torch.Tensor):
+    if residual.dtype != y.dtype or residual.numel() != y.numel():
+        raise ValueError("the shortcut tensor must have the dtype and size of y")
+    if residual.data_ptr() == y.data_ptr():
+        raise ValueError("the shortcut tensor must not overlap y")
+
+
+def sparse_conv_run_residual(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], residual: torch.Tensor,
+                             y: torch.Tensor, residual_relu: bool = False, x_rows: int = SC_ROWS_DENSE,
+                             y_rows: int = SC_ROWS_DENSE, dense: bool = False, stream=None):
+    """y = post(act(conv + bias) + residual): sparse_conv_run_residual, or dense_conv_run_residual with dense=True."""
+    return prepared_run_residual(plan, x, bias, residual, y, residual_relu, x_rows, y_rows, dense, stream)()
+
+
+def prepared_run_residual(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], residual: torch.Tensor,
+                          y: torch.Tensor, residual_relu: bool = False, x_rows: int = SC_ROWS_DENSE,
+                          y_rows: int = SC_ROWS_DENSE, dense: bool = False, stream=None):
+    """Validated once; the returned callable issues the fused run (no launch happens here)."""
+    if dense and (x_rows != SC_ROWS_DENSE or y_rows != SC_ROWS_DENSE):
+        raise ValueError("a dense run has dense operands")
+    _check_operands(plan, x, bias, y, x_rows == SC_ROWS_COMPACT, y_rows == SC_ROWS_COMPACT)
+    _check_residual(residual, y)
+    L = lib()
+    h, px, pb, pr, py, st = plan.handle, _dev_ptr(x, "x"), _dev_ptr(bias, "bias"), _dev_ptr(residual, "residual"), \
+        _dev_ptr(y, "y"), _stream_handle(stream)
+    rr = 1 if residual_relu else 0
+    keep = (plan, x, bias, residual, y)
+
+    def call(stream_handle=None):
+        s = st if stream_handle is None else stream_handle
+        if dense:
+            rc = L.dense_conv_run_residual(h, px, pb, pr, rr, py, s)
+        else:
+            rc = L.sparse_conv_run_residual(h, px, x_rows, pb, pr, rr, py, y_rows, s)
+        if rc != SC_OK:
+            raise ScError(rc, "dense_conv_run_residual" if dense else "sparse_conv_run_residual")
+        return keep[4]
 
     return call
 

@@ -43,6 +43,10 @@ struct ConvParams {
   // compact row formats (NHWC): x holds only the kept rows of the input map, row i = pixel row_idx[i]
   // (pointwise stride-1 layers); y receives only the kept rows, row i = result of row_idx[i]
   int32_t x_compact, y_compact;
+  // fused shortcut sum: y = post(act(conv + bias) + residual), residual in the layout of y (may alias it);
+  // a dropped row of a dense-layout output receives post(residual) instead of zeros
+  const void* residual;    // null: none
+  int32_t residual_relu;
   int32_t m_tiles, n_tiles;
   // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;

@@ -239,11 +239,15 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
     const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
     if (zc < valid) {
       unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
+      const int64_t res_at = (int64_t)n0 * EB + zc * 16;     // the same group of the shortcut tensor
       const v4i z = {0, 0, 0, 0};
 #pragma unroll
       for (int u = 0; u < ZB; ++u) {
         const int r = z_lo + zr + u * RPI;
-        if (r < z_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+        if (r < z_hi && mk[u] == 0) {
+          const int64_t at = (int64_t)r * p.c_out * EB;
+          sc_store16(reinterpret_cast<v4i*>(ybase + at), p.residual ? dropped_row_group<DT>(p.residual, res_at + at, p.residual_relu) : z);
+        }
       }
       for (int r0 = z_lo + zr + ZB * RPI; r0 < z_hi; r0 += 4 * RPI) {   // tiles that own more rows
         unsigned char m4[4];
@@ -256,7 +260,10 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = r0 + u * RPI;
-          if (r < z_hi && m4[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+          if (r < z_hi && m4[u] == 0) {
+            const int64_t at = (int64_t)r * p.c_out * EB;
+            sc_store16(reinterpret_cast<v4i*>(ybase + at), p.residual ? dropped_row_group<DT>(p.residual, res_at + at, p.residual_relu) : z);
+          }
         }
       }
     }
@@ -271,8 +278,8 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
-      store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1, p.c_out,
-                           p.ho_wo, 0, 0, 0);
+      store_kept_block_res<DT>(acc[mi][ni], rr, c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1, p.c_out,
+                               p.ho_wo, 0, 0, 0, static_cast<const T*>(p.residual), p.residual_relu);
     }
   }
 }

@@ -196,6 +196,7 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
       const int zc = t % CPR, zr = t / CPR;
       if (zc < valid) {
         unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
+        const int64_t res_at = (int64_t)n0 * EB + zc * 16;     // the same group of the shortcut tensor
         const v4i z = {0, 0, 0, 0};
         for (int r0 = lo + zr; r0 < hi; r0 += 4 * RPI) {
           unsigned char mk[4];
@@ -208,7 +209,10 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
             const int r = r0 + u * RPI;
-            if (r < hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+            if (r < hi && mk[u] == 0) {
+              const int64_t at = (int64_t)r * p.c_out * EB;
+              sc_store16(reinterpret_cast<v4i*>(ybase + at), p.residual ? dropped_row_group<DT>(p.residual, res_at + at, p.residual_relu) : z);
+            }
           }
         }
       }
@@ -219,7 +223,13 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
         int mr = p.mask_spatial ? r % p.ho_wo : r;
         if (c < p.c_out && p.mask[mr] == 0) {
           int n = r / p.ho_wo, rem = r - n * p.ho_wo;
-          y[n * p.ys_n + (int64_t)rem * p.ys_p + (int64_t)c * p.ys_c] = E::from_float(0.0f);
+          const int64_t at = n * p.ys_n + (int64_t)rem * p.ys_p + (int64_t)c * p.ys_c;
+          float fill = 0.0f;
+          if (p.residual) {
+            fill += (float)static_cast<const T*>(p.residual)[at];
+            if (p.residual_relu) fill = fmaxf(fill, 0.0f);
+          }
+          y[at] = E::from_float(fill);
         }
       }
     }
@@ -294,8 +304,8 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
-      store_kept_block<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, p.vec_out, p.c_out, p.ho_wo, p.ys_n, p.ys_p,
-                           p.ys_c);
+      store_kept_block_res<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, p.vec_out, p.c_out, p.ho_wo, p.ys_n, p.ys_p,
+                               p.ys_c, static_cast<const T*>(p.residual), p.residual_relu);
     }
   }
 }

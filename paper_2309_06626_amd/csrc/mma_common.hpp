@@ -57,17 +57,41 @@ __device__ __forceinline__ void sc_store16(v4i* dst, v4i v) { *dst = v; }
 // c_out; the only mode the LDS-direct, band and row-panel kernels are launched with, as a literal, so their
 // epilogue stays as lean as it was); 2 = 16-byte stores, c_out a multiple of the 16-byte group only (the
 // register-staged tiled kernel).
+//
+// `res` (may be null): a shortcut tensor in the layout of y that is added after the layer's own activation, with
+// `post_relu` applied to the sum -- y = post(act(conv + bias) + res), the fused form of a block's conv -> add.
 template <int DT>
-__device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* __restrict__ y,
-                                                 const float* __restrict__ bias, int bias_at, int relu, int vec_out,
-                                                 int c_out,
-                                                 int ho_wo, int64_t ys_n, int ys_p, int ys_c) {
+__device__ __forceinline__ void store_kept_block_res(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* y,
+                                                     const float* __restrict__ bias, int bias_at, int relu, int vec_out,
+                                                     int c_out, int ho_wo, int64_t ys_n, int ys_p, int ys_c,
+                                                     const typename Elem<DT>::T* res, int post_relu) {
   using E = Elem<DT>;
   using T = typename E::T;
   constexpr int EB = sizeof(T);
   float vals[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) vals[v] = acc[v];
+  // the shortcut's 16 channels of this row (whole 16-byte groups), added after the layer's activation
+  auto add_shortcut = [&](int groups_ok) {
+    if (res) {
+      constexpr int GC = 16 / EB;
+      const v4i* src = reinterpret_cast<const v4i*>(res + ((int64_t)rr * c_out + c0));
+#pragma unroll
+      for (int q = 0; q < 16 * EB / 16; ++q) {
+        if (q < groups_ok) {
+          const v4i g = src[q];
+          T e[GC];
+          __builtin_memcpy(e, &g, 16);
+#pragma unroll
+          for (int i = 0; i < GC; ++i) vals[q * GC + i] += (float)e[i];
+        }
+      }
+    }
+    if (post_relu) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
+    }
+  };
   if (vec_out == 1) {
     // every 16-channel block lies inside c_out (c_out is a multiple of 16): the plain path
     if (bias) {
@@ -82,6 +106,7 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
 #pragma unroll
       for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
     }
+    add_shortcut(16 * EB / 16);
     T outv[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
@@ -109,6 +134,7 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
 #pragma unroll
       for (int v = 0; v < 16; ++v) vals[v] = fmaxf(vals[v], 0.0f);
     }
+    add_shortcut(groups_ok);
     T outv[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) outv[v] = E::from_float(vals[v]);
@@ -120,17 +146,48 @@ __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, in
       if (q < groups_ok) sc_store16(dst + q, pk[q]);
   } else {
     const int n = rr / ho_wo, rem = rr - n * ho_wo;
-    T* dst = y + n * ys_n + (int64_t)rem * ys_p;
+    const int64_t at = n * ys_n + (int64_t)rem * ys_p;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       int c = c0 + v;
       if (c < c_out) {
         float f = vals[v] + (bias ? bias[bias_at + v] : 0.0f);
         if (relu) f = fmaxf(f, 0.0f);
-        dst[(int64_t)c * ys_c] = E::from_float(f);
+        if (res) f += (float)res[at + (int64_t)c * ys_c];
+        if (post_relu) f = fmaxf(f, 0.0f);
+        y[at + (int64_t)c * ys_c] = E::from_float(f);
       }
     }
   }
+}
+
+template <int DT>
+__device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* __restrict__ y,
+                                                 const float* __restrict__ bias, int bias_at, int relu, int vec_out,
+                                                 int c_out, int ho_wo, int64_t ys_n, int ys_p, int ys_c) {
+  store_kept_block_res<DT>(acc, rr, c0, y, bias, bias_at, relu, vec_out, c_out, ho_wo, ys_n, ys_p, ys_c, nullptr, 0);
+}
+
+// What a dropped row of a dense-layout output receives in place of its 16-byte group `at` (byte offset into y):
+// zeros (Alg. 2, mask == 0 branch), or post(shortcut) when a shortcut tensor is fused into the launch -- the
+// convolution contributes +0.0 there, added in float like everywhere else (so -0.0 of the shortcut becomes +0.0).
+template <int DT>
+__device__ __forceinline__ v4i dropped_row_group(const void* res, int64_t at, int post_relu) {
+  using T = typename Elem<DT>::T;
+  constexpr int GC = 16 / (int)sizeof(T);
+  if (!res) return v4i{0, 0, 0, 0};
+  const v4i g = *reinterpret_cast<const v4i*>(static_cast<const unsigned char*>(res) + at);
+  T e[GC];
+  __builtin_memcpy(e, &g, 16);
+#pragma unroll
+  for (int i = 0; i < GC; ++i) {
+    float f = 0.0f + (float)e[i];
+    if (post_relu) f = fmaxf(f, 0.0f);
+    e[i] = Elem<DT>::from_float(f);
+  }
+  v4i out;
+  __builtin_memcpy(&out, e, 16);
+  return out;
 }
 
 }  // namespace sc

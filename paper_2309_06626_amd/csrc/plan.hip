@@ -321,6 +321,18 @@ __global__ void add_kernel(const T* __restrict__ a, const T* __restrict__ b, T* 
   }
 }
 
+// y = post(0 + shortcut): what a fused launch leaves when the mask keeps no row at all
+template <typename T>
+__global__ void shortcut_only_kernel(const T* __restrict__ res, T* __restrict__ y, int64_t count, int relu) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; i < count; i += stride) {
+    float v = 0.0f + (float)res[i];
+    if (relu) v = fmaxf(v, 0.0f);
+    y[i] = (T)v;
+  }
+}
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
 
@@ -711,8 +723,11 @@ static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
 }
 
 
+// residual (may be null): shortcut tensor in the format of y, fused into the epilogue of a tiled kernel:
+// y = post(act(conv + bias) + residual); dropped rows of a dense-layout output receive post(residual).
 static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const float* bias, void* y,
-                             hipStream_t stream, bool x_compact = false, bool y_compact = false) {
+                             hipStream_t stream, bool x_compact = false, bool y_compact = false,
+                             const void* residual = nullptr, int residual_relu = 0) {
   const sc_conv_desc& d = pl->desc;
   const Geometry& g = pl->geo;
   const int which = dense ? 1 : 0;
@@ -726,7 +741,16 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const bool compact = !identity && (x_compact || y_compact);
   const int eb = elem_bytes(d.dtype);
   if (rows == 0) {
-    if (d.out_mode == SC_OUT_ZERO_FILL && !y_compact) {
+    if (d.out_mode == SC_OUT_ZERO_FILL && !y_compact && residual) {
+      const dim3 grid((unsigned)std::min<int64_t>((g.y_elems + 255) / 256, 65536)), block(256);
+      if (d.dtype == SC_F32)
+        hipLaunchKernelGGL(shortcut_only_kernel<float>, grid, block, 0, stream, (const float*)residual, (float*)y, g.y_elems, residual_relu);
+      else if (d.dtype == SC_F16)
+        hipLaunchKernelGGL(shortcut_only_kernel<_Float16>, grid, block, 0, stream, (const _Float16*)residual, (_Float16*)y, g.y_elems, residual_relu);
+      else
+        hipLaunchKernelGGL(shortcut_only_kernel<__bf16>, grid, block, 0, stream, (const __bf16*)residual, (__bf16*)y, g.y_elems, residual_relu);
+      SC_HIP(hipGetLastError());
+    } else if (d.out_mode == SC_OUT_ZERO_FILL && !y_compact) {
       int64_t bytes = g.y_elems * eb;
       int64_t n16 = bytes / 16;
       int ntail = (int)(bytes - n16 * 16);
@@ -740,6 +764,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   // the streaming variant measured no faster than the tiled kernel on the benchmark layers, so the
   // automatic choice takes it only on request
   if (g.depthwise) {
+    if (residual) return SC_ERR_UNSUPPORTED;
     DepthwiseParams q;
     std::memset(&q, 0, sizeof(q));
     q.x = x;
@@ -768,7 +793,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   }
   // the band kernels address input and output by dense position: runs with a compact operand take a tiled kernel
   const BandPlan& band = dense ? pl->band_dense : pl->band;
-  const bool use_band = band.ok && !x_compact && !y_compact &&
+  // (the band and row-panel kernels have no shortcut path: a fused launch takes a tiled kernel)
+  const bool use_band = band.ok && !x_compact && !y_compact && !residual &&
                         (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream));
   if (use_band) {
     const BandPlan& b = band;
@@ -820,7 +846,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const TilePick tp = pick_tile(pl, which, rows);
   const int ti = tp.ti, splits = tp.splits;
   const KernelEntry& ke = pl->table[ti];
-  const bool panel = use_panel(pl, which, rows);
+  const bool panel = !residual && use_panel(pl, which, rows);
   ConvParams p;
   std::memset(&p, 0, sizeof(p));
   p.x = x;
@@ -853,6 +879,8 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   p.vec_out = g.vec_out ? 1 : g.vec_out8 ? 2 : 0;
   p.x_compact = compact && x_compact ? 1 : 0;
   p.y_compact = compact && y_compact ? 1 : 0;
+  p.residual = residual;
+  p.residual_relu = residual_relu ? 1 : 0;
 #ifdef SC_TIMING
   p.dbg = g_dbg;
 #endif
@@ -1163,6 +1191,35 @@ sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x
   // every pixel up in the rank map of its input
   if (xc && !pixel_window && !(plan->geo.depthwise && plan->x_rank_set)) return SC_ERR_UNSUPPORTED;
   return launch_conv(plan, false, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream), xc, yc);
+}
+
+sc_status sparse_conv_run_residual(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
+                                   const void* residual_dev, int32_t residual_relu, void* y_dev, int32_t y_rows,
+                                   void* hip_stream) {
+  sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (s != SC_OK) return s;
+  if (!residual_dev) return SC_ERR_NULL;
+  if ((uintptr_t)residual_dev & 15) return SC_ERR_ALIGN;
+  if ((x_rows != SC_ROWS_DENSE && x_rows != SC_ROWS_COMPACT) || (y_rows != SC_ROWS_DENSE && y_rows != SC_ROWS_COMPACT))
+    return SC_ERR_UNSUPPORTED;
+  const sc_conv_desc& d = plan->desc;
+  const bool xc = x_rows == SC_ROWS_COMPACT, yc = y_rows == SC_ROWS_COMPACT;
+  if ((xc || yc) && d.layout != SC_NHWC) return SC_ERR_UNSUPPORTED;
+  const bool pixel_window = d.kh == 1 && d.kw == 1 && d.stride_h == 1 && d.stride_w == 1 && d.pad_h == 0 && d.pad_w == 0;
+  if (plan->geo.depthwise || (xc && !pixel_window)) return SC_ERR_UNSUPPORTED;
+  return launch_conv(plan, false, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream), xc, yc, residual_dev,
+                     residual_relu);
+}
+
+sc_status dense_conv_run_residual(const sc_plan* plan, const void* x_dev, const float* bias_dev,
+                                  const void* residual_dev, int32_t residual_relu, void* y_dev, void* hip_stream) {
+  sc_status s = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (s != SC_OK) return s;
+  if (!residual_dev) return SC_ERR_NULL;
+  if ((uintptr_t)residual_dev & 15) return SC_ERR_ALIGN;
+  if (plan->geo.depthwise) return SC_ERR_UNSUPPORTED;
+  return launch_conv(plan, true, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream), false, false,
+                     residual_dev, residual_relu);
 }
 
 sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
