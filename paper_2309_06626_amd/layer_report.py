@@ -114,11 +114,12 @@ def measure_layer(spec, base_seed, steps, out_mode, x_host=None, library=False):
     return rec
 
 
-def chain_time(ops, base_seed, steps, dense=False, propagated_masks=False, compact=False):
+def chain_time(ops, base_seed, steps, dense=False, propagated_masks=False, compact=False, fused=False):
     """Whole network with fixed buffers: (us per pass launched call by call, us per pass as a HIP graph replay).
 
     propagated_masks: every layer's 2-D mask comes from one score through the mask generator (Alg. 1,
-    getMask), so layers of one resolution share it; compact: tensors between such layers stay compact."""
+    getMask), so layers of one resolution share it; compact: tensors between such layers stay compact; fused: shortcut
+    sums ride in the epilogue of the convolution before them where the planner accepts it."""
     import numpy as np
     import torch
 
@@ -142,7 +143,7 @@ def chain_time(ops, base_seed, steps, dense=False, propagated_masks=False, compa
         if op.kind == "conv" and op.src.startswith("synthetic:"):
             tensors[op.src] = R.to_device(W.gen_activations(op.spec.x_shape(), base_seed + 500 + op.spec.layer_index, dtype), dtype)
     net = R.NetworkRunner(ops, tensors, layers, dense=dense,
-                          row_formats=R.plan_row_formats(ops, layers) if compact else None)
+                          row_formats=R.plan_row_formats(ops, layers) if compact else None, fuse_shortcuts=fused)
 
     def timed(fn):
         for _ in range(max(steps // 5, 3)):
@@ -358,6 +359,8 @@ def main():
             emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
         cs = max(args.steps // 10, 5)
         chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), cs)
+        chains["config 3, shortcut sums fused into the convolution before them (layers 2-4)"] = \
+            chain_time(ops, W.base_seed(3), cs, fused=True)
         chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3), cs)
         chains["config 3, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(3), cs, dense=True)
     if 4 in want:
@@ -388,6 +391,8 @@ def main():
             chains[tag + ", dense tensors"] = chain_time(ops, W.base_seed(6), cs, propagated_masks=True)
             chains[tag + ", compact tensors between layers that share a mask"] = \
                 chain_time(ops, W.base_seed(6), cs, propagated_masks=True, compact=True)
+            chains[tag + ", compact tensors and fused shortcut sums"] = \
+                chain_time(ops, W.base_seed(6), cs, propagated_masks=True, compact=True, fused=True)
         chains["MobileNetV2-style stack, every conv through dense_conv_run"] = \
             chain_time(ops, W.base_seed(6), cs, dense=True, propagated_masks=True)
     if chains:

@@ -143,6 +143,48 @@ def plan_row_formats(ops, layers: Dict[str, "ConvLayer"]) -> Dict[str, bool]:
     return compact
 
 
+def plan_shortcut_fusions(ops, layers: Dict[str, "ConvLayer"], row_formats: Optional[Dict[str, bool]] = None,
+                          dense: bool = False) -> Dict[str, tuple]:
+    """Which sums of a graph can ride in the epilogue of the convolution before them.
+
+    Returns {name of the sum's result: (name of the conv layer, name of the other operand, relu after the sum)}.
+    A sum is fused into the operand-producing conv that comes last in the op list, if that conv's result feeds
+    nothing else, the other operand exists by then, both have the row format of the result, and the layer runs
+    in a tiled kernel anyway (band and row-panel kernels have no shortcut path and are faster than a tiled
+    kernel plus a saved launch).  Host-side bookkeeping only."""
+    fmt = row_formats or {}
+    position = {op.out: i for i, op in enumerate(ops)}
+    producer = {op.out: op for op in ops}
+    uses: Dict[str, int] = {}
+    for op in ops:
+        for src in (op.src, op.src2):
+            if src:
+                uses[src] = uses.get(src, 0) + 1
+    fused = {}
+    for op in ops:
+        if op.kind not in ("add", "add_relu"):
+            continue
+        best = None
+        for mine, other in ((op.src, op.src2), (op.src2, op.src)):
+            conv = producer.get(mine)
+            if conv is None or conv.kind != "conv" or uses.get(mine, 0) != 1 or conv.spec.groups != 1:
+                continue
+            if position.get(other, -1) >= position[mine]:
+                continue                                   # the other operand is computed later
+            if not (fmt.get(mine, False) == fmt.get(other, False) == fmt.get(op.out, False)):
+                continue
+            kernel = B.sparse_conv_plan_kernel(layers[conv.spec.name].plan, 1 if dense else 0)
+            if fmt.get(mine, False):
+                kernel = "tile"                            # runs with compact operands take a tiled kernel anyway
+            if not kernel.startswith("tile") or kernel == "tile_row_panel":
+                continue
+            if best is None or position[mine] > position[best[0]]:
+                best = (mine, other)
+        if best is not None:
+            fused[op.out] = (producer[best[0]].spec.name, best[1], op.kind == "add_relu")
+    return fused
+
+
 def run_network(ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer]) -> Dict[str, torch.Tensor]:
     """Interpret a workload op list on the device (conv = sparse_conv_run, plus the glue ops)."""
     t = dict(tensors)
@@ -166,11 +208,15 @@ class NetworkRunner:
     a HIP graph: the library launches kernels only, no memsets, no allocations, no synchronisation)."""
 
     def __init__(self, ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer], dense: bool = False,
-                 row_formats: Optional[Dict[str, bool]] = None):
-        """row_formats: the result of plan_row_formats, to keep those tensors compact (sparse runs only)."""
+                 row_formats: Optional[Dict[str, bool]] = None, fuse_shortcuts: bool = False):
+        """row_formats: the result of plan_row_formats, to keep those tensors compact (sparse runs only).
+        fuse_shortcuts: sums that plan_shortcut_fusions accepts run in the epilogue of their conv; the conv's own
+        result is then never materialised (its name is absent from the tensors)."""
         self.tensors = dict(tensors)
         self.calls: List[Callable] = []
         self.row_formats = {} if (dense or row_formats is None) else dict(row_formats)
+        self.fusions = plan_shortcut_fusions(ops, layers, self.row_formats, dense) if fuse_shortcuts else {}
+        fused_conv = {v[0]: (k, v[1], v[2]) for k, v in self.fusions.items()}   # conv layer -> (sum, other operand, relu)
         fmt = lambda name: B.SC_ROWS_COMPACT if self.row_formats.get(name, False) else B.SC_ROWS_DENSE
         t = self.tensors
         rows_mask: Dict[str, torch.Tensor] = {}       # the mask whose kept rows a tensor holds when compact
@@ -181,6 +227,16 @@ class NetworkRunner:
             else:
                 rows_mask[op.out] = layers[op.spec.name].mask
         for op in ops:
+            if op.kind == "conv" and op.spec.name in fused_conv:
+                layer = layers[op.spec.name]
+                out, other, relu = fused_conv[op.spec.name]
+                xf, yf = fmt(op.src), fmt(out)
+                t[out] = torch.empty_like(t[other])
+                self.calls.append(B.prepared_run_residual(layer.plan, t[op.src], layer.bias, t[other], t[out], relu, xf, yf,
+                                                          dense=dense))
+                continue
+            if op.kind in ("add", "add_relu") and op.out in self.fusions:
+                continue
             if op.kind == "conv":
                 layer = layers[op.spec.name]
                 xf, yf = fmt(op.src), fmt(op.out)

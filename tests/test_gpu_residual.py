@@ -151,3 +151,63 @@ def test_refusals():
         B.sparse_conv_run_residual(layer.plan, x, layer.bias, y, y)          # the shortcut must not overlap y
     assert B.lib().sparse_conv_run_residual(layer.plan.handle, x.data_ptr(), 0, layer.bias.data_ptr(), None, 0, y.data_ptr(), 0,
                                            None) == B.SC_ERR_NULL
+
+
+@pytest.mark.parametrize("dense", [False, True])
+def test_resnet18_stack_with_shortcut_sums_fused_into_their_convolutions(dense):
+    """The ResNet18 op list with every sum the planner accepts riding in its convolution's epilogue: the sums'
+    results against the oracle's interpreter (which rounds the convolution and the sum separately, so the fused
+    run differs by at most that one intermediate rounding -- well inside the layer tolerance), the unfused
+    tensors bit for bit against the unfused runner, and once more as a graph replay."""
+    ops = W.config3(batch=2)
+    bs = W.base_seed(3)
+    params = {}
+
+    def layer_inputs(spec):
+        if spec.name not in params:
+            ci = W.make_conv_inputs(spec, bs, x=np.zeros(1, np.float32))
+            w, bias, mask = ci.w, ci.bias, ci.mask
+            params[spec.name] = (w, bias, np.ones_like(mask) if dense else mask)
+        return params[spec.name]
+
+    host = {"input": W.gen_activations(W.network_input_shape(ops), bs, "bf16")}
+    layers = {}
+    for s in W.conv_specs(ops):
+        w, bias, _ = layer_inputs(s)
+        layers[s.name] = R.ConvLayer(s, w, bias, W.make_conv_inputs(s, bs, x=np.zeros(1, np.float32)).mask)
+    x = R.to_device(host["input"], "bf16")
+    net = R.NetworkRunner(ops, {"input": x}, layers, dense=dense, fuse_shortcuts=True)
+    sums = [op.out for op in ops if op.kind in ("add", "add_relu")]
+    assert net.fusions and set(net.fusions) <= set(sums)
+    fused_convs = {v[0] for v in net.fusions.values()}
+    for op in ops:
+        if op.kind == "conv" and op.spec.name in fused_convs:
+            assert op.out not in net.tensors                 # never materialised
+    ref = oracle.run_network(ops, host, layer_inputs)
+    tol = TOL["bf16"]
+
+    def check():
+        torch.cuda.synchronize()
+        for op in ops:
+            if op.out not in net.tensors:
+                continue
+            g, r = R.to_host_f32(net.tensors[op.out]), ref[op.out]
+            nr = np.linalg.norm(r.astype(np.float64))
+            err = np.linalg.norm(g.astype(np.float64) - r.astype(np.float64)) / max(nr, 1e-30)
+            assert err <= tol, f"{op.out}: normwise {err:.3e}"
+            assert np.abs(g - r).max() <= tol * max(np.abs(r).max(), 1e-30), op.out
+            if op.kind == "conv" and not dense:
+                bits = rows_view(op.spec, R.bits_of(net.tensors[op.out]))
+                assert (bits[params[op.spec.name][2] == 0] == 0).all(), f"{op.out}: dropped rows must be zero"
+
+    net.run()
+    check()
+    first = {name: R.bits_of(net.tensors[name]).copy() for name in sums}
+    graph = net.capture()
+    for _ in range(2):
+        for name in sums:
+            net.tensors[name].fill_(float("nan"))
+        graph.replay()
+        check()
+        for name in sums:
+            assert np.array_equal(R.bits_of(net.tensors[name]), first[name]), name
