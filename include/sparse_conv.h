@@ -229,7 +229,14 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
 /* SC_OPT_ROW_PANEL: 0 = automatic, 1 = never, 2 = always where it applies.  The row-panel kernel
  * (16-bit NHWC layers with K <= 2 K tiles, i.e. pointwise layers with up to 128 input channels, and
  * at most 1024 output channels) gathers 128 kept rows once and walks all channel tiles with them. */
-enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2 };
+/* SC_OPT_STREAM_K: 0 = automatic, 1 = never, n >= 2 = run the tiled kernel as n persistent workgroups
+ * (rounded up to a multiple of 8, at most 1024) that share the K steps of all output tiles evenly, wherever
+ * that kernel applies (the layers SC_OPT_SPLIT_K names whose input channels are a multiple of 64); tiles
+ * whose K walk is shared are completed from float partial sums added in a fixed order.  n is clamped so that
+ * two partial-sum slots per workgroup fit the 16 MiB buffer and every workgroup has at least four K steps.
+ * Measured slower than the ordinary launch on every benchmark layer (the partial sums cross the fabric
+ * between the XCDs' caches), so automatic means off. */
+enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2, SC_OPT_STREAM_K = 3 };
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
 
 void sparse_conv_plan_destroy(sc_plan* plan);

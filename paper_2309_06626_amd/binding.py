@@ -399,6 +399,7 @@ def sparse_conv_plan_set_tiles(plan: Plan, which: int, tile_m: int, tile_n: int)
 SC_OPT_GATHER_PIPELINE = 0
 SC_OPT_SPLIT_K = 1
 SC_OPT_ROW_PANEL = 2
+SC_OPT_STREAM_K = 3
 
 
 def sparse_conv_plan_set_option(plan: Plan, option: int, value: int):

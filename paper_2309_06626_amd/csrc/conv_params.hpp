@@ -56,6 +56,8 @@ struct ConvParams {
   int32_t splits;
   float* partial;          // [m_tiles * n_tiles][splits][BM * BN] float partial sums
   int32_t* counters;       // [m_tiles * n_tiles] arrival counters, zero between launches
+  // stream-K launches only: persistent workgroups (a multiple of 8), each with two partial-sum slots in `partial`
+  int32_t stream_wgs;
 #ifdef SC_TIMING
   long long* dbg;          // development builds only: per-workgroup phase time stamps
 #endif
@@ -140,6 +142,9 @@ struct KernelEntry {
   LaunchFn splitk; // direct-to-LDS gather, deep ring, K divided among several workgroups (null: no such shape)
   size_t lds_bytes;
 };
+
+// the stream-K form of tile bm x bn for a 16-bit dtype, or null (igemm_streamk.hip)
+LaunchFn streamk_kernel(int dtype, int bm, int bn);
 
 // the row-segment-gather form of tile bm x bn for a 16-bit dtype, or null (igemm_rowseg.hip)
 LaunchFn rowseg_kernel(int dtype, int bm, int bn);

@@ -15,6 +15,7 @@
 #include "bandstream_kernel.hpp"
 #include "conv_params.hpp"
 #include "igemm_buf_kernel.hpp"
+#include "igemm_streamk_kernel.hpp"
 #include "igemm_panel_kernel.hpp"
 
 namespace sc {
@@ -338,6 +339,7 @@ static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
 
 // float partial sums of a split-K launch at most (one BM x BN block per workgroup)
 constexpr size_t kSplitKPartialBytes = (size_t)16 << 20;
+constexpr int kStreamKMostWgs = 1024;   // persistent workgroups of a stream-K launch at most
 constexpr int kSplitKMost = 64;   // splits per output tile at most
 
 struct Geometry {
@@ -647,6 +649,7 @@ struct sc_plan {
   int gather_pipeline;             // 0 = automatic, 1 = through registers, 2 = straight into LDS
   int split_k;                     // 0 = automatic, 1 = never, n >= 2 = n splits wherever the kernel applies
   int row_panel;                   // 0 = automatic, 1 = never, 2 = wherever the kernel applies
+  int stream_k;                    // 0 = automatic, 1 = never, n >= 2 = n persistent workgroups wherever the kernel applies
   bool x_rank_set;                 // sparse_conv_plan_set_input_mask has filled the rank map of a compact input
 };
 constexpr int kForceBand = -2;
@@ -698,6 +701,38 @@ static int most_splits(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
   const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
   const int64_t by_buffer = (int64_t)(kSplitKPartialBytes / ((size_t)ke.bm * ke.bn * sizeof(float))) / std::max<int64_t>(tiles, 1);
   return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(by_buffer, g.k_tiles / 4), kSplitKMost));
+}
+
+// Buffer-load form of the tiled kernel: Cin a multiple of the K tile (a K tile then lies inside one tap),
+// windows up to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31).
+static bool buf_applies(const sc_plan* pl, const KernelEntry& ke) {
+  const sc_conv_desc& d = pl->desc;
+  const Geometry& g = pl->geo;
+  if (d.dtype == SC_F32) return false;
+  const int eb = 2;
+  const uint64_t xb = (uint64_t)d.n * d.h * d.w * d.c_in * eb, wb = (uint64_t)g.cout_pad * g.k_stride * eb;
+  return buf_kernel(d.dtype == SC_BF16 ? kBF16 : kF16, ke.bm, ke.bn, g.k_tiles <= 2) && g.vec_gather && g.vec_out &&
+         pl->gather_pipeline == 0 && d.c_in % 64 == 0 && d.kh <= 8 && d.kw <= 8 && xb < ((uint64_t)1 << 31) &&
+         wb < ((uint64_t)1 << 31) && !g.rowseg;
+}
+
+// Stream-K launch of the buffer-load tiled kernel: how many persistent workgroups (0: an ordinary launch).
+// Needs the split-K workspace (counters per tile, two partial-sum slots per workgroup), at least four K
+// steps per workgroup, and step counts the kernel's 32-bit arithmetic holds.
+static int stream_k_workgroups(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
+  const Geometry& g = pl->geo;
+  if (!g.splitk_ok || pl->stream_k == 1 || g.k_tiles <= 2 || !buf_applies(pl, ke)) return 0;
+  if (!streamk_kernel(pl->desc.dtype == SC_BF16 ? kBF16 : kF16, ke.bm, ke.bn)) return 0;
+  int want = pl->stream_k >= 2 ? pl->stream_k : 0;      // automatic: off
+  if (want == 0) return 0;
+  want = std::min((want + 7) / 8 * 8, kStreamKMostWgs);
+  const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
+  const int64_t total = tiles * g.k_tiles;
+  const int64_t by_buffer = (int64_t)(kSplitKPartialBytes / (2 * (size_t)ke.bm * ke.bn * sizeof(float))) / 8 * 8;
+  want = (int)std::min<int64_t>(want, by_buffer);
+  want = (int)std::min<int64_t>(want, total / 4 / 8 * 8);
+  if (want < 8 || total * (want + 1) >= ((int64_t)1 << 31)) return 0;
+  return want;
 }
 
 static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
@@ -912,17 +947,23 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     p.seg_tail = d.kw * d.c_in - (p.seg_gpk - 1) * 8;
     fn = rs;
   }
-  {
-    // buffer-load form: Cin a multiple of the K tile (a K tile then lies inside one tap), windows up
-    // to 8 x 8, tensors below 2 GiB (the out-of-range marker is offset 2^31)
-    const int dt = d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32;
-    const uint64_t xb = (uint64_t)d.n * d.h * d.w * d.c_in * eb, wb = (uint64_t)g.cout_pad * g.k_stride * eb;
-    LaunchFn bf = buf_kernel(dt, ke.bm, ke.bn, g.k_tiles <= 2);
-    if (bf && g.vec_gather && g.vec_out && pl->gather_pipeline == 0 && d.dtype != SC_F32 && d.c_in % 64 == 0 &&
-        d.kh <= 8 && d.kw <= 8 && xb < ((uint64_t)1 << 31) && wb < ((uint64_t)1 << 31)) {
-      p.x_bytes = (uint32_t)xb;
-      p.w_bytes = (uint32_t)wb;
-      fn = bf;
+  bool fn_is_buf = false;
+  if (buf_applies(pl, ke)) {
+    const int dt = d.dtype == SC_BF16 ? kBF16 : kF16;
+    p.x_bytes = (uint32_t)((uint64_t)d.n * d.h * d.w * d.c_in * eb);
+    p.w_bytes = (uint32_t)((uint64_t)g.cout_pad * g.k_stride * eb);
+    fn = buf_kernel(dt, ke.bm, ke.bn, g.k_tiles <= 2);
+    fn_is_buf = true;
+  }
+  if (fn_is_buf && splits == 1 && !panel) {
+    const int dt = d.dtype == SC_BF16 ? kBF16 : kF16;
+    const int wgs = stream_k_workgroups(pl, ke, rows);
+    LaunchFn sk = wgs ? streamk_kernel(dt, ke.bm, ke.bn) : nullptr;
+    if (sk) {
+      p.stream_wgs = wgs;
+      p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);
+      p.counters = reinterpret_cast<int32_t*>(pl->ws + g.off_counters);
+      fn = sk;
     }
   }
   if (splits > 1) {
@@ -1107,6 +1148,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->gather_pipeline = 0;
   pl->split_k = 0;
   pl->row_panel = 0;
+  pl->stream_k = 0;
   pl->x_rank_set = false;
   pl->tile_splitk = -1;
   for (int i = 0; i < pl->table_count; ++i)
@@ -1277,6 +1319,8 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
   if (tile_m) *tile_m = ke.bm;
   if (tile_n) *tile_n = ke.bn;
   if (workgroups) *workgroups = ((rows + ke.bm - 1) / ke.bm) * ((plan->desc.c_out + ke.bn - 1) / ke.bn) * splits;
+  const int sk = splits == 1 ? stream_k_workgroups(plan, ke, rows) : 0;
+  if (sk && workgroups) *workgroups = sk;      // persistent workgroups of a stream-K launch
   return SC_OK;
 }
 
@@ -1288,7 +1332,9 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
     return band.stream ? "band_stream" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
-  if (pick_tile(plan, which, which ? g.m : plan->kept).splits > 1) return "tile_split_k";
+  const TilePick tp = pick_tile(plan, which, which ? g.m : plan->kept);
+  if (tp.splits > 1) return "tile_split_k";
+  if (stream_k_workgroups(plan, plan->table[tp.ti], which ? g.m : plan->kept)) return "tile_stream_k";
   if (g.rowseg) return "tile_row_segments";
   if (!g.vec_gather) return "tile_elements";
   return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
@@ -1314,6 +1360,7 @@ sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t val
   if (option == SC_OPT_GATHER_PIPELINE && value >= 0 && value <= 2) { plan->gather_pipeline = value; return SC_OK; }
   if (option == SC_OPT_ROW_PANEL && value >= 0 && value <= 2) { plan->row_panel = value; return SC_OK; }
   if (option == SC_OPT_SPLIT_K && value >= 0 && value <= kSplitKMost) { plan->split_k = value; return SC_OK; }
+  if (option == SC_OPT_STREAM_K && value >= 0 && value <= kStreamKMostWgs) { plan->stream_k = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }
 

@@ -21,11 +21,15 @@ def spec_of(n, cin, h, w, cout, k=3, s=1, p=None, dtype="bf16", layout="nhwc", r
 
 
 def check(spec, seed, post_relu, want_kernel=None, out_mode=B.SC_OUT_ZERO_FILL, split_k=None, y_compact=False,
-          x_compact=False):
+          x_compact=False, stream_k=None):
     ci = W.make_conv_inputs(spec, seed)
     layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, out_mode=out_mode)
     if split_k:
         B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, split_k)
+    if stream_k:
+        B.sparse_conv_plan_set_tiles(layer.plan, 0, 64, 128)
+        B.sparse_conv_plan_set_tiles(layer.plan, 1, 64, 128)
+        B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_STREAM_K, stream_k)
     rm = row_mask(spec, ci.mask)
     kept = rm == 1
     tol = TOL[spec.dtype]
