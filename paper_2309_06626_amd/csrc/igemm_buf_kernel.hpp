@@ -31,7 +31,7 @@ template <int OFF> __device__ __forceinline__ v4i lds_read16_big(unsigned addr) 
 }
 
 template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
-__global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p) {
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const ConvParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
   constexpr int V = E::V;
@@ -39,10 +39,13 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
   constexpr int BK = 8 * V;
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
   constexpr int MI = WM / 32, NI = WN / 32;
-  constexpr int A_LOADS = BM / 32, B_LOADS = BN / 32;
+  constexpr int NT = WAVES_M * WAVES_N * 64;   // threads: four wavefronts, or eight (two per SIMD) for the largest tile
+  constexpr int RPR = NT / 8;                  // tile rows one transfer of the whole workgroup covers
+  constexpr int A_LOADS = BM / RPR, B_LOADS = BN / RPR;
   constexpr int LPT = A_LOADS + B_LOADS;
   constexpr int STAGE_BYTES = (BM + BN) * kRowBytes;
-  static_assert(WAVES_M * WAVES_N * 64 == kThreads, "four wavefronts");
+  static_assert(NT == 256 || NT == 512, "four or eight wavefronts");
+  static_assert(BM % RPR == 0 && BN % RPR == 0, "whole transfers");
   static_assert(STAGES >= 2 && (STAGES - 2) * LPT <= 63, "vmcnt is a 6-bit counter");
   static_assert(EB == 2, "16-bit operands");
 
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
   int32_t a_row[A_LOADS];
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    const int icc = min(m0 + lrow + 32 * j, p.rows - 1);
+    const int icc = min(m0 + lrow + RPR * j, p.rows - 1);
     a_row[j] = p.row_idx ? p.row_idx[icc] : icc;
   }
   float bias_v = 0.0f;
@@ -90,10 +93,10 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
   uint32_t a_taps[A_LOADS];
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    const bool present = m0 + lrow + 32 * j < p.rows;
-    const int ic = m0 + lrow + 32 * j;                       // position in the compacted GEMM
+    const bool present = m0 + lrow + RPR * j < p.rows;
+    const int ic = m0 + lrow + RPR * j;                      // position in the compacted GEMM
     const int rr = present ? (p.y_compact ? ic : a_row[j]) : -1;   // row the epilogue stores to
-    if (c16 == 0) s_rows[lrow + 32 * j] = rr;
+    if (c16 == 0) s_rows[lrow + RPR * j] = rr;
     const int rc = present ? (p.x_compact ? ic : a_row[j]) : 0;    // row the window is read from
     const int n = fast_div(rc, p.div_howo_mul, p.div_howo_shift), rem = rc - n * p.ho_wo;
     const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
@@ -107,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
   const uint32_t b_voff = (uint32_t)((lrow * p.k_pad + lc * V) * EB);
 
   constexpr int CPR = BN * EB / 16;        // 16-byte groups per output row slice
-  constexpr int RPI = kThreads / CPR;      // dense rows per fill pass of the workgroup
+  constexpr int RPI = NT / CPR;           // dense rows per fill pass of the workgroup
   constexpr int ZB = 4;                    // passes whose mask bytes are fetched up front
   const int zc = t % CPR, zr = t / CPR;
   unsigned mk[ZB];
@@ -137,12 +140,12 @@ __global__ __launch_bounds__(kThreads) void igemm_buf_kernel(const ConvParams p)
     for (int j = 0; j < A_LOADS; ++j) {
       const bool ok = (a_taps[j] & s_bits) == s_bits;
       const uint32_t voff = ok ? (uint32_t)(a_voff[j] + s_off) : kOutOfRange;   // out of range: LDS gets zeros
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void*)(sa + j * 32 * kRowBytes), 16, voff, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void*)(sa + j * RPR * kRowBytes), 16, voff, 0, 0, 0);
     }
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void*)(sb + j * 32 * kRowBytes), 16, b_voff,
-                                               s_boff + j * 32 * p.k_pad * EB, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rw, (lds_void*)(sb + j * RPR * kRowBytes), 16, b_voff,
+                                               s_boff + j * RPR * p.k_pad * EB, 0, 0);
     s_boff += BK * EB;
     s_ci += BK;
     s_off += BK * EB;
@@ -297,7 +300,7 @@ hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
   }
   const int nwg = p.m_tiles * p.n_tiles;
   const int grid = ((nwg + 7) / 8) * 8;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, stream, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * 64), lds, stream, p);
   return hipGetLastError();
 }
 
