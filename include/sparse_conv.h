@@ -125,6 +125,10 @@ sc_status sparse_conv_plan_set_filters(sc_plan* plan, const void* w_dev, void* h
  * left alone in SC_OUT_SCATTER_ONLY mode).
  * x_dev: activations; bias_dev: float[Cout] or NULL when has_bias == 0; y_dev: output, fully
  * overwritten in SC_OUT_ZERO_FILL mode.  x_dev and y_dev must not overlap.
+ * Enqueues on `hip_stream` only: no allocation, no synchronisation.  Runs of ONE plan may overlap on
+ * different streams unless a K split or stream-K launch was requested for it (SC_OPT_SPLIT_K,
+ * SC_OPT_STREAM_K): those keep partial sums and arrival counters in the plan's workspace, which
+ * overlapping runs of that plan would share.
  */
 sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
                           void* hip_stream);
