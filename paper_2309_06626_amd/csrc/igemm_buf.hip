@@ -7,6 +7,7 @@ namespace sc {
 template <int DT>
 static LaunchFn pick_shallow(int bm, int bn) {
   if (bm == 128 && bn == 64) return igemm_buf_launch<DT, 128, 64, 2, 2, 2>;
+  if (bm == 96 && bn == 128) return igemm_buf_launch<DT, 96, 128, 1, 4, 2>;
   if (bm == 64 && bn == 128) return igemm_buf_launch<DT, 64, 128, 2, 2, 2>;
   if (bm == 64 && bn == 64) return igemm_buf_launch<DT, 64, 64, 2, 2, 2>;
   if (bm == 128 && bn == 32) return igemm_buf_launch<DT, 128, 32, 4, 1, 2>;
@@ -18,6 +19,7 @@ template <int DT>
 static LaunchFn pick(int bm, int bn) {
   if (bm == 128 && bn == 128) return igemm_buf_launch<DT, 128, 128, 2, 4, 3>;   // eight wavefronts
   if (bm == 128 && bn == 64) return igemm_buf_launch<DT, 128, 64, 2, 2, 3>;
+  if (bm == 96 && bn == 128) return igemm_buf_launch<DT, 96, 128, 1, 4, 3>;
   if (bm == 64 && bn == 128) return igemm_buf_launch<DT, 64, 128, 2, 2, 3>;
   if (bm == 64 && bn == 64) return igemm_buf_launch<DT, 64, 64, 2, 2, 3>;
   if (bm == 128 && bn == 32) return igemm_buf_launch<DT, 128, 32, 4, 1, 3>;

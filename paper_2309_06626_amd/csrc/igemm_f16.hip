@@ -12,6 +12,7 @@ static const KernelEntry g_table[] = {
     SC_KERNEL_ENTRY_SPLITK(kF16, 128, 64, 2, 2, 4, 3, 6),
     SC_KERNEL_ENTRY_SPLITK(kF16, 64, 128, 2, 2, 4, 3, 6),
     SC_KERNEL_ENTRY_SPLITK(kF16, 64, 64, 2, 2, 4, 3, 8),
+    SC_KERNEL_ENTRY(kF16, 96, 128, 1, 4, 2, 3),
     SC_KERNEL_ENTRY(kF16, 128, 32, 4, 1, 4, 3),
     SC_KERNEL_ENTRY(kF16, 32, 128, 1, 4, 4, 3),
 };

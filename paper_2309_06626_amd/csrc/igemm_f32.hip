@@ -11,6 +11,7 @@ static const KernelEntry g_table[] = {
     SC_KERNEL_ENTRY(kF32, 128, 64, 2, 2, 4, 3),
     SC_KERNEL_ENTRY(kF32, 64, 128, 2, 2, 4, 3),
     SC_KERNEL_ENTRY(kF32, 64, 64, 2, 2, 4, 3),
+    SC_KERNEL_ENTRY(kF32, 96, 128, 1, 4, 2, 3),
     SC_KERNEL_ENTRY(kF32, 128, 32, 4, 1, 4, 3),
     SC_KERNEL_ENTRY(kF32, 32, 128, 1, 4, 4, 3),
 };

@@ -89,7 +89,7 @@ def test_compact_output_across_gather_kernels(shape, sparsity):
 
 def test_compact_output_with_forced_tiles_pipelines_and_split_k():
     spec = layer_spec("ct", 2, 128, 16, 256, sparsity=0.5)
-    for tiles in [(128, 128), (128, 64), (64, 128), (64, 64), (32, 128)]:
+    for tiles in [(128, 128), (128, 64), (96, 128), (64, 128), (64, 64), (32, 128)]:
         check_compact_output(spec, 107, tiles=tiles)
     check_compact_output(spec, 107, gather_pipeline=1)
     check_compact_output(spec, 107, gather_pipeline=2)

@@ -13,7 +13,7 @@ from parity import TOL, assert_close, check_layer, compare_network, rows_view
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [(256, 128), (128, 128), (256, 64), (128, 64), (64, 128), (64, 64), (128, 32), (32, 128)]
+ALL_TILES = [(256, 128), (128, 128), (256, 64), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)]
 
 
 def spec_of(n, cin, h, w, cout, k=3, s=1, p=1, d=1, dtype="bf16", layout="nhwc", bias=True, relu=True, sp=0.5,
@@ -237,7 +237,7 @@ BUFFER_CASES = [
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (64, 128), (64, 64), (128, 32), (32, 128)])
+@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)])
 @pytest.mark.parametrize("case", range(len(BUFFER_CASES)))
 def test_buffer_load_tiled_kernel(case, tile, dtype):
     spec = spec_of(dtype=dtype, **BUFFER_CASES[case])
