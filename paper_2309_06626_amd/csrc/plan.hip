@@ -48,8 +48,11 @@ __device__ __forceinline__ int wave_sum(int v) {
   return v;
 }
 
+// (copy, may be null: the plan's private copy of the mask, mask_len bytes, written on the way -- the first mask_len
+// rows read exactly those bytes)
 __global__ __launch_bounds__(256) void mask_count_kernel(const uint8_t* __restrict__ mask, int m, int period,
-                                                         int nseg, int32_t* __restrict__ counts) {
+                                                         int nseg, int32_t* __restrict__ counts,
+                                                         uint8_t* __restrict__ copy, int mask_len) {
   const int lane = threadIdx.x & 63;
   const int seg = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (seg >= nseg) return;
@@ -57,7 +60,9 @@ __global__ __launch_bounds__(256) void mask_count_kernel(const uint8_t* __restri
   int cnt = 0;
   for (int it = 0; it < kSeg / 64; ++it) {
     int r = r0 + it * 64 + lane;
-    bool keep = r < m && mask[period ? r % period : r] != 0;
+    const uint8_t v = r < m ? mask[period ? r % period : r] : (uint8_t)0;
+    if (copy && r < mask_len) copy[r] = v;
+    bool keep = v != 0;
     cnt += __popcll(__ballot(keep));
   }
   if (lane == 0) counts[seg] = cnt;
@@ -82,7 +87,10 @@ __global__ __launch_bounds__(256) void mask_scatter_kernel(const uint8_t* __rest
     if (keep) row_idx[base + rank] = r;
     base += __popcll(b);
   }
-  if (seg == nseg - 1 && lane == 0) *kept_out = base;
+  if (seg == nseg - 1 && lane == 0) {
+    kept_out[0] = base;
+    kept_out[1] = 0;      // the per-band maximum, raised by band_rows_kernel
+  }
 }
 
 // The inverse map for a compact tensor: rank[r] = position of row r among the kept rows, -1 for a dropped
@@ -209,17 +217,13 @@ __global__ void band_start_kernel(const int32_t* __restrict__ row_idx, const int
   band_i0[b] = lo;
 }
 
-// Largest number of kept rows in any band (sizes the accumulator blocks of the streaming band kernel).
-__global__ void band_max_kernel(const int32_t* __restrict__ band_i0, int n_bands, int32_t* __restrict__ out) {
-  int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b < n_bands) atomicMax(out, band_i0[b + 1] - band_i0[b]);
-}
-
 // Band-ordered copy of the kept-row list: the kept rows of band b, ascending, stored from index
 // r_lo(b) (the band's first dense row) on, so the band kernel finds them without knowing counts.
+// The first kept row of every band also raises band_max to the band's kept-row count (it sizes the accumulator blocks of
+// the streaming kernel and picks the MFMA block shape of the others: the fullest band is the one a launch waits for).
 __global__ void band_rows_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
                                  const int32_t* __restrict__ band_i0, int32_t* __restrict__ band_rows,
-                                 int bands_per_image, int bh, int split, int ho, int wo) {
+                                 int bands_per_image, int bh, int split, int ho, int wo, int32_t* __restrict__ band_max) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= *kept_dev) return;
   const int r = row_idx[i];
@@ -229,7 +233,9 @@ __global__ void band_rows_kernel(const int32_t* __restrict__ row_idx, const int3
   const int band = img * bands_per_image + bi;
   int first, end;
   band_pixel_range(bi, bh, split, ho, wo, &first, &end);
-  band_rows[img * ho_wo + first + (i - band_i0[band])] = r;
+  const int i0 = band_i0[band];
+  band_rows[img * ho_wo + first + (i - i0)] = r;
+  if (i == i0) atomicMax(band_max, band_i0[band + 1] - i0);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1035,17 +1041,15 @@ static sc_status pack_filters(const sc_conv_desc& d, const Geometry& g, unsigned
 static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsigned char* ws, const uint8_t* mask_dev,
                                   hipStream_t stream, BandPlan* bp_io, int32_t* kept_out) {
   BandPlan& bp = *bp_io;
-  // a private copy of the mask (the zero fill of every run reads it)
-  SC_HIP(hipMemcpyAsync(ws + g.off_mask, mask_dev, (size_t)g.mask_len, hipMemcpyDeviceToDevice, stream));
-
   // compaction
   const int period = d.mask_mode == SC_MASK_SPATIAL ? g.ho * g.wo : 0;
   int32_t* counts = reinterpret_cast<int32_t*>(ws + g.off_counts);
   int32_t* rows = reinterpret_cast<int32_t*>(ws + g.off_rows);
   int32_t* kept_dev = reinterpret_cast<int32_t*>(ws + g.off_kept);
   const int cgrid = (g.nseg + 3) / 4;
-  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
-                     g.nseg, counts);
+  // pass 1 also leaves the plan's private copy of the mask (the zero fill of every run reads it)
+  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, mask_dev, (int)g.m, period,
+                     g.nseg, counts, ws + g.off_mask, (int)g.mask_len);
   SC_HIP(hipGetLastError());
   hipLaunchKernelGGL(mask_scatter_kernel, dim3(cgrid), dim3(256), 0, stream, ws + g.off_mask, (int)g.m, period,
                      g.nseg, counts, rows, kept_dev);
@@ -1057,15 +1061,11 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
     hipLaunchKernelGGL(band_start_kernel, dim3((bp.n_bands + 1 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<int32_t*>(ws + g.off_band), bp.n_bands, bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);
     SC_HIP(hipGetLastError());
-    // kept_dev + 1 holds the per-band maximum (it sizes the accumulator blocks of the streaming kernel and picks
-    // the MFMA block shape of the others: the fullest band is the one the launch waits for)
-    SC_HIP(hipMemsetAsync(kept_dev + 1, 0, sizeof(int32_t), stream));
-    hipLaunchKernelGGL(band_max_kernel, dim3((bp.n_bands + 255) / 256), dim3(256), 0, stream,
-                       reinterpret_cast<const int32_t*>(ws + g.off_band), bp.n_bands, kept_dev + 1);
-    SC_HIP(hipGetLastError());
+    // kept_dev + 1 holds the per-band maximum (zeroed by the scatter pass, raised by band_rows_kernel)
     hipLaunchKernelGGL(band_rows_kernel, dim3((unsigned)((g.m + 255) / 256)), dim3(256), 0, stream, rows, kept_dev,
                        reinterpret_cast<const int32_t*>(ws + g.off_band),
-                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo);
+                       reinterpret_cast<int32_t*>(ws + g.off_band_rows), bp.bands_per_image, bp.bh, bp.split, g.ho, g.wo,
+                       kept_dev + 1);
     SC_HIP(hipGetLastError());
   }
 
@@ -1197,7 +1197,7 @@ sc_status sparse_conv_plan_set_input_mask(sc_plan* plan, const uint8_t* mask_in_
   int32_t* counts = reinterpret_cast<int32_t*>(plan->ws + g.off_xcounts);
   int32_t* kept_dev = counts + nseg;
   const int cgrid = (nseg + 3) / 4;
-  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, mask_in_dev, (int)pixels, period, nseg, counts);
+  hipLaunchKernelGGL(mask_count_kernel, dim3(cgrid), dim3(256), 0, stream, mask_in_dev, (int)pixels, period, nseg, counts, nullptr, 0);
   SC_HIP(hipGetLastError());
   hipLaunchKernelGGL(mask_rank_kernel, dim3(cgrid), dim3(256), 0, stream, mask_in_dev, (int)pixels, period, nseg, counts,
                      reinterpret_cast<int32_t*>(plan->ws + g.off_xrank), kept_dev);
