@@ -316,6 +316,9 @@ def main():
                     help="also time a MobileNetV2-style stack with propagated masks, with dense and with compact tensors")
     ap.add_argument("--backward", action="store_true", help="also time the backward pass of a few layers")
     ap.add_argument("--depthwise", action="store_true", help="also time the depthwise layers of a MobileNetV2-style body")
+    ap.add_argument("--profile-layer", default="",
+                    help="NAME[:BMxBN][:dense] -- only launch that layer of config 2 (s = 0.5), 3 or 5 --steps times (sparse run, "
+                         "or the dense run), optionally with a forced tile of the tiled kernel: the target of a rocprofv3 run")
     args = ap.parse_args()
 
     import torch
@@ -329,6 +332,29 @@ def main():
     if os.environ.get("SPARSE_CONV_LIBRARY"):
         B.LIB_PATH = os.environ["SPARSE_CONV_LIBRARY"]
     B.lib()
+    if args.profile_layer:
+        from paper_2309_06626_amd import runtime as R
+        parts = args.profile_layer.split(":")
+        specs = {s.name: (s, cfg) for cfg, ops in ((3, W.config3()), (5, W.config5())) for s in W.conv_specs(ops)}
+        specs[W.config2(0.5).name] = (W.config2(0.5), 2)
+        spec, cfg = specs[parts[0]]
+        ci = W.make_conv_inputs(spec, W.base_seed(cfg))
+        layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+        dense = "dense" in parts[1:]
+        for part in parts[1:]:
+            if "x" in part:
+                bm, bn = (int(v) for v in part.split("x"))
+                B.sparse_conv_plan_set_tiles(layer.plan, 0, bm, bn)
+                B.sparse_conv_plan_set_tiles(layer.plan, 1, bm, bn)
+        x, y = R.to_device(ci.x, spec.dtype), layer.new_output()
+        call = B.prepared_run(layer.plan, x, layer.bias, y, dense=dense)
+        for _ in range(args.steps):
+            call()
+        torch.cuda.synchronize()
+        which = 1 if dense else 0
+        print(f"{spec.name}: {args.steps} launches of {B.sparse_conv_plan_kernel(layer.plan, which)} "
+              f"{B.sparse_conv_plan_tiles(layer.plan, which)}, rows {spec.m if dense else ci.keep}, K {spec.k}, Cout {spec.c_out}")
+        return
     want = {int(c) for c in args.configs.split(",")}
     records = []
 
