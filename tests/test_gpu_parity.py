@@ -82,6 +82,16 @@ def test_tile_choice_follows_the_reduced_row_count():
         B.sparse_conv_plan_set_tiles(wide.plan, 0, 48, 48)
 
 
+def test_tall_tile_for_deep_layers_whose_tiles_just_overfill_the_cus():
+    """The deepest detector layer at s = 0.3: 4 480 kept rows make 280 tiles of 64 x 128 on 256 CUs; the plan takes
+    96 x 128 tiles (188: one round) for the sparse run, keeps 64 x 128 for its dense run, and matches the oracle."""
+    spec = spec_of(16, 512, 20, 20, 512, dtype="bf16", sp=0.3)
+    layer = check_layer(W.make_conv_inputs(spec, 975), sample_rows=256)
+    assert B.sparse_conv_plan_tiles(layer.plan, 0) == (96, 128, 188)
+    assert B.sparse_conv_plan_tiles(layer.plan, 1) == (64, 128, 400)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+
+
 BAND_CASES = [
     dict(n=3, cin=64, h=20, w=20, cout=64),                         # 3x3, two filter blocks
     dict(n=2, cin=32, h=23, w=17, cout=32, sp=0.3),                 # one filter block, ragged band at the bottom
