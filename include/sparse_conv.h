@@ -162,8 +162,9 @@ sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x
  * dense-layout y receives post(residual) (in SC_OUT_SCATTER_ONLY mode it is left alone, as always).  residual_dev
  * has the dtype and the row format of y (dense map, or [kept][Cout] with y_rows = SC_ROWS_COMPACT), is 16-byte
  * aligned and must not overlap y.  The sum is formed in float before the one rounding to the layer dtype.
- * Runs in the tiled kernels (never the band, row-panel or depthwise kernels, whatever the plan would pick for
- * the plain run): SC_ERR_UNSUPPORTED for depthwise plans; x_rows / y_rows as in sparse_conv_run_rows.
+ * Runs in the tiled kernels or the alternating-group band kernel (never the other band kernels, the row-panel or
+ * the depthwise kernels, whatever the plan would pick for the plain run): SC_ERR_UNSUPPORTED for depthwise plans;
+ * x_rows / y_rows as in sparse_conv_run_rows.
  * dense_conv_run_residual: the same with the identity row map (every row kept).
  */
 sc_status sparse_conv_run_residual(const sc_plan* plan, const void* x_dev, int32_t x_rows, const float* bias_dev,
@@ -205,10 +206,13 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_lds_direct",
+ * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_stream_k", "tile_lds_direct",
  * "tile_registers", "tile_row_segments", "tile_elements" or "depthwise".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
+/* The same for a launch fused with a shortcut sum (sparse_conv_run_residual / dense_conv_run_residual with dense
+ * operands): "band_alternating" or one of the "tile_..." names; NULL also for depthwise plans (no fused form). */
+const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which);
 
 /* Tuning hook: force the kernel of later runs.  (0,0) restores the automatic choice; tile_m > 0
  * selects the tiled gather kernel of that shape; tile_m < 0 selects the band kernel (band height

@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_plan_tiles.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i64)]
         L.sparse_conv_plan_kernel.restype = ctypes.c_char_p
         L.sparse_conv_plan_kernel.argtypes = [vp, i32]
+        L.sparse_conv_plan_fused_kernel.restype = ctypes.c_char_p
+        L.sparse_conv_plan_fused_kernel.argtypes = [vp, i32]
         L.sparse_conv_plan_set_tiles.restype = ctypes.c_int
         L.sparse_conv_plan_set_tiles.argtypes = [vp, i32, i32, i32]
         L.sparse_conv_plan_set_option.restype = ctypes.c_int
@@ -388,7 +390,14 @@ def sparse_conv_plan_tiles(plan: Plan, which: int) -> Tuple[int, int, int]:
 def sparse_conv_plan_kernel(plan: Plan, which: int) -> str:
     name = lib().sparse_conv_plan_kernel(plan.handle, which)
     if name is None:
-        raise ScError("sparse_conv_plan_kernel: bad plan or launch selector")
+        raise ScError(SC_ERR_UNSUPPORTED, "sparse_conv_plan_kernel (bad plan or launch selector)")
+    return name.decode()
+
+
+def sparse_conv_plan_fused_kernel(plan: Plan, which: int) -> str:
+    name = lib().sparse_conv_plan_fused_kernel(plan.handle, which)
+    if name is None:
+        raise ScError(SC_ERR_UNSUPPORTED, "sparse_conv_plan_fused_kernel (bad launch selector, or a plan without a fused form)")
     return name.decode()
 
 

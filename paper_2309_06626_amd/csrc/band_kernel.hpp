@@ -38,6 +38,10 @@ struct BandParams {
   int32_t b_bytes;           // LDS bytes of the filter slab
   int32_t x_groups;          // 16-byte groups reserved for the input slab (a zeroed KiB follows)
   int32_t relu, zero_fill, mask_spatial;
+  // fused shortcut sum (alternating-group kernel, RES instantiations only): y = post(act(conv + bias) + residual),
+  // residual in the dense layout of y; a dropped row receives post(residual)
+  const void* residual;
+  int32_t residual_relu;
 #ifdef SC_TIMING
   long long* dbg;            // development builds only: per-workgroup phase time stamps
 #endif

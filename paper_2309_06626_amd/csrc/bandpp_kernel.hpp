@@ -26,7 +26,10 @@ constexpr int kPPMaxRows = 512;     // tallest band (output rows x width)
 // LDS behind the filter slab: a zeroed KiB, 128 bias floats, then the two input slabs
 constexpr int kPPFixedLds = 1024 + 512;
 
-template <int DT, int NI, int MI, int KH, int KW, int CPP>
+// RES: the run is fused with the shortcut sum that follows it (sparse_conv_run_residual): the epilogue adds the
+// shortcut tensor in float before the one rounding, and the transferring group writes post(shortcut) instead of
+// zeros at the dropped rows.  A separate instantiation, so the plain run keeps its registers and its code.
+template <int DT, int NI, int MI, int KH, int KW, int CPP, bool RES = false>
 __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
@@ -154,16 +157,21 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
     if (p.zero_fill) {
       const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
       const v4i z = {0, 0, 0, 0};
-      unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
+      const int64_t col_at = (int64_t)n0 * EB + zc * 16;     // byte offset of this thread's group inside a row
+      unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + col_at;
+      auto fill = [&](int r) {
+        const int64_t at = (int64_t)r * p.c_out * EB;
+        if constexpr (RES) sc_store16(reinterpret_cast<v4i*>(ybase + at), dropped_row_group<DT>(p.residual, col_at + at, p.residual_relu));
+        else sc_store16(reinterpret_cast<v4i*>(ybase + at), z);
+      };
       if (zc < valid) {
 #pragma unroll
         for (int u = 0; u < ZIT; ++u) {
           const int r = g.r_lo + zr + u * RPI;
-          if (r < g.r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+          if (r < g.r_hi && mk[u] == 0) fill(r);
         }
         for (int r = g.r_lo + zr + ZIT * RPI; r < g.r_hi; r += RPI)
-          if (p.mask[p.mask_spatial ? r - g.img * ho_wo : r] == 0)
-            sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+          if (p.mask[p.mask_spatial ? r - g.img * ho_wo : r] == 0) fill(r);
       }
     }
   };
@@ -272,8 +280,12 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
         for (int ni = 0; ni < NI; ++ni) {
           const int c0 = n0 + ni * 32 + 16 * fh;
           if (c0 >= p.c_out) continue;
-          store_kept_block<DT>(acc[mi][ni], rr[mi], c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1,
-                               p.c_out, ho_wo, 0, 0, 0);
+          if constexpr (RES)
+            store_kept_block_res<DT>(acc[mi][ni], rr[mi], c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1,
+                                     p.c_out, ho_wo, 0, 0, 0, static_cast<const T*>(p.residual), p.residual_relu);
+          else
+            store_kept_block<DT>(acc[mi][ni], rr[mi], c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1,
+                                 p.c_out, ho_wo, 0, 0, 0);
         }
       }
     }
@@ -307,9 +319,9 @@ __global__ __launch_bounds__(kPPThreads) void bandpp_kernel(const BandParams p) 
 #endif
 }
 
-template <int DT, int NI, int MI, int KH, int KW, int CPP>
+template <int DT, int NI, int MI, int KH, int KW, int CPP, bool RES = false>
 hipError_t bandpp_launch(const BandParams& p, size_t lds, int grid, hipStream_t stream) {
-  auto kern = bandpp_kernel<DT, NI, MI, KH, KW, CPP>;
+  auto kern = bandpp_kernel<DT, NI, MI, KH, KW, CPP, RES>;
   static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -323,14 +335,18 @@ hipError_t bandpp_launch(const BandParams& p, size_t lds, int grid, hipStream_t 
 
 using BandPPLaunchFn = hipError_t (*)(const BandParams&, size_t, int, hipStream_t);
 
-// fn[shape 0: 3x3 window, 8 groups per pixel; 1: 3x3 window, 4 groups per pixel][NI - 1][MI - 1]
-struct BandPPTable { BandPPLaunchFn fn[2][2][2]; };
+// fn[shape 0: 3x3 window, 8 groups per pixel; 1: 3x3 window, 4 groups per pixel][NI - 1][MI - 1];
+// fn_res: the same fused with a shortcut sum
+struct BandPPTable { BandPPLaunchFn fn[2][2][2]; BandPPLaunchFn fn_res[2][2][2]; };
 const BandPPTable* bandpp_bf16();
 const BandPPTable* bandpp_f16();
 
 #define SC_BANDPP_SHAPE(DT, CPP)                                                         \
   { { bandpp_launch<DT, 1, 1, 3, 3, CPP>, bandpp_launch<DT, 1, 2, 3, 3, CPP> },          \
     { bandpp_launch<DT, 2, 1, 3, 3, CPP>, bandpp_launch<DT, 2, 2, 3, 3, CPP> } }
-#define SC_BANDPP_TABLE(DT) { { SC_BANDPP_SHAPE(DT, 8), SC_BANDPP_SHAPE(DT, 4) } }
+#define SC_BANDPP_SHAPE_RES(DT, CPP)                                                                  \
+  { { bandpp_launch<DT, 1, 1, 3, 3, CPP, true>, bandpp_launch<DT, 1, 2, 3, 3, CPP, true> },          \
+    { bandpp_launch<DT, 2, 1, 3, 3, CPP, true>, bandpp_launch<DT, 2, 2, 3, 3, CPP, true> } }
+#define SC_BANDPP_TABLE(DT) { { SC_BANDPP_SHAPE(DT, 8), SC_BANDPP_SHAPE(DT, 4) }, { SC_BANDPP_SHAPE_RES(DT, 8), SC_BANDPP_SHAPE_RES(DT, 4) } }
 
 }  // namespace sc

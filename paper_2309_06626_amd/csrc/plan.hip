@@ -838,8 +838,9 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   }
   // the band kernels address input and output by dense position: runs with a compact operand take a tiled kernel
   const BandPlan& band = dense ? pl->band_dense : pl->band;
-  // (the band and row-panel kernels have no shortcut path: a fused launch takes a tiled kernel)
-  const bool use_band = band.ok && !x_compact && !y_compact && !residual &&
+  // (of the band and row-panel kernels only the alternating-group band kernel has a shortcut path: any other
+  // fused launch takes a tiled kernel)
+  const bool use_band = band.ok && !x_compact && !y_compact && (!residual || (band.pp && !band.stream)) &&
                         (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream));
   if (use_band) {
     const BandPlan& b = band;
@@ -880,7 +881,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     const int band_px = (std::min(b.bh, g.ho) * g.wo + (b.split ? 1 : 0)) / (b.split ? 2 : 1);
     band_units(dense || identity ? (double)band_px : (double)b.max_kept, &mi_idx);
     if (b.pp) {
-      SC_HIP(pl->pp_table->fn[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
+      q.residual = residual;
+      q.residual_relu = residual_relu ? 1 : 0;
+      const auto& table = residual ? pl->pp_table->fn_res : pl->pp_table->fn;
+      SC_HIP(table[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][mi_idx](q, b.lds, b.pp_grid, stream));
       return SC_OK;
     }
     const int cpp = d.c_in / g.vec;
@@ -1328,6 +1332,17 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
   return SC_OK;
 }
 
+// name of the tiled kernel a launch of this plan takes when no band or row-panel kernel applies
+static const char* tiled_kernel_name(const sc_plan* plan, int32_t which) {
+  const Geometry& g = plan->geo;
+  const TilePick tp = pick_tile(plan, which, which ? g.m : plan->kept);
+  if (tp.splits > 1) return "tile_split_k";
+  if (stream_k_workgroups(plan, plan->table[tp.ti], which ? g.m : plan->kept)) return "tile_stream_k";
+  if (g.rowseg) return "tile_row_segments";
+  if (!g.vec_gather) return "tile_elements";
+  return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
+}
+
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1)) return nullptr;
   if (plan->geo.depthwise) return "depthwise";
@@ -1336,12 +1351,15 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
     return band.stream ? "band_stream" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
-  const TilePick tp = pick_tile(plan, which, which ? g.m : plan->kept);
-  if (tp.splits > 1) return "tile_split_k";
-  if (stream_k_workgroups(plan, plan->table[tp.ti], which ? g.m : plan->kept)) return "tile_stream_k";
-  if (g.rowseg) return "tile_row_segments";
-  if (!g.vec_gather) return "tile_elements";
-  return (g.vec_out && plan->gather_pipeline != 1) ? "tile_lds_direct" : "tile_registers";
+  return tiled_kernel_name(plan, which);
+}
+
+const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which) {
+  if (!plan || (which != 0 && which != 1) || plan->geo.depthwise) return nullptr;
+  const BandPlan& band = which ? plan->band_dense : plan->band;
+  if (band.ok && band.pp && !band.stream && (plan->forced[which] == kForceBand || plan->forced[which] == -1))
+    return "band_alternating";
+  return tiled_kernel_name(plan, which);
 }
 
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n) {

@@ -385,7 +385,7 @@ def main():
             emit(3, measure_layer(spec, W.base_seed(3), args.steps, B.SC_OUT_ZERO_FILL, library=args.library_conv))
         cs = max(args.steps // 10, 5)
         chains["config 3 (ResNet18 stack, batch 64, s=0.5)"] = chain_time(ops, W.base_seed(3), cs)
-        chains["config 3, shortcut sums fused into the convolution before them (layers 2-4)"] = \
+        chains["config 3, shortcut sums fused into the convolution before them"] = \
             chain_time(ops, W.base_seed(3), cs, fused=True)
         chains["config 3, downsample convs dense"] = chain_time(W.config3(sparse_downsample=False), W.base_seed(3), cs)
         chains["config 3, every conv through dense_conv_run"] = chain_time(ops, W.base_seed(3), cs, dense=True)

@@ -150,8 +150,9 @@ def plan_shortcut_fusions(ops, layers: Dict[str, "ConvLayer"], row_formats: Opti
     Returns {name of the sum's result: (name of the conv layer, name of the other operand, relu after the sum)}.
     A sum is fused into the operand-producing conv that comes last in the op list, if that conv's result feeds
     nothing else, the other operand exists by then, both have the row format of the result, and the layer runs
-    in a tiled kernel anyway (band and row-panel kernels have no shortcut path and are faster than a tiled
-    kernel plus a saved launch).  Host-side bookkeeping only."""
+    in a kernel with a shortcut path anyway (the tiled kernels and the alternating-group band kernel; the other
+    band kernels and the row-panel kernel have none and are faster than a tiled kernel plus a saved launch).
+    Host-side bookkeeping only."""
     fmt = row_formats or {}
     position = {op.out: i for i, op in enumerate(ops)}
     producer = {op.out: op for op in ops}
@@ -173,11 +174,15 @@ def plan_shortcut_fusions(ops, layers: Dict[str, "ConvLayer"], row_formats: Opti
                 continue                                   # the other operand is computed later
             if not (fmt.get(mine, False) == fmt.get(other, False) == fmt.get(op.out, False)):
                 continue
-            kernel = B.sparse_conv_plan_kernel(layers[conv.spec.name].plan, 1 if dense else 0)
-            if fmt.get(mine, False):
-                kernel = "tile"                            # runs with compact operands take a tiled kernel anyway
-            if not kernel.startswith("tile") or kernel == "tile_row_panel":
-                continue
+            plan = layers[conv.spec.name].plan
+            plain = B.sparse_conv_plan_kernel(plan, 1 if dense else 0)
+            # the fused launch must not be a step down from the plain one: the same band kernel, or a tiled
+            # kernel where the plain run takes one too (runs with compact operands always do)
+            if not fmt.get(mine, False):
+                if plain in ("band", "band_stream", "tile_row_panel"):
+                    continue
+                if plain == "band_alternating" and B.sparse_conv_plan_fused_kernel(plan, 1 if dense else 0) != plain:
+                    continue
             if best is None or position[mine] > position[best[0]]:
                 best = (mine, other)
         if best is not None:

@@ -63,7 +63,7 @@ def check(spec, seed, post_relu, want_kernel=None, out_mode=B.SC_OUT_ZERO_FILL, 
     B.sparse_conv_run_residual(layer.plan, x_dev, layer.bias, res_dev, y, post_relu)
     torch.cuda.synchronize()
     if want_kernel:
-        assert B.sparse_conv_plan_kernel(layer.plan, 0) in want_kernel
+        assert B.sparse_conv_plan_fused_kernel(layer.plan, 0) in want_kernel
     g, bits = rows_view(spec, R.to_host_f32(y)), rows_view(spec, R.bits_of(y))
     refr = rows_view(spec, ref)
     assert_close(g[kept], refr[kept], bound[kept], tol, "kept rows, fused shortcut")
@@ -137,6 +137,47 @@ def test_compact_rows_with_a_fused_shortcut(x_compact, post_relu):
     """The projection of an inverted-residual block: 1x1, linear, compact in and out, shortcut compact as well."""
     check(spec_of(2, 96, 14, 14, 32, k=1, mask_mode="spatial"), 1240, post_relu, y_compact=True, x_compact=x_compact)
     check(spec_of(1, 144, 9, 9, 24, k=1), 1241, post_relu, y_compact=True, x_compact=x_compact)
+
+
+BAND_CASES = [
+    dict(n=2, cin=64, h=20, w=20, cout=64),                          # 8 channel groups per pixel, two filter blocks
+    dict(n=3, cin=32, h=17, w=19, cout=32, sp=0.3),                  # 4 groups per pixel, one filter block
+    dict(n=2, cin=64, h=18, w=18, cout=128, sp=0.4),                 # two channel tiles per band
+    dict(n=2, cin=32, h=21, w=21, cout=48, k=3, s=2, p=1, sp=0.5),   # stride 2, ragged channel tile
+    dict(n=2, cin=32, h=14, w=14, cout=64, sp=0.0),                  # every row kept
+    dict(n=1, cin=64, h=12, w=12, cout=64, sp=0.95),                 # bands with almost no kept rows
+    dict(n=2, cin=64, h=16, w=16, cout=64, relu=True),               # the layer's own ReLU acts before the sum
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("post_relu", [False, True])
+@pytest.mark.parametrize("case", range(len(BAND_CASES)))
+def test_fused_shortcut_in_the_alternating_band_kernel(case, post_relu, mask_mode, dtype, monkeypatch):
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    spec = spec_of(dtype=dtype, mask_mode=mask_mode, **BAND_CASES[case])
+    layer = check(spec, 1260 + case, post_relu, want_kernel=("band_alternating",))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating" == B.sparse_conv_plan_fused_kernel(layer.plan, 1)
+
+
+@pytest.mark.parametrize("bh,n,h,w,sp", [(7, 3, 23, 20, 0.5), (5, 2, 17, 9, 0.4), (7, 40, 56, 16, 0.5), (1, 8, 100, 8, 0.5)])
+def test_fused_shortcut_in_the_alternating_band_kernel_split_bands_and_many_steps(bh, n, h, w, sp, monkeypatch):
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", f"{bh},split" if bh > 1 else str(bh))
+    spec = spec_of(n, 64 if bh > 1 else 32, h, w, 64, dtype="bf16", sp=sp)
+    check(spec, 1280 + bh + h, True, want_kernel=("band_alternating",))
+
+
+def test_fused_shortcut_in_the_alternating_band_kernel_scatter_only(monkeypatch):
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "alternating")
+    check(spec_of(2, 64, 20, 20, 64), 1290, False, want_kernel=("band_alternating",), out_mode=B.SC_OUT_SCATTER_ONLY)
+
+
+def test_other_band_kernels_hand_a_fused_launch_to_the_tiled_kernel():
+    spec = spec_of(2, 64, 20, 20, 64)             # few bands: the one-band-per-workgroup kernel
+    layer = check(spec, 1291, True, want_kernel=("tile_lds_direct",))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 
 
 def test_refusals():
