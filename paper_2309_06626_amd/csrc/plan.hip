@@ -1080,10 +1080,14 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
   bp.max_kept = host_vals[1];
 
   if (d.sparsity >= 0.0f) {
-    // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up)
-    int64_t want = (int64_t)std::floor((1.0 - (double)d.sparsity) * (double)g.mask_len + 0.5);
+    // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up).  The descriptor carries
+    // the ratio as a float: where the product falls on a half within that float's rounding interval (0.9 of 135
+    // rows), either neighbour is the count the caller's own ratio demands, and both are accepted.
+    const double sp = (double)d.sparsity, eps = std::ldexp(std::fabs(sp), -24) + 1e-12;
+    const int64_t want_hi = (int64_t)std::floor((1.0 - (sp - eps)) * (double)g.mask_len + 0.5);
+    const int64_t want_lo = (int64_t)std::floor((1.0 - (sp + eps)) * (double)g.mask_len + 0.5);
     int64_t have = d.mask_mode == SC_MASK_ROW ? host_vals[0] : host_vals[0] / d.n;
-    if (want != have) return SC_ERR_MASK_COUNT;
+    if (have < want_lo || have > want_hi) return SC_ERR_MASK_COUNT;
   }
   return SC_OK;
 }

@@ -445,6 +445,24 @@ def test_mask_count_must_match_the_sparsity_ratio():
     R.ConvLayer(spec, ci.w, ci.bias, bad, check_count=False)      # a negative ratio disables the check
 
 
+def test_mask_count_at_a_half_within_the_float_rounding_of_the_ratio():
+    """(1 - 0.9) * 135 is 13.5 up to the rounding of 0.9: in double the count is 13, from the descriptor's float 14.  A
+    mask with either count is the one the caller's ratio demands; 12 and 15 are not."""
+    spec = spec_of(1, 64, 7, 13, 16, k=3, p=3, d=2, dtype="bf16", sp=0.9, mask_mode="spatial")
+    assert spec.ho * spec.wo == 135
+    ci = W.make_conv_inputs(spec, 24)
+    assert int(ci.mask.sum()) == 13
+    for kept, ok in ((12, False), (13, True), (14, True), (15, False)):
+        mask = np.zeros(135, np.uint8)
+        mask[:kept] = 1
+        if ok:
+            R.ConvLayer(spec, ci.w, ci.bias, mask)
+        else:
+            with pytest.raises(B.ScError) as e:
+                R.ConvLayer(spec, ci.w, ci.bias, mask)
+            assert e.value.status == B.SC_ERR_MASK_COUNT
+
+
 @pytest.mark.parametrize("m", [1, 63, 64, 65, 1023, 1024, 1025, 4096, 100352, 802816])
 def test_compaction_sizes(m):
     # a0 on its own: m one-pixel "images" of a pointwise layer; the row list must equal the oracle's
