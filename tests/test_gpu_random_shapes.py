@@ -78,3 +78,46 @@ def test_random_layers_with_the_automatic_kernel_choice(seed):
                 check_depthwise(spec, 7000 + 100 * seed + it, rnd.choice([B.SC_OUT_ZERO_FILL, B.SC_OUT_SCATTER_ONLY]))
             else:
                 check_compact_input(spec, 7000 + 100 * seed + it, in_sparsity=rnd.choice([0.0, 0.4, 0.6]))
+
+
+@pytest.mark.parametrize("seed", [5, 13])
+def test_random_backward_passes_compact_outputs_and_generated_masks(seed):
+    """The widened rows under the same treatment: gradients (strides 1-3, dilation, ragged channel counts in multiples of 8),
+    compact outputs of pointwise and 3x3 layers, and masks from random scores (tie-heavy ones among them)."""
+    import numpy as np
+
+    import test_gpu_backward as TB
+    import test_gpu_compact as TC
+    import test_gpu_mask as TM
+    from oracle import mask_oracle as MO
+
+    rnd = random.Random(seed)
+    for it in range(45):
+        kind = rnd.choice(["bwd", "bwd", "compact", "mask"])
+        if kind == "bwd":
+            k = rnd.choice([1, 3, 3, 5]); s = rnd.choice([1, 1, 2, 3]); d = rnd.choice([1, 1, 2]) if k > 1 else 1
+            cin, cout = 8 * rnd.randint(1, 20), 8 * rnd.randint(1, 24)
+            lo = max(5, d * (k - 1) + 1)
+            spec = TB.spec_of(rnd.randint(1, 4), cin, rnd.randint(lo, 24), cout, k=k, s=s, d=d, dtype=rnd.choice(["bf16", "f16"]),
+                              sparsity=rnd.choice([0.0, 0.3, 0.5, 0.8]), relu=rnd.choice([True, False]),
+                              mask_mode=rnd.choice(["row", "spatial"]), w=rnd.randint(lo, 24))
+            print(f"seed {seed} case {it}: backward {spec}", flush=True)
+            TB.run_backward(spec, 9000 + 100 * seed + it)
+        elif kind == "compact":
+            k = rnd.choice([1, 1, 3, 3])
+            cin = rnd.choice([8, 16, 32, 48, 64, 96, 128, 192, 256]); cout = rnd.choice([16, 32, 48, 64, 96, 128, 160, 192, 576])
+            spec = TC.layer_spec("c", rnd.randint(1, 5), cin, rnd.randint(5, 30), cout, k=k, s=rnd.choice([1, 1, 2]),
+                                 dtype=rnd.choice(["bf16", "f16", "f32"]), sparsity=rnd.choice([0.0, 0.3, 0.5, 0.9]),
+                                 mask_mode=rnd.choice(["row", "spatial"]), w=rnd.randint(5, 30))
+            print(f"seed {seed} case {it}: compact output {spec}", flush=True)
+            TC.check_compact_output(spec, 9000 + 100 * seed + it)
+        else:
+            ho, wo = rnd.randint(1, 90), rnd.randint(1, 90)
+            ry, rx = rnd.choice([1, 1, 2, 3, 4, 8]), rnd.choice([1, 1, 2, 3, 4, 8])
+            h, w = ho * ry + rnd.randint(0, ry - 1), wo * rx + rnd.randint(0, rx - 1)
+            s = rnd.choice([0.0, 0.1, 0.25, 0.5, 0.7, 0.93, 1.0])
+            score = W.gen_score(h, w, seed=9000 + 100 * seed + it)
+            if rnd.random() < 0.3:
+                score = np.round(score * rnd.choice([2, 5, 17])).astype(np.float32)     # a handful of levels: ties everywhere
+            print(f"seed {seed} case {it}: mask {h}x{w} -> {ho}x{wo} s={s}", flush=True)
+            assert np.array_equal(TM.gpu_mask(score, ho, wo, s), MO.layer_mask(score, ho, wo, TM.f32(s)))
