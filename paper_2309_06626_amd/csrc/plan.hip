@@ -675,12 +675,17 @@ static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_ou
   const int64_t wg_96x128 = ((rows + 95) / 96) * ((c_out + 127) / 128);
   if (rowseg) { bm = 64; bn = c_out <= 32 ? 32 : 64; if (c_out <= 32) bm = 128; }   // window-row gather (stems): measured best
   else if (!vec_gather) { bm = 128; bn = 64; }       // element gather: fewer, fatter workgroups
-  else if (c_out <= 32) { bm = 128; bn = 32; }
+  // (few rows: four times the workgroups with the wide tile, three quarters of it idle, still wins -- 192 -> 32 channels
+  // on 14 x 14 and 7 x 7 maps, batch 64: 5.4 -> 4.8 us sparse, 4.7 -> 3.9 us dense)
+  else if (c_out <= 32) { bm = rows <= 16384 ? 32 : 128; bn = rows <= 16384 ? 128 : 32; }
   // a few 64 x 128 tiles more than CUs (two on some CUs, one on the rest) but at most one 96 x 128 tile per CU:
   // one round of the taller tile (detector y8, 4 480 kept rows: 280 -> 188 tiles, 38.4 -> 35.6 us; y7 22.2 -> 21.2 us)
   else if (deep_16bit && c_out % 128 == 0 && k_tiles >= 32 && wg_64x128 > 256 && wg_64x128 <= 320 && wg_96x128 <= 256) { bm = 96; bn = 128; }
   else if (c_out % 128 == 0 && wg_64x128 >= (k_tiles >= 32 ? 256 : 384)) { bm = 64; bn = 128; }   // long K: one per CU is enough
   else if (rows <= 8192 && c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
+  // (very long GEMMs whose channel count is no multiple of 128: the taller tile halves the filter re-reads --
+  // 576 -> 160 channels on a 56 x 56 map, batch 64, dense run: 102.6 -> 91.5 us)
+  else if (rows >= 150000 && c_out > 64) { bm = 128; bn = 64; }
   else { bm = 64; bn = 64; }
   for (int i = 0; i < count; ++i)
     if (tab[i].bm == bm && tab[i].bn == bn) return i;
