@@ -302,7 +302,7 @@ __global__ void maxpool_nhwc_vec8_kernel(const T* __restrict__ x, T* __restrict_
 }
 
 template <typename T, bool RELU>
-__global__ void add_vec8_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t groups) {
+__global__ void add_vec8_kernel(const T* a, const T* b, T* y, int64_t groups) {   // y may alias a or b
   typedef T vec8 __attribute__((ext_vector_type(8)));
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -319,7 +319,7 @@ __global__ void add_vec8_kernel(const T* __restrict__ a, const T* __restrict__ b
 }
 
 template <typename T, bool RELU>
-__global__ void add_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ y, int64_t count) {
+__global__ void add_kernel(const T* a, const T* b, T* y, int64_t count) {   // y may alias a or b
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; i < count; i += stride) {
@@ -824,7 +824,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     // zero-fill runs walk the dense rows and look at the mask; the others walk the kept rows
     q.row_idx = (identity || zero_fill) ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
     q.mask = identity ? nullptr : pl->ws + g.off_mask;
-    q.items = q.row_idx ? rows : g.m;
+    // Only the zero-fill walk visits all M dense rows.  Every other run visits `rows` items: M for a dense run or
+    // a mask that keeps everything, the kept rows otherwise -- through the row list, or as the identity over the
+    // kept rows when both operands are compact (x and y then hold kept * C elements, not M * C).
+    q.items = zero_fill ? g.m : rows;
     q.zero_fill = zero_fill ? 1 : 0;
     q.rank = (compact && y_compact) ? reinterpret_cast<const int32_t*>(pl->ws + g.off_band_rows) : nullptr;
     q.n = d.n; q.ho = g.ho;
@@ -835,7 +838,13 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
     q.x_compact = (compact && x_compact) || ranked_input ? 1 : 0;
     q.y_compact = compact && y_compact ? 1 : 0;
-    q.x_rank = ranked_input ? reinterpret_cast<const int32_t*>(pl->ws + g.off_xrank) : nullptr;
+    // A 1x1 layer whose compact input feeds a zero-filled dense output walks the dense rows, so the item number is
+    // no longer the row of x: a kept pixel finds its row in the layer's own rank table (input and output pixels
+    // coincide for such a window; dropped pixels leave before they read).
+    const bool own_rank_input = compact && x_compact && !ranked_input && zero_fill;
+    q.x_rank = ranked_input     ? reinterpret_cast<const int32_t*>(pl->ws + g.off_xrank)
+               : own_rank_input ? reinterpret_cast<const int32_t*>(pl->ws + g.off_band_rows)
+                                : nullptr;
     magic_div((uint32_t)q.ho_wo, &q.div_howo_mul, &q.div_howo_shift);
     magic_div((uint32_t)q.wo, &q.div_wo_mul, &q.div_wo_shift);
     SC_HIP(depthwise_launch(d.dtype == SC_BF16 ? kBF16 : d.dtype == SC_F16 ? kF16 : kF32, q, stream));

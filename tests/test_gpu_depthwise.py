@@ -84,6 +84,55 @@ def test_depthwise_sparsities_and_modes(sparsity):
     check_depthwise(dw_spec(1, 16, 9, 9, sparsity=0.3, relu=False, bias=False), 421)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("mask_mode", ["row", "spatial"])
+@pytest.mark.parametrize("out_mode", [B.SC_OUT_ZERO_FILL, B.SC_OUT_SCATTER_ONLY])
+def test_pointwise_depthwise_layer_with_compact_operands(dtype, mask_mode, out_mode):
+    """1x1 window, stride 1, no padding: the window is the pixel itself, so the layer takes the kept rows of its
+    input as they are.  Every combination of row formats; the compact buffers hold exactly the kept rows plus guard
+    rows of NaN that no launch may read from or write to."""
+    spec = dw_spec(3, 24, 9, 7, k=1, dtype=dtype, sparsity=0.6, mask_mode=mask_mode)
+    ci = W.make_conv_inputs(spec, 461)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, out_mode=out_mode)
+    rm = row_mask(spec, ci.mask)
+    kept = rm == 1
+    n_kept = int(kept.sum())
+    assert 0 < n_kept < spec.m
+    ref, absum = oracle.masked_depthwise_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask, want_absum=True)
+    ref, absum = rows_view(spec, ref), rows_view(spec, absum)
+    via_compact = oracle.masked_depthwise_conv2d_compact(spec, oracle.to_compact(ci.x, rm), ci.w, ci.bias, ci.mask,
+                                                         x_mask=ci.mask, y_compact=True)
+    assert np.array_equal(via_compact, ref[kept])
+    td = B.TORCH_DTYPE[dtype]
+    D, C = B.SC_ROWS_DENSE, B.SC_ROWS_COMPACT
+    # the compact input: kept rows, then guard rows whose NaN would show in any result that read them
+    xc = torch.empty((n_kept + 3, spec.c_in), dtype=td, device="cuda:0").fill_(float("nan"))
+    xc[:n_kept] = R.to_device(np.ascontiguousarray(ci.x.reshape(-1, spec.c_in)[kept]), dtype)
+    x = R.to_device(ci.x, dtype)
+    tol = TOL[dtype]
+    # reference bits: the dense-format run
+    sentinel = float("nan") if out_mode == B.SC_OUT_ZERO_FILL else 7.0
+    y = layer.new_output()
+    y.fill_(sentinel)
+    layer.sparse(x, y)
+    torch.cuda.synchronize()
+    bits = rows_view(spec, R.bits_of(y))
+    assert_close(rows_view(spec, R.to_host_f32(y))[kept], ref[kept], absum[kept], tol, "1x1 depthwise")
+    # compact in, dense out
+    y2 = layer.new_output()
+    y2.fill_(sentinel)
+    B.sparse_conv_run_rows(layer.plan, xc[:n_kept], layer.bias, y2, C, D)
+    torch.cuda.synchronize()
+    assert np.array_equal(rows_view(spec, R.bits_of(y2)), bits)
+    # dense in, compact out and compact in, compact out: the kept rows and nothing behind them
+    for x_in, fmt in ((x, D), (xc[:n_kept], C)):
+        buf = torch.empty((n_kept + 3, spec.c_out), dtype=td, device="cuda:0").fill_(float("nan"))
+        B.sparse_conv_run_rows(layer.plan, x_in, layer.bias, buf[:n_kept], fmt, C)
+        torch.cuda.synchronize()
+        assert np.array_equal(R.bits_of(buf[:n_kept]), bits[kept])
+        assert np.isnan(R.to_host_f32(buf[n_kept:])).all(), "nothing may be written behind the last kept row"
+
+
 def test_depthwise_all_rows_dropped():
     spec = dw_spec(1, 16, 8, 8)
     ci = W.make_conv_inputs(spec, 431)
