@@ -310,6 +310,24 @@ sc_status sparse_mask_generate(const float* score_dev, int32_t in_h, int32_t in_
                                void* hip_stream);
 
 /*
+ * sparse_mask_generate for callers that cannot allocate device memory and so have no workspace to hand over: code
+ * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * two kernels and bit-identical masks; the scratch (one 64-bit key per layer pixel) is a fixed array inside the
+ * library's code object instead of the caller's workspace.
+ *   - at most SC_STATIC_MASK_PIXELS layer pixels (ho * wo); a larger map returns SC_ERR_WORKSPACE and launches nothing;
+ *   - the array (2 MiB) exists once per GPU the library runs on and is held until the process ends; the first call
+ *     on a device asks the runtime for its address (no allocation), so make that call outside a graph capture;
+ *   - calls no hipMalloc / hipFree or other allocating routine and never synchronises;
+ *   - every call on one GPU uses that GPU's one array: calls whose work overlaps on a GPU (two streams, two threads)
+ *     race on it and give wrong masks -- order them on one stream or with events.  Nothing needs clearing between
+ *     calls: the first kernel overwrites every key the second reads.
+ * Errors otherwise as for sparse_mask_generate (SC_ERR_NULL, SC_ERR_BAD_SHAPE, SC_ERR_HIP).
+ */
+#define SC_STATIC_MASK_PIXELS (1 << 18)
+sc_status sparse_mask_generate_static(const float* score_dev, int32_t in_h, int32_t in_w, int32_t ho, int32_t wo,
+                                      float sparsity, uint8_t* mask_dev, void* hip_stream);
+
+/*
  * Glue operators of the test networks (ResNet- and MobileNet-style stacks), NHWC device tensors of `dtype`.
  * They are not part of the paper's method; they only connect conv layers in network runs.
  *   sc_maxpool2d_nhwc: window k, stride s, zero-free padding p (padded taps never win).

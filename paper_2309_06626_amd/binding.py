@@ -120,6 +120,8 @@ def lib() -> ctypes.CDLL:
         L.sparse_mask_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.sparse_mask_generate.restype = ctypes.c_int
         L.sparse_mask_generate.argtypes = [vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
+        L.sparse_mask_generate_static.restype = ctypes.c_int
+        L.sparse_mask_generate_static.argtypes = [vp, i32, i32, i32, i32, ctypes.c_float, vp, vp]
         _lib = L
     return _lib
 
@@ -517,6 +519,24 @@ def sparse_mask_generate(score: torch.Tensor, ho: int, wo: int, sparsity: float,
     _check(lib().sparse_mask_generate(_dev_ptr(score, "score"), in_h, in_w, ho, wo, float(sparsity),
                                       _dev_ptr(mask, "mask"), _dev_ptr(workspace, "workspace"), workspace.numel(),
                                       _stream_handle(stream)), "sparse_mask_generate")
+    return mask
+
+
+SC_STATIC_MASK_PIXELS = 1 << 18
+
+
+def sparse_mask_generate_static(score: torch.Tensor, ho: int, wo: int, sparsity: float, mask: torch.Tensor,
+                                stream=None) -> torch.Tensor:
+    """sparse_mask_generate without a workspace: the library's fixed scratch array holds the keys.  The caller
+    passes the output tensor; nothing is allocated here or in the library."""
+    if score.dim() != 2 or score.dtype != torch.float32:
+        raise ValueError("score must be a 2-D float32 tensor")
+    in_h, in_w = score.shape
+    if mask.numel() != ho * wo or mask.dtype != torch.uint8:
+        raise ValueError("mask must hold ho*wo bytes")
+    _check(lib().sparse_mask_generate_static(_dev_ptr(score, "score"), in_h, in_w, ho, wo, float(sparsity),
+                                             _dev_ptr(mask, "mask"), _stream_handle(stream)),
+           "sparse_mask_generate_static")
     return mask
 
 

@@ -16,6 +16,7 @@
 
 #include <cmath>
 #include <cstdint>
+#include <mutex>
 
 namespace sc {
 
@@ -239,6 +240,58 @@ static inline int64_t kept_of(double sparsity, int64_t n) {
   return (int64_t)std::floor((1.0 - sparsity) * (double)n + 0.5);
 }
 
+static sc_status check_mask_args(int32_t in_h, int32_t in_w, int32_t ho, int32_t wo, float sparsity) {
+  if (in_h < 1 || in_w < 1 || ho < 1 || wo < 1 || ho > in_h || wo > in_w) return SC_ERR_BAD_SHAPE;
+  if ((int64_t)in_h * in_w > (1 << 26)) return SC_ERR_BAD_SHAPE;
+  if (!(sparsity >= 0.0f && sparsity <= 1.0f)) return SC_ERR_BAD_SHAPE;   // also rejects NaN
+  return SC_OK;
+}
+
+// The two launches of one mask; `keys` is device scratch of ho * wo 64-bit words, every one of which the first
+// kernel writes before the second reads it (nothing has to be cleared between calls).
+static sc_status launch_mask(const float* score_dev, int32_t in_h, int32_t in_w, int32_t ho, int32_t wo, float sparsity,
+                             uint8_t* mask_dev, unsigned long long* keys, hipStream_t stream) {
+  const int n = ho * wo;
+  const int n_drop = n - (int)kept_of((double)sparsity, n);
+  const int rh = in_h / ho, rw = in_w / wo;
+  if ((int64_t)rh * rw >= 64)
+    hipLaunchKernelGGL(score_key_wave_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, score_dev, in_w,
+                       rh, rw, ho, wo, keys);
+  else
+    hipLaunchKernelGGL(score_key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, score_dev, in_w,
+                       rh, rw, ho, wo, keys);
+  hipLaunchKernelGGL(mask_select_kernel, dim3(1), dim3(kSelThreads), 0, stream, (const unsigned long long*)keys, n,
+                     n_drop, mask_dev);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) { note_hip_error((int32_t)e); return SC_ERR_HIP; }
+  return SC_OK;
+}
+
+// Scratch of the entry point that allocates nothing: one array per GPU inside the library's code object, held
+// until the process ends.  On the host the array's name is only a handle; the device address comes from
+// hipGetSymbolAddress, asked once per device with that device current, and is what the kernels receive.
+constexpr int kStaticMaskPixels = SC_STATIC_MASK_PIXELS;      // 512 x 512 layer pixels: 2 MiB of keys
+constexpr int kMostDevices = 64;
+static __device__ __align__(256) unsigned long long scratch[kStaticMaskPixels];
+static unsigned long long* g_scratch_ptr[kMostDevices];   // per device, null until asked
+static std::mutex g_scratch_lock;
+
+static sc_status static_scratch(unsigned long long** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { note_hip_error((int32_t)e); return SC_ERR_HIP; }
+  if (dev < 0 || dev >= kMostDevices) return SC_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) { note_hip_error((int32_t)e); return SC_ERR_HIP; }
+    g_scratch_ptr[dev] = static_cast<unsigned long long*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return SC_OK;
+}
+
 }  // namespace sc
 
 extern "C" {
@@ -255,30 +308,27 @@ sc_status sparse_mask_generate(const float* score_dev, int32_t in_h, int32_t in_
                                float sparsity, uint8_t* mask_dev, void* workspace_dev, size_t workspace_bytes,
                                void* hip_stream) {
   if (!score_dev || !mask_dev || !workspace_dev) return SC_ERR_NULL;
-  if (in_h < 1 || in_w < 1 || ho < 1 || wo < 1 || ho > in_h || wo > in_w) return SC_ERR_BAD_SHAPE;
-  if ((int64_t)in_h * in_w > (1 << 26)) return SC_ERR_BAD_SHAPE;
-  if (!(sparsity >= 0.0f && sparsity <= 1.0f)) return SC_ERR_BAD_SHAPE;   // also rejects NaN
+  sc_status s = sc::check_mask_args(in_h, in_w, ho, wo, sparsity);
+  if (s != SC_OK) return s;
   size_t need = 0;
-  sc_status s = sparse_mask_workspace_bytes(ho, wo, &need);
+  s = sparse_mask_workspace_bytes(ho, wo, &need);
   if (s != SC_OK) return s;
   if (workspace_bytes < need) return SC_ERR_WORKSPACE;
   if ((uintptr_t)workspace_dev & 7) return SC_ERR_ALIGN;
-  const int n = ho * wo;
-  const int n_drop = n - (int)sc::kept_of((double)sparsity, n);
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  unsigned long long* keys = static_cast<unsigned long long*>(workspace_dev);
-  const int rh = in_h / ho, rw = in_w / wo;
-  if ((int64_t)rh * rw >= 64)
-    hipLaunchKernelGGL(sc::score_key_wave_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, score_dev, in_w,
-                       rh, rw, ho, wo, keys);
-  else
-    hipLaunchKernelGGL(sc::score_key_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, score_dev, in_w,
-                       rh, rw, ho, wo, keys);
-  hipLaunchKernelGGL(sc::mask_select_kernel, dim3(1), dim3(sc::kSelThreads), 0, stream,
-                     (const unsigned long long*)keys, n, n_drop, mask_dev);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
-  return SC_OK;
+  return sc::launch_mask(score_dev, in_h, in_w, ho, wo, sparsity, mask_dev,
+                         static_cast<unsigned long long*>(workspace_dev), static_cast<hipStream_t>(hip_stream));
+}
+
+sc_status sparse_mask_generate_static(const float* score_dev, int32_t in_h, int32_t in_w, int32_t ho, int32_t wo,
+                                      float sparsity, uint8_t* mask_dev, void* hip_stream) {
+  if (!score_dev || !mask_dev) return SC_ERR_NULL;
+  sc_status s = sc::check_mask_args(in_h, in_w, ho, wo, sparsity);
+  if (s != SC_OK) return s;
+  if ((int64_t)ho * wo > sc::kStaticMaskPixels) return SC_ERR_WORKSPACE;   // the fixed scratch array is too small
+  unsigned long long* keys = nullptr;
+  s = sc::static_scratch(&keys);
+  if (s != SC_OK) return s;
+  return sc::launch_mask(score_dev, in_h, in_w, ho, wo, sparsity, mask_dev, keys, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"
