@@ -164,7 +164,7 @@ sc_status sparse_conv_run_rows(const sc_plan* plan, const void* x_dev, int32_t x
  * dense-layout y receives post(residual) (in SC_OUT_SCATTER_ONLY mode it is left alone, as always).  residual_dev
  * has the dtype and the row format of y (dense map, or [kept][Cout] with y_rows = SC_ROWS_COMPACT), is 16-byte
  * aligned and must not overlap y.  The sum is formed in float before the one rounding to the layer dtype.
- * Runs in the tiled kernels or the alternating-group band kernel (never the other band kernels, the row-panel or
+ * Runs in the tiled kernels, the alternating-group or the tap-pipelined band kernel (never the other band kernels, the row-panel or
  * the depthwise kernels, whatever the plan would pick for the plain run): SC_ERR_UNSUPPORTED for depthwise plans;
  * x_rows / y_rows as in sparse_conv_run_rows.
  * dense_conv_run_residual: the same with the identity row map (every row kept).
@@ -208,7 +208,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_stream", "tile_row_panel", "tile_split_k", "tile_stream_k", "tile_lds_direct",
+ * "band_alternating", "band_tap", "band_stream", "tile_row_panel", "tile_split_k", "tile_stream_k", "tile_lds_direct",
  * "tile_registers", "tile_row_segments", "tile_elements" or "depthwise".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
@@ -224,10 +224,13 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
 /* Environment (read by sparse_conv_plan; tuning and tests only):
  *   SPARSE_CONV_BAND_HEIGHT=<rows>               fixes the band height of the streaming and of the
  *                                                alternating-group band kernels (automatic otherwise)
- *   SPARSE_CONV_BAND_KERNEL=single|alternating   band kernel with one band per workgroup, or the
- *                                                persistent one whose two wavefront groups alternate
- *                                                between transfer and matrix work (3x3 windows, 16-bit
- *                                                types, 32 or 64 input channels); automatic otherwise */
+ *   SPARSE_CONV_BAND_KERNEL=single|alternating|tap|no-tap
+ *                                                band kernel with one band per workgroup; the persistent one
+ *                                                whose two wavefront groups alternate between transfer and
+ *                                                matrix work; the one whose filters arrive window row by
+ *                                                window row under the matrix work (both: 3x3 windows, 16-bit
+ *                                                types, 32 or 64 input channels); the automatic choice
+ *                                                without the last; automatic otherwise */
 
 /* Tuning hook: SC_OPT_GATHER_PIPELINE selects how the tiled gather kernel moves its K tiles:
  * 0 = automatic, 1 = global -> registers -> LDS, 2 = global -> LDS directly (NHWC with 16-byte

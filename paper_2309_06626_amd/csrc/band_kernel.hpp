@@ -42,6 +42,7 @@ struct BandParams {
   // residual in the dense layout of y; a dropped row receives post(residual)
   const void* residual;
   int32_t residual_relu;
+  uint32_t div_wo_mul, div_wo_shift;   // n / wo as (n * mul) >> shift (tap-pipelined kernel)
 #ifdef SC_TIMING
   long long* dbg;            // development builds only: per-workgroup phase time stamps
 #endif

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -13,6 +14,7 @@
 #include "band_kernel.hpp"
 #include "bandpp_kernel.hpp"
 #include "bandstream_kernel.hpp"
+#include "bandtap_kernel.hpp"
 #include "conv_params.hpp"
 #include "igemm_buf_kernel.hpp"
 #include "igemm_streamk_kernel.hpp"
@@ -473,6 +475,7 @@ struct BandPlan {
   bool ok;
   bool stream;       // filters streamed through an LDS ring instead of resident
   bool pp;           // persistent workgroups, two wavefront groups alternating between transfer and MFMA
+  bool tap;          // one band per workgroup of eight wavefronts, filters arriving tap by tap under the MFMAs
   int pp_grid;       // workgroups of that kernel
   int max_kept;      // most kept rows in one band
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
@@ -493,6 +496,9 @@ static double band_units(double cnt, int* mi_idx) {
   return std::min(units1, units2);
 }
 
+static bool tap_is_automatic(const sc_conv_desc& d, const Geometry& g, const BandPlan& tp, int64_t rows);
+static int device_cus();
+
 // `rows`: the rows the run is expected to contract (the kept rows of a sparse run, M of a dense one).
 static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows) {
   BandPlan bp;
@@ -509,10 +515,47 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows
   // Alternating-group kernel (persistent workgroups, filters resident, two input slabs): 3x3
   // windows of 16-bit operands with 4 or 8 channel groups per pixel.  It pays once a workgroup
   // walks several bands (measured on MI355X: from three steps on); with fewer, one band per
-  // workgroup is faster.  SPARSE_CONV_BAND_KERNEL=single|alternating overrides (tuning and tests).
+  // workgroup is faster.  SPARSE_CONV_BAND_KERNEL=single|alternating|tap|no-tap overrides (tuning and tests).
   const char* variant = std::getenv("SPARSE_CONV_BAND_KERNEL");
   const bool want_single = variant && std::strcmp(variant, "single") == 0;
   const bool want_pp = variant && std::strcmp(variant, "alternating") == 0;
+  const bool want_tap = variant && std::strcmp(variant, "tap") == 0;
+  const bool no_tap = variant && std::strcmp(variant, "no-tap") == 0;      // the automatic choice among the other kernels
+  // Tap-pipelined kernel: 3x3 windows of 16-bit operands with 4 or 8 channel groups per pixel, one band per
+  // workgroup; the tallest band that fits LDS and 512 rows and costs the fewest rounds of workgroups.
+  if (!want_single && !want_pp && !no_tap && d.kh == 3 && d.kw == 3 && d.dtype != SC_F32 &&
+      (d.c_in / g.vec == 8 || d.c_in / g.vec == 4)) {
+    BandPlan tp = bp;
+    tp.ni = d.c_out <= 32 ? 1 : 2;
+    tp.ni_idx = tp.ni - 1;
+    tp.n_tiles = (d.c_out + 32 * tp.ni - 1) / (32 * tp.ni);
+    tp.b_bytes = (size_t)9 * 32 * tp.ni * (d.c_in / g.vec) * 16;
+    const char* env = std::getenv("SPARSE_CONV_BAND_HEIGHT");
+    const int forced_bh = env ? std::atoi(env) : 0;
+    double best = 1e300;
+    for (int bh = 1; bh <= g.ho; ++bh) {
+      const int64_t ih = (int64_t)(bh - 1) * d.stride_h + (int64_t)2 * d.dil_h + 1;
+      const size_t xbytes = align_up((size_t)ih * d.w * d.c_in * eb, 1024);
+      if (tp.b_bytes + kTapFixedLds + xbytes > kLdsLimit) break;
+      if ((int64_t)bh * g.wo > kTapMaxRows) break;
+      const int bpi = (g.ho + bh - 1) / bh;
+      const int64_t nb = (int64_t)d.n * bpi * tp.n_tiles;
+      const double rounds = std::ceil((double)nb / (double)device_cus());
+      const double cost = rounds * ((double)xbytes + (double)tp.b_bytes + 64.0 * bh * g.wo);
+      const bool take = forced_bh > 0 ? bh == forced_bh : cost <= best;
+      if (take) {
+        best = cost;
+        tp.ok = true;
+        tp.tap = true;
+        tp.bh = bh;
+        tp.bands_per_image = bpi;
+        tp.n_bands = d.n * bpi;
+        tp.x_bytes = xbytes;
+        tp.lds = tp.b_bytes + kTapFixedLds + xbytes;
+      }
+    }
+    if (tp.ok && (want_tap || tap_is_automatic(d, g, tp, rows))) return tp;
+  }
   if (!want_single && d.kh == 3 && d.kw == 3 && d.dtype != SC_F32 &&
       (d.c_in / g.vec == 8 || d.c_in / g.vec == 4)) {
     BandPlan pp = bp;
@@ -632,6 +675,30 @@ static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows
   return bp;
 }
 
+// Compute units of the current device (256 on MI355X), asked once per process.
+static int device_cus() {
+  static std::atomic<int> cached{0};
+  int v = cached.load();
+  if (v > 0) return v;
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+    (void)hipGetLastError();
+    cus = 256;
+  }
+  cached.store(cus);
+  return cus;
+}
+
+// When the tap-pipelined kernel is the automatic choice: one channel tile (two would transfer every band twice) and
+// at most one workgroup per compute unit.  Measured on MI355X, sparse run / dense run in us: ResNet18 stage-1 layer
+// at batch 32, s = 0.5: 8.7 / 11.4 against 10.9 / 13.9 with the alternating-group kernel (s = 0.25: 10.5 against
+// 13.6 with one band per workgroup); detector y2: 10.5 / 11.6 against 17.4 / 17.2; at batch 64 (two rounds of
+// workgroups, nothing to overlap the second round's transfers with) 17.8 against 16.6 for persistent workgroups.
+static bool tap_is_automatic(const sc_conv_desc& d, const Geometry& g, const BandPlan& tp, int64_t rows) {
+  (void)d; (void)g; (void)rows;
+  return tp.n_tiles == 1 && (int64_t)tp.n_bands * tp.n_tiles <= device_cus();
+}
+
 }  // namespace sc
 
 using namespace sc;
@@ -644,6 +711,7 @@ struct sc_plan {
   const BandTable* band_table;
   const BandStreamTable* stream_table;
   const BandPPTable* pp_table;
+  const BandTapTable* tap_table;
   unsigned char* ws;
   int64_t kept;
   const KernelEntry* table;
@@ -854,7 +922,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const BandPlan& band = dense ? pl->band_dense : pl->band;
   // (of the band and row-panel kernels only the alternating-group band kernel has a shortcut path: any other
   // fused launch takes a tiled kernel)
-  const bool use_band = band.ok && !x_compact && !y_compact && (!residual || (band.pp && !band.stream)) &&
+  const bool use_band = band.ok && !x_compact && !y_compact && (!residual || ((band.pp || band.tap) && !band.stream)) &&
                         (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream));
   if (use_band) {
     const BandPlan& b = band;
@@ -878,6 +946,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     q.relu = d.relu;
     q.zero_fill = zero_fill ? 1 : 0;
     q.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
+    magic_div((uint32_t)g.wo, &q.div_wo_mul, &q.div_wo_shift);
 #ifdef SC_TIMING
     q.dbg = g_dbg;
 #endif
@@ -894,6 +963,16 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     int mi_idx = 0;
     const int band_px = (std::min(b.bh, g.ho) * g.wo + (b.split ? 1 : 0)) / (b.split ? 2 : 1);
     band_units(dense || identity ? (double)band_px : (double)b.max_kept, &mi_idx);
+    if (b.tap) {
+      // 32-row blocks b = wave, wave + 8: one or two per wavefront, by the fullest band of the run
+      const int most = dense || identity ? band_px : b.max_kept;
+      if (most > kTapMaxRows) return SC_ERR_UNSUPPORTED;   // cannot happen: the planner caps the band rows
+      q.residual = residual;
+      q.residual_relu = residual_relu ? 1 : 0;
+      const auto& table = residual ? pl->tap_table->fn_res : pl->tap_table->fn;
+      SC_HIP(table[d.c_in / g.vec == 8 ? 0 : 1][b.ni - 1][most > 256 ? 1 : 0](q, b.lds, stream));
+      return SC_OK;
+    }
     if (b.pp) {
       q.residual = residual;
       q.residual_relu = residual_relu ? 1 : 0;
@@ -1185,6 +1264,7 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
   pl->pp_table = d.dtype == SC_BF16 ? bandpp_bf16() : d.dtype == SC_F16 ? bandpp_f16() : nullptr;
+  pl->tap_table = d.dtype == SC_BF16 ? bandtap_bf16() : d.dtype == SC_F16 ? bandtap_f16() : nullptr;
   pl->panel = d.dtype == SC_BF16 ? panel_bf16() : d.dtype == SC_F16 ? panel_f16() : nullptr;
   (void)eb;
   *out = pl;
@@ -1329,7 +1409,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
   if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream))) {
     if (tile_m) *tile_m = -band.bh;     // (rows per run; split bands hold half a run each)
     if (tile_n) *tile_n = 32 * band.ni;
-    if (workgroups) *workgroups = band.pp ? band.pp_grid : (int64_t)band.n_bands * band.n_tiles;
+    if (workgroups) *workgroups = band.pp && !band.tap ? band.pp_grid : (int64_t)band.n_bands * band.n_tiles;
     return SC_OK;
   }
   int64_t rows = which ? plan->geo.m : plan->kept;
@@ -1366,7 +1446,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (plan->geo.depthwise) return "depthwise";
   const BandPlan& band = which ? plan->band_dense : plan->band;
   if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream)))
-    return band.stream ? "band_stream" : band.pp ? "band_alternating" : "band";
+    return band.stream ? "band_stream" : band.tap ? "band_tap" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
   return tiled_kernel_name(plan, which);
@@ -1375,8 +1455,8 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
 const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1) || plan->geo.depthwise) return nullptr;
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && band.pp && !band.stream && (plan->forced[which] == kForceBand || plan->forced[which] == -1))
-    return "band_alternating";
+  if (band.ok && (band.pp || band.tap) && !band.stream && (plan->forced[which] == kForceBand || plan->forced[which] == -1))
+    return band.tap ? "band_tap" : "band_alternating";
   return tiled_kernel_name(plan, which);
 }
 

@@ -181,7 +181,7 @@ def plan_shortcut_fusions(ops, layers: Dict[str, "ConvLayer"], row_formats: Opti
             if not fmt.get(mine, False):
                 if plain in ("band", "band_stream", "tile_row_panel"):
                     continue
-                if plain == "band_alternating" and B.sparse_conv_plan_fused_kernel(plan, 1 if dense else 0) != plain:
+                if plain in ("band_alternating", "band_tap") and B.sparse_conv_plan_fused_kernel(plan, 1 if dense else 0) != plain:
                     continue
             if best is None or position[mine] > position[best[0]]:
                 best = (mine, other)

@@ -170,8 +170,19 @@ def test_alternating_band_kernel_with_split_bands(bh, n, h, w, sp, s, dtype, mon
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
 
 
-def test_split_bands_are_the_automatic_choice_when_every_workgroup_gets_one_run():
-    """The benchmark layer: 256 runs of 7 rows for 256 workgroups; sparse and dense runs decide separately."""
+def test_tap_kernel_is_the_automatic_choice_when_one_round_of_workgroups_covers_the_layer():
+    """The benchmark layer: 256 runs of 7 rows for 256 compute units; sparse and dense runs alike."""
+    for sp in (0.5, 0.7, 0.4, 0.25):
+        spec = spec_of(32, 64, 56, 56, 64, dtype="bf16", sp=sp)
+        layer = R.ConvLayer(spec, *_wbm(spec, 3))
+        assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_tap", sp
+        assert B.sparse_conv_plan_kernel(layer.plan, 1) == "band_tap"
+        assert B.sparse_conv_plan_tiles(layer.plan, 1) == (-7, 64, 256)
+
+
+def test_split_bands_of_the_alternating_kernel_when_every_workgroup_gets_one_run(monkeypatch):
+    """Without the tap-pipelined kernel: sparse and dense runs decide separately whether to cut their runs of rows."""
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "no-tap")
     for sp, want in [(0.5, "band_alternating"), (0.7, "band_alternating"), (0.4, "band"), (0.25, "band")]:
         spec = spec_of(32, 64, 56, 56, 64, dtype="bf16", sp=sp)
         layer = R.ConvLayer(spec, *_wbm(spec, 3))
@@ -180,11 +191,14 @@ def test_split_bands_are_the_automatic_choice_when_every_workgroup_gets_one_run(
         assert B.sparse_conv_plan_tiles(layer.plan, 1) == (-7, 64, 256)
 
 
-def test_alternating_band_kernel_is_the_automatic_choice_for_long_band_lists():
+def test_alternating_band_kernel_is_the_automatic_choice_for_long_band_lists(monkeypatch):
     big = spec_of(64, 64, 56, 56, 64, dtype="bf16", sp=0.5)
     layer = R.ConvLayer(big, *_wbm(big, 3))
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_alternating"
     small = spec_of(2, 64, 20, 20, 64, dtype="bf16", sp=0.5)
+    layer = R.ConvLayer(small, *_wbm(small, 3))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_tap"
+    monkeypatch.setenv("SPARSE_CONV_BAND_KERNEL", "no-tap")
     layer = R.ConvLayer(small, *_wbm(small, 3))
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 

@@ -175,7 +175,7 @@ def test_fused_shortcut_in_the_alternating_band_kernel_scatter_only(monkeypatch)
 
 
 def test_other_band_kernels_hand_a_fused_launch_to_the_tiled_kernel():
-    spec = spec_of(2, 64, 20, 20, 64)             # few bands: the one-band-per-workgroup kernel
+    spec = spec_of(2, 16, 20, 20, 64)             # two channel groups per pixel: the plain one-band-per-workgroup kernel
     layer = check(spec, 1291, True, want_kernel=("tile_lds_direct",))
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 
