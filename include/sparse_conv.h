@@ -221,6 +221,19 @@ const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which);
  * stays automatic).  Returns SC_ERR_UNSUPPORTED when the library has no such kernel for the layer. */
 sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_m, int32_t tile_n);
 
+/*
+ * Measured kernel choice.  sparse_conv_plan prices its candidate launches (tile shape, K splits, band or tiled
+ * kernel, and for small layers the variant that contracts every row and lets the mask decide at the store) with a
+ * model of the device; this call times the serious candidates of the sparse and of the dense run on the caller's
+ * real buffers and keeps the fastest of each.  x_dev, bias_dev, y_dev as for sparse_conv_run; y_dev is overwritten
+ * many times and holds the masked convolution of x when the call returns.  Candidates are timed as captured graphs
+ * of back-to-back launches on a stream the call creates and destroys (with two events; default priority), so that
+ * layers of a few microseconds are not measured at the host's launch rate; `hip_stream` is synchronised first and
+ * last; no device memory is allocated.  Choices forced with
+ * sparse_conv_plan_set_tiles stay as they are; sparse_conv_plan_set_mask returns the sparse run to the model's choice.
+ */
+sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev, void* hip_stream);
+
 /* Environment (read by sparse_conv_plan; tuning and tests only):
  *   SPARSE_CONV_BAND_HEIGHT=<rows>               fixes the band height of the streaming and of the
  *                                                alternating-group band kernels (automatic otherwise)
@@ -249,7 +262,12 @@ sc_status sparse_conv_plan_set_tiles(sc_plan* plan, int32_t which, int32_t tile_
  * two partial-sum slots per workgroup fit the 16 MiB buffer and every workgroup has at least four K steps.
  * Measured slower than the ordinary launch on every benchmark layer (the partial sums cross the fabric
  * between the XCDs' caches), so automatic means off. */
-enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2, SC_OPT_STREAM_K = 3 };
+/* SC_OPT_MASKED_STORE: 0 = automatic, 1 = never, 2 = always where it applies.  A sparse run of dense NHWC operands
+ * (no shortcut tensor, not the row-segment gather) may contract EVERY row with the identity row map and let the mask
+ * decide at the store -- zeros for a dropped row, or nothing in scatter-only mode: the results are those of Alg. 2,
+ * the work is the dense layer's.  Taken where the kept-row list costs more (a dependent round trip to memory before
+ * the first transfer) than the rows it removes: layers of a few microseconds. */
+enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2, SC_OPT_STREAM_K = 3, SC_OPT_MASKED_STORE = 4 };
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
 
 void sparse_conv_plan_destroy(sc_plan* plan);

@@ -116,6 +116,8 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_backward_run.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp]
         L.sparse_conv_backward_destroy.restype = None
         L.sparse_conv_backward_destroy.argtypes = [vp]
+        L.sparse_conv_plan_tune.restype = ctypes.c_int
+        L.sparse_conv_plan_tune.argtypes = [vp, vp, vp, vp, vp]
         L.sparse_mask_workspace_bytes.restype = ctypes.c_int
         L.sparse_mask_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.sparse_mask_generate.restype = ctypes.c_int
@@ -344,6 +346,11 @@ def prepared_run_residual(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tens
     return call
 
 
+def sparse_conv_plan_tune(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):
+    """Times the plan's candidate launches on these buffers and keeps the fastest (y ends up holding the sparse run)."""
+    return _run(lib().sparse_conv_plan_tune, "sparse_conv_plan_tune", plan, x, bias, y, stream)
+
+
 def dense_conv_run(plan: Plan, x: torch.Tensor, bias: Optional[torch.Tensor], y: torch.Tensor, stream=None):
     return _run(lib().dense_conv_run, "dense_conv_run", plan, x, bias, y, stream)
 
@@ -411,6 +418,7 @@ SC_OPT_GATHER_PIPELINE = 0
 SC_OPT_SPLIT_K = 1
 SC_OPT_ROW_PANEL = 2
 SC_OPT_STREAM_K = 3
+SC_OPT_MASKED_STORE = 4
 
 
 def sparse_conv_plan_set_option(plan: Plan, option: int, value: int):

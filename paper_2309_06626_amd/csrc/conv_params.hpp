@@ -47,6 +47,10 @@ struct ConvParams {
   // a dropped row of a dense-layout output receives post(residual) instead of zeros
   const void* residual;    // null: none
   int32_t residual_relu;
+  // 1 / 2: the run contracts every row (identity row map, rows = M) and the mask decides at the store: the result of a
+  // dropped row is replaced by zeros (1: zero-fill mode) or not stored (2: scatter-only mode).  For layers so small
+  // that the kept-row indirection costs more than the rows it saves.  Not with compact operands or a shortcut tensor.
+  int32_t masked_store;
   int32_t m_tiles, n_tiles;
   // n / ho_wo and n / wo for 0 <= n < 2^31 as (n * mul) >> shift in 64 bits (exact; host-computed)
   uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;

@@ -7,6 +7,7 @@ namespace sc {
 
 static const KernelEntry g_table[] = {
     SC_KERNEL_ENTRY(kBF16, 256, 128, 2, 2, 2, 3),
+    SC_KERNEL_ENTRY(kBF16, 128, 256, 2, 2, 2, 3),
     SC_KERNEL_ENTRY_SPLITK(kBF16, 128, 128, 2, 2, 3, 3, 4),
     SC_KERNEL_ENTRY(kBF16, 256, 64, 4, 1, 2, 3),
     SC_KERNEL_ENTRY_SPLITK(kBF16, 128, 64, 2, 2, 4, 3, 6),

@@ -17,6 +17,8 @@ static LaunchFn pick_shallow(int bm, int bn) {
 
 template <int DT>
 static LaunchFn pick(int bm, int bn) {
+  if (bm == 256 && bn == 128) return igemm_buf_launch<DT, 256, 128, 4, 2, 3>;   // eight wavefronts
+  if (bm == 128 && bn == 256) return igemm_buf_launch<DT, 128, 256, 2, 4, 3>;   // eight wavefronts
   if (bm == 128 && bn == 128) return igemm_buf_launch<DT, 128, 128, 2, 4, 3>;   // eight wavefronts
   if (bm == 128 && bn == 64) return igemm_buf_launch<DT, 128, 64, 2, 2, 3>;
   if (bm == 96 && bn == 128) return igemm_buf_launch<DT, 96, 128, 1, 4, 3>;
@@ -24,6 +26,22 @@ static LaunchFn pick(int bm, int bn) {
   if (bm == 64 && bn == 64) return igemm_buf_launch<DT, 64, 64, 2, 2, 3>;
   if (bm == 128 && bn == 32) return igemm_buf_launch<DT, 128, 32, 4, 1, 3>;
   if (bm == 32 && bn == 128) return igemm_buf_launch<DT, 32, 128, 1, 4, 3>;
+  return nullptr;
+}
+
+template <int DT>
+static LaunchFn pick_splitk(int bm, int bn) {
+  if (bm == 256 && bn == 128) return igemm_buf_launch<DT, 256, 128, 4, 2, 3, true>;
+  if (bm == 128 && bn == 256) return igemm_buf_launch<DT, 128, 256, 2, 4, 3, true>;
+  if (bm == 128 && bn == 128) return igemm_buf_launch<DT, 128, 128, 2, 4, 3, true>;
+  if (bm == 96 && bn == 128) return igemm_buf_launch<DT, 96, 128, 1, 4, 3, true>;
+  if (bm == 64 && bn == 128) return igemm_buf_launch<DT, 64, 128, 2, 2, 3, true>;
+  return nullptr;
+}
+
+LaunchFn buf_splitk_kernel(int dtype, int bm, int bn) {
+  if (dtype == kBF16) return pick_splitk<kBF16>(bm, bn);
+  if (dtype == kF16) return pick_splitk<kF16>(bm, bn);
   return nullptr;
 }
 

@@ -30,7 +30,23 @@ template <int OFF> __device__ __forceinline__ v4i lds_read16_big(unsigned addr) 
   else return lds_read16_at<0>(addr + (unsigned)OFF);
 }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+// 16-byte accesses at device scope (the partial sums of a split K walk): they write through to, and read from,
+// the point where the L2 caches of the chip's dies agree, like the relaxed device-scope atomics of the other
+// split kernels, but four floats at a time.  The caller orders them with s_waitcnt vmcnt(0).
+__device__ __forceinline__ void store16_device_scope(void* dst, v4i v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v) : "memory");
+}
+__device__ __forceinline__ v4i load16_device_scope(const void* src) {
+  v4i v;
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(src) : "memory");
+  return v;
+}
+
+// SPLITK: grid = output tiles x p.splits; the workgroups of one tile are neighbours (one die, so the tile's rows
+// are shared in its L2), each contracts its share of the K tiles and leaves float partial sums; the one that
+// arrives last at the tile's counter adds them in split order (the result does not depend on who was last) and
+// runs the epilogue.  Nobody waits for anybody.
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool SPLITK = false>
 __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const ConvParams p) {
   using E = Elem<DT>;
   using T = typename E::T;
@@ -53,14 +69,19 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const
   int32_t* s_rows = reinterpret_cast<int32_t*>(smem + STAGES * STAGE_BYTES);   // [BM], then one spare group
   float* s_bias = reinterpret_cast<float*>(s_rows + BM + 4);                   // [BN]
 
-  const int nwg = p.m_tiles * p.n_tiles;
+  const int splits = SPLITK ? p.splits : 1;
+  const int nwg = p.m_tiles * p.n_tiles * splits;
   const int per_xcd = (nwg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (logical >= nwg) return;
-  const int tile_m = logical / p.n_tiles;
-  const int tile_n = logical - tile_m * p.n_tiles;
+  const int tile = logical / splits;
+  const int split = logical - tile * splits;
+  const int tile_m = tile / p.n_tiles;
+  const int tile_n = tile - tile_m * p.n_tiles;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int n_kt = p.k_tiles;
+  const int kt_lo = SPLITK ? (int)((int64_t)split * p.k_tiles / splits) : 0;
+  const int kt_hi = SPLITK ? (int)((int64_t)(split + 1) * p.k_tiles / splits) : p.k_tiles;
+  const int n_kt = kt_hi - kt_lo;
 
   const int t = threadIdx.x;
   const int lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -84,6 +105,18 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const
   if (p.zero_fill) {
     if (tile_m != 0) z_lo = p.row_idx[m0];
     if (m0 + BM < p.rows) z_hi = p.row_idx[m0 + BM];
+  }
+
+  // a run that contracts every row and lets the mask decide at the store: the mask bytes of this lane's rows,
+  // requested here, looked at after the K loop
+  unsigned mkeep[A_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    mkeep[j] = 1;
+    if (p.masked_store) {
+      const int r = min(m0 + lrow + RPR * j, p.rows - 1);
+      mkeep[j] = p.mask[p.mask_spatial ? r - fast_div(r, p.div_howo_mul, p.div_howo_shift) * p.ho_wo : r];
+    }
   }
 
   // per kept row: byte offset of (n, iy0, ix0, this lane's channel group) -- possibly negative, valid
@@ -126,12 +159,16 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const
   const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.wp), 0, (int)p.w_bytes, kBufferWord3);
   typedef __attribute__((address_space(3))) void lds_void;
 
-  // scalar walk over the window: K tile kt lies in tap (s_ky, s_kx) at channel s_ci
-  int s_ci = 0, s_kx = 0, s_ky = 0;
-  int s_off = 0;                              // byte offset of that tap and channel
-  uint32_t s_bits = 1u | (1u << 8);           // its two validity bits
+  // scalar walk over the window, entered at K tile kt_lo: K tile kt lies in tap (s_ky, s_kx) at channel s_ci
   const int step_x = p.dil_w * p.xs_w * EB, step_y = p.dil_h * p.xs_h * EB;
-  int s_boff = n0 * p.k_pad * EB;             // byte offset of filter row n0 at the current K tile
+  const int k_first = kt_lo * BK;
+  const int tap_first = k_first / p.c_in;
+  int s_ci = k_first - tap_first * p.c_in;
+  int s_ky = tap_first / p.kw;
+  int s_kx = tap_first - s_ky * p.kw;
+  int s_off = s_ci * EB + s_kx * step_x + s_ky * step_y;     // byte offset of that tap and channel
+  uint32_t s_bits = (1u << s_ky) | (1u << (8 + s_kx));        // its two validity bits
+  int s_boff = (n0 * p.k_pad + k_first) * EB;                 // byte offset of filter row n0 at the current K tile
   // transfer `idx` of a K tile (the A rows first, then the filter rows); the last one steps the walk
   auto issue_one = [&](auto stage_c, auto idx_c) {
     constexpr int ST = decltype(stage_c)::value;
@@ -287,9 +324,83 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const
     if constexpr (STAGES >= 4) if (kt + 3 < n_kt) k_tile(std::integral_constant<int, 3 % STAGES>{}, kt + 3);
   }
 
+  // ---- split K: leave the partial sums; the last workgroup of the tile adds them up ----------------------
+  if constexpr (SPLITK) {
+    if (splits > 1) {
+      // Order: stores acknowledged (vmcnt 0) -> workgroup barrier -> arrival counter (device scope); the last
+      // arrival reads after it has seen every other arrival.  No cache-wide fence anywhere.
+      constexpr int CHUNKS = MI * NI * 4;                    // 16-byte chunks per lane
+      constexpr int64_t SLOT = (int64_t)(NT / 64) * CHUNKS * 64;   // chunks per (tile, split)
+      v4i* part = reinterpret_cast<v4i*>(p.partial) + (int64_t)tile * splits * SLOT;
+      v4i* mine = part + (int64_t)split * SLOT + (int64_t)wave * CHUNKS * 64 + lane;
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            v4f v = {acc[mi][ni][4 * q], acc[mi][ni][4 * q + 1], acc[mi][ni][4 * q + 2], acc[mi][ni][4 * q + 3]};
+            store16_device_scope(mine + ((mi * NI + ni) * 4 + q) * 64, __builtin_bit_cast(v4i, v));
+          }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      int32_t* s_flag = s_rows + BM;             // one word behind the row list
+      if (t == 0) {
+        const int old = __hip_atomic_fetch_add(p.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // everybody has arrived: leave the counter at zero for the next launch
+        if (old == splits - 1) __hip_atomic_store(p.counters + tile, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_flag = old;
+      }
+      __syncthreads();
+      if (*s_flag != splits - 1) return;          // not the last one: done; the last one also writes the tile's zeros
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+      // fixed order: the sum does not depend on who came last.  The partial sums of split sp + 1 are requested
+      // before those of split sp are added (each request is a round trip to the memory side of the L2s).
+      constexpr int CH = MI * NI * 4;
+      v4i got[2][CH];
+      auto request = [&](int sp, v4i (&dst)[CH]) {
+        const v4i* src = part + (int64_t)sp * SLOT + (int64_t)wave * CHUNKS * 64 + lane;
+#pragma unroll
+        for (int c = 0; c < CH; ++c) dst[c] = load16_device_scope(src + c * 64);
+      };
+      auto add = [&](v4i (&src)[CH]) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+          for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              asm volatile("" : "+v"(src[(mi * NI + ni) * 4 + q]));     // not before the wait that precedes
+              const v4f v = __builtin_bit_cast(v4f, src[(mi * NI + ni) * 4 + q]);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[mi][ni][4 * q + e] += v[e];
+            }
+      };
+      request(0, got[0]);
+      for (int sp = 0; sp < splits; sp += 2) {
+        if (sp + 1 < splits) { request(sp + 1, got[1]); wait_vmcnt<CH>(); } else wait_vmcnt<0>();
+        add(got[0]);
+        if (sp + 1 < splits) {
+          if (sp + 2 < splits) { request(sp + 2, got[0]); wait_vmcnt<CH>(); } else wait_vmcnt<0>();
+          add(got[1]);
+        }
+      }
+    }
+  }
+
+  if (p.masked_store) {
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j)
+      if (c16 == 0 && mkeep[j] == 0 && m0 + lrow + RPR * j < p.rows) s_rows[lrow + RPR * j] = dropped_row_code(m0 + lrow + RPR * j);
+  }
   // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) --------------------
   if (t < BN) s_bias[t] = bias_v;
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS only: the bias slice
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");   // LDS only: the bias slice and the row codes
   if (p.zero_fill) {
     const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
     if (zc < valid) {
@@ -328,21 +439,22 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void igemm_buf_kernel(const
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int rr = s_rows[wm0 + mi * 32 + fp];
-    if (rr < 0) continue;
+    if (rr == -1 || (rr < -1 && p.masked_store != 1)) continue;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
+      if (rr < 0) { store_zero_block<DT>(-2 - rr, c0, y, 1, p.c_out, p.ho_wo, 0, 0, 0); continue; }
       store_kept_block_res<DT>(acc[mi][ni], rr, c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1, p.c_out,
                                p.ho_wo, 0, 0, 0, static_cast<const T*>(p.residual), p.residual_relu);
     }
   }
 }
 
-template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES>
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool SPLITK = false>
 hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
   constexpr size_t lds = igemm_dma_lds_bytes<BM, BN, STAGES>();
-  auto kern = igemm_buf_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES>;
+  auto kern = igemm_buf_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES, SPLITK>;
   static std::atomic<bool> attr_set{false};
   if (lds > 64 * 1024 && !attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -350,7 +462,7 @@ hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int nwg = p.m_tiles * p.n_tiles;
+  const int nwg = p.m_tiles * p.n_tiles * (SPLITK ? p.splits : 1);
   const int grid = ((nwg + 7) / 8) * 8;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(WAVES_M * WAVES_N * 64), lds, stream, p);
   return hipGetLastError();
@@ -358,5 +470,7 @@ hipError_t igemm_buf_launch(const ConvParams& p, hipStream_t stream) {
 
 // the buffer-load form of tile bm x bn for a 16-bit dtype (shallow: ring of two K tiles), or null
 LaunchFn buf_kernel(int dtype, int bm, int bn, bool shallow);
+// its split-K form, or null
+LaunchFn buf_splitk_kernel(int dtype, int bm, int bn);
 
 }  // namespace sc

@@ -132,6 +132,17 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
     if (tile_m != 0) z_lo = p.row_idx[m0];
     if (m0 + BM < p.rows) z_hi = p.row_idx[m0 + BM];
   }
+  // a run that contracts every row and lets the mask decide at the store: the mask bytes of this lane's rows,
+  // requested here, looked at after the K loop
+  unsigned mkeep[A_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    mkeep[j] = 1;
+    if (p.masked_store) {
+      const int r = min(m0 + lrow + 32 * j, p.rows - 1);
+      mkeep[j] = p.mask[p.mask_spatial ? r - fast_div(r, p.div_howo_mul, p.div_howo_shift) * p.ho_wo : r];
+    }
+  }
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const bool present = m0 + lrow + 32 * j < p.rows;
@@ -329,6 +340,11 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
   }
 
   SC_DMA_STAMP(5);
+  if (p.masked_store) {
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j)
+      if (c16 == 0 && mkeep[j] == 0 && m0 + lrow + 32 * j < p.rows) s_rows[lrow + 32 * j] = dropped_row_code(m0 + lrow + 32 * j);
+  }
   // ---- zero fill of the dropped rows this workgroup owns (Alg. 2, mask == 0 branch) --------------------
   if (t < BN) s_bias[t] = bias_v;
   // LDS-only barrier (the bias slice): no global-memory wait, the zero stores below just drain
@@ -371,11 +387,12 @@ __global__ __launch_bounds__(kThreads) void igemm_dma_kernel(const ConvParams p)
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int rr = s_rows[wm0 + mi * 32 + fp];
-    if (rr < 0) continue;
+    if (rr == -1 || (rr < -1 && p.masked_store != 1)) continue;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
+      if (rr < 0) { store_zero_block<DT>(-2 - rr, c0, y, 1, p.c_out, p.ho_wo, 0, 0, 0); continue; }
       store_kept_block_res<DT>(acc[mi][ni], rr, c0, y, p.bias ? s_bias + (c0 - n0) : nullptr, 0, p.relu, 1, p.c_out,
                                p.ho_wo, 0, 0, 0, static_cast<const T*>(p.residual), p.residual_relu);
     }

@@ -6,6 +6,7 @@ namespace sc {
 
 static const KernelEntry g_table[] = {
     SC_KERNEL_ENTRY(kF32, 256, 128, 2, 2, 2, 3),
+    SC_KERNEL_ENTRY(kF32, 128, 256, 2, 2, 2, 3),
     SC_KERNEL_ENTRY(kF32, 128, 128, 2, 2, 3, 3),
     SC_KERNEL_ENTRY(kF32, 256, 64, 4, 1, 2, 3),
     SC_KERNEL_ENTRY(kF32, 128, 64, 2, 2, 4, 3),

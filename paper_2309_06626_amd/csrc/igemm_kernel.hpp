@@ -78,7 +78,12 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
     const int ic = m0 + lrow + 32 * j;
     int rr = -1;
     if (ic < p.rows) rr = p.row_idx ? p.row_idx[ic] : ic;
-    s_rows[lrow + 32 * j] = (rr >= 0 && p.y_compact) ? ic : rr;   // row the epilogue stores to (eight threads write the same value)
+    int code = (rr >= 0 && p.y_compact) ? ic : rr;                // row the epilogue stores to
+    if (p.masked_store && rr >= 0) {
+      const int mr = p.mask_spatial ? rr - fast_div(rr, p.div_howo_mul, p.div_howo_shift) * p.ho_wo : rr;
+      if (p.mask[mr] == 0) code = dropped_row_code(rr);
+    }
+    s_rows[lrow + 32 * j] = code;                                 // (eight threads write the same value)
     if (rr >= 0 && p.x_compact) rr = ic;                          // row the window is read from
     if (rr >= 0) {
       int n = fast_div(rr, p.div_howo_mul, p.div_howo_shift), rem = rr - n * p.ho_wo;
@@ -299,11 +304,12 @@ __global__ __launch_bounds__(kThreads) void igemm_kernel(const ConvParams p) {
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     const int rr = s_rows[wm0 + mi * 32 + fp];
-    if (rr < 0) continue;
+    if (rr == -1 || (rr < -1 && p.masked_store != 1)) continue;
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni) {
       const int c0 = n0 + wn0 + ni * 32 + 16 * fh;
       if (c0 >= p.c_out) continue;
+      if (rr < 0) { store_zero_block<DT>(-2 - rr, c0, y, p.vec_out, p.c_out, p.ho_wo, p.ys_n, p.ys_p, p.ys_c); continue; }
       store_kept_block_res<DT>(acc[mi][ni], rr, c0, y, p.bias, c0, p.relu, p.vec_out, p.c_out, p.ho_wo, p.ys_n, p.ys_p,
                                p.ys_c, static_cast<const T*>(p.residual), p.residual_relu);
     }

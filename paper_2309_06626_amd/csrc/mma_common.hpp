@@ -161,6 +161,20 @@ __device__ __forceinline__ void store_kept_block_res(const floatx16& acc, int rr
   }
 }
 
+// Row code of a tile row in the kernels' row lists: >= 0 the dense row the result goes to, -1 no such row,
+// <= -2 a row the mask drops in a run that contracts every row (masked_store): -2 - row.
+__device__ __forceinline__ int dropped_row_code(int row) { return -2 - row; }
+
+// the zeros of such a row (Alg. 2, mask == 0 branch) for the lane's 16 channels
+template <int DT>
+__device__ __forceinline__ void store_zero_block(int rr, int c0, typename Elem<DT>::T* y, int vec_out, int c_out, int ho_wo,
+                                                 int64_t ys_n, int ys_p, int ys_c) {
+  floatx16 z;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) z[v] = 0.0f;
+  store_kept_block_res<DT>(z, rr, c0, y, nullptr, 0, 0, vec_out, c_out, ho_wo, ys_n, ys_p, ys_c, nullptr, 0);
+}
+
 template <int DT>
 __device__ __forceinline__ void store_kept_block(const floatx16& acc, int rr, int c0, typename Elem<DT>::T* __restrict__ y,
                                                  const float* __restrict__ bias, int bias_at, int relu, int vec_out,

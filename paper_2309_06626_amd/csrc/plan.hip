@@ -346,7 +346,7 @@ static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; 
 static inline int elem_bytes(int dtype) { return dtype == SC_F32 ? 4 : 2; }
 
 // float partial sums of a split-K launch at most (one BM x BN block per workgroup)
-constexpr size_t kSplitKPartialBytes = (size_t)16 << 20;
+constexpr size_t kSplitKPartialBytes = (size_t)48 << 20;
 constexpr int kStreamKMostWgs = 1024;   // persistent workgroups of a stream-K launch at most
 constexpr int kSplitKMost = 64;   // splits per output tile at most
 
@@ -716,7 +716,11 @@ struct sc_plan {
   int64_t kept;
   const KernelEntry* table;
   int table_count;
-  int tile_sparse, tile_dense;     // chosen indices into table
+  struct Pick { int ti, splits; bool masked; };
+  Pick pick[2];                    // tiled launch of the sparse / dense run when nothing is forced: tile, K splits, and
+                                   // (sparse run) whether every row is contracted and the mask decides at the store
+  bool prefer_tiled[2];            // measured by sparse_conv_plan_tune: the tiled launch beat the band / row-panel kernel
+  bool tuned;                      // pick and prefer_tiled come from measurements on this device, not from the cost model
   LaunchFn panel;                  // row-panel kernel of the plan's dtype (null: none)
   int tile_splitk;                 // index of the 64 x 128 entry, the tile of automatic split-K launches (-1: none)
   int forced[2];                   // -1 = automatic, >= 0 generic tile index, kForceBand = band kernel
@@ -724,46 +728,115 @@ struct sc_plan {
   int split_k;                     // 0 = automatic, 1 = never, n >= 2 = n splits wherever the kernel applies
   int row_panel;                   // 0 = automatic, 1 = never, 2 = wherever the kernel applies
   int stream_k;                    // 0 = automatic, 1 = never, n >= 2 = n persistent workgroups wherever the kernel applies
+  int masked_store;                // 0 = automatic, 1 = never, 2 = wherever it applies (sparse runs of dense NHWC operands)
   bool x_rank_set;                 // sparse_conv_plan_set_input_mask has filled the rank map of a compact input
 };
 constexpr int kForceBand = -2;
 
 namespace sc {
 
-// Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a heavily
-// masked layer gets narrower tiles than its dense twin (Sec. 3.2: the GEMM range shrinks with the
-// sparsity).  The rules come from sweeps over the ResNet18 / pointwise / detector layer shapes on
-// MI355X: 64 x 128 tiles move the fewest operand bytes per FLOP of the shapes that still leave enough
-// workgroups, so they are taken once they give about one and a half workgroups per CU; below that the
-// 64 x 64 shape (twice the workgroups) wins, and short GEMMs with wide outputs take 32 x 128.
-static int choose_tile(const KernelEntry* tab, int count, int64_t rows, int c_out, bool vec_gather, int k_tiles,
-                       bool rowseg, bool deep_16bit) {
-  int bm, bn;
-  const int64_t wg_64x128 = ((rows + 63) / 64) * ((c_out + 127) / 128);
-  const int64_t wg_96x128 = ((rows + 95) / 96) * ((c_out + 127) / 128);
-  if (rowseg) { bm = 64; bn = c_out <= 32 ? 32 : 64; if (c_out <= 32) bm = 128; }   // window-row gather (stems): measured best
-  else if (!vec_gather) { bm = 128; bn = 64; }       // element gather: fewer, fatter workgroups
-  // (few rows: four times the workgroups with the wide tile, three quarters of it idle, still wins -- 192 -> 32 channels
-  // on 14 x 14 and 7 x 7 maps, batch 64: 5.4 -> 4.8 us sparse, 4.7 -> 3.9 us dense)
-  else if (c_out <= 32) { bm = rows <= 16384 ? 32 : 128; bn = rows <= 16384 ? 128 : 32; }
-  // a few 64 x 128 tiles more than CUs (two on some CUs, one on the rest) but at most one 96 x 128 tile per CU:
-  // one round of the taller tile (detector y8, 4 480 kept rows: 280 -> 188 tiles, 38.4 -> 35.6 us; y7 22.2 -> 21.2 us)
-  else if (deep_16bit && c_out % 128 == 0 && k_tiles >= 32 && wg_64x128 > 256 && wg_64x128 <= 320 && wg_96x128 <= 256) { bm = 96; bn = 128; }
-  else if (c_out % 128 == 0 && wg_64x128 >= (k_tiles >= 32 ? 256 : 384)) { bm = 64; bn = 128; }   // long K: one per CU is enough
-  else if (rows <= 8192 && c_out >= 128 && rows * c_out < (int64_t)2 << 20) { bm = 32; bn = 128; }
-  // (very long GEMMs whose channel count is no multiple of 128: the taller tile halves the filter re-reads --
-  // 576 -> 160 channels on a 56 x 56 map, batch 64, dense run: 102.6 -> 91.5 us)
-  else if (rows >= 150000 && c_out > 64) { bm = 128; bn = 64; }
-  else { bm = 64; bn = 64; }
-  for (int i = 0; i < count; ++i)
-    if (tab[i].bm == bm && tab[i].bn == bn) return i;
-  return 0;
+// Tile choice for a GEMM of `rows` x c_out x K.  The row count is the compacted one, so a heavily masked layer
+// gets other tiles than its dense twin (Sec. 3.2: the GEMM range shrinks with the sparsity).  Every candidate
+// (tile shape x K splits, and for the sparse run the variant that contracts every row and masks at the store)
+// is priced with a small model of one launch on this device and the cheapest wins.  The constants are
+// measurements on MI355X, each of one quantity:
+//   kLaunchUs     what a launch costs beyond the lifetime of its workgroups (dispatch ramp and drain)
+//   kWgFixedUs    set-up and epilogue of a workgroup; kRowListUs more when rows come through the row list
+//                 (a dependent round trip to memory before the first transfer, and the zero fill)
+//   kIngestKBus   what a compute unit moves from L2 into LDS per microsecond with 1, 2, 3+ workgroups resident
+//                 (the K loops of these kernels are bound by that path, not by the matrix pipes)
+//   kMfmaShare    share of the matrix peak a K loop sustains when it is the bound
+//   kExchangeKBus rate at which float partial sums of a split K walk travel between workgroups (device-scope
+//                 stores and loads: across the fabric between the dies' L2 caches)
+// The model is good to about 15 %; sparse_conv_plan_tune replaces its choice by a measured one.
+constexpr double kLaunchUs = 3.0, kWgFixedUs = 1.0, kRowListUs = 0.6, kMfmaShare = 0.85, kExchangeKBus = 4000.0;
+constexpr double kIngestKBus[3] = {62.0, 110.0, 120.0};
+constexpr double kIngestEightWavesKBus = 76.0;      // one resident workgroup of eight wavefronts
+constexpr double kClockPerUs = 2100.0;
+
+// LDS bytes of the kernel form a tile of this layer runs (decides how many workgroups share a compute unit)
+static size_t tile_lds_bytes(const sc_plan* pl, const KernelEntry& ke) {
+  const Geometry& g = pl->geo;
+  if (g.vec_gather && g.vec_out && pl->gather_pipeline != 1) {
+    const int stages = g.k_tiles <= 2 ? 2 : 3;
+    return (size_t)stages * (ke.bm + ke.bn) * kRowBytes + (ke.bm + 4) * 4 + (size_t)ke.bn * 4;
+  }
+  return 2 * (size_t)(ke.bm + ke.bn) * kRowBytes + (size_t)ke.bm * 4;
+}
+
+// predicted microseconds of one tiled launch: `rows` rows through tile ke with K cut into `splits`;
+// `listed`: rows come through the kept-row list and dropped rows are zero-filled by their owners
+static double predict_us(const sc_plan* pl, const KernelEntry& ke, int64_t rows, int splits, bool listed) {
+  const Geometry& g = pl->geo;
+  const sc_conv_desc& d = pl->desc;
+  const int cus = device_cus();
+  const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((d.c_out + ke.bn - 1) / ke.bn);
+  const int64_t wgs = tiles * splits;
+  const int n_kt = (g.k_tiles + splits - 1) / splits;
+  const double kb_wg = (double)(ke.bm + ke.bn) * kRowBytes * n_kt / 1024.0;          // through the L1 path
+  const double peak = d.dtype == SC_F32 ? 4096.0 * 157.3 / 2500.0 : 4096.0;          // FLOP per clock and compute unit
+  const int bk = kRowBytes / elem_bytes(d.dtype);
+  const double mfma_us = 2.0 * ke.bm * ke.bn * bk * n_kt / (peak * kMfmaShare * kClockPerUs);
+  const bool eight_waves = ke.bm * ke.bn >= 128 * 128 && g.vec_gather && g.vec_out && d.dtype != SC_F32 && d.c_in % 64 == 0;
+  int occ = (int)std::min<size_t>(kLdsLimit / std::max<size_t>(tile_lds_bytes(pl, ke), 1), eight_waves ? 2 : 4);
+  occ = std::max(occ, 1);
+  const int c = (int)std::max<int64_t>(1, std::min<int64_t>(occ, (wgs + cus - 1) / cus));   // resident per compute unit
+  const double rounds = std::ceil((double)wgs / ((double)cus * c));
+  const double ingest = c == 1 && eight_waves ? kIngestEightWavesKBus : kIngestKBus[std::min(c, 3) - 1];
+  const double round_us = kWgFixedUs + (listed ? kRowListUs : 0.0) + std::max(c * kb_wg / ingest, c * mfma_us);
+  double t = kLaunchUs + rounds * round_us;
+  if (splits > 1)   // every split writes its tile of floats, the last arrival reads them all
+    t += 2.0 * (double)tiles * splits * ke.bm * ke.bn * 4.0 / 1024.0 / kExchangeKBus;
+  return t;
+}
+
+static int most_splits(const sc_plan* pl, const KernelEntry& ke, int64_t rows);
+static LaunchFn splitk_launcher(const sc_plan* pl, const KernelEntry& ke);
+static bool buf_applies(const sc_plan* pl, const KernelEntry& ke);
+
+// K splits the automatic choice considers for a tile: up to four, and only the buffer-load form of the split kernel
+// (the older form of the small tiles measured slower than their unsplit launches everywhere)
+static int split_candidates(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
+  if (pl->split_k == 1 || !buf_applies(pl, ke) || pl->geo.k_tiles <= 2) return 1;
+  if (!buf_splitk_kernel(pl->desc.dtype == SC_BF16 ? kBF16 : kF16, ke.bm, ke.bn)) return 1;
+  return std::min(4, most_splits(pl, ke, rows));
+}
+
+// the cheapest tiled launch by the model.  Layers the fast gathers do not serve keep their one measured shape.
+static sc_plan::Pick model_pick(const sc_plan* pl, int which, int64_t rows) {
+  const Geometry& g = pl->geo;
+  const sc_conv_desc& d = pl->desc;
+  sc_plan::Pick best = {0, 1, false};
+  auto find = [&](int bm, int bn) {
+    for (int i = 0; i < pl->table_count; ++i)
+      if (pl->table[i].bm == bm && pl->table[i].bn == bn) return i;
+    return 0;
+  };
+  if (g.rowseg) { best.ti = d.c_out <= 32 ? find(128, 32) : find(64, 64); return best; }   // window-row gather (stems)
+  if (!g.vec_gather) { best.ti = find(128, 64); return best; }                              // element gather
+  double best_us = 1e300;
+  const bool can_mask = which == 0 && rows < g.m && rows > 0;
+  for (int i = 0; i < pl->table_count; ++i) {
+    const KernelEntry& ke = pl->table[i];
+    if (tile_lds_bytes(pl, ke) > kLdsLimit) continue;
+    if (ke.bn > 128 && d.c_out <= 128) continue;                      // more than half of such a tile would be padding
+    const int most = split_candidates(pl, ke, rows);
+    for (int sp = 1; sp <= most; ++sp) {
+      const double t = predict_us(pl, ke, rows, sp, which == 0 && rows < g.m);
+      if (t < best_us) { best_us = t; best = {i, sp, false}; }
+    }
+    if (can_mask && pl->masked_store != 1) {       // every row contracted, the mask decides at the store: the dense launch plus a mask byte per row
+      const double t = predict_us(pl, ke, g.m, 1, false) + 0.1;
+      if (t < best_us) { best_us = t; best = {i, 1, true}; }
+    }
+  }
+  return best;
 }
 
 // Split K?  Layers deep in a network have few rows and a long K: large output tiles cannot fill
 // 256 CUs, and with small tiles every workgroup walks the whole K, one L2 round trip after the other.
 // Dividing K among workgroups shortens that walk and still gives every CU work.
-struct TilePick { int ti, splits; };
+struct TilePick { int ti, splits; bool masked; };
 
 // Row-panel kernel: short K (pointwise layers), several 64-channel tiles, enough rows to fill the
 // CUs with 128-row panels.  There the tiled kernels are bound by the instructions every
@@ -771,16 +844,28 @@ struct TilePick { int ti, splits; };
 static bool use_panel(const sc_plan* pl, int which, int64_t rows) {
   const Geometry& g = pl->geo;
   const sc_conv_desc& d = pl->desc;
-  const bool applies = pl->panel && pl->forced[which] < 0 && pl->gather_pipeline != 1 && pl->row_panel != 1 &&
+  const bool applies = pl->panel && pl->forced[which] < 0 && !(pl->prefer_tiled[which] && pl->row_panel != 2) &&
+                       pl->gather_pipeline != 1 && pl->row_panel != 1 &&
                        g.vec_gather && g.vec_out && g.k_tiles <= kPanelMaxKTiles && d.c_out <= 1024;
   // (from 96 channels on, i.e. more than one channel tile per panel: 16 -> 96 channels on a 112 x 112 map,
   // batch 64, measured 52 -> 44 us with dense and 38 -> 27 us with compact operands)
   return applies && (pl->row_panel == 2 || (d.c_out >= 96 && rows >= 128 * 256));
 }
 
+static bool buf_applies(const sc_plan* pl, const KernelEntry& ke);
+
+// the split-K launcher of a tile: the buffer-load form where the layer admits it, else the direct-to-LDS form
+static LaunchFn splitk_launcher(const sc_plan* pl, const KernelEntry& ke) {
+  if (buf_applies(pl, ke) && pl->geo.k_tiles > 2) {
+    LaunchFn fn = buf_splitk_kernel(pl->desc.dtype == SC_BF16 ? kBF16 : kF16, ke.bm, ke.bn);
+    if (fn) return fn;
+  }
+  return ke.splitk;
+}
+
 static int most_splits(const sc_plan* pl, const KernelEntry& ke, int64_t rows) {
   const Geometry& g = pl->geo;
-  if (!g.splitk_ok || !ke.splitk || pl->split_k == 1 || pl->gather_pipeline == 1) return 1;
+  if (!g.splitk_ok || !splitk_launcher(pl, ke) || pl->split_k == 1 || pl->gather_pipeline == 1) return 1;
   const int64_t tiles = ((rows + ke.bm - 1) / ke.bm) * ((pl->desc.c_out + ke.bn - 1) / ke.bn);
   const int64_t by_buffer = (int64_t)(kSplitKPartialBytes / ((size_t)ke.bm * ke.bn * sizeof(float))) / std::max<int64_t>(tiles, 1);
   return (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(by_buffer, g.k_tiles / 4), kSplitKMost));
@@ -820,22 +905,19 @@ static int stream_k_workgroups(const sc_plan* pl, const KernelEntry& ke, int64_t
 
 static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
   TilePick tp;
+  tp.masked = false;
   if (pl->forced[which] >= 0) {          // tuning: the forced tile, split as requested
     tp.ti = pl->forced[which];
     tp.splits = pl->split_k >= 2 ? std::min(pl->split_k, most_splits(pl, pl->table[tp.ti], rows)) : 1;
+    tp.masked = pl->masked_store == 2 && which == 0;
     return tp;
   }
-  tp.ti = which ? pl->tile_dense : pl->tile_sparse;
-  tp.splits = 1;
-  if (pl->tile_splitk >= 0) {
-    const KernelEntry& ke = pl->table[pl->tile_splitk];
-    const int most = most_splits(pl, ke, rows);
-    // Measured on MI355X (ResNet18 / detector shapes): the partial-sum round trip costs more than the
-    // shorter K walk saves -- the unsplit 64 x 64 / 32 x 128 tiles are faster on every benchmark layer
-    // (ResNet18 layer 4: 22 us against 27 us with two splits) -- so K is split only on request.
-    int want = pl->split_k >= 2 ? pl->split_k : 1;
-    want = std::min(want, most);
-    if (want >= 2) { tp.ti = pl->tile_splitk; tp.splits = want; }
+  tp.ti = pl->pick[which].ti;
+  tp.splits = pl->split_k == 1 ? 1 : std::min(pl->pick[which].splits, most_splits(pl, pl->table[tp.ti], rows));
+  tp.masked = pl->masked_store == 2 ? which == 0 : pl->masked_store == 1 ? false : pl->pick[which].masked;
+  if (pl->split_k >= 2 && pl->tile_splitk >= 0) {      // on request: that many splits of the 64 x 128 tile
+    const int want = std::min(pl->split_k, most_splits(pl, pl->table[pl->tile_splitk], rows));
+    if (want >= 2) { tp.ti = pl->tile_splitk; tp.splits = want; tp.masked = false; }
   }
   return tp;
 }
@@ -923,7 +1005,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   // (of the band and row-panel kernels only the alternating-group band kernel has a shortcut path: any other
   // fused launch takes a tiled kernel)
   const bool use_band = band.ok && !x_compact && !y_compact && (!residual || ((band.pp || band.tap) && !band.stream)) &&
-                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream));
+                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream && !pl->prefer_tiled[which]));
   if (use_band) {
     const BandPlan& b = band;
     BandParams q;
@@ -985,21 +1067,26 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     SC_HIP(pl->band_table->fn[shape][b.ni_idx][mi_idx](q, b.lds, stream));
     return SC_OK;
   }
-  const TilePick tp = pick_tile(pl, which, rows);
-  const int ti = tp.ti, splits = tp.splits;
+  TilePick tp = pick_tile(pl, which, rows);
+  // every row contracted, the mask looked at only at the store: plain sparse runs of dense operands without a shortcut
+  const bool masked = tp.masked && !dense && !identity && !compact && !x_compact && !y_compact && !residual &&
+                      d.layout == SC_NHWC && !g.rowseg;
+  if (tp.masked && !masked) tp = {tp.ti, 1, false};
+  const int ti = tp.ti, splits = masked ? 1 : tp.splits;
   const KernelEntry& ke = pl->table[ti];
-  const bool panel = !residual && use_panel(pl, which, rows);
+  const bool panel = !residual && !masked && use_panel(pl, which, rows);
   ConvParams p;
   std::memset(&p, 0, sizeof(p));
   p.x = x;
   p.wp = pl->ws + g.off_wp;
   p.bias = d.has_bias ? bias : nullptr;
   p.y = y;
-  p.row_idx = identity ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+  p.row_idx = (identity || masked) ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
   p.mask = pl->ws + g.off_mask;
   p.ktab = reinterpret_cast<const KEntry*>(pl->ws + g.off_ktab);
   p.zeros = pl->ws + g.off_zeros;
-  p.rows = (int32_t)rows;
+  p.rows = (int32_t)(masked ? g.m : rows);
+  p.masked_store = masked ? (d.out_mode == SC_OUT_ZERO_FILL ? 1 : 2) : 0;
   p.m_total = (int32_t)g.m;
   p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
   magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
@@ -1016,7 +1103,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     p.ys_n = (int64_t)d.c_out * p.ho_wo; p.ys_p = 1; p.ys_c = p.ho_wo;
   }
   p.relu = d.relu;
-  p.zero_fill = zero_fill ? 1 : 0;
+  p.zero_fill = zero_fill && !masked ? 1 : 0;
   p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
   p.vec_out = g.vec_out ? 1 : g.vec_out8 ? 2 : 0;
   p.x_compact = compact && x_compact ? 1 : 0;
@@ -1026,7 +1113,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
 #ifdef SC_TIMING
   p.dbg = g_dbg;
 #endif
-  p.m_tiles = (int32_t)((rows + ke.bm - 1) / ke.bm);
+  p.m_tiles = (int32_t)(((masked ? g.m : rows) + ke.bm - 1) / ke.bm);
   p.n_tiles = (d.c_out + ke.bn - 1) / ke.bn;
   // shallow K (pointwise layers): the workgroup lives for one or two K tiles, so residency, not
   // read-ahead, hides the latency -- take the two-tile ring and fit more workgroups per CU
@@ -1062,7 +1149,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     fn = buf_kernel(dt, ke.bm, ke.bn, g.k_tiles <= 2);
     fn_is_buf = true;
   }
-  if (fn_is_buf && splits == 1 && !panel) {
+  if (fn_is_buf && splits == 1 && !panel && !masked) {
     const int dt = d.dtype == SC_BF16 ? kBF16 : kF16;
     const int wgs = stream_k_workgroups(pl, ke, rows);
     LaunchFn sk = wgs ? streamk_kernel(dt, ke.bm, ke.bn) : nullptr;
@@ -1077,7 +1164,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     p.splits = splits;
     p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);
     p.counters = reinterpret_cast<int32_t*>(pl->ws + g.off_counters);
-    fn = ke.splitk;
+    fn = splitk_launcher(pl, ke);
   }
   if (panel) {
     p.m_tiles = (int32_t)((rows + kPanelBM - 1) / kPanelBM);
@@ -1247,18 +1334,21 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->table = d.dtype == SC_BF16 ? kernels_bf16(&pl->table_count)
               : d.dtype == SC_F16 ? kernels_f16(&pl->table_count)
                                   : kernels_f32(&pl->table_count);
-  pl->tile_sparse = choose_tile(pl->table, pl->table_count, pl->kept, d.c_out, g.vec_gather, g.k_tiles, g.rowseg, d.dtype != SC_F32 && g.vec_out && d.c_in % 64 == 0);
-  pl->tile_dense = choose_tile(pl->table, pl->table_count, g.m, d.c_out, g.vec_gather, g.k_tiles, g.rowseg, d.dtype != SC_F32 && g.vec_out && d.c_in % 64 == 0);
   pl->forced[0] = pl->forced[1] = -1;
+  pl->prefer_tiled[0] = pl->prefer_tiled[1] = false;
+  pl->tuned = false;
   pl->gather_pipeline = 0;
   pl->split_k = 0;
   pl->row_panel = 0;
   pl->stream_k = 0;
+  pl->masked_store = 0;
   pl->x_rank_set = false;
   pl->tile_splitk = -1;
   for (int i = 0; i < pl->table_count; ++i)
     if (pl->table[i].splitk && pl->table[i].bm == 64 && pl->table[i].bn == 128) pl->tile_splitk = i;
   if (pl->tile_splitk < 0) pl->geo.splitk_ok = false;
+  pl->pick[0] = model_pick(pl, 0, pl->kept);
+  pl->pick[1] = model_pick(pl, 1, g.m);
   pl->band = bp;
   pl->band_dense = plan_band(d, g, g.m);
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
@@ -1281,7 +1371,8 @@ sc_status sparse_conv_plan_set_mask(sc_plan* plan, const uint8_t* mask_dev, void
   if (s != SC_OK) return s;
   plan->kept = kept_host;
   plan->band = bp;
-  plan->tile_sparse = choose_tile(plan->table, plan->table_count, plan->kept, d.c_out, g.vec_gather, g.k_tiles, g.rowseg, d.dtype != SC_F32 && g.vec_out && d.c_in % 64 == 0);
+  plan->pick[0] = model_pick(plan, 0, plan->kept);      // (a measured choice belonged to the previous mask's row count)
+  plan->prefer_tiled[0] = false;
   return SC_OK;
 }
 
@@ -1377,6 +1468,115 @@ sc_status dense_conv_run(const sc_plan* plan, const void* x_dev, const float* bi
   return launch_conv(plan, true, x_dev, bias_dev, y_dev, static_cast<hipStream_t>(hip_stream));
 }
 
+sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev, void* hip_stream) {
+  sc_status st = check_run_args(plan, x_dev, bias_dev, y_dev);
+  if (st != SC_OK) return st;
+  if (plan->geo.depthwise) return SC_OK;       // one kernel per window shape: nothing to choose
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  SC_HIP(hipStreamSynchronize(stream));
+  // Candidates are timed as graphs of back-to-back launches on a stream of the library's own: launched one by one
+  // from the host, layers of a few microseconds would all measure the host's launch rate.
+  hipStream_t ts = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  SC_HIP(hipStreamCreateWithFlags(&ts, hipStreamNonBlocking));
+  if (hip_failed(hipEventCreate(&e0))) { (void)hipStreamDestroy(ts); return SC_ERR_HIP; }
+  if (hip_failed(hipEventCreate(&e1))) { (void)hipEventDestroy(e0); (void)hipStreamDestroy(ts); return SC_ERR_HIP; }
+  // microseconds per launch of the run as the plan stands (negative: something failed)
+  auto time_us = [&](bool dense, int launches, int replays) -> double {
+    if (launch_conv(plan, dense, x_dev, bias_dev, y_dev, ts) != SC_OK) return -1.0;     // also sets kernel attributes
+    if (hipStreamBeginCapture(ts, hipStreamCaptureModeThreadLocal) != hipSuccess) return -1.0;
+    bool ok = true;
+    for (int i = 0; i < launches && ok; ++i) ok = launch_conv(plan, dense, x_dev, bias_dev, y_dev, ts) == SC_OK;
+    hipGraph_t graph = nullptr;
+    if (hipStreamEndCapture(ts, &graph) != hipSuccess || !ok || !graph) {
+      if (graph) (void)hipGraphDestroy(graph);
+      (void)hipGetLastError();
+      return -1.0;
+    }
+    hipGraphExec_t exec = nullptr;
+    double best = -1.0;
+    if (hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess) {
+      for (int rep = 0; rep <= replays; ++rep) {       // replay 0 warms up
+        float ms = 0.0f;
+        if (hipEventRecord(e0, ts) != hipSuccess || hipGraphLaunch(exec, ts) != hipSuccess ||
+            hipEventRecord(e1, ts) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { best = -1.0; break; }
+        const double us = (double)ms * 1e3 / launches;
+        if (rep > 0 && (best < 0.0 || us < best)) best = us;
+      }
+      (void)hipGraphExecDestroy(exec);
+    }
+    (void)hipGraphDestroy(graph);
+    return best;
+  };
+  sc_status result = SC_OK;
+  for (int which = 0; which < 2 && result == SC_OK; ++which) {
+    const bool dense = which == 1;
+    const int64_t rows = dense ? plan->geo.m : plan->kept;
+    if (plan->forced[which] != -1 || rows == 0) continue;
+    plan->pick[which] = model_pick(plan, which, rows);
+    plan->prefer_tiled[which] = false;
+    if (time_us(dense, 100, 4) < 0.0) { result = SC_ERR_HIP; break; }     // clocks up before anything is compared
+    sc_plan::Pick best_pick = plan->pick[which];
+    bool best_tiled = false;
+    double best_us = time_us(dense, 40, 3);
+    if (best_us < 0.0) { result = SC_ERR_HIP; break; }
+    if (!plan->geo.vec_gather || plan->geo.rowseg) continue;           // one tile shape serves these gathers
+    // candidates: every tile x split (and the masked-store variant) the model prices within 1.6 x of its best
+    struct Cand { sc_plan::Pick pick; double predicted; };
+    Cand cands[128];
+    int n = 0;
+    double best_pred = 1e300;
+    const bool can_mask = which == 0 && rows < plan->geo.m;
+    for (int i = 0; i < plan->table_count && n < 120; ++i) {
+      const KernelEntry& ke = plan->table[i];
+      if (tile_lds_bytes(plan, ke) > kLdsLimit) continue;
+      const int most = split_candidates(plan, ke, rows);
+      for (int sp = 1; sp <= most; ++sp) {
+        cands[n] = {{i, sp, false}, predict_us(plan, ke, rows, sp, which == 0 && rows < plan->geo.m)};
+        best_pred = std::min(best_pred, cands[n++].predicted);
+      }
+      if (can_mask && plan->masked_store != 1) {
+        cands[n] = {{i, 1, true}, predict_us(plan, ke, plan->geo.m, 1, false) + 0.1};
+        best_pred = std::min(best_pred, cands[n++].predicted);
+      }
+    }
+    for (int c = 0; c < n; ++c) {
+      if (cands[c].predicted > 1.6 * best_pred) continue;
+      plan->pick[which] = cands[c].pick;
+      plan->prefer_tiled[which] = true;
+      const double us = time_us(dense, 40, 3);
+      if (us > 0.0 && us < 0.985 * best_us) { best_us = us; best_pick = cands[c].pick; best_tiled = true; }
+    }
+    plan->pick[which] = best_pick;
+    plan->prefer_tiled[which] = best_tiled;
+  }
+  // A sparse run must not lose to the dense run of its own plan: where it still does, try the dense run's tile with
+  // every row contracted and the mask applied at the store.
+  if (result == SC_OK && plan->forced[0] == -1 && plan->forced[1] == -1 && plan->kept > 0 && plan->kept < plan->geo.m &&
+      plan->masked_store != 1 && plan->geo.vec_gather && !plan->geo.rowseg && plan->desc.layout == SC_NHWC) {
+    const double us_sparse = time_us(false, 40, 3), us_dense = time_us(true, 40, 3);
+    const BandPlan& bd = plan->band_dense;
+    const bool dense_is_tiled = !(bd.ok && !bd.stream && !plan->prefer_tiled[1]) && !use_panel(plan, 1, plan->geo.m);
+    if (us_sparse > 0.0 && us_dense > 0.0 && us_sparse > us_dense && dense_is_tiled) {
+      const sc_plan::Pick keep = plan->pick[0];
+      const bool keep_tiled = plan->prefer_tiled[0];
+      plan->pick[0] = {plan->pick[1].ti, 1, true};
+      plan->prefer_tiled[0] = true;
+      const double us = time_us(false, 40, 3);
+      if (!(us > 0.0 && us < us_sparse)) { plan->pick[0] = keep; plan->prefer_tiled[0] = keep_tiled; }
+    }
+  }
+  plan->tuned = result == SC_OK;
+  if (hip_failed(hipStreamSynchronize(ts)) && result == SC_OK) result = SC_ERR_HIP;
+  if (result == SC_OK) result = launch_conv(plan, false, x_dev, bias_dev, y_dev, stream);   // y = the masked convolution
+  if (hip_failed(hipStreamSynchronize(stream)) && result == SC_OK) result = SC_ERR_HIP;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  (void)hipStreamDestroy(ts);
+  return result;
+}
+
 sc_status sparse_conv_plan_info(const sc_plan* plan, int64_t* m, int64_t* kept, int32_t* ho, int32_t* wo,
                                 const int32_t** row_idx_dev) {
   if (!plan) return SC_ERR_NULL;
@@ -1406,7 +1606,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     return SC_OK;
   }
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream))) {
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which]))) {
     if (tile_m) *tile_m = -band.bh;     // (rows per run; split bands hold half a run each)
     if (tile_n) *tile_n = 32 * band.ni;
     if (workgroups) *workgroups = band.pp && !band.tap ? band.pp_grid : (int64_t)band.n_bands * band.n_tiles;
@@ -1420,7 +1620,8 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     return SC_OK;
   }
   const TilePick tp = pick_tile(plan, which, rows);
-  const int splits = tp.splits;
+  const int splits = tp.masked ? 1 : tp.splits;
+  if (tp.masked && which == 0) rows = plan->geo.m;
   const KernelEntry& ke = plan->table[tp.ti];
   if (tile_m) *tile_m = ke.bm;
   if (tile_n) *tile_n = ke.bn;
@@ -1434,7 +1635,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 static const char* tiled_kernel_name(const sc_plan* plan, int32_t which) {
   const Geometry& g = plan->geo;
   const TilePick tp = pick_tile(plan, which, which ? g.m : plan->kept);
-  if (tp.splits > 1) return "tile_split_k";
+  if (tp.splits > 1 && !tp.masked) return "tile_split_k";
   if (stream_k_workgroups(plan, plan->table[tp.ti], which ? g.m : plan->kept)) return "tile_stream_k";
   if (g.rowseg) return "tile_row_segments";
   if (!g.vec_gather) return "tile_elements";
@@ -1445,7 +1646,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1)) return nullptr;
   if (plan->geo.depthwise) return "depthwise";
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream)))
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which])))
     return band.stream ? "band_stream" : band.tap ? "band_tap" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
@@ -1455,7 +1656,8 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
 const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1) || plan->geo.depthwise) return nullptr;
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && (band.pp || band.tap) && !band.stream && (plan->forced[which] == kForceBand || plan->forced[which] == -1))
+  if (band.ok && (band.pp || band.tap) && !band.stream &&
+      (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->prefer_tiled[which])))
     return band.tap ? "band_tap" : "band_alternating";
   return tiled_kernel_name(plan, which);
 }
@@ -1481,6 +1683,7 @@ sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t val
   if (option == SC_OPT_ROW_PANEL && value >= 0 && value <= 2) { plan->row_panel = value; return SC_OK; }
   if (option == SC_OPT_SPLIT_K && value >= 0 && value <= kSplitKMost) { plan->split_k = value; return SC_OK; }
   if (option == SC_OPT_STREAM_K && value >= 0 && value <= kStreamKMostWgs) { plan->stream_k = value; return SC_OK; }
+  if (option == SC_OPT_MASKED_STORE && value >= 0 && value <= 2) { plan->masked_store = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }
 

@@ -13,7 +13,7 @@ from parity import TOL, assert_close, check_layer, compare_network, rows_view
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [(256, 128), (128, 128), (256, 64), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)]
+ALL_TILES = [(256, 128), (128, 256), (128, 128), (256, 64), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)]
 
 
 def spec_of(n, cin, h, w, cout, k=3, s=1, p=1, d=1, dtype="bf16", layout="nhwc", bias=True, relu=True, sp=0.5,
@@ -82,14 +82,92 @@ def test_tile_choice_follows_the_reduced_row_count():
         B.sparse_conv_plan_set_tiles(wide.plan, 0, 48, 48)
 
 
-def test_tall_tile_for_deep_layers_whose_tiles_just_overfill_the_cus():
-    """The deepest detector layer at s = 0.3: 4 480 kept rows make 280 tiles of 64 x 128 on 256 CUs; the plan takes
-    96 x 128 tiles (188: one round) for the sparse run, keeps 64 x 128 for its dense run, and matches the oracle."""
+def test_deep_layer_choice_fills_the_compute_units_in_one_round():
+    """The deepest detector layer at s = 0.3: 4 480 kept rows would make 280 tiles of 64 x 128 on 256 compute units (two
+    on some, one on the rest).  The priced choice stays within one round of workgroups, and matches the oracle."""
     spec = spec_of(16, 512, 20, 20, 512, dtype="bf16", sp=0.3)
     layer = check_layer(W.make_conv_inputs(spec, 975), sample_rows=256)
-    assert B.sparse_conv_plan_tiles(layer.plan, 0) == (96, 128, 188)
-    assert B.sparse_conv_plan_tiles(layer.plan, 1) == (64, 128, 400)
-    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+    assert wgs <= 256 and tm * tn >= 96 * 128
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) in ("tile_lds_direct", "tile_split_k")
+
+
+def test_masked_store_variant_matches_the_row_list_variant():
+    """A sparse run that contracts every row and applies the mask at the store (small layers): same kernels, same K
+    order, so the kept rows carry the bits of the row-list run, and the dropped rows are zeros or untouched."""
+    cases = [dict(n=4, cin=192, h=14, w=14, cout=32, k=1, p=0),            # buffer-load form
+             dict(n=2, cin=32, h=9, w=11, cout=192, k=1, p=0, sp=0.3),     # direct-to-LDS form, one K tile
+             dict(n=1, cin=24, h=13, w=13, cout=40, sp=0.6),                # register-staged form, 16-byte groups only
+             dict(n=2, cin=128, h=10, w=10, cout=128, sp=0.5, mask_mode="spatial"),
+             dict(n=1, cin=5, h=9, w=8, cout=7, sp=0.5)]                    # element gather and element stores
+    for i, case in enumerate(cases):
+        for dtype in ("bf16", "f32"):
+            for out_mode in (B.SC_OUT_ZERO_FILL, B.SC_OUT_SCATTER_ONLY):
+                spec = spec_of(dtype=dtype, **case)
+                ci = W.make_conv_inputs(spec, 1100 + i)
+                layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask, out_mode=out_mode)
+                B.sparse_conv_plan_set_tiles(layer.plan, 0, 64, 64)
+                x = R.to_device(ci.x, dtype)
+                sentinel = float("nan") if out_mode == B.SC_OUT_ZERO_FILL else 7.0
+                B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_MASKED_STORE, 1)
+                a = layer.new_output().fill_(sentinel)
+                layer.sparse(x, a)
+                B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_MASKED_STORE, 2)
+                assert B.sparse_conv_plan_tiles(layer.plan, 0)[2] == -(-spec.m // 64) * -(-spec.c_out // 64)   # every row
+                b = layer.new_output().fill_(sentinel)
+                layer.sparse(x, b)
+                torch.cuda.synchronize()
+                assert np.array_equal(R.bits_of(a), R.bits_of(b)), (case, dtype, out_mode)
+    # and against the oracle, with the tile left to the plan
+    spec = spec_of(8, 192, 7, 7, 32, k=1, p=0, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 1111)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_MASKED_STORE, 2)
+    y = layer.new_output(fill_nan=True)
+    layer.sparse(R.to_device(ci.x, "bf16"), y)
+    torch.cuda.synchronize()
+    ref, absum = oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask, want_absum=True)
+    kept = ci.mask == 1
+    assert (rows_view(spec, R.bits_of(y))[~kept] == 0).all()
+    assert_close(rows_view(spec, R.to_host_f32(y))[kept], rows_view(spec, ref)[kept], rows_view(spec, absum)[kept], TOL["bf16"])
+
+
+@pytest.mark.parametrize("case", [
+    dict(n=16, cin=512, h=7, w=7, cout=512, sp=0.5),             # deep: K splits are candidates
+    dict(n=8, cin=192, h=7, w=7, cout=32, k=1, p=0, sp=0.5),     # tiny pointwise layer: the masked-store variant is one
+    dict(n=4, cin=64, h=28, w=28, cout=64, sp=0.5),              # a band-kernel layer
+    dict(n=2, cin=96, h=28, w=28, cout=576, k=1, p=0, sp=0.5),   # row-panel kernel
+    dict(n=1, cin=3, h=64, w=64, cout=64, k=7, s=2, p=3, sp=0.5),  # row-segment gather: one shape, nothing to choose
+])
+def test_measured_choice_keeps_the_results(case):
+    """sparse_conv_plan_tune replaces the model's choice by the fastest measured one; whatever it picks, both runs match
+    the oracle, y holds the sparse run on return, and a new mask returns the sparse run to the model's choice."""
+    spec = spec_of(dtype="bf16", **case)
+    ci = W.make_conv_inputs(spec, 1120)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    x = R.to_device(ci.x, "bf16")
+    y = layer.new_output(fill_nan=True)
+    B.sparse_conv_plan_tune(layer.plan, x, layer.bias, y)
+    torch.cuda.synchronize()
+    ref, absum = oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, ci.mask, want_absum=True)
+    kept = ci.mask == 1
+    assert (rows_view(spec, R.bits_of(y))[~kept] == 0).all()
+    assert_close(rows_view(spec, R.to_host_f32(y))[kept], rows_view(spec, ref)[kept], rows_view(spec, absum)[kept], TOL["bf16"])
+    yd = layer.new_output(fill_nan=True)
+    layer.dense(x, yd)
+    torch.cuda.synchronize()
+    refd, absd = oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, np.ones_like(ci.mask), want_absum=True)
+    assert_close(rows_view(spec, R.to_host_f32(yd)), rows_view(spec, refd), rows_view(spec, absd), TOL["bf16"])
+    # a refreshed mask: the plan still computes the right thing with its new row count
+    mask2 = W.gen_mask(spec.m, W.n_keep(0.5, spec.m), 77)
+    B.sparse_conv_plan_set_mask(layer.plan, torch.from_numpy(mask2).to("cuda:0"))
+    y2 = layer.new_output(fill_nan=True)
+    layer.sparse(x, y2)
+    torch.cuda.synchronize()
+    ref2, abs2 = oracle.masked_conv2d(spec, ci.x, ci.w, ci.bias, mask2, want_absum=True)
+    k2 = mask2 == 1
+    assert (rows_view(spec, R.bits_of(y2))[~k2] == 0).all()
+    assert_close(rows_view(spec, R.to_host_f32(y2))[k2], rows_view(spec, ref2)[k2], rows_view(spec, abs2)[k2], TOL["bf16"])
 
 
 BAND_CASES = [
@@ -225,7 +303,7 @@ def test_split_k_kernel(case, splits, dtype):
     assert (tm, tn) == (64, 128) and wgs % tiles == 0 and 2 <= wgs // tiles <= splits
 
 
-@pytest.mark.parametrize("tile", [(128, 128), (64, 128), (128, 64), (64, 64)])
+@pytest.mark.parametrize("tile", [(256, 128), (128, 256), (128, 128), (96, 128), (64, 128), (128, 64), (64, 64)])
 def test_split_k_every_tile_shape(tile):
     spec = spec_of(2, 256, 12, 12, 160, dtype="bf16", sp=0.4)        # 36 K tiles, ragged rows and channels
     layer = check_layer(W.make_conv_inputs(spec, 989), tiles=tile, split_k=5)
@@ -234,11 +312,15 @@ def test_split_k_every_tile_shape(tile):
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
 
 
-def test_split_k_runs_only_on_request():
+def test_split_k_on_request_and_never():
     spec = spec_of(64, 512, 7, 7, 512, dtype="bf16", sp=0.5)        # the deepest ResNet18 layers at batch 64
     ci = W.make_conv_inputs(spec, 990)
     layer = check_layer(ci, sample_rows=128)
-    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    # automatic: at most four splits of a tile that has the buffer-load split kernel, priced against the unsplit launches
+    if B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k":
+        tm, tn, wgs = B.sparse_conv_plan_tiles(layer.plan, 0)
+        assert (tm, tn) in ((256, 128), (128, 256), (128, 128), (96, 128), (64, 128))
+        assert 2 <= wgs // (-(-layer.info["kept"] // tm) * -(-512 // tn)) <= 4
     B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, 2)
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_split_k"
     assert B.sparse_conv_plan_tiles(layer.plan, 0) == (64, 128, 2 * 25 * 4)
@@ -261,7 +343,7 @@ BUFFER_CASES = [
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
-@pytest.mark.parametrize("tile", [(128, 128), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)])
+@pytest.mark.parametrize("tile", [(256, 128), (128, 256), (128, 128), (128, 64), (96, 128), (64, 128), (64, 64), (128, 32), (32, 128)])
 @pytest.mark.parametrize("case", range(len(BUFFER_CASES)))
 def test_buffer_load_tiled_kernel(case, tile, dtype):
     spec = spec_of(dtype=dtype, **BUFFER_CASES[case])
