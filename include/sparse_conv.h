@@ -363,6 +363,18 @@ sc_status sc_add_relu(const void* a_dev, const void* b_dev, void* y_dev, int32_t
                       void* hip_stream);
 sc_status sc_add(const void* a_dev, const void* b_dev, void* y_dev, int32_t dtype, int64_t count, void* hip_stream);
 
+/*
+ * Measurement probes (not part of the method): what the device sustains on the two roofs the kernels are priced against.
+ *   sc_probe_stream_copy  enqueues a plain copy of `bytes` (a multiple of 16; both pointers 16-byte aligned, device, not
+ *                         overlapping): read + write bandwidth of the memory system is 2 * bytes / time.
+ *   sc_probe_mfma_bf16    enqueues `workgroups` workgroups of four wavefronts that each issue `iterations` x 4 independent
+ *                         32x32x16 bf16 MFMAs on register operands; out_dev: float[workgroups * 256], written so that the
+ *                         loop is live; *flops (host, may be NULL) receives the FLOP count of the launch.
+ * Enqueue only.  Errors: SC_ERR_NULL, SC_ERR_ALIGN, SC_ERR_BAD_SHAPE, SC_ERR_HIP.
+ */
+sc_status sc_probe_stream_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream);
+sc_status sc_probe_mfma_bf16(int32_t iterations, int32_t workgroups, float* out_dev, double* flops, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

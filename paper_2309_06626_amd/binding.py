@@ -118,6 +118,10 @@ def lib() -> ctypes.CDLL:
         L.sparse_conv_backward_destroy.argtypes = [vp]
         L.sparse_conv_plan_tune.restype = ctypes.c_int
         L.sparse_conv_plan_tune.argtypes = [vp, vp, vp, vp, vp]
+        L.sc_probe_stream_copy.restype = ctypes.c_int
+        L.sc_probe_stream_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+        L.sc_probe_mfma_bf16.restype = ctypes.c_int
+        L.sc_probe_mfma_bf16.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.sparse_mask_workspace_bytes.restype = ctypes.c_int
         L.sparse_mask_workspace_bytes.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         L.sparse_mask_generate.restype = ctypes.c_int
@@ -528,6 +532,25 @@ def sparse_mask_generate(score: torch.Tensor, ho: int, wo: int, sparsity: float,
                                       _dev_ptr(mask, "mask"), _dev_ptr(workspace, "workspace"), workspace.numel(),
                                       _stream_handle(stream)), "sparse_mask_generate")
     return mask
+
+
+def sc_probe_stream_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    """Enqueues the library's plain copy kernel (measurement probe)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("copy probe: sizes differ")
+    _check(lib().sc_probe_stream_copy(_dev_ptr(dst, "dst"), _dev_ptr(src, "src"), nbytes, _stream_handle(stream)),
+           "sc_probe_stream_copy")
+
+
+def sc_probe_mfma_bf16(iterations: int, workgroups: int, out: torch.Tensor, stream=None) -> float:
+    """Enqueues the register-resident MFMA loop (measurement probe); returns its FLOP count."""
+    if out.numel() < workgroups * 256 or out.dtype != torch.float32:
+        raise ValueError("mfma probe: out must hold workgroups * 256 floats")
+    flops = ctypes.c_double()
+    _check(lib().sc_probe_mfma_bf16(iterations, workgroups, _dev_ptr(out, "out"), ctypes.byref(flops),
+                                    _stream_handle(stream)), "sc_probe_mfma_bf16")
+    return float(flops.value)
 
 
 SC_STATIC_MASK_PIXELS = 1 << 18
