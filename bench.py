@@ -93,45 +93,11 @@ def cpu_baseline(spec, ci, budget_s: float = 12.0):
     return out
 
 
-class StepGraph:
-    """K back-to-back launches of one prepared run, recorded once and replayed with one host call."""
-
-    def __init__(self, call, steps: int):
-        import torch
-
-        self.steps = steps
-        self.stream = torch.cuda.Stream()
-        self.graph = torch.cuda.CUDAGraph()
-        handle = self.stream.cuda_stream
-        with torch.cuda.stream(self.stream):
-            call(handle)                       # first launch outside the capture (kernel attributes, code load)
-            self.stream.synchronize()
-            with torch.cuda.graph(self.graph, stream=self.stream):
-                for _ in range(steps):
-                    call(handle)
-        self.call, self.handle = call, handle
-
-    def timed_replay(self, warmup: int):
-        """(wall seconds, event seconds) of one replay of the K steps after `warmup` untimed launches."""
-        import torch
-
-        with torch.cuda.stream(self.stream):
-            for _ in range(warmup):
-                self.call(self.handle)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            self.stream.synchronize()
-            t0 = time.perf_counter()
-            e0.record(self.stream)
-            self.graph.replay()
-            e1.record(self.stream)
-            self.stream.synchronize()
-            wall = time.perf_counter() - t0
-        return wall, e0.elapsed_time(e1) * 1e-3
-
-
 def median_times(call, steps: int, warmup: int, repeats: int = REPEATS):
-    g = StepGraph(call, steps)
-    runs = [g.timed_replay(warmup) for _ in range(repeats)]
+    from paper_2309_06626_amd.metrics import LaunchGraph
+
+    g = LaunchGraph(call, steps)
+    runs = [g.replay(warmup) for _ in range(repeats)]
     wall = statistics.median(r[0] for r in runs) / steps
     ev = statistics.median(r[1] for r in runs) / steps
     return wall, ev, [r[1] / steps for r in runs]
@@ -201,16 +167,29 @@ def main():
     import workloads as W
     from paper_2309_06626_amd import binding as B
     from paper_2309_06626_amd import runtime as R
-    from paper_2309_06626_amd.metrics import algorithmic_bytes, buffer_sets_for_cold_runs, time_launches, time_rotating
+    from paper_2309_06626_amd.metrics import algorithmic_bytes, buffer_sets_for_cold_runs, time_rotating
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     B.lib()
 
+    def eager_times(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
     def timed(call, steps, warm):
         if args.eager:
-            w, e = time_launches(call, steps, warm)
+            w, e = eager_times(call, steps, warm)
             return w, e, [e]
         return median_times(call, steps, warm)
 
@@ -260,10 +239,10 @@ def main():
             cs = [B.prepared_run(layer.plan, a, layer.bias, b) for a, b in zip(xs, ys)]
             cd = [B.prepared_run(layer.plan, a, layer.bias, b, dense=True) for a, b in zip(xs, ys)]
             n_cold = max(steps // 4, 4 * nsets)
-            ev_c = statistics.median(time_rotating(cs, n_cold, nsets) for _ in range(5))
-            ev_cd = statistics.median(time_rotating(cd, n_cold, nsets) for _ in range(5))
+            ev_c = time_rotating(cs, n_cold, nsets, repeats=5)
+            ev_cd = time_rotating(cd, n_cold, nsets, repeats=5)
             cold = {"kernel_us": ev_c * 1e6, "dense_kernel_us": ev_cd * 1e6, "speedup_vs_dense": ev_cd / ev_c,
-                    "buffer_sets": nsets, "how": "eager launches rotating through the buffer sets, median of 5"}
+                    "buffer_sets": nsets, "how": "graph of launches rotating through the buffer sets, median of 5 replays"}
             del xs, ys, cs, cd
         results[s] = dict(spec=spec, ci=ci, layer=layer, wall=wall_s, ev=ev_s, wall_dense=wall_d, ev_dense=ev_d,
                           plan_ms=plan_ms, tune_ms=tune_ms, steps=steps, warm=warm, cold=cold, reps=reps_s)

@@ -336,19 +336,25 @@ def add_relu(a: np.ndarray, b: np.ndarray) -> np.ndarray:
     return y
 
 
-def run_network(ops, tensors: Dict[str, np.ndarray], layer_inputs) -> Dict[str, np.ndarray]:
+def run_network(ops, tensors: Dict[str, np.ndarray], layer_inputs, absums: Optional[Dict[str, np.ndarray]] = None
+                ) -> Dict[str, np.ndarray]:
     """Interpret a list of workload ops on the CPU.
 
     ``tensors`` holds the named inputs (float32, values representable in the storage dtype);
     ``layer_inputs(spec)`` returns (w, bias, mask) for a conv.  Every op's result is rounded to
     the storage dtype, as a runtime that keeps activations in that dtype would.
+    ``absums``: when a dict is passed it receives, per convolution output, the sum of the magnitudes of
+    every product and the bias behind each element (the condition-aware error bound of the layer tests).
     """
     t = dict(tensors)
     for op in ops:
         if op.kind == "conv":
             w, b, m = layer_inputs(op.spec)
             conv = masked_depthwise_conv2d if op.spec.groups > 1 else masked_conv2d
-            y = conv(op.spec, t[op.src], w, b, m)
+            if absums is not None:
+                y, absums[op.out] = conv(op.spec, t[op.src], w, b, m, want_absum=True)
+            else:
+                y = conv(op.spec, t[op.src], w, b, m)
             t[op.out] = round_storage(y, op.spec.dtype)
         elif op.kind == "maxpool":
             t[op.out] = maxpool2d_nhwc(t[op.src], 3, 2, 1)

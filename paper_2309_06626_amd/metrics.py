@@ -40,40 +40,78 @@ def algorithmic_flops(spec, keep: int) -> float:
     return 2.0 * keep * spec.k * spec.c_out
 
 
-def time_launches(fn, steps: int, warmup: int):
-    """(wall seconds, event seconds) per launch of `steps` back-to-back launches on the current stream."""
+def warm_clocks(fn, seconds: float = 0.03):
+    """Launch for `seconds` before anything is timed: the first launches after an idle period run at ramping clocks, and
+    a run of a thousand launches of a few microseconds each would measure mostly that."""
     import torch
 
-    for _ in range(warmup):
-        fn()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        fn()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    return wall / steps, e0.elapsed_time(e1) * 1e-3 / steps
+    t_end = time.perf_counter() + seconds
+    while time.perf_counter() < t_end:
+        for _ in range(100):
+            fn()
+        torch.cuda.synchronize()
 
 
-def time_rotating(fns, steps: int, warmup: int):
+class LaunchGraph:
+    """`steps` back-to-back launches, cycling through `calls` (callables taking a stream handle), recorded once as a HIP
+    graph on a stream of its own and replayed with one host call: device time per launch without the host's launch rate
+    in it (layers of a few microseconds are otherwise timed at the speed of the Python loop that launches them)."""
+
+    def __init__(self, calls, steps: int):
+        import torch
+
+        self.calls = list(calls) if isinstance(calls, (list, tuple)) else [calls]
+        self.steps = steps
+        self.stream = torch.cuda.Stream()
+        self.graph = torch.cuda.CUDAGraph()
+        self.handle = self.stream.cuda_stream
+        with torch.cuda.stream(self.stream):
+            for c in self.calls:                  # first launches outside the capture (kernel attributes, code load)
+                c(self.handle)
+            self.stream.synchronize()
+            with torch.cuda.graph(self.graph, stream=self.stream):
+                for i in range(steps):
+                    self.calls[i % len(self.calls)](self.handle)
+
+    def replay(self, warmup: int = 0):
+        """(wall seconds, event seconds) of one replay after `warmup` untimed launches."""
+        import torch
+
+        with torch.cuda.stream(self.stream):
+            for i in range(warmup):
+                self.calls[i % len(self.calls)](self.handle)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            self.stream.synchronize()
+            t0 = time.perf_counter()
+            e0.record(self.stream)
+            self.graph.replay()
+            e1.record(self.stream)
+            self.stream.synchronize()
+            wall = time.perf_counter() - t0
+        return wall, e0.elapsed_time(e1) * 1e-3
+
+
+def time_launches(fn, steps: int, warmup: int, repeats: int = 3):
+    """(wall seconds, event seconds) per launch: `steps` back-to-back launches replayed as a graph, median of
+    `repeats` replays, after the clocks have been warmed up."""
+    import statistics
+
+    warm_clocks(fn)
+    g = LaunchGraph(fn, steps)
+    runs = [g.replay(warmup) for _ in range(repeats)]
+    return statistics.median(r[0] for r in runs) / steps, statistics.median(r[1] for r in runs) / steps
+
+
+def time_rotating(fns, steps: int, warmup: int, repeats: int = 3):
     """Event seconds per launch when the launches cycle through `fns` -- the same operation on different
     buffer sets whose total size exceeds the caches, so every launch finds its operands in HBM only."""
-    import torch
+    import statistics
 
     n = len(fns)
-    for i in range(warmup):
-        fns[i % n]()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(steps):
-        fns[i % n]()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e-3 / steps
+    steps = max(steps, 2 * n)
+    warm_clocks(fns[0])
+    g = LaunchGraph(fns, steps)
+    return statistics.median(g.replay(warmup)[1] for _ in range(repeats)) / steps
 
 
 def buffer_sets_for_cold_runs(bytes_per_set: int, total_bytes: int = 768 << 20, most: int = 64) -> int:

@@ -213,10 +213,12 @@ class NetworkRunner:
     a HIP graph: the library launches kernels only, no memsets, no allocations, no synchronisation)."""
 
     def __init__(self, ops, tensors: Dict[str, torch.Tensor], layers: Dict[str, ConvLayer], dense: bool = False,
-                 row_formats: Optional[Dict[str, bool]] = None, fuse_shortcuts: bool = False):
+                 row_formats: Optional[Dict[str, bool]] = None, fuse_shortcuts: bool = False, tune: bool = False):
         """row_formats: the result of plan_row_formats, to keep those tensors compact (sparse runs only).
         fuse_shortcuts: sums that plan_shortcut_fusions accepts run in the epilogue of their conv; the conv's own
-        result is then never materialised (its name is absent from the tensors)."""
+        result is then never materialised (its name is absent from the tensors).
+        tune: every convolution with dense operands gets its kernels chosen by measurement on the network's own
+        buffers (sparse_conv_plan_tune) before the launches are prepared."""
         self.tensors = dict(tensors)
         self.calls: List[Callable] = []
         self.row_formats = {} if (dense or row_formats is None) else dict(row_formats)
@@ -249,6 +251,8 @@ class NetworkRunner:
                     B.sparse_conv_plan_set_input_mask(layer.plan, rows_mask[op.src])
                 if xf == B.SC_ROWS_DENSE and yf == B.SC_ROWS_DENSE:
                     t[op.out] = layer.new_output()
+                    if tune:
+                        B.sparse_conv_plan_tune(layer.plan, t[op.src], layer.bias, t[op.out])
                     self.calls.append(B.prepared_run(layer.plan, t[op.src], layer.bias, t[op.out], dense=dense))
                     continue
                 if yf == B.SC_ROWS_COMPACT:

@@ -130,7 +130,12 @@ def check_layer(ci: W.ConvInputs, tiles=None, out_mode=B.SC_OUT_ZERO_FILL, check
     return layer
 
 
-def compare_network(ops, dev, ref, params, tol):
+def compare_network(ops, dev, ref, params, tol, absums=None):
+    """Every tensor of a network run against the oracle's: normwise, against the largest reference magnitude, and --
+    with `absums` from the oracle's interpreter -- element by element against tol * (sum |x*w| + |bias|) of the
+    convolution that produced it, the bound check_layer applies to single layers.  (Both sides feed every layer with
+    their own rounded previous outputs, so an element's error also carries what its inputs differed by; the bound
+    is the same one all the same.)"""
     for op in ops:
         g, r = R.to_host_f32(dev[op.out]), ref[op.out]
         assert g.shape == r.shape
@@ -138,6 +143,10 @@ def compare_network(ops, dev, ref, params, tol):
         err = np.linalg.norm(g.astype(np.float64) - r.astype(np.float64)) / max(nr, 1e-30)
         assert err <= tol, f"{op.out}: normwise {err:.3e}"
         assert np.abs(g - r).max() <= tol * max(np.abs(r).max(), 1e-30), op.out
+        if absums is not None and op.kind == "conv":
+            bound = tol * absums[op.out].reshape(r.shape) + 1e-30
+            worst = (np.abs(g.astype(np.float64) - r) / bound).max()
+            assert worst <= 1.0, f"{op.out}: element error is {worst:.3f} x the allowed tol*sum|x*w|"
         if op.kind == "conv":
             mask = params[op.spec.name][2]
             bits = rows_view(op.spec, R.bits_of(dev[op.out]))
