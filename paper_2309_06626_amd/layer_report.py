@@ -378,8 +378,9 @@ def main():
     ap.add_argument("--oracle-times", action="store_true",
                     help="also time the CPU oracle on every configuration (all host cores; one thread for configs 1 and 2)")
     ap.add_argument("--profile-layer", default="",
-                    help="NAME[:BMxBN][:dense] -- only launch that layer of config 2 (s = 0.5), 3 or 5 --steps times (sparse run, "
-                         "or the dense run), optionally with a forced tile of the tiled kernel: the target of a rocprofv3 run")
+                    help="NAME[:BMxBN][:splitN][:dense][:cold] -- only launch that layer of config 2 (s = 0.5), 3, 4 or 5 --steps times "
+                         "(sparse run, or the dense run), optionally with a forced tile of the tiled kernel and N splits of K, "
+                         "optionally rotating through buffer copies larger than the memory-side cache: the target of a rocprofv3 run")
     args = ap.parse_args()
 
     import torch
@@ -395,22 +396,32 @@ def main():
     B.lib()
     if args.profile_layer:
         from paper_2309_06626_amd import runtime as R
+        from paper_2309_06626_amd.metrics import buffer_sets_for_cold_runs
         parts = args.profile_layer.split(":")
         specs = {s.name: (s, cfg) for cfg, ops in ((3, W.config3()), (5, W.config5())) for s in W.conv_specs(ops)}
+        specs.update({s.name: (s, 4) for s in W.config4()})
         specs[W.config2(0.5).name] = (W.config2(0.5), 2)
         spec, cfg = specs[parts[0]]
         ci = W.make_conv_inputs(spec, W.base_seed(cfg))
         layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
         dense = "dense" in parts[1:]
         for part in parts[1:]:
-            if "x" in part:
+            if part.startswith("split"):
+                B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, int(part[5:]))
+            elif "x" in part:
                 bm, bn = (int(v) for v in part.split("x"))
                 B.sparse_conv_plan_set_tiles(layer.plan, 0, bm, bn)
                 B.sparse_conv_plan_set_tiles(layer.plan, 1, bm, bn)
         x, y = R.to_device(ci.x, spec.dtype), layer.new_output()
-        call = B.prepared_run(layer.plan, x, layer.bias, y, dense=dense)
-        for _ in range(args.steps):
-            call()
+        if "cold" in parts[1:]:                     # rotate through copies beyond the memory-side cache
+            nsets = buffer_sets_for_cold_runs(x.numel() * x.element_size() + y.numel() * y.element_size())
+            calls = [B.prepared_run(layer.plan, x.clone(), layer.bias, torch.empty_like(y), dense=dense) for _ in range(nsets)]
+            for i in range(max(args.steps, 2 * nsets)):
+                calls[i % nsets]()
+        else:
+            call = B.prepared_run(layer.plan, x, layer.bias, y, dense=dense)
+            for _ in range(args.steps):
+                call()
         torch.cuda.synchronize()
         which = 1 if dense else 0
         print(f"{spec.name}: {args.steps} launches of {B.sparse_conv_plan_kernel(layer.plan, which)} "
