@@ -208,7 +208,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_tap", "band_stream", "tile_row_panel", "tile_split_k", "tile_stream_k", "tile_lds_direct",
+ * "band_alternating", "band_tap", "band_stream", "tile_row_panel", "tile_split_k", "tile_masked_store", "tile_stream_k", "tile_lds_direct",
  * "tile_registers", "tile_row_segments", "tile_elements" or "depthwise".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);
@@ -321,7 +321,9 @@ void sparse_conv_backward_destroy(sc_bwd_plan* plan);
  *   mask_dev    uint8[ho * wo], device: 1 = keep, 0 = drop (the SC_MASK_SPATIAL mask of sparse_conv_plan).
  *   workspace_dev  at least sparse_mask_workspace_bytes(ho, wo) bytes, 8-byte aligned, device; scratch,
  *               owned by the caller, free for reuse once the stream has passed the call.
- * Enqueues two kernels on `hip_stream` and returns; no allocation, no synchronisation.
+ *               (one 64-bit key per layer pixel and about 130 KiB of selection state.)
+ * Enqueues two kernels on `hip_stream` (four for maps of more than 16 384 pixels, whose ranking is spread over many
+ * workgroups) and returns; no allocation, no synchronisation.
  * Errors: SC_ERR_NULL, SC_ERR_BAD_SHAPE (extents, sparsity outside [0, 1], more than 2^26 pixels),
  * SC_ERR_WORKSPACE, SC_ERR_ALIGN, SC_ERR_HIP.
  */
@@ -333,15 +335,15 @@ sc_status sparse_mask_generate(const float* score_dev, int32_t in_h, int32_t in_
 /*
  * sparse_mask_generate for callers that cannot allocate device memory and so have no workspace to hand over: code
  * under HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same arguments, same
- * two kernels and bit-identical masks; the scratch (one 64-bit key per layer pixel) is a fixed array inside the
- * library's code object instead of the caller's workspace.
+ * kernels and bit-identical masks; the scratch (one 64-bit key per layer pixel, then the selection state) is a fixed
+ * array inside the library's code object instead of the caller's workspace.
  *   - at most SC_STATIC_MASK_PIXELS layer pixels (ho * wo); a larger map returns SC_ERR_WORKSPACE and launches nothing;
- *   - the array (2 MiB) exists once per GPU the library runs on and is held until the process ends; the first call
+ *   - the array (2 MiB + 128 KiB) exists once per GPU the library runs on and is held until the process ends; the first call
  *     on a device asks the runtime for its address (no allocation), so make that call outside a graph capture;
  *   - calls no hipMalloc / hipFree or other allocating routine and never synchronises;
  *   - every call on one GPU uses that GPU's one array: calls whose work overlaps on a GPU (two streams, two threads)
  *     race on it and give wrong masks -- order them on one stream or with events.  Nothing needs clearing between
- *     calls: the first kernel overwrites every key the second reads.
+ *     calls: the first kernel overwrites every key the later ones read and clears the counters they add to.
  * Errors otherwise as for sparse_mask_generate (SC_ERR_NULL, SC_ERR_BAD_SHAPE, SC_ERR_HIP).
  */
 #define SC_STATIC_MASK_PIXELS (1 << 18)

@@ -1635,7 +1635,8 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
 static const char* tiled_kernel_name(const sc_plan* plan, int32_t which) {
   const Geometry& g = plan->geo;
   const TilePick tp = pick_tile(plan, which, which ? g.m : plan->kept);
-  if (tp.splits > 1 && !tp.masked) return "tile_split_k";
+  if (tp.masked) return "tile_masked_store";
+  if (tp.splits > 1) return "tile_split_k";
   if (stream_k_workgroups(plan, plan->table[tp.ti], which ? g.m : plan->kept)) return "tile_stream_k";
   if (g.rowseg) return "tile_row_segments";
   if (!g.vec_gather) return "tile_elements";

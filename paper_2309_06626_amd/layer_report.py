@@ -300,7 +300,7 @@ def backward_times(steps):
 
 
 def mask_generator_times(steps):
-    """us per call of the mask generator (two launches) for the layer resolutions of the two networks."""
+    """us per call of the mask generator (two launches; four for maps above 16 384 pixels) for the layer resolutions of the two networks."""
     import torch
 
     import workloads as W
@@ -545,7 +545,7 @@ def main():
     if args.masks:
         mask_rows = mask_generator_times(max(args.steps // 4, 20))
         print()
-        print("| mask generator: score | layer map | s | kept pixels | us per mask (pooling + ranking, two launches) |")
+        print("| mask generator: score | layer map | s | kept pixels | us per mask (pooling + ranking: two launches, four above 16 384 pixels) |")
         print("|---|---|---|---|---|")
         for r in mask_rows:
             print(f"| {r['score']} | {r['layer']} | {r['sparsity']:.2f} | {r['kept']} | {r['us']:.1f} |")

@@ -108,7 +108,7 @@ def test_missing_library_is_a_loud_error(monkeypatch, tmp_path):
 def test_mask_generator_rejects_bad_arguments_before_any_gpu_work():
     L = B.lib()
     size = ctypes.c_size_t(123)
-    assert L.sparse_mask_workspace_bytes(7, 5, ctypes.byref(size)) == B.SC_OK and size.value == 7 * 5 * 8
+    assert L.sparse_mask_workspace_bytes(7, 5, ctypes.byref(size)) == B.SC_OK and size.value >= 7 * 5 * 8 and size.value % 8 == 0
     assert L.sparse_mask_workspace_bytes(7, 5, None) == B.SC_ERR_NULL
     assert L.sparse_mask_workspace_bytes(0, 5, ctypes.byref(size)) == B.SC_ERR_BAD_SHAPE and size.value == 0
     assert L.sparse_mask_workspace_bytes(1 << 14, 1 << 14, ctypes.byref(size)) == B.SC_ERR_BAD_SHAPE

@@ -30,6 +30,8 @@ def gpu_mask(score, ho, wo, s):
 @pytest.mark.parametrize("h,w,ho,wo", [
     (224, 224, 112, 112), (224, 224, 56, 56), (224, 224, 28, 28), (224, 224, 14, 14), (224, 224, 7, 7),
     (64, 64, 64, 64), (33, 47, 16, 15), (9, 9, 4, 4), (15, 10, 7, 3), (5, 3, 1, 1), (1, 1, 1, 1), (640, 640, 80, 80),
+    (640, 640, 320, 320), (640, 640, 20, 20), (300, 270, 10, 9), (100, 100, 2, 2), (70, 70, 1, 1), (130, 129, 128, 129),
+    (200, 300, 200, 150),
 ])
 @pytest.mark.parametrize("s", [0.25, 0.5, 0.7])
 def test_masks_match_the_oracle(h, w, ho, wo, s):
@@ -64,6 +66,66 @@ def test_negative_scores_zero_signs_and_infinities():
     score[3, 3], score[20, 7] = np.inf, -np.inf
     for ho, s in [(40, 0.5), (40, 0.25), (20, 0.5), (10, 0.6)]:
         assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+
+
+@pytest.mark.parametrize("levels", [1, 2, 5, 3000, 200000])
+def test_ties_on_a_large_map(levels):
+    """More than 16 384 pixels (the selection spread over many workgroups): one key for the whole map, a few keys shared
+    by more pixels than the candidate list holds (the last workgroup selects from memory), and many keys that each
+    a handful of pixels share (ties inside the candidate list)."""
+    rng = np.random.default_rng(levels)
+    score = rng.integers(0, levels, size=(180, 160)).astype(np.float32)
+    for (ho, wo), s in [((180, 160), 0.5), ((180, 160), 0.31), ((180, 160), 0.002), ((90, 160), 0.7)]:
+        assert np.array_equal(gpu_mask(score, ho, wo, s), MO.layer_mask(score, ho, wo, f32(s))), (ho, wo, s)
+
+
+def test_keys_of_both_signs_and_infinities_on_a_large_map():
+    rng = np.random.default_rng(81)
+    score = rng.standard_normal((200, 200)).astype(np.float32)
+    score[rng.random((200, 200)) < 0.1] = 0.0
+    score[5, 5], score[100, 7], score[199, 199] = np.inf, -np.inf, np.inf
+    for ho, s in [(200, 0.5), (200, 0.9)]:
+        assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+
+
+@pytest.mark.parametrize("h,w,ho,wo", [(256, 256, 8, 8), (70, 70, 1, 1), (100, 100, 2, 2), (640, 640, 20, 20), (640, 320, 40, 10)])
+def test_large_windows_whose_sums_round(h, w, ho, wo):
+    """Windows of 64 values and more with magnitudes spread over forty binades: additions round, so only the
+    row-major chain gives the oracle's sums (scores on a 2^-24 grid never get there: their sums are exact in any order)."""
+    rng = np.random.default_rng(h + wo)
+    score = (rng.standard_normal((h, w)) * 10.0 ** rng.uniform(-9, 3, size=(h, w))).astype(np.float32)
+    for s in (0.5, 0.3):
+        assert np.array_equal(gpu_mask(score, ho, wo, s), MO.layer_mask(score, ho, wo, f32(s)))
+
+
+def test_a_window_that_stops_being_exact_in_a_later_piece():
+    """50 x 50 windows arrive in pieces; a tiny value late in one window makes that pixel switch to the chain."""
+    score = W.gen_score(100, 100, seed=77)
+    score[45, 10] = np.float32(1e-30)
+    score[97, 60] = np.float32(-3e-33)
+    for s in (0.5, 0.25, 0.75):
+        assert np.array_equal(gpu_mask(score, 2, 2, s), MO.layer_mask(score, 2, 2, f32(s)))
+
+
+@pytest.mark.parametrize("ho,win", [(8, 32), (4, 50), (12, 8), (16, 5)])
+def test_windows_that_hold_the_same_values_in_different_orders(ho, win):
+    """Every window is a permutation of one set of values spread over forty binades: the exact sums are equal, the
+    sums in double differ only by where the additions rounded, so the ranking follows the order of the additions --
+    any order but the row-major one gives another mask."""
+    rng = np.random.default_rng(ho * win)
+    base = (rng.standard_normal(win * win) * 10.0 ** rng.uniform(-9, 3, size=win * win)).astype(np.float32)
+    score = np.empty((ho * win, ho * win), dtype=np.float32)
+    for oy in range(ho):
+        for ox in range(ho):
+            score[oy * win:(oy + 1) * win, ox * win:(ox + 1) * win] = rng.permutation(base).reshape(win, win)
+    sums = MO.layer_score_sums(score, ho, ho)
+    assert len(np.unique(sums)) >= 3                     # the orders do round differently
+    for s in (0.5, 0.3):
+        assert np.array_equal(gpu_mask(score, ho, ho, s), MO.layer_mask(score, ho, ho, f32(s)))
+    grid = np.round(score.astype(np.float64) * 2.0 ** 10).astype(np.float32)      # same idea where no addition rounds
+    grid = np.clip(grid, -2.0 ** 20, 2.0 ** 20)
+    assert len(np.unique(MO.layer_score_sums(grid, ho, ho))) == 1
+    assert np.array_equal(gpu_mask(grid, ho, ho, 0.4), MO.layer_mask(grid, ho, ho, f32(0.4)))
 
 
 def test_large_map_with_narrow_score_range():

@@ -114,6 +114,7 @@ def test_masked_store_variant_matches_the_row_list_variant():
                 layer.sparse(x, a)
                 B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_MASKED_STORE, 2)
                 assert B.sparse_conv_plan_tiles(layer.plan, 0)[2] == -(-spec.m // 64) * -(-spec.c_out // 64)   # every row
+                assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_masked_store"
                 b = layer.new_output().fill_(sentinel)
                 layer.sparse(x, b)
                 torch.cuda.synchronize()
