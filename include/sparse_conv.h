@@ -293,8 +293,10 @@ int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on th
  *                         (float [Cout]) are each optional (NULL = not wanted).  dx is the ordinary convolution of g (with
  *                         zeros interleaved for strided layers) with the rotated filters and runs through the
  *                         forward kernels; SC_ERR_UNSUPPORTED only when the layer's padding exceeds
- *                         dil * (k - 1).  Additions happen in a fixed order:
- *                         results do not depend on scheduling.  Enqueues only; no allocation, no synchronisation.
+ *                         dil * (k - 1).  Additions happen in a fixed order: results do not depend on
+ *                         scheduling, and dw and db are the same bits whether or not dx is asked for (without dx no g
+ *                         map is written: the filter-gradient kernel gates dy by y itself).  Enqueues only; no
+ *                         allocation, no synchronisation.
  *   sparse_conv_backward_set_filters   new filter values (after an optimiser step) for the input gradient.
  */
 typedef struct sc_bwd_plan sc_bwd_plan;

@@ -8,8 +8,11 @@
 //     dx        = the transposed convolution of g  -- for stride 1 an ordinary convolution of the g map
 //                                                     with the filters rotated by 180 degrees and
 //                                                     transposed; it runs through the forward kernels
-// Kernels here: g map with its column sums (db), the filter-gradient GEMM on the matrix cores with
-// a deterministic two-pass reduction over row splits, and the filter rotation for the input gradient.
+// Kernels here: the filter-gradient GEMM on the matrix cores in two forms -- operands straight into LDS, dy gated by
+// y on the way and db summed from the same tiles (the form that runs wherever the tensors fit 32-bit offsets), and an
+// older register-staged form that reads a g map -- each with a deterministic second pass over its row splits; the g
+// map with its column sums (written only when the input gradient, a convolution of the g map, is asked for); and the
+// filter rotation for the input gradient.
 #include "../../include/sparse_conv.h"
 
 #include <hip/hip_runtime.h>
@@ -19,6 +22,7 @@
 #include <new>
 
 #include "conv_params.hpp"
+#include "igemm_buf_kernel.hpp"
 #include "mma_common.hpp"
 
 namespace sc {
@@ -343,6 +347,398 @@ static hipError_t wgrad_launch(WgradParams p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// ---- filter gradient, second form: operands straight into LDS ---------------------------------------------------
+// The kernel above moves every staged row through registers, one stage ahead: a workgroup waits a memory round
+// trip per 64 rows.  This form keeps several stages in flight without registers:
+//   * a stage = 32 kept rows; its tiles lie in LDS as panels of 32 rows x 128 bytes (64 channels or window entries of
+//     a 16-bit type), filled by `buffer_load ... lds` transfers: wavefront w fills rows 8w .. 8w+7 of every panel, lane
+//     l the 16-byte group l % 8 of row 8w + l / 8 -- a lane decodes ONE row per stage (from the split's row list, which
+//     sits in LDS) and derives every panel's offset from it; an offset past the end of the buffer makes the hardware
+//     write zeros, which serves padded taps, absent rows and columns beyond Cout or K;
+//   * the upstream gradient is gated on the fly: the tiles of dy and of y arrive side by side, and a lane keeps the
+//     elements of its dy fragment whose y is positive (g of Alg. 1's backward, never written to memory); the column sums
+//     of the gated fragments are db, accumulated by the wavefronts of the first K tile in a fixed order;
+//   * 16-byte groups are placed at (group ^ 2 * (row % 4)), so the four rows x 32 bytes that 16 lanes of a
+//     transposing read touch cover all banks once;
+//   * ring of STAGES stages; a wavefront waits for "all but the newest STAGES-2 stages of MY transfers have landed",
+//     then a barrier, then refills the slot the previous stage left.
+//   workgroup = BM output channels x BN window entries x one split of the kept rows; four wavefronts
+//   result    = float partial sums per split, [Cout x K] then [Cout] (db); wgrad_reduce_kernel adds the splits
+struct Wgrad2Params {
+  const void* x;
+  const void* dy;            // upstream gradient [M][Cout] (or the g map, with y null)
+  const void* y;             // forward output [M][Cout] when the layer has a ReLU, else null
+  const int32_t* row_idx;    // kept rows, or null for the identity
+  float* out;                // [splits][Cout * K + Cout]
+  int64_t split_stride;      // Cout * K + Cout
+  int32_t rows, rows_per_split, splits;
+  int32_t h, w, c_in, ho_wo, wo, c_out;
+  int32_t kh, kw, sh, sw, ph, pw, dil_h, dil_w;
+  int32_t k;                 // kh * kw * c_in
+  int32_t co_tiles, k_tiles;
+  uint32_t div_howo_mul, div_howo_shift, div_wo_mul, div_wo_shift;
+  uint32_t x_bytes, dy_bytes;
+};
+
+constexpr int kW2Rows = 32;               // kept rows per stage
+constexpr int kW2PanelBytes = kW2Rows * 128;
+constexpr int kW2MostSplitRows = 2048;    // rows of one split (its row list lies in LDS)
+
+template <int I, int N, class Fn> __device__ __forceinline__ void for_constants(Fn&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    for_constants<I + 1, N>(f);
+  }
+}
+typedef int v2i __attribute__((ext_vector_type(2)));
+// An LDS word read the compiler does not see as one (it would wait for every transfer in flight before a read of
+// LDS that transfers may write); the value is complete when this returns.
+__device__ __forceinline__ int lds_word_now(unsigned addr) {
+  int v;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr));
+  return v;
+}
+// ds_read_b64_tr_b16: within 16 lanes, result lane j, element t = source lane 4t + j/4, element j%4.  With source
+// lane s addressing row s/4, columns 4(s%4) .. +3 of a 4 x 16 block, result lane j holds rows 0..3 of column j.
+template <int OFF> __device__ __forceinline__ v2i lds_read_tr(unsigned addr) {
+  v2i v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// wait until at most N LDS operations are outstanding; the halves pass through so that no use moves above the wait
+template <int N, int CNT> __device__ __forceinline__ void wait_halves(v2i (&h)[CNT]) {
+  static_assert((CNT == 8 || CNT == 12 || CNT == 14) && N <= 15, "halves of 4, 6 or 7 fragments; the counter has four bits");
+  if constexpr (CNT == 8)
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7])
+                 : "n"(N));
+  if constexpr (CNT == 12)
+    asm volatile("s_waitcnt lgkmcnt(%12)"
+                 : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7]),
+                   "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11])
+                 : "n"(N));
+  if constexpr (CNT == 14)
+    asm volatile("s_waitcnt lgkmcnt(%14)"
+                 : "+v"(h[0]), "+v"(h[1]), "+v"(h[2]), "+v"(h[3]), "+v"(h[4]), "+v"(h[5]), "+v"(h[6]), "+v"(h[7]),
+                   "+v"(h[8]), "+v"(h[9]), "+v"(h[10]), "+v"(h[11]), "+v"(h[12]), "+v"(h[13])
+                 : "n"(N));
+}
+
+#ifdef SC_TIMING
+__device__ long long g_w2_stamps[1024 * 8];       // development builds: per workgroup, clock at the phase boundaries
+#define SC_W2_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_w2_stamps[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define SC_W2_STAMP(slot) do { } while (0)
+#endif
+
+__device__ __forceinline__ void lds_store16(unsigned addr, v4i v) {
+  asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(v) : "memory");
+}
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GATE>
+__global__ __launch_bounds__(256) void wgrad2_kernel(const Wgrad2Params p) {
+  using E = Elem<DT>;
+  using T = typename E::T;
+  constexpr int R = kW2Rows;
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int GP = BM / 64, AP = BN / 64;                 // panels of the dy (and y) tile, of the window tile
+  constexpr int YP0 = GP, AP0 = GATE ? 2 * GP : GP;         // first panel of the y tile, of the window tile
+  constexpr int LPT = AP0 + AP;                             // transfers per wavefront and stage
+  constexpr int STAGE_BYTES = LPT * kW2PanelBytes;
+  constexpr int F = MI + NI;                                // fragments per 16-row step
+  static_assert(WAVES_M * WAVES_N == 4 && BM % 64 == 0 && BN % 64 == 0 && WM % 32 == 0 && WN % 32 == 0, "shape");
+  static_assert(STAGES >= 3 && (STAGES - 2) * LPT <= 63, "vmcnt is a 6-bit counter");
+  static_assert(STAGE_BYTES + 2048 + 512 < 65536, "fragment offsets are immediates");
+  static_assert(2 * F <= 15, "LDS reads of one 16-row step in flight: the counter has four bits");
+  static_assert(STAGES * STAGE_BYTES >= R * BM * 4, "the ring doubles as scratch of the db sums");
+  extern __shared__ __align__(16) unsigned char smem[];
+  int32_t* s_rows = reinterpret_cast<int32_t*>(smem + STAGES * STAGE_BYTES);      // [kW2MostSplitRows]
+
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int fp = lane & 31, fh = lane >> 5;
+  const int wm0 = (wave / WAVES_N) * WM, wn0 = (wave % WAVES_N) * WN;
+  // consecutive workgroup numbers go round the chip's eight dies: renumbered so that the tiles of one split, and
+  // neighbouring splits, share a die -- each die's L2 then holds its own eighth of the rows instead of all of them
+  const int tiles = p.co_tiles * p.k_tiles;
+  const int nwg = tiles * p.splits;
+  const int per_xcd = (nwg + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= nwg) return;
+  const int split = logical / tiles, tile = logical - split * tiles;
+  const int co0 = (tile / p.k_tiles) * BM, k0 = (tile % p.k_tiles) * BN;
+  const bool sums_db = tile % p.k_tiles == 0;               // the workgroups of the first K tile also sum db
+  const int i_begin = split * p.rows_per_split, i_end = min(p.rows, i_begin + p.rows_per_split);
+  const int n_st = (i_end - i_begin + R - 1) / R;
+  SC_W2_STAMP(0);
+
+  // the split's row numbers
+  if (p.row_idx)
+    for (int i = t; i < i_end - i_begin; i += 256) s_rows[i] = p.row_idx[i_begin + i];
+  __syncthreads();
+
+  // what this lane transfers: row slot 8 * wave + lane / 8 of every panel, the 16-byte group that lands at
+  // position lane % 8 of that row
+  const int slot = wave * 8 + (lane >> 3);
+  const int lc = (lane & 7) ^ (2 * ((lane >> 3) & 3));      // logical group (8 elements) within a panel row
+  int g_col[GP];                                            // element offset of that group in a row of dy, or -1 beyond Cout
+#pragma unroll
+  for (int q = 0; q < GP; ++q) {
+    const int c = co0 + 64 * q + 8 * lc;
+    g_col[q] = c < p.c_out ? c : -1;                        // (Cout is a multiple of 8)
+  }
+  int a_dy[AP], a_dx[AP], a_off[AP];                        // tap displacement and element offset of the group; a_off < 0 beyond K
+#pragma unroll
+  for (int q = 0; q < AP; ++q) {
+    const int kk = k0 + 64 * q + 8 * lc;                    // (Cin is a multiple of 8: a group lies inside one tap)
+    const int tap = kk < p.k ? kk / p.c_in : 0, ci = kk - tap * p.c_in;
+    const int ky = tap / p.kw, kx = tap - ky * p.kw;
+    a_dy[q] = ky * p.dil_h;
+    a_dx[q] = kx * p.dil_w;
+    a_off[q] = kk < p.k ? (a_dy[q] * p.w + a_dx[q]) * p.c_in + ci : -1;
+  }
+  const __amdgpu_buffer_rsrc_t rx = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, kBufferWord3);
+  const __amdgpu_buffer_rsrc_t rdy = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.dy), 0, (int)p.dy_bytes, kBufferWord3);
+  const __amdgpu_buffer_rsrc_t ry =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(GATE ? p.y : p.dy), 0, (int)p.dy_bytes, kBufferWord3);
+  typedef __attribute__((address_space(3))) void lds_void;
+  const unsigned lds0 = (unsigned)(unsigned long long)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned rows_addr = lds0 + (unsigned)(STAGES * STAGE_BYTES);
+
+  // the row this lane transfers in stage `st`: decoded once, then one transfer per panel
+  bool t_present = false;
+  uint32_t t_row_off = 0;
+  int t_xrow = 0, t_iy0 = 0, t_ix0 = 0;
+  auto prepare_stage = [&](int st) {
+    const int i = i_begin + st * R + slot;
+    t_present = i < i_end;
+    const int r = t_present ? (p.row_idx ? lds_word_now(rows_addr + 4u * (unsigned)(i - i_begin)) : i) : 0;
+    t_row_off = (uint32_t)r * (uint32_t)p.c_out;
+    const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
+    const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
+    t_iy0 = oy * p.sh - p.ph;
+    t_ix0 = ox * p.sw - p.pw;
+    t_xrow = ((n * p.h + t_iy0) * p.w + t_ix0) * p.c_in;              // may be negative: used with in-range taps only
+  };
+  // transfer `IDX` of the prepared stage into ring slot `ring`: the dy panels (each followed by its y panel), then the
+  // window panels
+  auto issue_one = [&](auto idx_c, int ring) {
+    constexpr int IDX = decltype(idx_c)::value;
+    unsigned char* base = smem + ring * STAGE_BYTES + wave * 1024;      // this wavefront's 8 rows of panel 0
+    if constexpr (IDX < AP0) {
+      constexpr int q = GATE ? IDX / 2 : IDX;
+      constexpr bool is_y = GATE && (IDX & 1);
+      const bool ok = t_present & (g_col[q] >= 0);          // (bitwise: one transfer instruction, no branch around it)
+      const uint32_t voff = ok ? (t_row_off + (uint32_t)g_col[q]) * 2u : kOutOfRange;
+      if constexpr (is_y) __builtin_amdgcn_raw_ptr_buffer_load_lds(ry, (lds_void*)(base + (YP0 + q) * kW2PanelBytes), 16, voff, 0, 0, 0);
+      else __builtin_amdgcn_raw_ptr_buffer_load_lds(rdy, (lds_void*)(base + q * kW2PanelBytes), 16, voff, 0, 0, 0);
+    } else {
+      constexpr int q = IDX - AP0;
+      const bool ok = t_present & (a_off[q] >= 0) & ((unsigned)(t_iy0 + a_dy[q]) < (unsigned)p.h) &
+                      ((unsigned)(t_ix0 + a_dx[q]) < (unsigned)p.w);
+      const uint32_t voff = ok ? (uint32_t)(t_xrow + a_off[q]) * 2u : kOutOfRange;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_void*)(base + (AP0 + q) * kW2PanelBytes), 16, voff, 0, 0, 0);
+    }
+  };
+  auto issue_stage = [&](int st, int ring) {
+    prepare_stage(st);
+    for_constants<0, LPT>([&](auto idx_c) { issue_one(idx_c, ring); });
+  };
+
+  floatx16 acc[MI][NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+  float dbsum[GP][8];                   // this lane's groups of dy (one per panel), summed over its rows of every stage
+#pragma unroll
+  for (int q = 0; q < GP; ++q)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) dbsum[q][j] = 0.0f;
+
+  // A lane's own groups of a stage, once they have landed and before anybody reads fragments: the group of dy keeps
+  // the elements whose y is positive (written back in place: the fragments below are fragments of g), and in the
+  // workgroups of the first K tile the lane adds the group to its db sums.  No other lane touches these 16 bytes
+  // before the barrier that follows.
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  constexpr int OWN = GATE ? 2 * GP : GP;
+  static_assert(GP <= 2, "one or two panels of output channels");
+  const bool owns = GATE || sums_db;
+  v4i own[OWN];                        // the groups of dy, then those of y; the reads write these registers when they complete
+  unsigned own_at = 0;
+  auto own_read = [&](unsigned ring_off) {
+    if (!owns) return;
+    own_at = lds0 + ring_off + (unsigned)t * 16u;
+    own[0] = lds_read16_at<0>(own_at);
+    if constexpr (GP == 2) own[1] = lds_read16_at<kW2PanelBytes>(own_at);
+    if constexpr (GATE) {
+      own[GP] = lds_read16_at<YP0 * kW2PanelBytes>(own_at);
+      if constexpr (GP == 2) own[GP + 1] = lds_read16_at<(YP0 + 1) * kW2PanelBytes>(own_at);
+    }
+  };
+  auto own_finish = [&]() {
+    if (!owns) return;
+    wait_frags<0>(own);
+#pragma unroll
+    for (int q = 0; q < GP; ++q) {
+      v4i gq = own[q];
+      if constexpr (GATE) {
+        const s16x8 keep = __builtin_bit_cast(s16x8, own[GP + q]) > (short)0;    // y > 0 for both 16-bit float types
+        gq = __builtin_bit_cast(v4i, __builtin_bit_cast(s16x8, gq) & keep);
+        lds_store16(own_at + q * kW2PanelBytes, gq);
+      }
+      if (sums_db) {
+        struct alignas(16) Grp { T v[8]; };
+        const Grp gr = __builtin_bit_cast(Grp, gq);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dbsum[q][j] += (float)gr.v[j];
+      }
+    }
+  };
+
+  // fragment addresses in ring slot 0, 16-row step 0: the lane addresses row 8 * fh + (lane % 16) / 4 (the second
+  // read 4 rows further), columns 16 * ((lane % 32) / 16) + 4 * (lane % 4) .. +3 of its 32-column block
+  const int l16 = lane & 15;
+  const int frow = 8 * fh + (l16 >> 2), fswz = 2 * (l16 >> 2);
+  auto frag_addr = [&](int col) -> unsigned {              // col: column within the tile (multiple of 4)
+    const int panel = col >> 6, cin = col & 63;
+    return lds0 + (unsigned)(panel * kW2PanelBytes + frow * 128 + (((cin >> 3) ^ fswz) << 4) + (cin & 7) * 2);
+  };
+  unsigned g_addr[MI], a_addr[NI];
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) g_addr[mi] = frag_addr(wm0 + 32 * mi + 16 * ((lane & 31) >> 4) + 4 * (l16 & 3));
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+    a_addr[ni] = frag_addr(wn0 + 32 * ni + 16 * ((lane & 31) >> 4) + 4 * (l16 & 3)) + AP0 * kW2PanelBytes;
+
+  auto read_step = [&](unsigned ring_off, auto ks_c, v2i (&h)[2 * F]) {
+    constexpr int KO = decltype(ks_c)::value * 16 * 128;
+    int at = 0;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      h[at++] = lds_read_tr<KO>(g_addr[mi] + ring_off);
+      h[at++] = lds_read_tr<KO + 512>(g_addr[mi] + ring_off);
+    }
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      h[at++] = lds_read_tr<KO>(a_addr[ni] + ring_off);
+      h[at++] = lds_read_tr<KO + 512>(a_addr[ni] + ring_off);
+    }
+  };
+  // The MFMAs of one 16-row step with one side job issued behind each: the transfers of the stage that enters the
+  // ring (a wavefront that issues them back to back sits in the issue stage while the address unit takes them; behind
+  // an MFMA the slot is free), then the lane's own groups of the next stage.  JOB0 = number of the first side job.
+  constexpr int JOBS = LPT + 2;
+  static_assert(JOBS <= 2 * MI * NI, "a slot behind an MFMA for every side job");
+  static_assert(LPT >= MI * NI || 2 * F + OWN <= 15, "own-group reads issued while a step's fragment reads are in flight");
+  auto mma_step = [&](const v2i (&h)[2 * F], auto job0_c, int fill_ring, bool fill, unsigned next_off, bool next) {
+    constexpr int JOB0 = decltype(job0_c)::value;
+    v4i gf[MI], af[NI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) gf[mi] = v4i{h[2 * mi][0], h[2 * mi][1], h[2 * mi + 1][0], h[2 * mi + 1][1]};
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+      af[ni] = v4i{h[2 * MI + 2 * ni][0], h[2 * MI + 2 * ni][1], h[2 * MI + 2 * ni + 1][0], h[2 * MI + 2 * ni + 1][1]};
+    for_constants<0, MI * NI>([&](auto i_c) {
+      constexpr int I = decltype(i_c)::value;
+      constexpr int mi = I / NI, ni = I % NI;
+      E::mma(acc[mi][ni], gf[mi], af[ni]);
+      constexpr int JOB = JOB0 + I;
+      if constexpr (JOB < JOBS) {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (JOB < LPT) { if (fill) issue_one(std::integral_constant<int, JOB>{}, fill_ring); }
+        if constexpr (JOB == LPT) { if (next) own_read(next_off); }
+        if constexpr (JOB == LPT + 1) { if (next) own_finish(); }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    });
+  };
+
+  SC_W2_STAMP(1);
+#pragma unroll
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < n_st) issue_stage(s, s);
+  // Step st: my transfers of stage st + 1 have landed (so have those of stage st); barrier -- stage st is complete
+  // and gated for everybody, and everybody has left stage st - 1, whose slot the stage st + STAGES - 1 now takes;
+  // fragments and MFMAs of stage st, with the side jobs behind them.
+  if (n_st > 0) {
+    if (STAGES - 2 < n_st) wait_vmcnt<(STAGES - 2) * LPT>();
+    else wait_vmcnt<0>();
+    own_read(0);
+    own_finish();
+  }
+  int ring = 0;
+  for (int st = 0; st < n_st; ++st) {
+    if (st + STAGES - 2 < n_st) wait_vmcnt<(STAGES - 3) * LPT>();
+    else wait_vmcnt<0>();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");       // my gated groups of stage st are written
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    const unsigned ring_off = (unsigned)(ring * STAGE_BYTES);
+    const int next_ring = ring + 1 == STAGES ? 0 : ring + 1;
+    const bool fill = st + STAGES - 1 < n_st, next = st + 1 < n_st;
+    if (fill) prepare_stage(st + STAGES - 1);
+    v2i h0[2 * F], h1[2 * F];          // (one step's reads in flight at a time: two would overrun the counter)
+    read_step(ring_off, std::integral_constant<int, 0>{}, h0);
+    wait_halves<0>(h0);
+    read_step(ring_off, std::integral_constant<int, 1>{}, h1);     // lands under the MFMAs of step 0
+    mma_step(h0, std::integral_constant<int, 0>{}, ring == 0 ? STAGES - 1 : ring - 1, fill, (unsigned)(next_ring * STAGE_BYTES), next);
+    wait_halves<0>(h1);
+    mma_step(h1, std::integral_constant<int, MI * NI>{}, ring == 0 ? STAGES - 1 : ring - 1, fill, (unsigned)(next_ring * STAGE_BYTES), next);
+    ring = next_ring;
+  }
+
+  SC_W2_STAMP(2);
+  // MFMA result row 8j + 4h + i sits in register 4j + i of lane half h; column = lane % 32
+  float* __restrict__ out = p.out + (int64_t)split * p.split_stride;
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) {
+      const int kcol = k0 + wn0 + 32 * ni + fp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = co0 + wm0 + 32 * mi + 8 * (v >> 2) + 4 * fh + (v & 3);
+        if (co < p.c_out && kcol < p.k) out[(int64_t)co * p.k + kcol] = acc[mi][ni][v];
+      }
+    }
+  if (sums_db) {      // the 32 row slots of every channel, added in slot order through LDS (the ring is free now)
+    __syncthreads();
+    float* s_db = reinterpret_cast<float*>(smem);          // [32 row slots][BM channels]
+#pragma unroll
+    for (int q = 0; q < GP; ++q)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s_db[slot * BM + 64 * q + 8 * lc + j] = dbsum[q][j];
+    __syncthreads();
+    if (t < BM && co0 + t < p.c_out) {
+      float tot = 0.0f;
+      for (int r = 0; r < R; ++r) tot += s_db[r * BM + t];
+      out[(int64_t)p.c_out * p.k + co0 + t] = tot;
+    }
+  }
+  SC_W2_STAMP(3);
+}
+
+template <int DT, int BM, int BN, int WAVES_M, int WAVES_N, int STAGES, bool GATE>
+static hipError_t wgrad2_launch(Wgrad2Params p, hipStream_t stream) {
+  constexpr size_t lds = (size_t)STAGES * ((GATE ? 2 : 1) * (BM / 64) + BN / 64) * kW2PanelBytes + kW2MostSplitRows * 4;
+  static_assert(lds <= 160 * 1024, "LDS of a compute unit");
+  p.co_tiles = (p.c_out + BM - 1) / BM;
+  p.k_tiles = (p.k + BN - 1) / BN;
+  const unsigned grid = (unsigned)((p.co_tiles * p.k_tiles * p.splits + 7) / 8 * 8);
+  static std::atomic<bool> attr_set{false};                       // (one flag per instantiation)
+  if (lds > 64 * 1024 && !attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad2_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES, GATE>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((wgrad2_kernel<DT, BM, BN, WAVES_M, WAVES_N, STAGES, GATE>), dim3(grid), dim3(256), lds, stream, p);
+  return hipGetLastError();
+}
+
 // dw[i] = sum over the splits of partial[s][i].  A workgroup owns 64 consecutive elements (16 groups of
 // four); 16 lanes per group each add every 16th split (independent 16-byte loads in flight), then the 16
 // sub-sums are added in lane order: the order of additions is fixed.  (Cout * K is a multiple of 64.)
@@ -370,6 +766,36 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
   }
 }
 
+// The same for the partial results of wgrad2_kernel: per split Cout * K filter-gradient sums, then Cout bias-gradient
+// sums (`stride` floats in all); dw and db may each be null.
+__global__ __launch_bounds__(256) void wgrad2_reduce_kernel(const float* __restrict__ partial, int splits, int64_t stride,
+                                                            int64_t count_dw, float* __restrict__ dw, float* __restrict__ db) {
+  __shared__ v4f s_sub[16][17];
+  const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
+  const int64_t i = ((int64_t)blockIdx.x * 16 + e) * 4;
+  v4f acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (i < stride)
+    for (int s = sl; s < splits; s += 16) {
+      const v4f v = *reinterpret_cast<const v4f*>(partial + (int64_t)s * stride + i);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] += v[j];
+    }
+  s_sub[sl][e] = acc;
+  __syncthreads();
+  if (threadIdx.x < 16 && i < stride) {
+    v4f tot = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int l = 0; l < 16; ++l)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tot[j] += s_sub[l][threadIdx.x][j];
+    if (i < count_dw) {
+      if (dw) *reinterpret_cast<v4f*>(dw + i) = tot;
+    } else if (db) {
+      *reinterpret_cast<v4f*>(db + (i - count_dw)) = tot;
+    }
+  }
+}
+
 constexpr size_t kWgradPartialBytes = (size_t)64 << 20;   // most workspace the row splits may take
 
 static int wgrad_splits(int64_t rows, int c_out, int k) {
@@ -379,6 +805,22 @@ static int wgrad_splits(int64_t rows, int c_out, int k) {
   want = std::min<int64_t>(want, (rows + 8 * kWgRows - 1) / (8 * kWgRows));        // at least eight stages per split
   want = std::min<int64_t>(want, (int64_t)(kWgradPartialBytes / ((size_t)c_out * k * 4)));
   return (int)std::max<int64_t>(want, 1);
+}
+
+// Row splits of wgrad2_kernel: one workgroup per compute unit (its LDS admits no second one), every split's row list
+// within kW2MostSplitRows, the partial sums within kWgradPartialBytes.  0 = the layer does not fit (the first form runs).
+constexpr int kW2Workgroups = 256;
+static int wgrad2_tile_m(int c_out) { return c_out <= 64 ? 64 : 128; }
+static int wgrad2_tile_n(int, bool) { return 256; }
+static int wgrad2_splits(int64_t rows, int c_out, int k, bool gate) {
+  const int bm = wgrad2_tile_m(c_out), bn = wgrad2_tile_n(c_out, gate);
+  const int64_t tiles = (int64_t)((c_out + bm - 1) / bm) * ((k + bn - 1) / bn);
+  int64_t want = std::max<int64_t>(kW2Workgroups / tiles, 1);
+  want = std::min<int64_t>(want, (rows + 4 * kW2Rows - 1) / (4 * kW2Rows));      // at least four stages per split
+  want = std::max<int64_t>(want, (rows + kW2MostSplitRows - 1) / kW2MostSplitRows);
+  want = std::max<int64_t>(want, 1);
+  if ((size_t)want * ((size_t)c_out * k + c_out) * 4 > kWgradPartialBytes) return 0;
+  return (int)want;
 }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -426,7 +868,9 @@ static sc_status backward_layout(const sc_conv_desc* d, sc_bwd_plan* L, sc_conv_
   *off_g = off;      off = align_up(off + (size_t)*m * d->c_out * eb, 256);
   *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRowsLeast - 1) / kSumRowsLeast) * d->c_out * 4, 256);
   *off_partial = off;
-  off = align_up(off + (size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4, 256);   // the dense row count bounds every mask
+  // (the dense row count bounds every mask's; both forms of the kernel fit)
+  off = align_up(off + std::max((size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4,
+                                (size_t)wgrad2_splits(*m, d->c_out, (int)k, d->relu != 0) * ((size_t)d->c_out * k + d->c_out) * 4), 256);
   *off_ones = *off_wrot = *off_inner = *off_gup = off;
   if (*has_inner) {
     std::memset(inner, 0, sizeof(*inner));
@@ -545,48 +989,94 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   const int period = d.mask_mode == SC_MASK_SPATIAL ? plan->ho * plan->wo : 0;
   _Float16* g = reinterpret_cast<_Float16*>(plan->ws + plan->off_g);    // 16-bit patterns; compared as the real type below
 
+  // Which form of the filter-gradient kernel: the LDS-direct one wherever the tensors fit 32-bit buffer offsets and
+  // the splits fit the workspace.  It gates dy itself and sums db on the way, so the g map is written only when the
+  // input gradient (a convolution of the g map) is asked for.
+  const int k = d.kh * d.kw * d.c_in;
+  const int64_t count = (int64_t)d.c_out * k;
+  const uint64_t x_bytes = (uint64_t)d.n * d.h * d.w * d.c_in * 2, dy_bytes = (uint64_t)m * d.c_out * 2;
+  const bool fits = dw_dev && kept > 0 && x_bytes < (1ull << 31) && dy_bytes < (1ull << 31);
+  // (the splits do not depend on whether dx is asked for: dw and db come out bit-identical either way)
+  const int splits2 = fits ? sc::wgrad2_splits(kept, d.c_out, k, d.relu != 0) : 0;
+  const bool direct = splits2 > 0;
+  const bool want_g = dx_dev || !direct;
+
   // g map, with the column sums of its slabs on the side
   const int slab_rows = sc::colsum_slab_rows(m);
   const int slabs = (int)((m + slab_rows - 1) / slab_rows);
   float* colsum = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
-  if (dt == sc::kBF16)
-    hipLaunchKernelGGL(sc::grad_map_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)y_dev,
-                       (const __bf16*)dy_dev, mask, (__bf16*)g, m, d.c_out, slab_rows, d.relu, period, colsum);
-  else
-    hipLaunchKernelGGL(sc::grad_map_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, (const _Float16*)y_dev,
-                       (const _Float16*)dy_dev, mask, g, m, d.c_out, slab_rows, d.relu, period, colsum);
-  // db
-  if (db_dev)
-    hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 3) / 4), dim3(256), 0, stream, colsum, slabs, d.c_out, db_dev);
-  // dw
-  if (dw_dev) {
-    const int k = d.kh * d.kw * d.c_in;
-    const int64_t count = (int64_t)d.c_out * k;
-    if (kept == 0) {
-      hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
-                         (const float*)nullptr, 0, count, dw_dev);
+  if (want_g) {
+    if (dt == sc::kBF16)
+      hipLaunchKernelGGL(sc::grad_map_kernel<__bf16>, dim3(slabs), dim3(256), 0, stream, (const __bf16*)y_dev,
+                         (const __bf16*)dy_dev, mask, (__bf16*)g, m, d.c_out, slab_rows, d.relu, period, colsum);
+    else
+      hipLaunchKernelGGL(sc::grad_map_kernel<_Float16>, dim3(slabs), dim3(256), 0, stream, (const _Float16*)y_dev,
+                         (const _Float16*)dy_dev, mask, g, m, d.c_out, slab_rows, d.relu, period, colsum);
+  }
+  if (direct) {
+    sc::Wgrad2Params p;
+    std::memset(&p, 0, sizeof(p));
+    p.x = x_dev;
+    const bool gate = !want_g && d.relu;            // with a g map at hand the kernel reads that, ungated
+    p.dy = want_g ? (const void*)g : dy_dev;
+    p.y = gate ? y_dev : nullptr;
+    p.row_idx = kept == m ? nullptr : rows_dev;
+    p.rows = (int32_t)kept;
+    p.rows_per_split = (int32_t)(((kept + splits2 - 1) / splits2 + sc::kW2Rows - 1) / sc::kW2Rows * sc::kW2Rows);
+    p.splits = (int32_t)((kept + p.rows_per_split - 1) / p.rows_per_split);
+    p.split_stride = count + d.c_out;
+    p.out = reinterpret_cast<float*>(plan->ws + plan->off_partial);
+    p.h = d.h; p.w = d.w; p.c_in = d.c_in; p.ho_wo = plan->ho * plan->wo; p.wo = plan->wo; p.c_out = d.c_out;
+    p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+    p.dil_h = d.dil_h; p.dil_w = d.dil_w;
+    p.k = k;
+    p.x_bytes = (uint32_t)x_bytes; p.dy_bytes = (uint32_t)dy_bytes;
+    sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+    sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
+    hipError_t e;
+    const bool narrow = sc::wgrad2_tile_m(d.c_out) == 64;
+    if (dt == sc::kBF16) {
+      if (narrow) e = gate ? sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 5, true>(p, stream) : sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 5, false>(p, stream);
+      else e = gate ? sc::wgrad2_launch<sc::kBF16, 128, 256, 2, 2, 4, true>(p, stream) : sc::wgrad2_launch<sc::kBF16, 128, 256, 2, 2, 5, false>(p, stream);
     } else {
-      sc::WgradParams p;
-      std::memset(&p, 0, sizeof(p));
-      p.x = x_dev; p.g = g;
-      p.row_idx = kept == m ? nullptr : rows_dev;
-      p.splits = sc::wgrad_splits(kept, d.c_out, k);
-      p.rows = (int32_t)kept;
-      p.rows_per_split = (int32_t)(((kept + p.splits - 1) / p.splits + sc::kWgRows - 1) / sc::kWgRows * sc::kWgRows);
-      p.splits = (int32_t)((kept + p.rows_per_split - 1) / p.rows_per_split);
-      p.out = p.splits == 1 ? dw_dev : reinterpret_cast<float*>(plan->ws + plan->off_partial);
-      p.h = d.h; p.w = d.w; p.c_in = d.c_in; p.ho_wo = plan->ho * plan->wo; p.wo = plan->wo; p.c_out = d.c_out;
-      p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
-      p.dil_h = d.dil_h; p.dil_w = d.dil_w;
-      p.k = k;
-      sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
-      sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
-      hipError_t e;
-      e = dt == sc::kBF16 ? sc::wgrad_launch<sc::kBF16, 128, 128>(p, stream) : sc::wgrad_launch<sc::kF16, 128, 128>(p, stream);
-      if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
-      if (p.splits > 1)
+      if (narrow) e = gate ? sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 5, true>(p, stream) : sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 5, false>(p, stream);
+      else e = gate ? sc::wgrad2_launch<sc::kF16, 128, 256, 2, 2, 4, true>(p, stream) : sc::wgrad2_launch<sc::kF16, 128, 256, 2, 2, 5, false>(p, stream);
+    }
+    if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+    hipLaunchKernelGGL(sc::wgrad2_reduce_kernel, dim3((unsigned)((p.split_stride / 4 + 15) / 16)), dim3(256), 0, stream,
+                       (const float*)p.out, p.splits, p.split_stride, count, dw_dev, db_dev);
+  } else {
+    // db
+    if (db_dev)
+      hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 3) / 4), dim3(256), 0, stream, colsum, slabs, d.c_out, db_dev);
+    // dw
+    if (dw_dev) {
+      if (kept == 0) {
         hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
-                           (const float*)p.out, p.splits, count, dw_dev);
+                           (const float*)nullptr, 0, count, dw_dev);
+      } else {
+        sc::WgradParams p;
+        std::memset(&p, 0, sizeof(p));
+        p.x = x_dev; p.g = g;
+        p.row_idx = kept == m ? nullptr : rows_dev;
+        p.splits = sc::wgrad_splits(kept, d.c_out, k);
+        p.rows = (int32_t)kept;
+        p.rows_per_split = (int32_t)(((kept + p.splits - 1) / p.splits + sc::kWgRows - 1) / sc::kWgRows * sc::kWgRows);
+        p.splits = (int32_t)((kept + p.rows_per_split - 1) / p.rows_per_split);
+        p.out = p.splits == 1 ? dw_dev : reinterpret_cast<float*>(plan->ws + plan->off_partial);
+        p.h = d.h; p.w = d.w; p.c_in = d.c_in; p.ho_wo = plan->ho * plan->wo; p.wo = plan->wo; p.c_out = d.c_out;
+        p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+        p.dil_h = d.dil_h; p.dil_w = d.dil_w;
+        p.k = k;
+        sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+        sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
+        hipError_t e;
+        e = dt == sc::kBF16 ? sc::wgrad_launch<sc::kBF16, 128, 128>(p, stream) : sc::wgrad_launch<sc::kF16, 128, 128>(p, stream);
+        if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
+        if (p.splits > 1)
+          hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
+                             (const float*)p.out, p.splits, count, dw_dev);
+      }
     }
   }
   hipError_t e = hipGetLastError();
@@ -609,6 +1099,12 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   }
   return SC_OK;
 }
+
+#ifdef SC_TIMING
+sc_status sc_debug_w2_stamps(long long* out_host) {
+  return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(sc::g_w2_stamps), sizeof(long long) * 1024 * 8) == hipSuccess ? SC_OK : SC_ERR_HIP;
+}
+#endif
 
 void sparse_conv_backward_destroy(sc_bwd_plan* plan) {
   if (!plan) return;

@@ -535,7 +535,7 @@ def main():
     if args.backward:
         bw_rows = backward_times(max(args.steps // 2, 20))
         print()
-        print("| backward pass: layer | M x K x Cout | s | forward us | dw + db us (g map, column sums, row-contraction GEMM, reduce) | "
+        print("| backward pass: layer | M x K x Cout | s | forward us | dw + db us (row-contraction GEMM that gates dy by y and sums db, then the reduction over row splits) | "
               "TFLOP/s of that GEMM | dx us (g map + convolution with rotated filters) | dx + dw + db us |")
         print("|---|---|---|---|---|---|---|---|")
         for r in bw_rows:

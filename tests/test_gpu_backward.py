@@ -84,6 +84,22 @@ def test_many_rows_and_row_splits():
 
 
 @pytest.mark.parametrize("shape", [
+    dict(n=4, c_in=64, hw=28, c_out=128),                        # wide tile, K = 576: three 192-entry tiles, two 256-entry ones
+    dict(n=2, c_in=256, hw=14, c_out=256, sparsity=0.5),         # two channel tiles, K = 2304
+    dict(n=2, c_in=40, hw=13, c_out=72, sparsity=0.4),           # groups that straddle nothing, ragged tiles (K = 360)
+    dict(n=6, c_in=64, hw=20, c_out=64, sparsity=0.0),           # every row kept: identity row map, narrow tile
+    dict(n=3, c_in=96, hw=12, c_out=576, k=1, sparsity=0.5),     # pointwise expansion: five channel tiles, one K tile
+    dict(n=2, c_in=64, hw=24, c_out=64, relu=False),             # no gate
+    dict(n=40, c_in=32, hw=16, c_out=48, sparsity=0.2, mask_mode="spatial"),
+])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_filter_gradient_with_and_without_the_g_map(dtype, shape):
+    """dw and db with the input gradient asked for (the kernel reads the g map) and without (it gates dy by y on the fly):
+    run_backward checks both against the oracle and that they agree bit for bit."""
+    run_backward(spec_of(dtype=dtype, **shape), 851)
+
+
+@pytest.mark.parametrize("shape", [
     dict(n=2, c_in=32, hw=16, c_out=64, s=2),                   # the forward pass leaves the last input row unused
     dict(n=2, c_in=32, hw=15, c_out=64, s=2),                   # every input row used
     dict(n=1, c_in=64, hw=14, c_out=128, k=1, s=2),             # pointwise downsample

@@ -403,7 +403,7 @@ def test_row_panel_kernel_scatter_only_and_switch():
     layer = check_layer(W.make_conv_inputs(spec, 969), out_mode=B.SC_OUT_SCATTER_ONLY, row_panel=2)
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_panel"
     B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_ROW_PANEL, 0)      # too few rows for the automatic choice
-    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_lds_direct"
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) in ("tile_lds_direct", "tile_masked_store")
     big = spec_of(64, 96, 56, 56, 576, k=1, p=0, dtype="bf16", sp=0.5)
     layer = R.ConvLayer(big, *_wbm(big, 3))
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_panel"

@@ -176,7 +176,7 @@ def test_fused_shortcut_in_the_alternating_band_kernel_scatter_only(monkeypatch)
 
 def test_other_band_kernels_hand_a_fused_launch_to_the_tiled_kernel():
     spec = spec_of(2, 16, 20, 20, 64)             # two channel groups per pixel: the plain one-band-per-workgroup kernel
-    layer = check(spec, 1291, True, want_kernel=("tile_lds_direct",))
+    layer = check(spec, 1291, True, want_kernel=("tile_lds_direct", "tile_masked_store"))
     assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band"
 
 
