@@ -127,10 +127,13 @@ sc_status sparse_conv_plan_set_filters(sc_plan* plan, const void* w_dev, void* h
  * left alone in SC_OUT_SCATTER_ONLY mode).
  * x_dev: activations; bias_dev: float[Cout] or NULL when has_bias == 0; y_dev: output, fully
  * overwritten in SC_OUT_ZERO_FILL mode.  x_dev and y_dev must not overlap.
- * Enqueues on `hip_stream` only: no allocation, no synchronisation.  Runs of ONE plan may overlap on
- * different streams unless a K split or stream-K launch was requested for it (SC_OPT_SPLIT_K,
- * SC_OPT_STREAM_K): those keep partial sums and arrival counters in the plan's workspace, which
- * overlapping runs of that plan would share.
+ * Enqueues on `hip_stream` only: no allocation, no synchronisation.  Runs of ONE plan may overlap in time (on
+ * different streams) only when the launch keeps no state in the plan's workspace.  Two kinds of launch do:
+ * launches that divide K among workgroups -- chosen automatically on deep layers, and by SC_OPT_SPLIT_K /
+ * SC_OPT_STREAM_K; sparse_conv_plan_kernel reports "tile_split_k", "tile_stream_k", or "tile_slab" with more
+ * workgroups than output tiles -- keep partial sums and arrival counters there; and plans of 16-bit NHWC layers
+ * with few input channels ("tile_row_segments", e.g. a 3-channel stem) rewrite a zero-margined copy of x there in
+ * every run.  Overlapping runs of such a plan race and give wrong results without an error: use one plan per stream.
  */
 sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
                           void* hip_stream);
@@ -267,7 +270,14 @@ sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* b
  * decide at the store -- zeros for a dropped row, or nothing in scatter-only mode: the results are those of Alg. 2,
  * the work is the dense layer's.  Taken where the kept-row list costs more (a dependent round trip to memory before
  * the first transfer) than the rows it removes: layers of a few microseconds. */
-enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2, SC_OPT_STREAM_K = 3, SC_OPT_MASKED_STORE = 4 };
+/* SC_OPT_SLAB: 0 = automatic, 1 = never, 2 = always where it applies, 128 / 256 = always, with tiles of that many kept
+ * rows.  The slab form of the tiled kernel serves 3x3 layers with stride 1, no dilation, 16-bit NHWC tensors, input
+ * channels a multiple of 32 and output channels a multiple of 16 (at least 96): per chunk of 32 input channels a
+ * workgroup keeps the input pixels under the windows of its kept rows (Sec. 3.2: only those rows are lowered) in LDS and
+ * reads them once per window tap, instead of fetching the nine-fold lowered rows.  A K split (SC_OPT_SPLIT_K) divides
+ * the chunks; the split-K note on overlapping runs applies. */
+enum { SC_OPT_GATHER_PIPELINE = 0, SC_OPT_SPLIT_K = 1, SC_OPT_ROW_PANEL = 2, SC_OPT_STREAM_K = 3, SC_OPT_MASKED_STORE = 4,
+       SC_OPT_SLAB = 5 };
 sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t value);
 
 void sparse_conv_plan_destroy(sc_plan* plan);
@@ -280,8 +290,8 @@ int32_t sc_last_hip_error(void); /* hipError_t of the last failed HIP call on th
  * With g[r, co] = dy[r, co] where mask[r] == 1 and (no ReLU or y[r, co] > 0), and 0 elsewhere:
  *     db[co] = sum_r g[r, co]      dw[co, k] = sum_r g[r, co] * A[r, k]      dx = transposed convolution of g
  * (A = lowered activations, Sec. 3).  The contraction for dw runs over the kept rows only, like the
- * forward GEMM (Sec. 3.2).  NHWC layers with one group, bf16 or fp16, Cin and Cout multiples of 8;
- * SC_ERR_UNSUPPORTED otherwise.
+ * forward GEMM (Sec. 3.2).  NHWC layers with one group, bf16, fp16 or float (the paper's own arithmetic:
+ * a plainer kernel on the 32 x 32 x 2 float MFMA), Cin and Cout multiples of 8; SC_ERR_UNSUPPORTED otherwise.
  *   sparse_conv_backward_plan   `fwd` is the layer's forward plan (it supplies the mask and the row list and must
  *                         outlive the backward plan; after sparse_conv_plan_set_mask the backward plan follows);
  *                         `desc` the descriptor the forward plan was made from; w_dev the filters.  workspace_dev:

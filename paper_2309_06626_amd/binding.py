@@ -423,6 +423,7 @@ SC_OPT_SPLIT_K = 1
 SC_OPT_ROW_PANEL = 2
 SC_OPT_STREAM_K = 3
 SC_OPT_MASKED_STORE = 4
+SC_OPT_SLAB = 5
 
 
 def sparse_conv_plan_set_option(plan: Plan, option: int, value: int):

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparse_conv.so")
-SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "bandtap.hip", "igemm_panel.hip", "igemm_buf.hip", "igemm_streamk.hip", "igemm_rowseg.hip", "mask_gen.hip", "depthwise.hip", "backward.hip", "probes.hip"]
+SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "bandtap.hip", "igemm_panel.hip", "igemm_buf.hip", "igemm_slab.hip", "igemm_streamk.hip", "igemm_rowseg.hip", "mask_gen.hip", "depthwise.hip", "backward.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-value",
@@ -41,8 +41,19 @@ def build_library(jobs: int = 8, extra_flags=(), out: str = LIB, obj_dir: str = 
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":
-    print(build_library())
+    # python -m paper_2309_06626_amd.build [--define NAME=VALUE ...] [--out PATH]: a development build beside the
+    # library (time-stamp or probe macros of the kernels), with its own object folder
+    import argparse
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--define", action="append", default=[])
+    ap.add_argument("--out", default=LIB)
+    a = ap.parse_args()
+    out = os.path.abspath(a.out)
+    build_library(extra_flags=tuple("-D" + d for d in a.define), out=out,
+                  obj_dir=OBJ if out == LIB else out + ".objs")
+    print(out)

@@ -62,6 +62,10 @@ struct ConvParams {
   int32_t* counters;       // [m_tiles * n_tiles] arrival counters, zero between launches
   // stream-K launches only: persistent workgroups (a multiple of 8), each with two partial-sum slots in `partial`
   int32_t stream_wgs;
+  // slab launches only (igemm_slab_kernel): bytes of one slab buffer in LDS, height and width of the virtual
+  // zero-padded image (H + 2 * pad_h, W + 2 * pad_w) and their multiply-shift divisors
+  int32_t slab_bytes, slab_hp, slab_wp;
+  uint32_t div_hp_mul, div_hp_shift, div_wp_mul, div_wp_shift;
 #ifdef SC_TIMING
   long long* dbg;          // development builds only: per-workgroup phase time stamps
 #endif

@@ -17,6 +17,7 @@
 #include "bandtap_kernel.hpp"
 #include "conv_params.hpp"
 #include "igemm_buf_kernel.hpp"
+#include "igemm_slab_kernel.hpp"
 #include "igemm_streamk_kernel.hpp"
 #include "igemm_panel_kernel.hpp"
 
@@ -92,6 +93,24 @@ __global__ __launch_bounds__(256) void mask_scatter_kernel(const uint8_t* __rest
   if (seg == nseg - 1 && lane == 0) {
     kept_out[0] = base;
     kept_out[1] = 0;      // the per-band maximum, raised by band_rows_kernel
+    kept_out[2] = 0;      // the widest slab of a 128-row / 256-row tile, raised by slab_span_kernel
+    kept_out[3] = 0;
+  }
+}
+
+// Slab kernel (igemm_slab_kernel.hpp): virtual rows between the window corner of the first and of the last kept row of
+// every tile of 128 and of 256 kept rows, plus the window height; the maximum over the tiles sizes the LDS slab.
+__global__ __launch_bounds__(256) void slab_span_kernel(const int32_t* __restrict__ row_idx, const int32_t* __restrict__ kept_dev,
+                                                        int ho_wo, int wo, int hp, int kh, int32_t* __restrict__ span_out) {
+  const int kept = kept_dev[0];
+  const int tile = blockIdx.x * 256 + threadIdx.x;
+  auto vrow = [&](int r) { return (r / ho_wo) * hp + (r % ho_wo) / wo; };
+  for (int b = 0; b < 2; ++b) {
+    const int bm = 128 << b;
+    const int64_t m0 = (int64_t)tile * bm;
+    if (m0 >= kept) continue;
+    const int last = (int)min((int64_t)kept, m0 + bm) - 1;
+    atomicMax(span_out + b, vrow(row_idx[last]) + kh - vrow(row_idx[m0]));
   }
 }
 
@@ -730,6 +749,12 @@ struct sc_plan {
   int stream_k;                    // 0 = automatic, 1 = never, n >= 2 = n persistent workgroups wherever the kernel applies
   int masked_store;                // 0 = automatic, 1 = never, 2 = wherever it applies (sparse runs of dense NHWC operands)
   bool x_rank_set;                 // sparse_conv_plan_set_input_mask has filled the rank map of a compact input
+  // slab form of the tiled kernel (deep 3x3 layers)
+  struct Slab { int bm, splits; };
+  bool slab_ok;                    // the layer's geometry admits it
+  int slab;                        // 0 = automatic, 1 = never, 2 = wherever it applies, 128 / 256 = with tiles of that many rows
+  int slab_span[2][2];             // [sparse, dense run][128-row, 256-row tiles]: virtual rows of the widest tile's slab
+  Slab slab_auto[2];               // what an automatic launch of the sparse / dense run takes (bm == 0: another kernel)
 };
 constexpr int kForceBand = -2;
 
@@ -903,6 +928,53 @@ static int stream_k_workgroups(const sc_plan* pl, const KernelEntry& ke, int64_t
   return want;
 }
 
+// ---- slab form of the tiled kernel --------------------------------------------------------------------
+// 3x3 windows, stride 1, no dilation, 16-bit NHWC, input channels in chunks of 32, tensors below 2 GiB.
+static bool slab_geometry_ok(const sc_conv_desc& d, const Geometry& g) {
+  if (g.depthwise || g.rowseg || d.dtype == SC_F32 || d.layout != SC_NHWC || !g.vec_out) return false;
+  if (d.kh != 3 || d.kw != 3 || d.stride_h != 1 || d.stride_w != 1 || d.dil_h != 1 || d.dil_w != 1) return false;
+  if (d.pad_h > 2 || d.pad_w > 2 || d.c_in % kSlabCh != 0 || d.c_out < 96) return false;
+  const uint64_t xb = (uint64_t)d.n * d.h * d.w * d.c_in * 2, wb = (uint64_t)g.cout_pad * g.k_stride * 2;
+  return xb < ((uint64_t)1 << 31) && wb < ((uint64_t)1 << 31) && (int64_t)d.n * (d.h + 2 * d.pad_h) < ((int64_t)1 << 30);
+}
+// bytes of one slab buffer for tiles of bm rows whose widest slab spans `span` virtual rows (0: it does not fit)
+static int slab_buffer_bytes(const sc_conv_desc& d, int bm, int span) {
+  const int round = (bm == 256 ? 512 : 256) * 16;      // what one transfer of the whole workgroup covers
+  const int64_t bytes = ((int64_t)span * (d.w + 2 * d.pad_w) * kSlabPixelBytes + round - 1) / round * round;
+  return span > 0 && bytes <= kSlabMostBytes ? (int)bytes : 0;
+}
+// dense run: tiles are runs of bm consecutive pixels
+static int slab_dense_span(const sc_conv_desc& d, const Geometry& g, int bm) {
+  const int hp = d.h + 2 * d.pad_h, ho_wo = g.ho * g.wo;
+  auto vrow = [&](int64_t r) { return (int)(r / ho_wo) * hp + (int)(r % ho_wo) / g.wo; };
+  int span = 0;
+  for (int64_t m0 = 0; m0 < g.m; m0 += bm) span = std::max(span, vrow(std::min<int64_t>(g.m, m0 + bm) - 1) + d.kh - vrow(m0));
+  return span;
+}
+// K splits (by chunks of input channels) of a slab launch with tiles of bm rows: one workgroup per compute unit
+static int slab_splits(const sc_plan* pl, int bm, int64_t rows) {
+  const Geometry& g = pl->geo;
+  if (!g.splitk_ok || pl->split_k == 1) return 1;
+  const int64_t tiles = ((rows + bm - 1) / bm) * ((pl->desc.c_out + kSlabBN - 1) / kSlabBN);
+  int64_t want = pl->split_k >= 2 ? pl->split_k : std::max<int64_t>(1, device_cus() / std::max<int64_t>(tiles, 1));
+  const int64_t by_buffer = (int64_t)(kSplitKPartialBytes / ((size_t)bm * kSlabBN * sizeof(float))) / std::max<int64_t>(tiles, 1);
+  want = std::min<int64_t>(std::min<int64_t>(want, by_buffer), std::min<int64_t>(pl->desc.c_in / kSlabCh, kSplitKMost));
+  return (int)std::max<int64_t>(want, 1);
+}
+// the slab launch the options ask for, or the automatic one (bm == 0: none)
+static sc_plan::Slab slab_pick(const sc_plan* pl, int which, int64_t rows) {
+  const sc_plan::Slab none = {0, 1};
+  if (!pl->slab_ok || pl->slab == 1 || rows == 0 || pl->gather_pipeline == 1) return none;
+  if (pl->slab == 0) {
+    if (pl->forced[which] != -1 || pl->split_k != 0 || pl->stream_k >= 2 || pl->masked_store == 2) return none;
+    return pl->slab_auto[which];
+  }
+  for (int bm = 256; bm >= 128; bm >>= 1) {
+    if (pl->slab >= 128 && pl->slab != bm) continue;
+    if (slab_buffer_bytes(pl->desc, bm, pl->slab_span[which][bm == 256])) return {bm, slab_splits(pl, bm, rows)};
+  }
+  return none;
+}
 static TilePick pick_tile(const sc_plan* pl, int which, int64_t rows) {
   TilePick tp;
   tp.masked = false;
@@ -1004,8 +1076,10 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
   const BandPlan& band = dense ? pl->band_dense : pl->band;
   // (of the band and row-panel kernels only the alternating-group band kernel has a shortcut path: any other
   // fused launch takes a tiled kernel)
+  const sc_plan::Slab slab = x_compact ? sc_plan::Slab{0, 1} : slab_pick(pl, which, rows);
   const bool use_band = band.ok && !x_compact && !y_compact && (!residual || ((band.pp || band.tap) && !band.stream)) &&
-                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream && !pl->prefer_tiled[which]));
+                        (pl->forced[which] == kForceBand || (pl->forced[which] == -1 && !band.stream && !pl->prefer_tiled[which])) &&
+                        !(slab.bm && pl->slab >= 2);
   if (use_band) {
     const BandPlan& b = band;
     BandParams q;
@@ -1065,6 +1139,54 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
     const int cpp = d.c_in / g.vec;
     const int shape = (d.kh == 3 && d.kw == 3 && cpp == 8) ? 1 : (d.kh == 3 && d.kw == 3 && cpp == 4) ? 2 : 0;
     SC_HIP(pl->band_table->fn[shape][b.ni_idx][mi_idx](q, b.lds, stream));
+    return SC_OK;
+  }
+  if (slab.bm) {
+    ConvParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.x = x;
+    p.wp = pl->ws + g.off_wp;
+    p.bias = d.has_bias ? bias : nullptr;
+    p.y = y;
+    p.row_idx = identity ? nullptr : reinterpret_cast<const int32_t*>(pl->ws + g.off_rows);
+    p.mask = pl->ws + g.off_mask;
+    p.rows = (int32_t)rows;
+    p.m_total = (int32_t)g.m;
+    p.h = d.h; p.w = d.w; p.ho_wo = g.ho * g.wo; p.wo = g.wo;
+    magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+    magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
+    p.sh = 1; p.sw = 1; p.ph = d.pad_h; p.pw = d.pad_w;
+    p.c_in = d.c_in; p.kh = d.kh; p.kw = d.kw; p.dil_h = 1; p.dil_w = 1;
+    p.c_out = d.c_out;
+    p.k_pad = g.k_stride; p.k_tiles = g.k_tiles;
+    p.relu = d.relu;
+    p.zero_fill = zero_fill ? 1 : 0;
+    p.mask_spatial = d.mask_mode == SC_MASK_SPATIAL;
+    p.vec_out = 1;
+    p.y_compact = compact && y_compact ? 1 : 0;
+    p.residual = residual;
+    p.residual_relu = residual_relu ? 1 : 0;
+    p.m_tiles = (int32_t)((rows + slab.bm - 1) / slab.bm);
+    p.n_tiles = (d.c_out + kSlabBN - 1) / kSlabBN;
+    p.x_bytes = (uint32_t)((uint64_t)d.n * d.h * d.w * d.c_in * eb);
+    p.w_bytes = (uint32_t)((uint64_t)g.cout_pad * g.k_stride * eb);
+    // (a mask that keeps every row runs over the identity map: its tiles are those of the dense run)
+    p.slab_bytes = slab_buffer_bytes(d, slab.bm, std::max(pl->slab_span[which][slab.bm == 256],
+                                                          identity ? pl->slab_span[1][slab.bm == 256] : 0));
+    p.slab_hp = d.h + 2 * d.pad_h;
+    p.slab_wp = d.w + 2 * d.pad_w;
+    magic_div((uint32_t)p.slab_hp, &p.div_hp_mul, &p.div_hp_shift);
+    magic_div((uint32_t)p.slab_wp, &p.div_wp_mul, &p.div_wp_shift);
+    if (p.slab_bytes == 0) return SC_ERR_UNSUPPORTED;    // cannot happen: slab_pick checked the span
+    const int splits = std::min(slab.splits, d.c_in / kSlabCh);
+    if (splits > 1) {
+      p.splits = splits;
+      p.partial = reinterpret_cast<float*>(pl->ws + g.off_partial);
+      p.counters = reinterpret_cast<int32_t*>(pl->ws + g.off_counters);
+    }
+    LaunchFn fn = slab_kernel(d.dtype == SC_BF16 ? kBF16 : kF16, slab.bm, splits > 1);
+    if (!fn) return SC_ERR_UNSUPPORTED;
+    SC_HIP(fn(p, stream));
     return SC_OK;
   }
   TilePick tp = pick_tile(pl, which, rows);
@@ -1223,7 +1345,7 @@ static sc_status pack_filters(const sc_conv_desc& d, const Geometry& g, unsigned
 // Synchronises the stream (the kept count decides the launch shapes) and checks the count against the
 // descriptor's sparsity.
 static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsigned char* ws, const uint8_t* mask_dev,
-                                  hipStream_t stream, BandPlan* bp_io, int32_t* kept_out) {
+                                  hipStream_t stream, BandPlan* bp_io, int32_t* kept_out, int32_t* slab_span_out) {
   BandPlan& bp = *bp_io;
   // compaction
   const int period = d.mask_mode == SC_MASK_SPATIAL ? g.ho * g.wo : 0;
@@ -1253,11 +1375,19 @@ static sc_status build_row_tables(const sc_conv_desc& d, const Geometry& g, unsi
     SC_HIP(hipGetLastError());
   }
 
-  int32_t host_vals[2] = {-1, 0};   // kept count, most kept rows in one band
-  SC_HIP(hipMemcpyAsync(host_vals, kept_dev, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+  if (slab_geometry_ok(d, g)) {
+    hipLaunchKernelGGL(slab_span_kernel, dim3((unsigned)((g.m + 127) / 128 + 255) / 256), dim3(256), 0, stream, rows, kept_dev,
+                       g.ho * g.wo, g.wo, d.h + 2 * d.pad_h, d.kh, kept_dev + 2);
+    SC_HIP(hipGetLastError());
+  }
+
+  int32_t host_vals[4] = {-1, 0, 0, 0};   // kept count, most kept rows in one band, widest slab of a 128-row / 256-row tile
+  SC_HIP(hipMemcpyAsync(host_vals, kept_dev, 4 * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
   SC_HIP(hipStreamSynchronize(stream));
   *kept_out = host_vals[0];
   bp.max_kept = host_vals[1];
+  slab_span_out[0] = host_vals[2];
+  slab_span_out[1] = host_vals[3];
 
   if (d.sparsity >= 0.0f) {
     // Sec. 3.2: rows in the GEMM = output_size - sparsity * output_size (rounded half up).  The descriptor carries
@@ -1322,7 +1452,8 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   int32_t kept_host = 0;
   s = pack_filters(d, g, ws, w_dev, stream);
   if (s != SC_OK) return s;
-  s = build_row_tables(d, g, ws, mask_dev, stream, &bp, &kept_host);   // synchronises the stream
+  int32_t slab_span[2] = {0, 0};
+  s = build_row_tables(d, g, ws, mask_dev, stream, &bp, &kept_host, slab_span);   // synchronises the stream
   if (s != SC_OK) return s;
 
   sc_plan* pl = new (std::nothrow) sc_plan;
@@ -1351,6 +1482,14 @@ sc_status sparse_conv_plan(const sc_conv_desc* desc, const uint8_t* mask_dev, co
   pl->pick[1] = model_pick(pl, 1, g.m);
   pl->band = bp;
   pl->band_dense = plan_band(d, g, g.m);
+  pl->slab = 0;
+  pl->slab_ok = slab_geometry_ok(d, g) && slab_kernel(d.dtype == SC_BF16 ? kBF16 : kF16, 128, false);
+  pl->slab_span[0][0] = slab_span[0]; pl->slab_span[0][1] = slab_span[1];
+  pl->slab_span[1][0] = pl->slab_ok ? slab_dense_span(d, g, 128) : 0;
+  pl->slab_span[1][1] = pl->slab_ok ? slab_dense_span(d, g, 256) : 0;
+  // (automatic launches take the slab form only where sparse_conv_plan_tune measured it faster: the cost model's
+  // quantities -- bytes through the L1 path, matrix time -- do not rank it, its K loop is bound by LDS reads)
+  pl->slab_auto[0] = pl->slab_auto[1] = sc_plan::Slab{0, 1};
   pl->band_table = d.dtype == SC_BF16 ? band_bf16() : d.dtype == SC_F16 ? band_f16() : band_f32();
   pl->stream_table = d.dtype == SC_BF16 ? bandstream_bf16() : d.dtype == SC_F16 ? bandstream_f16() : nullptr;
   pl->pp_table = d.dtype == SC_BF16 ? bandpp_bf16() : d.dtype == SC_F16 ? bandpp_f16() : nullptr;
@@ -1367,12 +1506,15 @@ sc_status sparse_conv_plan_set_mask(sc_plan* plan, const uint8_t* mask_dev, void
   const Geometry& g = plan->geo;
   BandPlan bp = plan->band;
   int32_t kept_host = 0;
-  sc_status s = build_row_tables(d, g, plan->ws, mask_dev, static_cast<hipStream_t>(hip_stream), &bp, &kept_host);
+  int32_t slab_span[2] = {0, 0};
+  sc_status s = build_row_tables(d, g, plan->ws, mask_dev, static_cast<hipStream_t>(hip_stream), &bp, &kept_host, slab_span);
   if (s != SC_OK) return s;
   plan->kept = kept_host;
   plan->band = bp;
   plan->pick[0] = model_pick(plan, 0, plan->kept);      // (a measured choice belonged to the previous mask's row count)
   plan->prefer_tiled[0] = false;
+  plan->slab_span[0][0] = slab_span[0]; plan->slab_span[0][1] = slab_span[1];
+  plan->slab_auto[0] = sc_plan::Slab{0, 1};
   return SC_OK;
 }
 
@@ -1550,6 +1692,30 @@ sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* b
     }
     plan->pick[which] = best_pick;
     plan->prefer_tiled[which] = best_tiled;
+    // the slab form of the tiled kernel (deep 3x3 layers): both tile heights, the K splits around one workgroup per
+    // compute unit; it replaces the choice so far only where it measures faster
+    plan->slab_auto[which] = sc_plan::Slab{0, 1};
+    const BandPlan& bsel = dense ? plan->band_dense : plan->band;
+    if (plan->slab_ok && plan->slab == 0 && plan->split_k == 0 && !(bsel.ok && !bsel.stream && !best_tiled)) {
+      sc_plan::Slab best_slab = {0, 1};
+      for (int bm = 256; bm >= 128; bm >>= 1) {
+        if (!slab_buffer_bytes(plan->desc, bm, plan->slab_span[which][bm == 256])) continue;
+        const int around = slab_splits(plan, bm, rows);
+        int tried[4] = {0, 0, 0, 0}, n_tried = 0;
+        for (int sp : {around, around - 1, around + 1, 1}) {
+          if (sp < 1 || sp > plan->desc.c_in / kSlabCh || (sp > 1 && !plan->geo.splitk_ok)) continue;
+          if ((int64_t)((rows + bm - 1) / bm) * ((plan->desc.c_out + kSlabBN - 1) / kSlabBN) * sp * bm * kSlabBN * 4 > (int64_t)kSplitKPartialBytes) continue;
+          bool seen = false;
+          for (int i = 0; i < n_tried; ++i) seen = seen || tried[i] == sp;
+          if (seen) continue;
+          tried[n_tried++] = sp;
+          plan->slab_auto[which] = {bm, sp};
+          const double us = time_us(dense, 40, 3);
+          if (us > 0.0 && us < 0.985 * best_us) { best_us = us; best_slab = {bm, sp}; }
+        }
+      }
+      plan->slab_auto[which] = best_slab;
+    }
   }
   // A sparse run must not lose to the dense run of its own plan: where it still does, try the dense run's tile with
   // every row contracted and the mask applied at the store.
@@ -1606,13 +1772,20 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
     return SC_OK;
   }
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which]))) {
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which])) &&
+      !(plan->slab >= 2 && slab_pick(plan, which, which ? plan->geo.m : plan->kept).bm)) {
     if (tile_m) *tile_m = -band.bh;     // (rows per run; split bands hold half a run each)
     if (tile_n) *tile_n = 32 * band.ni;
     if (workgroups) *workgroups = band.pp && !band.tap ? band.pp_grid : (int64_t)band.n_bands * band.n_tiles;
     return SC_OK;
   }
   int64_t rows = which ? plan->geo.m : plan->kept;
+  if (const sc_plan::Slab sl = slab_pick(plan, which, rows); sl.bm) {
+    if (tile_m) *tile_m = sl.bm;
+    if (tile_n) *tile_n = kSlabBN;
+    if (workgroups) *workgroups = ((rows + sl.bm - 1) / sl.bm) * ((plan->desc.c_out + kSlabBN - 1) / kSlabBN) * std::min(sl.splits, plan->desc.c_in / kSlabCh);
+    return SC_OK;
+  }
   if (use_panel(plan, which, rows)) {
     if (tile_m) *tile_m = kPanelBM;
     if (tile_n) *tile_n = kPanelBN;
@@ -1647,9 +1820,11 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1)) return nullptr;
   if (plan->geo.depthwise) return "depthwise";
   const BandPlan& band = which ? plan->band_dense : plan->band;
-  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which])))
+  if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which])) &&
+      !(plan->slab >= 2 && slab_pick(plan, which, which ? plan->geo.m : plan->kept).bm))
     return band.stream ? "band_stream" : band.tap ? "band_tap" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
+  if (slab_pick(plan, which, which ? g.m : plan->kept).bm) return "tile_slab";
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";
   return tiled_kernel_name(plan, which);
 }
@@ -1658,8 +1833,10 @@ const char* sparse_conv_plan_fused_kernel(const sc_plan* plan, int32_t which) {
   if (!plan || (which != 0 && which != 1) || plan->geo.depthwise) return nullptr;
   const BandPlan& band = which ? plan->band_dense : plan->band;
   if (band.ok && (band.pp || band.tap) && !band.stream &&
-      (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->prefer_tiled[which])))
+      (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !plan->prefer_tiled[which])) &&
+      !(plan->slab >= 2 && slab_pick(plan, which, which ? plan->geo.m : plan->kept).bm))
     return band.tap ? "band_tap" : "band_alternating";
+  if (slab_pick(plan, which, which ? plan->geo.m : plan->kept).bm) return "tile_slab";
   return tiled_kernel_name(plan, which);
 }
 
@@ -1685,6 +1862,7 @@ sc_status sparse_conv_plan_set_option(sc_plan* plan, int32_t option, int32_t val
   if (option == SC_OPT_SPLIT_K && value >= 0 && value <= kSplitKMost) { plan->split_k = value; return SC_OK; }
   if (option == SC_OPT_STREAM_K && value >= 0 && value <= kStreamKMostWgs) { plan->stream_k = value; return SC_OK; }
   if (option == SC_OPT_MASKED_STORE && value >= 0 && value <= 2) { plan->masked_store = value; return SC_OK; }
+  if (option == SC_OPT_SLAB && ((value >= 0 && value <= 2) || value == 128 || value == 256)) { plan->slab = value; return SC_OK; }
   return SC_ERR_UNSUPPORTED;
 }
 

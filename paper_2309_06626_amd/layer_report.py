@@ -378,8 +378,8 @@ def main():
     ap.add_argument("--oracle-times", action="store_true",
                     help="also time the CPU oracle on every configuration (all host cores; one thread for configs 1 and 2)")
     ap.add_argument("--profile-layer", default="",
-                    help="NAME[:BMxBN][:splitN][:dense][:cold] -- only launch that layer of config 2 (s = 0.5), 3, 4 or 5 --steps times "
-                         "(sparse run, or the dense run), optionally with a forced tile of the tiled kernel and N splits of K, "
+                    help="NAME[:BMxBN][:splitN][:slabBM][:dense][:cold][:time] -- only launch that layer of config 2 (s = 0.5), 3, 4 or 5 --steps times "
+                         "(sparse run, or the dense run), optionally with a forced tile of the tiled kernel, N splits of K, the slab kernel with BM-row tiles, "
                          "optionally rotating through buffer copies larger than the memory-side cache: the target of a rocprofv3 run")
     args = ap.parse_args()
 
@@ -408,6 +408,8 @@ def main():
         for part in parts[1:]:
             if part.startswith("split"):
                 B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, int(part[5:]))
+            elif part.startswith("slab"):
+                B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SLAB, int(part[4:]))
             elif "x" in part:
                 bm, bn = (int(v) for v in part.split("x"))
                 B.sparse_conv_plan_set_tiles(layer.plan, 0, bm, bn)
@@ -426,6 +428,10 @@ def main():
         which = 1 if dense else 0
         print(f"{spec.name}: {args.steps} launches of {B.sparse_conv_plan_kernel(layer.plan, which)} "
               f"{B.sparse_conv_plan_tiles(layer.plan, which)}, rows {spec.m if dense else ci.keep}, K {spec.k}, Cout {spec.c_out}")
+        if "time" in parts[1:] and "cold" not in parts[1:]:      # device time per launch: graph replays, HIP events
+            from paper_2309_06626_amd.metrics import time_launches
+            us = time_launches(call, max(args.steps, 100), 20, 5)[1] * 1e6
+            print(f"{spec.name}: {us:.2f} us per launch (median of 5 replays of a graph of {max(args.steps, 100)} launches)")
         return
     want = {int(c) for c in args.configs.split(",")}
     records = []

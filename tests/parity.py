@@ -48,7 +48,7 @@ def assert_close(got, ref, absum, tol, what=""):
 
 
 def check_layer(ci: W.ConvInputs, tiles=None, out_mode=B.SC_OUT_ZERO_FILL, check_dense=True, sample_rows=None,
-                device="cuda:0", check_count=True, split_k=None, row_panel=None, stream_k=None):
+                device="cuda:0", check_count=True, split_k=None, row_panel=None, stream_k=None, options=None):
     """Plan + sparse run (+ dense run) of one layer, compared with the oracle.
 
     sample_rows: None = every row through the oracle, else that many random rows plus every
@@ -65,6 +65,8 @@ def check_layer(ci: W.ConvInputs, tiles=None, out_mode=B.SC_OUT_ZERO_FILL, check
         B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_ROW_PANEL, row_panel)
     if stream_k is not None:
         B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_STREAM_K, stream_k)
+    for option, value in (options or {}).items():
+        B.sparse_conv_plan_set_option(layer.plan, option, value)
     rm = row_mask(spec, ci.mask)
 
     # a0: compaction, bit-exact
