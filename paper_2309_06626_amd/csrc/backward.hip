@@ -8,9 +8,9 @@
 //     dx        = the transposed convolution of g  -- for stride 1 an ordinary convolution of the g map
 //                                                     with the filters rotated by 180 degrees and
 //                                                     transposed; it runs through the forward kernels
-// Kernels here: the filter-gradient GEMM on the matrix cores in two forms -- operands straight into LDS, dy gated by
+// Kernels here: the filter-gradient GEMM on the matrix cores in two 16-bit forms -- operands straight into LDS, dy gated by
 // y on the way and db summed from the same tiles (the form that runs wherever the tensors fit 32-bit offsets), and an
-// older register-staged form that reads a g map -- each with a deterministic second pass over its row splits; the g
+// older register-staged form that reads a g map -- and a float form, each with a deterministic second pass over its row splits; the g
 // map with its column sums (written only when the input gradient, a convolution of the g map, is asked for); and the
 // filter rotation for the input gradient.
 #include "../../include/sparse_conv.h"
@@ -796,6 +796,93 @@ __global__ __launch_bounds__(256) void wgrad2_reduce_kernel(const float* __restr
   }
 }
 
+// ---- filter gradient in float (the paper's arithmetic: App. A works on floats) -----------------------------------
+// The 32 x 32 x 2 float MFMA takes, per lane, ONE element of each operand: row (lane % 32) of its 32-wide block and
+// contraction entry lane / 32.  With the contraction over kept rows that is element [row 2s + lane / 32][column
+// lane % 32] of a row-major tile -- no transposition, plain 4-byte LDS reads; rows lie 96 floats apart so that
+// the two rows of a step fall into different halves of the banks.
+//   workgroup = 64 output channels x 64 window entries x one split of the kept rows; 2 x 2 wavefronts of 32 x 32
+//   stage     = 32 kept rows; a thread stages one column of both tiles for every fourth row, the next stage's values
+//               are fetched into registers before the MFMAs of the current one
+//   result    = float partial sums per split; wgrad_reduce_kernel adds the splits in order
+constexpr int kWfRows = 32, kWfPitch = 96, kWfTile = 64;
+__global__ __launch_bounds__(256) void wgrad_f32_kernel(const WgradParams p) {
+  __shared__ float s_g[kWfRows * kWfPitch], s_a[kWfRows * kWfPitch];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int fp = lane & 31, fh = lane >> 5;
+  const int wm0 = (wave >> 1) * 32, wn0 = (wave & 1) * 32;
+  const int tiles = p.co_tiles * p.k_tiles;
+  const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
+  const int co0 = (tile / p.k_tiles) * kWfTile, k0 = (tile % p.k_tiles) * kWfTile;
+  const int i_begin = split * p.rows_per_split, i_end = min(p.rows, i_begin + p.rows_per_split);
+  const int n_st = (i_end - i_begin + kWfRows - 1) / kWfRows;
+  const float* __restrict__ xg = static_cast<const float*>(p.x);
+  const float* __restrict__ gg = static_cast<const float*>(p.g);
+
+  // this thread's column of both tiles: output channel co, window entry kcol = (tap, ci)
+  const int col = t & 63, r0 = t >> 6;
+  const int co = co0 + col, kcol = k0 + col;
+  const bool co_ok = co < p.c_out, k_ok = kcol < p.k;
+  const int tap = k_ok ? kcol / p.c_in : 0, ci = kcol - tap * p.c_in;
+  const int ky = tap / p.kw, kx = tap - ky * p.kw;
+  const int tdy = ky * p.dil_h, tdx = kx * p.dil_w;
+  float gv[8], av[8];
+  auto fetch = [&](int st) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int i = i_begin + st * kWfRows + r0 + 4 * j;
+      gv[j] = 0.0f;
+      av[j] = 0.0f;
+      if (i < i_end) {
+        const int r = p.row_idx ? p.row_idx[i] : i;
+        if (co_ok) gv[j] = gg[(int64_t)r * p.c_out + co];
+        const int n = fast_div(r, p.div_howo_mul, p.div_howo_shift), rem = r - n * p.ho_wo;
+        const int oy = fast_div(rem, p.div_wo_mul, p.div_wo_shift), ox = rem - oy * p.wo;
+        const int iy = oy * p.sh - p.ph + tdy, ix = ox * p.sw - p.pw + tdx;
+        if (k_ok && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w)
+          av[j] = xg[(((int64_t)n * p.h + iy) * p.w + ix) * p.c_in + ci];
+      }
+    }
+  };
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  if (n_st > 0) fetch(0);
+  for (int st = 0; st < n_st; ++st) {
+    __syncthreads();                                   // everybody has read the previous stage
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      s_g[(r0 + 4 * j) * kWfPitch + col] = gv[j];
+      s_a[(r0 + 4 * j) * kWfPitch + col] = av[j];
+    }
+    __syncthreads();
+    if (st + 1 < n_st) fetch(st + 1);                  // in flight under the MFMAs below
+#pragma unroll
+    for (int s2 = 0; s2 < kWfRows / 2; ++s2) {
+      const float a = s_g[(2 * s2 + fh) * kWfPitch + wm0 + fp];
+      const float b = s_a[(2 * s2 + fh) * kWfPitch + wn0 + fp];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+  }
+  // MFMA result row 8j + 4h + i sits in register 4j + i of lane half h; column = lane % 32
+  float* __restrict__ out = p.out + (int64_t)split * p.c_out * p.k;
+  const int kc = k0 + wn0 + fp;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int c = co0 + wm0 + 8 * (v >> 2) + 4 * fh + (v & 3);
+    if (c < p.c_out && kc < p.k) out[(int64_t)c * p.k + kc] = acc[v];
+  }
+}
+
+// rows per split of the float kernel: about three workgroups per compute unit, at least eight stages per split
+static int wgrad_f32_splits(int64_t rows, int c_out, int k) {
+  const int64_t tiles = (int64_t)((c_out + kWfTile - 1) / kWfTile) * ((k + kWfTile - 1) / kWfTile);
+  int64_t want = (768 + tiles - 1) / tiles;
+  want = std::min<int64_t>(want, (rows + 8 * kWfRows - 1) / (8 * kWfRows));
+  want = std::min<int64_t>(want, (int64_t)(((size_t)64 << 20) / ((size_t)c_out * k * 4)));
+  return (int)std::max<int64_t>(want, 1);
+}
+
 constexpr size_t kWgradPartialBytes = (size_t)64 << 20;   // most workspace the row splits may take
 
 static int wgrad_splits(int64_t rows, int c_out, int k) {
@@ -849,11 +936,11 @@ static sc_status backward_layout(const sc_conv_desc* d, sc_bwd_plan* L, sc_conv_
          *off_partial = &L->off_partial, *off_colsum = &L->off_colsum, *off_gup = &L->off_gup;
   sc_status s = sparse_conv_output_shape(d, ho, wo, m);
   if (s != SC_OK) return s;
-  // the filter-gradient kernel gathers 16-byte channel groups of 16-bit values
-  if (d->groups != 1 || d->layout != SC_NHWC || (d->dtype != SC_BF16 && d->dtype != SC_F16) || d->c_in % 8 != 0 ||
-      d->c_out % 8 != 0)
+  // the 16-bit filter-gradient kernels gather 16-byte channel groups, and the g map is written in groups of eight channels
+  if (d->groups != 1 || d->layout != SC_NHWC || (d->dtype != SC_BF16 && d->dtype != SC_F16 && d->dtype != SC_F32) ||
+      d->c_in % 8 != 0 || d->c_out % 8 != 0)
     return SC_ERR_UNSUPPORTED;
-  const size_t eb = 2;
+  const size_t eb = d->dtype == SC_F32 ? 4 : 2;
   const int64_t k = (int64_t)d->kh * d->kw * d->c_in;
   // input gradient: an ordinary stride-1 convolution of the g map (zero-interleaved for strided layers) with
   // the rotated filters, padded by dil * (k - 1) - pad; the interleaved map gets as many extra zero rows /
@@ -869,7 +956,7 @@ static sc_status backward_layout(const sc_conv_desc* d, sc_bwd_plan* L, sc_conv_
   *off_colsum = off; off = align_up(off + (size_t)((*m + kSumRowsLeast - 1) / kSumRowsLeast) * d->c_out * 4, 256);
   *off_partial = off;
   // (the dense row count bounds every mask's; both forms of the kernel fit)
-  off = align_up(off + std::max((size_t)wgrad_splits(*m, d->c_out, (int)k) * d->c_out * k * 4,
+  off = align_up(off + std::max(std::max((size_t)wgrad_splits(*m, d->c_out, (int)k), (size_t)wgrad_f32_splits(*m, d->c_out, (int)k)) * d->c_out * k * 4,
                                 (size_t)wgrad2_splits(*m, d->c_out, (int)k, d->relu != 0) * ((size_t)d->c_out * k + d->c_out) * 4), 256);
   *off_ones = *off_wrot = *off_inner = *off_gup = off;
   if (*has_inner) {
@@ -899,8 +986,12 @@ static sc_status backward_layout(const sc_conv_desc* d, sc_bwd_plan* L, sc_conv_
 static sc_status rotate_filters(const sc_bwd_plan* bp, const void* w_dev, hipStream_t stream) {
   const sc_conv_desc& d = bp->desc;
   const int64_t total = (int64_t)d.c_out * d.kh * d.kw * d.c_in;
-  hipLaunchKernelGGL(rotate_filters_kernel<_Float16>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                     (const _Float16*)w_dev, (_Float16*)(bp->ws + bp->off_wrot), d.c_out, d.c_in, d.kh, d.kw);
+  if (d.dtype == SC_F32)
+    hipLaunchKernelGGL(rotate_filters_kernel<float>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const float*)w_dev, (float*)(bp->ws + bp->off_wrot), d.c_out, d.c_in, d.kh, d.kw);
+  else   // 16-bit patterns are moved verbatim
+    hipLaunchKernelGGL(rotate_filters_kernel<_Float16>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                       (const _Float16*)w_dev, (_Float16*)(bp->ws + bp->off_wrot), d.c_out, d.c_in, d.kh, d.kw);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) { note_hip_error((int32_t)e); return SC_ERR_HIP; }
   return SC_OK;
@@ -948,7 +1039,7 @@ sc_status sparse_conv_backward_plan(const sc_plan* fwd, const sc_conv_desc* desc
     s = sc::rotate_filters(&tmp, w_dev, stream);
     if (s != SC_OK) return s;
     if (tmp.hu > 0) {   // the zeros between the rows of g: written once, never overwritten
-      hipError_t e = hipMemsetAsync(tmp.ws + tmp.off_gup, 0, (size_t)desc->n * tmp.hu * tmp.wu * desc->c_out * 2, stream);
+      hipError_t e = hipMemsetAsync(tmp.ws + tmp.off_gup, 0, (size_t)desc->n * tmp.hu * tmp.wu * desc->c_out * (desc->dtype == SC_F32 ? 4 : 2), stream);
       if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }
     }
     s = sparse_conv_plan(&inner, tmp.ws + tmp.off_ones, tmp.ws + tmp.off_wrot, tmp.ws + tmp.off_inner,
@@ -985,9 +1076,66 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
   sc_status s = sparse_conv_plan_info(plan->fwd, &m, &kept, nullptr, nullptr, &rows_dev);
   if (s != SC_OK) return s;
   const uint8_t* mask = sparse_conv_plan_mask(plan->fwd);
-  const int dt = d.dtype == SC_BF16 ? sc::kBF16 : sc::kF16;
+  const int dt = d.dtype == SC_BF16 ? sc::kBF16 : d.dtype == SC_F16 ? sc::kF16 : sc::kF32;
   const int period = d.mask_mode == SC_MASK_SPATIAL ? plan->ho * plan->wo : 0;
   _Float16* g = reinterpret_cast<_Float16*>(plan->ws + plan->off_g);    // 16-bit patterns; compared as the real type below
+
+  if (dt == sc::kF32) {
+    // float layers: g map with its slab sums, column sums, the float filter-gradient kernel and its reduction
+    float* gf = reinterpret_cast<float*>(plan->ws + plan->off_g);
+    const int slab_rows = sc::colsum_slab_rows(m);
+    const int slabs = (int)((m + slab_rows - 1) / slab_rows);
+    float* colsum = reinterpret_cast<float*>(plan->ws + plan->off_colsum);
+    hipLaunchKernelGGL(sc::grad_map_kernel<float>, dim3(slabs), dim3(256), 0, stream, (const float*)y_dev, (const float*)dy_dev,
+                       mask, gf, m, d.c_out, slab_rows, d.relu, period, colsum);
+    if (db_dev)
+      hipLaunchKernelGGL(sc::colsum_final_kernel, dim3((d.c_out + 3) / 4), dim3(256), 0, stream, colsum, slabs, d.c_out, db_dev);
+    if (dw_dev) {
+      const int k = d.kh * d.kw * d.c_in;
+      const int64_t count = (int64_t)d.c_out * k;
+      sc::WgradParams p;
+      std::memset(&p, 0, sizeof(p));
+      p.x = x_dev; p.g = gf;
+      p.row_idx = kept == m ? nullptr : rows_dev;
+      p.rows = (int32_t)kept;
+      p.splits = kept > 0 ? sc::wgrad_f32_splits(kept, d.c_out, k) : 0;
+      if (p.splits > 0) {
+        p.rows_per_split = (int32_t)(((kept + p.splits - 1) / p.splits + sc::kWfRows - 1) / sc::kWfRows * sc::kWfRows);
+        p.splits = (int32_t)((kept + p.rows_per_split - 1) / p.rows_per_split);
+        p.out = reinterpret_cast<float*>(plan->ws + plan->off_partial);
+        p.h = d.h; p.w = d.w; p.c_in = d.c_in; p.ho_wo = plan->ho * plan->wo; p.wo = plan->wo; p.c_out = d.c_out;
+        p.kh = d.kh; p.kw = d.kw; p.sh = d.stride_h; p.sw = d.stride_w; p.ph = d.pad_h; p.pw = d.pad_w;
+        p.dil_h = d.dil_h; p.dil_w = d.dil_w;
+        p.k = k;
+        p.co_tiles = (d.c_out + sc::kWfTile - 1) / sc::kWfTile;
+        p.k_tiles = (k + sc::kWfTile - 1) / sc::kWfTile;
+        sc::magic_div((uint32_t)p.ho_wo, &p.div_howo_mul, &p.div_howo_shift);
+        sc::magic_div((uint32_t)p.wo, &p.div_wo_mul, &p.div_wo_shift);
+        hipLaunchKernelGGL(sc::wgrad_f32_kernel, dim3((unsigned)(p.co_tiles * p.k_tiles * p.splits)), dim3(256), 0, stream, p);
+      }
+      // (no kept row: zero splits, the reduction writes zeros)
+      hipLaunchKernelGGL(sc::wgrad_reduce_kernel, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream,
+                         (const float*)p.out, p.splits, count, dw_dev);
+    }
+    hipError_t ef = hipGetLastError();
+    if (ef != hipSuccess) { sc::note_hip_error((int32_t)ef); return SC_ERR_HIP; }
+    if (dx_dev) {
+      const void* src = gf;
+      if (plan->hu > 0) {
+        const int gpr = d.c_out / 4;
+        const int64_t groups = m * gpr;
+        sc::v4i* gu = reinterpret_cast<sc::v4i*>(plan->ws + plan->off_gup);
+        hipLaunchKernelGGL(sc::upsample_rows_kernel<0>, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, stream,
+                           reinterpret_cast<const sc::v4i*>(gf), gu, groups, gpr, plan->ho * plan->wo, plan->wo, d.stride_h,
+                           d.stride_w, plan->hu, plan->wu);
+        hipError_t e2 = hipGetLastError();
+        if (e2 != hipSuccess) { sc::note_hip_error((int32_t)e2); return SC_ERR_HIP; }
+        src = gu;
+      }
+      return dense_conv_run(plan->inner, src, nullptr, dx_dev, hip_stream);
+    }
+    return SC_OK;
+  }
 
   // Which form of the filter-gradient kernel: the LDS-direct one wherever the tensors fit 32-bit buffer offsets and
   // the splits fit the workspace.  It gates dy itself and sums db on the way, so the g map is written only when the

@@ -153,7 +153,7 @@ def test_backward_follows_a_refreshed_mask_and_refreshed_filters():
 def test_layers_the_backward_kernels_do_not_cover_are_refused():
     L = B.lib()
     size = ctypes.c_size_t()
-    for kw in (dict(dtype=B.SC_F32), dict(c_in=20), dict(c_out=20), dict(layout=B.SC_NCHW), dict(groups=16)):
+    for kw in (dict(c_in=20), dict(c_out=20), dict(layout=B.SC_NCHW), dict(groups=16)):
         args = dict(n=1, c_in=16, h=8, w=8, c_out=16)
         args.update(kw)
         d = B.make_desc(**args)
@@ -162,3 +162,23 @@ def test_layers_the_backward_kernels_do_not_cover_are_refused():
     assert L.sparse_conv_backward_workspace_bytes(ctypes.byref(d), ctypes.byref(size)) == B.SC_OK and size.value > 0
     assert L.sparse_conv_backward_workspace_bytes(ctypes.byref(d), None) == B.SC_ERR_NULL
     assert L.sparse_conv_backward_run(None, None, None, None, None, None, None, None) == B.SC_ERR_NULL
+
+
+# float layers: operands and products round in float on the device; with n terms per element the error of a sum is
+# about sqrt(n) * 2^-24 of its terms' magnitudes (a few thousand terms here), inside the 1e-5 the float forward pass
+# is held to
+@pytest.mark.parametrize("shape", [
+    dict(n=2, c_in=16, hw=16, c_out=16),                         # the float layer of the smallest configuration, batch 2
+    dict(n=2, c_in=64, hw=14, c_out=64, sparsity=0.3),           # one tile of each operand, K = 576
+    dict(n=3, c_in=24, hw=9, c_out=40, relu=False),              # ragged tiles in both directions
+    dict(n=2, c_in=128, hw=10, c_out=72, k=1),                   # pointwise, two channel tiles
+    dict(n=2, c_in=32, hw=15, c_out=64, s=2),                    # strided: zero-interleaved g map for dx
+    dict(n=1, c_in=16, hw=20, c_out=32, d=2),                    # dilation 2
+    dict(n=2, c_in=32, hw=11, c_out=48, w=7, mask_mode="spatial"),
+    dict(n=4, c_in=32, hw=28, c_out=32, sparsity=0.5),           # several row splits
+    dict(n=2, c_in=16, hw=8, c_out=16, sparsity=1.0),            # nothing kept
+])
+def test_float_layers(shape, monkeypatch):
+    import sys
+    monkeypatch.setattr(sys.modules[__name__], "TOL_F32_SUMS", 1e-5)
+    run_backward(spec_of(dtype="f32", **shape), 871)
