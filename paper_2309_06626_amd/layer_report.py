@@ -271,8 +271,10 @@ def backward_times(steps):
     from paper_2309_06626_amd.metrics import algorithmic_flops, time_launches
 
     c3 = {s.name: s for s in W.conv_specs(W.config3())}
+    import dataclasses
     specs = [W.config2(0.5), W.config2(0.0), c3["l2b0_conv2"], c3["l3b0_conv2"], c3["l4b0_conv2"],
-             [s for s in W.config4() if s.name == "c4_pw_96_576_28"][0]]
+             [s for s in W.config4() if s.name == "c4_pw_96_576_28"][0],
+             dataclasses.replace(W.config2(0.5), name="c2_resnet18_layer1 (fp32)", dtype="f32")]
     rows = []
     warm = max(steps // 10, 5)
     for spec in specs:
