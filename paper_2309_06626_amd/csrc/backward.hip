@@ -894,15 +894,18 @@ static int wgrad_splits(int64_t rows, int c_out, int k) {
   return (int)std::max<int64_t>(want, 1);
 }
 
-// Row splits of wgrad2_kernel: one workgroup per compute unit (its LDS admits no second one), every split's row list
-// within kW2MostSplitRows, the partial sums within kWgradPartialBytes.  0 = the layer does not fit (the first form runs).
+// Row splits of wgrad2_kernel: one workgroup per compute unit for the 128-channel tile (its LDS admits no second one), two
+// for the 64-channel tile (ring of three stages, 80 KB: the kernel spends its time issuing instructions -- row decode, gate,
+// db sums -- with one wavefront per SIMD, and a second workgroup fills the gaps: benchmark layer 26.4 -> 22.8 us), every
+// split's row list within kW2MostSplitRows, the partial sums within kWgradPartialBytes.  0 = the layer does not fit (the
+// first form runs).
 constexpr int kW2Workgroups = 256;
 static int wgrad2_tile_m(int c_out) { return c_out <= 64 ? 64 : 128; }
 static int wgrad2_tile_n(int, bool) { return 256; }
 static int wgrad2_splits(int64_t rows, int c_out, int k, bool gate) {
   const int bm = wgrad2_tile_m(c_out), bn = wgrad2_tile_n(c_out, gate);
   const int64_t tiles = (int64_t)((c_out + bm - 1) / bm) * ((k + bn - 1) / bn);
-  int64_t want = std::max<int64_t>(kW2Workgroups / tiles, 1);
+  int64_t want = std::max<int64_t>((bm == 64 ? 2 : 1) * kW2Workgroups / tiles, 1);
   want = std::min<int64_t>(want, (rows + 4 * kW2Rows - 1) / (4 * kW2Rows));      // at least four stages per split
   want = std::max<int64_t>(want, (rows + kW2MostSplitRows - 1) / kW2MostSplitRows);
   want = std::max<int64_t>(want, 1);
@@ -1184,10 +1187,10 @@ sc_status sparse_conv_backward_run(const sc_bwd_plan* plan, const void* x_dev, c
     hipError_t e;
     const bool narrow = sc::wgrad2_tile_m(d.c_out) == 64;
     if (dt == sc::kBF16) {
-      if (narrow) e = gate ? sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 5, true>(p, stream) : sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 5, false>(p, stream);
+      if (narrow) e = gate ? sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 3, true>(p, stream) : sc::wgrad2_launch<sc::kBF16, 64, 256, 1, 4, 3, false>(p, stream);
       else e = gate ? sc::wgrad2_launch<sc::kBF16, 128, 256, 2, 2, 4, true>(p, stream) : sc::wgrad2_launch<sc::kBF16, 128, 256, 2, 2, 5, false>(p, stream);
     } else {
-      if (narrow) e = gate ? sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 5, true>(p, stream) : sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 5, false>(p, stream);
+      if (narrow) e = gate ? sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 3, true>(p, stream) : sc::wgrad2_launch<sc::kF16, 64, 256, 1, 4, 3, false>(p, stream);
       else e = gate ? sc::wgrad2_launch<sc::kF16, 128, 256, 2, 2, 4, true>(p, stream) : sc::wgrad2_launch<sc::kF16, 128, 256, 2, 2, 5, false>(p, stream);
     }
     if (e != hipSuccess) { sc::note_hip_error((int32_t)e); return SC_ERR_HIP; }

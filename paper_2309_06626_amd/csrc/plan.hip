@@ -1722,15 +1722,16 @@ sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* b
   if (result == SC_OK && plan->forced[0] == -1 && plan->forced[1] == -1 && plan->kept > 0 && plan->kept < plan->geo.m &&
       plan->masked_store != 1 && plan->geo.vec_gather && !plan->geo.rowseg && plan->desc.layout == SC_NHWC) {
     const double us_sparse = time_us(false, 40, 3), us_dense = time_us(true, 40, 3);
-    const BandPlan& bd = plan->band_dense;
-    const bool dense_is_tiled = !(bd.ok && !bd.stream && !plan->prefer_tiled[1]) && !use_panel(plan, 1, plan->geo.m);
-    if (us_sparse > 0.0 && us_dense > 0.0 && us_sparse > us_dense && dense_is_tiled) {
+    // (where the dense run takes a band or row-panel kernel, the tile is the one the dense run would take as a tiled launch)
+    if (us_sparse > 0.0 && us_dense > 0.0 && us_sparse > us_dense) {
       const sc_plan::Pick keep = plan->pick[0];
       const bool keep_tiled = plan->prefer_tiled[0];
+      const sc_plan::Slab keep_slab = plan->slab_auto[0];
       plan->pick[0] = {plan->pick[1].ti, 1, true};
       plan->prefer_tiled[0] = true;
+      plan->slab_auto[0] = sc_plan::Slab{0, 1};
       const double us = time_us(false, 40, 3);
-      if (!(us > 0.0 && us < us_sparse)) { plan->pick[0] = keep; plan->prefer_tiled[0] = keep_tiled; }
+      if (!(us > 0.0 && us < us_sparse)) { plan->pick[0] = keep; plan->prefer_tiled[0] = keep_tiled; plan->slab_auto[0] = keep_slab; }
     }
   }
   plan->tuned = result == SC_OK;

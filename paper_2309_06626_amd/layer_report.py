@@ -380,7 +380,7 @@ def main():
     ap.add_argument("--oracle-times", action="store_true",
                     help="also time the CPU oracle on every configuration (all host cores; one thread for configs 1 and 2)")
     ap.add_argument("--profile-layer", default="",
-                    help="NAME[:BMxBN][:splitN][:slabBM][:dense][:cold][:time] -- only launch that layer of config 2 (s = 0.5), 3, 4 or 5 --steps times "
+                    help="NAME[:BMxBN][:splitN][:slabBM][:dense][:cold][:time][:backward[:dx]] -- only launch that layer of config 2 (s = 0.5), 3, 4 or 5 --steps times "
                          "(sparse run, or the dense run), optionally with a forced tile of the tiled kernel, N splits of K, the slab kernel with BM-row tiles, "
                          "optionally rotating through buffer copies larger than the memory-side cache: the target of a rocprofv3 run")
     args = ap.parse_args()
@@ -417,6 +417,23 @@ def main():
                 B.sparse_conv_plan_set_tiles(layer.plan, 0, bm, bn)
                 B.sparse_conv_plan_set_tiles(layer.plan, 1, bm, bn)
         x, y = R.to_device(ci.x, spec.dtype), layer.new_output()
+        if "backward" in parts[1:]:                 # the backward pass of the layer: dw + db, with `dx` also the input gradient
+            bwd = B.sparse_conv_backward_plan(layer.plan, layer.w)
+            layer.sparse(x, y)
+            dy = torch.randn(spec.y_shape(), device="cuda:0").to(B.TORCH_DTYPE[spec.dtype])
+            dx = torch.empty_like(x) if "dx" in parts[1:] else None
+            dw = torch.empty(spec.w_shape(), dtype=torch.float32, device="cuda:0")
+            db = torch.empty(spec.c_out, dtype=torch.float32, device="cuda:0")
+            call = B.prepared_backward_run(bwd, x, y, dy, dx, dw, db)
+            for _ in range(args.steps):
+                call()
+            torch.cuda.synchronize()
+            print(f"{spec.name}: {args.steps} backward runs (dw, db{', dx' if dx is not None else ''}), kept {ci.keep} of {spec.m} rows, K {spec.k}, Cout {spec.c_out}")
+            if "time" in parts[1:]:
+                from paper_2309_06626_amd.metrics import time_launches
+                us = time_launches(call, max(args.steps, 100), 20, 5)[1] * 1e6
+                print(f"{spec.name}: {us:.2f} us per backward run (median of 5 replays of a graph of {max(args.steps, 100)} runs)")
+            return
         if "cold" in parts[1:]:                     # rotate through copies beyond the memory-side cache
             nsets = buffer_sets_for_cold_runs(x.numel() * x.element_size() + y.numel() * y.element_size())
             calls = [B.prepared_run(layer.plan, x.clone(), layer.bias, torch.empty_like(y), dense=dense) for _ in range(nsets)]
