@@ -412,7 +412,7 @@ def main():
                 B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SPLIT_K, int(part[5:]))
             elif part.startswith("slab"):
                 B.sparse_conv_plan_set_option(layer.plan, B.SC_OPT_SLAB, int(part[4:]))
-            elif "x" in part:
+            elif part.replace("x", "").isdigit() and part.count("x") == 1:
                 bm, bn = (int(v) for v in part.split("x"))
                 B.sparse_conv_plan_set_tiles(layer.plan, 0, bm, bn)
                 B.sparse_conv_plan_set_tiles(layer.plan, 1, bm, bn)

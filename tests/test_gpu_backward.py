@@ -182,3 +182,47 @@ def test_float_layers(shape, monkeypatch):
     import sys
     monkeypatch.setattr(sys.modules[__name__], "TOL_F32_SUMS", 1e-5)
     run_backward(spec_of(dtype="f32", **shape), 871)
+
+
+def test_float_training_steps_follow_the_oracles_steps():
+    """Alg. 1 main loop on a float layer, three steps on both sides: getMask draws the step's mask from a fresh score,
+    maskedForward, a squared-error loss against a fixed target (dy = y - target), backward, a plain gradient step on the
+    filters and the bias.  Each side feeds on its own previous weights; after three steps they still agree."""
+    from oracle import mask_oracle as MO
+    spec = W.ConvSpec("train32", n=2, c_in=16, h=16, w=16, c_out=16, dtype="f32", sparsity=0.5, mask_mode="spatial")
+    ci = W.make_conv_inputs(spec, 881)
+    rng = np.random.default_rng(883)
+    target = rng.standard_normal(spec.y_shape()).astype(np.float32)
+    lr = np.float32(1e-3)
+    w_ref, b_ref = ci.w.astype(np.float64), ci.bias.astype(np.float64)
+    w_dev, b_dev = torch.from_numpy(ci.w).to("cuda:0"), torch.from_numpy(ci.bias).to("cuda:0")
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    bwd = B.sparse_conv_backward_plan(layer.plan, w_dev)
+    x_d, t_d = torch.from_numpy(ci.x).to("cuda:0"), torch.from_numpy(target).to("cuda:0")
+    dw_d = torch.empty(spec.w_shape(), dtype=torch.float32, device="cuda:0")
+    db_d = torch.empty(spec.c_out, dtype=torch.float32, device="cuda:0")
+    for step in range(3):
+        score = W.gen_score(64, 64, seed=890 + step)
+        mask_d = B.sparse_mask_generate(torch.from_numpy(score).to("cuda:0"), spec.ho, spec.wo, spec.sparsity)
+        mask = MO.layer_mask(score, spec.ho, spec.wo, np.float32(spec.sparsity)).reshape(-1)
+        assert np.array_equal(mask_d.cpu().numpy().reshape(-1), mask)
+        # device side
+        B.sparse_conv_plan_set_mask(layer.plan, mask_d)
+        B.sparse_conv_plan_set_filters(layer.plan, w_dev)
+        B.sparse_conv_backward_set_filters(bwd, w_dev)
+        y_d = B.sparse_conv_run(layer.plan, x_d, b_dev, layer.new_output())
+        dy_d = y_d - t_d
+        B.sparse_conv_backward_run(bwd, x_d, y_d, dy_d, None, dw_d, db_d)
+        w_dev = w_dev - lr * dw_d
+        b_dev = b_dev - lr * db_d
+        # oracle side (float weights as a float training loop holds them, sums in double)
+        w32, b32 = w_ref.astype(np.float32), b_ref.astype(np.float32)
+        y = oracle.round_storage(oracle.masked_conv2d(spec, ci.x, w32, b32, mask), "f32")
+        _, dw, db = oracle.masked_conv2d_backward(spec, ci.x, w32, y, (y - target).astype(np.float32), mask)
+        w_ref = (w32 - lr * dw.astype(np.float32)).astype(np.float64)
+        b_ref = (b32 - lr * db.astype(np.float32)).astype(np.float64)
+    torch.cuda.synchronize()
+    scale = np.abs(w_ref).max()
+    assert np.abs(w_dev.cpu().numpy() - w_ref).max() <= 1e-5 * scale
+    assert np.abs(b_dev.cpu().numpy() - b_ref).max() <= 1e-5 * max(np.abs(b_ref).max(), 1.0)
+    assert np.abs(w_ref - ci.w).max() > 1e-4 * scale          # the steps really moved the weights
