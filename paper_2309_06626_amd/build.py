@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsparse_conv.so")
-SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "bandtap.hip", "igemm_panel.hip", "igemm_buf.hip", "igemm_slab.hip", "igemm_streamk.hip", "igemm_rowseg.hip", "mask_gen.hip", "depthwise.hip", "backward.hip", "probes.hip"]
+SOURCES = ["plan.hip", "igemm_bf16.hip", "igemm_f16.hip", "igemm_f32.hip", "bandpp.hip", "bandtap.hip", "bandrow.hip", "igemm_panel.hip", "igemm_buf.hip", "igemm_slab.hip", "igemm_streamk.hip", "igemm_rowseg.hip", "mask_gen.hip", "depthwise.hip", "backward.hip", "probes.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-value",

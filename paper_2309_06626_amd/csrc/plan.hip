@@ -13,6 +13,7 @@
 
 #include "band_kernel.hpp"
 #include "bandpp_kernel.hpp"
+#include "bandrow_kernel.hpp"
 #include "bandstream_kernel.hpp"
 #include "bandtap_kernel.hpp"
 #include "conv_params.hpp"
@@ -500,6 +501,8 @@ struct BandPlan {
   int bh, bands_per_image, n_bands, n_tiles, ni_idx, ni;
   int split;         // alternating-group kernel only: every run of bh rows is two bands of half its pixels
   size_t b_bytes, x_bytes, lds;
+  bool rowband;      // small-channel layers: window rows read from a zero-margined slab (row-segment K order)
+  int rb_pitch, rb_left, rb_in_rows, rb_gpw, rb_tail;
 };
 
 constexpr size_t kLdsLimit = 160 * 1024;
@@ -518,12 +521,57 @@ static double band_units(double cnt, int* mi_idx) {
 static bool tap_is_automatic(const sc_conv_desc& d, const Geometry& g, const BandPlan& tp, int64_t rows);
 static int device_cus();
 
+// Band kernel of the small-channel layers (row-segment K order): window starts must be 4-byte aligned in the slab, K
+// at most 24 groups of 16 bytes, 64 output channels per workgroup, bands of at most 512 output pixels.  The tallest
+// such band that still leaves four workgroups per compute unit.
+static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
+  BandPlan bp;
+  std::memset(&bp, 0, sizeof(bp));
+  const int eb = elem_bytes(d.dtype);
+  const char* variant = std::getenv("SPARSE_CONV_BAND_KERNEL");
+  if (variant && std::strcmp(variant, "none") == 0) return bp;
+  if (eb != 2 || !g.vec_out || d.dil_w != 1 || (d.stride_w * d.c_in * eb) % 4 != 0) return bp;
+  const int gpw = g.epad / 8;
+  if (d.kh * gpw > kRowBandMostGroups || (int64_t)d.kh * g.epad > g.k_stride) return bp;
+  if (g.wo > kRowBandMaxRows) return bp;
+  const int64_t reach = (int64_t)(g.wo - 1) * d.stride_w * d.c_in * eb + (int64_t)gpw * 16;   // end of the last window row
+  const int64_t pitch = (int64_t)align_up((size_t)std::max<int64_t>((int64_t)(d.pad_w + d.w) * d.c_in * eb, reach), 16);
+  const char* env = std::getenv("SPARSE_CONV_BAND_HEIGHT");
+  const int forced_bh = env ? std::atoi(env) : 0;
+  auto fits = [&](int bh) {
+    const int64_t in_rows = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
+    return (int64_t)bh * g.wo <= kRowBandMaxRows && kRowBandSlabAt + in_rows * pitch <= (int64_t)kLdsLimit;
+  };
+  if (!fits(1)) return bp;
+  int bh = 1;
+  while (bh < g.ho && fits(bh + 1)) ++bh;
+  const int n_tiles = (d.c_out + 63) / 64;
+  while (bh > 1 && (int64_t)d.n * ((g.ho + bh - 1) / bh) * n_tiles < 4 * (int64_t)device_cus()) bh = (bh + 1) / 2;
+  if (forced_bh > 0) { if (!fits(forced_bh)) return bp; bh = forced_bh; }
+  bp.ok = bp.rowband = true;
+  bp.ni = 2; bp.ni_idx = 1;
+  bp.n_tiles = n_tiles;
+  bp.bh = bh;
+  bp.bands_per_image = (g.ho + bh - 1) / bh;
+  bp.n_bands = d.n * bp.bands_per_image;
+  bp.rb_pitch = (int)pitch;
+  bp.rb_left = d.pad_w;
+  bp.rb_in_rows = (bh - 1) * d.stride_h + (d.kh - 1) * d.dil_h + 1;
+  bp.rb_gpw = gpw;
+  bp.rb_tail = d.kw * d.c_in - (gpw - 1) * 8;
+  bp.b_bytes = kRowBandFilterBytes;
+  bp.x_bytes = (size_t)bp.rb_in_rows * pitch;
+  bp.lds = kRowBandSlabAt + bp.x_bytes;
+  return bp;
+}
+
 // `rows`: the rows the run is expected to contract (the kept rows of a sparse run, M of a dense one).
 static BandPlan plan_band(const sc_conv_desc& d, const Geometry& g, int64_t rows) {
   BandPlan bp;
   std::memset(&bp, 0, sizeof(bp));
   const int eb = elem_bytes(d.dtype);
   if (g.depthwise) return bp;
+  if (g.rowseg) return plan_rowband(d, g);
   if (d.layout != SC_NHWC || !g.vec_gather || !g.vec_out) return bp;
   if ((d.c_in / g.vec) % 2 != 0) return bp;      // a K step of two 16-byte groups must stay inside one tap
   if (d.kh * d.kw == 1) return bp;               // no window overlap to exploit: gather kept rows directly
@@ -1106,6 +1154,19 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
 #ifdef SC_TIMING
     q.dbg = g_dbg;
 #endif
+    if (b.rowband) {
+      RowBandParams rq;
+      rq.b = q;
+      rq.pitch = b.rb_pitch; rq.left = b.rb_left; rq.in_rows = b.rb_in_rows;
+      rq.gpw = b.rb_gpw; rq.groups = d.kh * b.rb_gpw; rq.tail = b.rb_tail;
+      magic_div((uint32_t)(b.rb_pitch / 16), &rq.div_cpr_mul, &rq.div_cpr_shift);
+      int mi_idx = 0;
+      band_units(dense || identity ? (double)(std::min(b.bh, g.ho) * g.wo) : (double)b.max_kept, &mi_idx);
+      RowBandLaunchFn fn = bandrow_kernel_for(d.dtype == SC_BF16 ? kBF16 : kF16, mi_idx + 1);
+      if (!fn) return SC_ERR_UNSUPPORTED;
+      SC_HIP(fn(rq, b.lds, stream));
+      return SC_OK;
+    }
     if (b.stream) {
       // every kept row of a band sits in accumulators: 128 rows per MI step
       const int most = dense ? b.bh * g.wo : b.max_kept;
@@ -1663,7 +1724,15 @@ sc_status sparse_conv_plan_tune(sc_plan* plan, const void* x_dev, const float* b
     bool best_tiled = false;
     double best_us = time_us(dense, 40, 3);
     if (best_us < 0.0) { result = SC_ERR_HIP; break; }
-    if (!plan->geo.vec_gather || plan->geo.rowseg) continue;           // one tile shape serves these gathers
+    if (!plan->geo.vec_gather || plan->geo.rowseg) {                   // one tile shape serves these gathers
+      const BandPlan& rb = dense ? plan->band_dense : plan->band;
+      if (rb.ok && rb.rowband) {                                       // band kernel of the small-channel layers or that tile
+        plan->prefer_tiled[which] = true;
+        const double us = time_us(dense, 40, 3);
+        if (!(us > 0.0 && us < 0.985 * best_us)) plan->prefer_tiled[which] = false;
+      }
+      continue;
+    }
     // candidates: every tile x split (and the masked-store variant) the model prices within 1.6 x of its best
     struct Cand { sc_plan::Pick pick; double predicted; };
     Cand cands[128];
@@ -1823,7 +1892,7 @@ const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which) {
   const BandPlan& band = which ? plan->band_dense : plan->band;
   if (band.ok && (plan->forced[which] == kForceBand || (plan->forced[which] == -1 && !band.stream && !plan->prefer_tiled[which])) &&
       !(plan->slab >= 2 && slab_pick(plan, which, which ? plan->geo.m : plan->kept).bm))
-    return band.stream ? "band_stream" : band.tap ? "band_tap" : band.pp ? "band_alternating" : "band";
+    return band.rowband ? "band_row_segments" : band.stream ? "band_stream" : band.tap ? "band_tap" : band.pp ? "band_alternating" : "band";
   const Geometry& g = plan->geo;
   if (slab_pick(plan, which, which ? g.m : plan->kept).bm) return "tile_slab";
   if (use_panel(plan, which, which ? g.m : plan->kept)) return "tile_row_panel";

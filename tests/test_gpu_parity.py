@@ -429,9 +429,12 @@ ROWSEG_CASES = [
 def test_row_segment_gather(case, mask_mode, dtype):
     spec = spec_of(dtype=dtype, mask_mode=mask_mode, **ROWSEG_CASES[case])
     layer = check_layer(W.make_conv_inputs(spec, 1020 + case))
-    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_segments"
+    # (window starts on 4-byte boundaries and 16-channel output groups: the band kernel of these layers serves the
+    # automatic launch)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == ("band_row_segments" if case in (0, 1, 5) else "tile_row_segments")
     for tile in ((64, 64), (128, 32)):
-        check_layer(W.make_conv_inputs(spec, 1020 + case), tiles=tile)
+        layer = check_layer(W.make_conv_inputs(spec, 1020 + case), tiles=tile)
+        assert B.sparse_conv_plan_kernel(layer.plan, 0) == "tile_row_segments"
 
 
 def test_row_segment_gather_ignores_non_finite_neighbours():
