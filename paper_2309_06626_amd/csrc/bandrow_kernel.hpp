@@ -50,7 +50,8 @@ __device__ __forceinline__ v4i lds_load_4dwords(unsigned addr) {
   return v4i{q[0], q[1], q[2], q[3]};
 }
 
-template <int DT, int MI>
+// KH, GPW > 0 fix the window rows and the groups per window row at compile time (the K loop unrolls); 0 = run-time shape.
+template <int DT, int MI, int KH, int GPW>
 __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParams q) {
   using E = Elem<DT>;
   using T = typename E::T;
@@ -60,13 +61,17 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
   constexpr int RPI = kThreads / CPR;   // output rows covered by one zero-fill pass of the workgroup
   constexpr int ZIT = kRowBandMaxRows / RPI;
   constexpr int RB = kRowBandMaxRows / (4 * 32 * MI);     // block groups per wavefront that cover the tallest band
+  constexpr int STEPS = (KH * GPW + 1) / 2;
   static_assert(EB == 2, "16-bit operands");
+  static_assert((KH > 0) == (GPW > 0), "both or neither");
   const BandParams& p = q.b;
+  const int gpw = GPW ? GPW : q.gpw, groups = KH ? KH * GPW : q.groups;
 
   extern __shared__ __align__(16) unsigned char smem[];
   const unsigned lds0 = lds_addr_of(smem);
   float* s_bias = reinterpret_cast<float*>(smem + kRowBandBiasAt);
 
+  SC_STAMP(0);
   const int nwg = p.n_bands * p.n_tiles;
   const int per_xcd = (nwg + 7) >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -121,12 +126,12 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
     for (int u = 0; u < kRowBandMostGroups / 4; ++u) {
       const int g = (t & 3) + 4 * u;
       wv[u] = v4i{0, 0, 0, 0};
-      if (g < q.groups) wv[u] = gw[g];
+      if (g < groups) wv[u] = gw[g];
     }
   }
   // slab: 16-byte pieces of LDS, piece i = (slab row i / cpr, piece i % cpr of the row); a piece inside the input row
-  // is one 16-byte load at a 2-byte aligned address, a piece across an end of the row is put together from halfwords,
-  // the others (margins, rows above and below the image) are zeros
+  // is one 16-byte load at a 2-byte aligned address, a piece across an end of the row is put together from halfwords
+  // (by the thread that owns that end of that row), the others (margins, rows above and below the image) are zeros
   {
     constexpr int U = 6;
     const int row_bytes = p.w * p.c_in * EB;                  // an input row in global memory
@@ -135,79 +140,89 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
     const int in_rows = min(q.in_rows, (oy1 - 1 - oy0) * p.sh + (p.kh - 1) * p.dil_h + 1);
     const int pieces = in_rows * cpr;
     const unsigned char* ximg = reinterpret_cast<const unsigned char*>(x) + (int64_t)img * p.h * row_bytes;
+    const int e0 = (lead & 15) ? lead >> 4 : -1, e1 = ((lead + row_bytes) & 15) ? (lead + row_bytes) >> 4 : -1;
+    // end piece e = (row e / 2, front or back end): its eight halfwords, those outside the row zero
+    auto end_piece = [&](int e, v4i* v) -> int {
+      const int r = e >> 1, c = (e & 1) ? e1 : e0;
+      const int iy = iy_base + r;
+      if (e >= 2 * in_rows || c < 0 || (unsigned)iy >= (unsigned)p.h) return -1;
+      const unsigned char* src = ximg + (int64_t)iy * row_bytes;
+      const int at = 16 * c - lead;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        unsigned short lo = 0, hi = 0;
+        if (at + 4 * k >= 0 && at + 4 * k < row_bytes) lo = *reinterpret_cast<const unsigned short*>(src + at + 4 * k);
+        if (at + 4 * k + 2 >= 0 && at + 4 * k + 2 < row_bytes) hi = *reinterpret_cast<const unsigned short*>(src + at + 4 * k + 2);
+        (*v)[k] = (int)((unsigned)lo | ((unsigned)hi << 16));
+      }
+      return r * cpr + c;
+    };
     for (int base = 0; base < pieces; base += kThreads * U) {
-      v4i v[U];
+      v4i v[U], ev;
+      bool whole[U];
+      int end_at = -1;
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = base + u * kThreads + t;
         const int r = fast_div(i, q.div_cpr_mul, q.div_cpr_shift);
-        const int at = 16 * (i - r * cpr) - lead;             // byte of the input row the piece starts at
+        const int c = i - r * cpr;
+        const int at = 16 * c - lead;                         // byte of the input row the piece starts at
         const int iy = iy_base + r;
-        const bool row_ok = i < pieces && (unsigned)iy < (unsigned)p.h;
+        const bool row_ok = (unsigned)iy < (unsigned)p.h;
         const unsigned char* src = ximg + (int64_t)(row_ok ? iy : 0) * row_bytes;
         v[u] = v4i{0, 0, 0, 0};
-        if (row_ok && at >= 0 && at + 16 <= row_bytes) __builtin_memcpy(&v[u], reinterpret_cast<const unsigned short*>(src + at), 16);
+        whole[u] = i < pieces && !(row_ok && (c == e0 || c == e1));      // (end pieces belong to end_piece)
+        if (i < pieces && row_ok && at >= 0 && at + 16 <= row_bytes) __builtin_memcpy(&v[u], reinterpret_cast<const unsigned short*>(src + at), 16);
       }
+      if (base == 0) end_at = end_piece(t, &ev);
       if (base == 0) {
+        // zero fill of the band's dropped rows (Alg. 2, mask == 0 branch): issued behind the loads, drains under the
+        // matrix work
+        if (p.zero_fill) {
+          const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
+          const v4i z = {0, 0, 0, 0};
+          unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
+          if (zc < valid) {
+#pragma unroll
+            for (int u = 0; u < ZIT; ++u) {
+              const int r = r_lo + zr + u * RPI;
+              if (r < r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
+            }
+          }
+        }
 #pragma unroll
         for (int u = 0; u < kRowBandMostGroups / 4; ++u) {
           const int g = (t & 3) + 4 * u;
-          if (g < q.groups) *reinterpret_cast<v4i*>(smem + (t >> 2) * kRowBandFilterPitch + g * 16) = wv[u];
+          if (g < groups) *reinterpret_cast<v4i*>(smem + (t >> 2) * kRowBandFilterPitch + g * 16) = wv[u];
         }
+        if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = base + u * kThreads + t;
-        if (i < pieces) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + i * 16) = v[u];
+        if (whole[u]) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + i * 16) = v[u];
       }
     }
-    // the pieces across the two ends of an input row (written as zeros above; other threads' writes: after a barrier)
-    const int e0 = (lead & 15) ? lead >> 4 : -1, e1 = ((lead + row_bytes) & 15) ? (lead + row_bytes) >> 4 : -1;
-    if (e0 >= 0 || e1 >= 0) {
-      __syncthreads();
-      for (int e = t; e < 2 * in_rows; e += kThreads) {
-        const int r = e >> 1, c = (e & 1) ? e1 : e0;
-        const int iy = iy_base + r;
-        if (c < 0 || (unsigned)iy >= (unsigned)p.h) continue;
-        const unsigned char* src = ximg + (int64_t)iy * row_bytes;
-        const int at = 16 * c - lead;
-        v4i v;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          unsigned short lo = 0, hi = 0;
-          if (at + 4 * k >= 0 && at + 4 * k < row_bytes) lo = *reinterpret_cast<const unsigned short*>(src + at + 4 * k);
-          if (at + 4 * k + 2 >= 0 && at + 4 * k + 2 < row_bytes) hi = *reinterpret_cast<const unsigned short*>(src + at + 4 * k + 2);
-          v[k] = (int)((unsigned)lo | ((unsigned)hi << 16));
-        }
-        *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + (r * cpr + c) * 16) = v;
-      }
+    for (int e = t + kThreads; e < 2 * in_rows; e += kThreads) {       // (slabs of more than 128 rows)
+      v4i ev;
+      const int end_at = end_piece(e, &ev);
+      if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
     }
     if (t < 16) *reinterpret_cast<v4i*>(smem + kRowBandZeroAt + t * 16) = v4i{0, 0, 0, 0};
     if (t < BN) s_bias[t] = bias_v;
   }
+  SC_STAMP(1);
   __syncthreads();   // filters, bias, zeros and the slab are in place
+  SC_STAMP(2);
 
-  // ---- zero fill of the band's dropped rows (Alg. 2, mask == 0 branch): issued now, drains under the matrix work -----
-  if (p.zero_fill) {
-    const int valid = (min(BN, p.c_out - n0) * EB) >> 4;
-    const v4i z = {0, 0, 0, 0};
-    unsigned char* ybase = reinterpret_cast<unsigned char*>(y) + (int64_t)n0 * EB + zc * 16;
-    if (zc < valid) {
-#pragma unroll
-      for (int u = 0; u < ZIT; ++u) {
-        const int r = r_lo + zr + u * RPI;
-        if (r < r_hi && mk[u] == 0) sc_store16(reinterpret_cast<v4i*>(ybase + (int64_t)r * p.c_out * EB), z);
-      }
-    }
-  }
-
+  SC_STAMP(3);
   // which entries of a window row's last group lie inside the window: dword i holds entries 2i, 2i + 1
   v4i tail_mask;
 #pragma unroll
   for (int i = 0; i < 4; ++i) tail_mask[i] = q.tail >= 2 * i + 2 ? -1 : q.tail == 2 * i + 1 ? 0xffff : 0;
   const unsigned zaddr = lds0 + kRowBandZeroAt;
   const unsigned slab = lds0 + kRowBandSlabAt;
-  const int steps = (q.groups + 1) >> 1;
+  const int steps = (groups + 1) >> 1;
   const int ky_pitch = p.dil_h * q.pitch;     // bytes between window rows in the slab
   const int nblk = (cnt + 32 * MI - 1) / (32 * MI);
 #pragma unroll
@@ -234,33 +249,58 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
+    if (bi == 0) SC_STAMP(5);
 
-    // K steps of two groups: this lane's group g = 2 * step + fh lies in window row g / gpw, at 16 * (g % gpw) bytes
+    // K steps of two groups: this lane's group g = 2 * step + fh lies in window row g / gpw, at 16 * (g % gpw) bytes.
+    // The fragments of step st + 1 are read while the MFMAs of step st run.
     int ky = 0, part = fh;
-    if (part >= q.gpw) { part -= q.gpw; ky = 1; }
-    for (int st = 0; st < steps; ++st) {
+    if (part >= gpw) { part -= gpw; ky = 1; }
+    auto read_step = [&](int st, v4i (&xf)[MI], v4i (&wf)[NI], bool& last) {
       const int g = 2 * st + fh;
-      const bool g_ok = g < q.groups;
+      const bool g_ok = g < groups;
+      if constexpr (GPW > 0) { ky = g / GPW; part = g - ky * GPW; }
       const unsigned off = (unsigned)(ky * ky_pitch + part * 16);
-      const bool last = part == q.gpw - 1;
-      v4i xf[MI], wf[NI];
+      last = part == gpw - 1;
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) xf[mi] = lds_load_4dwords(g_ok ? a_base[mi] + off : zaddr);
       const unsigned wat = lds0 + (unsigned)(fp * kRowBandFilterPitch + g * 16);   // (groups beyond K: zeros for both operands)
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni) wf[ni] = lds_load16(g_ok ? wat + ni * 32 * kRowBandFilterPitch : zaddr);
-      part += 2;   // next step's window row and group
-      while (part >= q.gpw) { part -= q.gpw; ++ky; }
-      if (last) {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) xf[mi] &= tail_mask;
+      if constexpr (GPW == 0) {          // next step's window row and group (gpw >= 1: at most two rows further)
+        part += 2;
+        if (part >= gpw) { part -= gpw; ++ky; }
+        if (part >= gpw) { part -= gpw; ++ky; }
       }
+    };
+    auto mma_step = [&](v4i (&xf)[MI], v4i (&wf)[NI], bool last) {
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) xf[mi] = last ? xf[mi] & tail_mask : xf[mi];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) E::mma(acc[mi][ni], wf[ni], xf[mi]);
+    };
+    v4i xa[MI], wa[NI], xb[MI], wb[NI];
+    bool la = false, lb = false;
+    read_step(0, xa, wa, la);
+    if constexpr (KH > 0) {
+#pragma unroll
+      for (int st = 0; st < STEPS; st += 2) {
+        if (st + 1 < STEPS) read_step(st + 1, xb, wb, lb);
+        mma_step(xa, wa, la);
+        if (st + 2 < STEPS) read_step(st + 2, xa, wa, la);
+        if (st + 1 < STEPS) mma_step(xb, wb, lb);
+      }
+    } else {
+      for (int st = 0; st < steps; st += 2) {
+        if (st + 1 < steps) read_step(st + 1, xb, wb, lb);
+        mma_step(xa, wa, la);
+        if (st + 2 < steps) read_step(st + 2, xa, wa, la);
+        if (st + 1 < steps) mma_step(xb, wb, lb);
+      }
     }
 
+    SC_STAMP(6);
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
       if (rr[mi] < 0) continue;
@@ -273,11 +313,15 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
       }
     }
   }
+  SC_STAMP(4);
+#ifdef SC_TIMING
+  if (p.dbg && threadIdx.x == 0) p.dbg[(size_t)blockIdx.x * 8 + 7] = wall_clock64();
+#endif
 }
 
-template <int DT, int MI>
+template <int DT, int MI, int KH, int GPW>
 hipError_t bandrow_launch(const RowBandParams& q, size_t lds, hipStream_t stream) {
-  auto kern = bandrow_kernel<DT, MI>;
+  auto kern = bandrow_kernel<DT, MI, KH, GPW>;
   static std::atomic<size_t> attr_bytes{0};   // (plans may be run from several host threads)
   if (lds > 64 * 1024 && lds > attr_bytes) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -291,7 +335,7 @@ hipError_t bandrow_launch(const RowBandParams& q, size_t lds, hipStream_t stream
 }
 
 using RowBandLaunchFn = hipError_t (*)(const RowBandParams&, size_t, hipStream_t);
-// the kernel for blocks of 32 * mi rows (mi = 1, 2) of a 16-bit dtype, or null
-RowBandLaunchFn bandrow_kernel_for(int dtype, int mi);
+// the kernel for blocks of 32 * mi rows (mi = 1, 2) of a 16-bit dtype and a window of kh rows of gpw groups, or null
+RowBandLaunchFn bandrow_kernel_for(int dtype, int mi, int kh, int gpw);
 
 }  // namespace sc

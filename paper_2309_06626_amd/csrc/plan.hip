@@ -1162,7 +1162,7 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
       magic_div((uint32_t)(b.rb_pitch / 16), &rq.div_cpr_mul, &rq.div_cpr_shift);
       int mi_idx = 0;
       band_units(dense || identity ? (double)(std::min(b.bh, g.ho) * g.wo) : (double)b.max_kept, &mi_idx);
-      RowBandLaunchFn fn = bandrow_kernel_for(d.dtype == SC_BF16 ? kBF16 : kF16, mi_idx + 1);
+      RowBandLaunchFn fn = bandrow_kernel_for(d.dtype == SC_BF16 ? kBF16 : kF16, mi_idx + 1, d.kh, b.rb_gpw);
       if (!fn) return SC_ERR_UNSUPPORTED;
       SC_HIP(fn(rq, b.lds, stream));
       return SC_OK;
