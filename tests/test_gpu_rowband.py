@@ -108,3 +108,39 @@ def test_tuned_plan_keeps_the_faster_kernel():
         sel = np.ones_like(kept) if dense else kept
         assert_close(rows_view(spec, R.to_host_f32(out))[rows][sel], ref[sel], absum[sel], TOL[spec.dtype], f"tuned, dense={dense}")
         assert B.sparse_conv_plan_kernel(layer.plan, int(dense)) in ("band_row_segments", "tile_row_segments")
+
+
+@pytest.mark.parametrize("seed", [11, 23])
+def test_random_small_channel_layers(seed):
+    """Seeded random window shapes, strides, paddings, dilations, channel counts and band heights of the layers this kernel takes."""
+    import os
+    import random
+    rnd = random.Random(seed)
+    done = 0
+    while done < 30:
+        cin = rnd.choice([1, 2, 3, 3, 4, 6])
+        kh, kw = rnd.randint(1, 8), rnd.randint(1, 7)
+        sw = rnd.choice([1, 2, 2, 4]) if cin % 2 else rnd.choice([1, 1, 2, 3])
+        sh = rnd.choice([1, 2, 2, 3])
+        dh = rnd.choice([1, 1, 2])
+        gpw = (kw * cin + 7) // 8
+        w = rnd.randint(max(kw, 4), 70)
+        if (sw * cin) % 2 or kh * kw == 1 or kh * gpw > 24 or (w * cin) % 8:
+            continue
+        ph, pw = rnd.randint(0, (kh - 1) * dh), rnd.randint(0, kw - 1)
+        h = rnd.randint(max((kh - 1) * dh + 1 - 2 * ph, 3), 40)
+        cout = 16 * rnd.randint(1, 9)
+        spec = spec_of(rnd.randint(1, 4), cin, h, w, cout, k=kh, kw=kw, s=sh, sw=sw, p=ph, pw=pw, d=dh, dw=1,
+                       dtype=rnd.choice(["bf16", "f16"]), sp=rnd.choice([0.0, 0.3, 0.5, 0.8, 0.97]),
+                       mask_mode=rnd.choice(["row", "spatial"]), relu=rnd.choice([True, False]), bias=rnd.choice([True, False]))
+        bh = rnd.choice([0, 0, 1, 2, 3])
+        if bh and bh * spec.wo <= 512:
+            os.environ["SPARSE_CONV_BAND_HEIGHT"] = str(bh)
+        print(f"seed {seed} case {done}: {spec} band height {bh}", flush=True)
+        try:
+            layer = check_layer(W.make_conv_inputs(spec, 1500 + 100 * seed + done),
+                                out_mode=rnd.choice([B.SC_OUT_ZERO_FILL, B.SC_OUT_ZERO_FILL, B.SC_OUT_SCATTER_ONLY]))
+        finally:
+            os.environ.pop("SPARSE_CONV_BAND_HEIGHT", None)
+        assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_row_segments"
+        done += 1
