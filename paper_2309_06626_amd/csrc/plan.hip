@@ -323,6 +323,44 @@ __global__ void maxpool_nhwc_vec8_kernel(const T* __restrict__ x, T* __restrict_
   *reinterpret_cast<vec8*>(y + pos * c + g * 8) = o;
 }
 
+// The same for the 3x3 window: the nine loads are unconditional (clamped coordinates; a padded tap is replaced by
+// minus infinity afterwards), so they are all in flight at once.
+template <typename T>
+__global__ void maxpool3_nhwc_vec8_kernel(const T* __restrict__ x, T* __restrict__ y, int n, int h, int w, int c, int s,
+                                          int p, int ho, int wo, uint32_t cg_mul, uint32_t cg_shift, uint32_t wo_mul,
+                                          uint32_t wo_shift, uint32_t ho_mul, uint32_t ho_shift) {
+  typedef T vec8 __attribute__((ext_vector_type(8)));
+  const int cg = c >> 3;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;          // (the launcher keeps n * ho * wo * cg below 2^31)
+  if (idx >= n * ho * wo * cg) return;
+  const int pos = fast_div(idx, cg_mul, cg_shift), g = idx - pos * cg;
+  const int row = fast_div(pos, wo_mul, wo_shift), ox = pos - row * wo;
+  const int b = fast_div(row, ho_mul, ho_shift), oy = row - b * ho;
+  const int iy0 = oy * s - p, ix0 = ox * s - p;
+  vec8 v[9];
+  bool ok[9];
+#pragma unroll
+  for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) {
+      const int iy = iy0 + ky, ix = ix0 + kx;
+      ok[ky * 3 + kx] = (unsigned)iy < (unsigned)h && (unsigned)ix < (unsigned)w;
+      const int cy = min(max(iy, 0), h - 1), cx = min(max(ix, 0), w - 1);
+      v[ky * 3 + kx] = *reinterpret_cast<const vec8*>(x + (((int64_t)b * h + cy) * w + cx) * c + g * 8);
+    }
+  float best[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], ok[tap] ? (float)v[tap][e] : -INFINITY);
+  vec8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (T)best[e];
+  *reinterpret_cast<vec8*>(y + (int64_t)pos * c + g * 8) = o;
+}
+
 template <typename T, bool RELU>
 __global__ void add_vec8_kernel(const T* a, const T* b, T* y, int64_t groups) {   // y may alias a or b
   typedef T vec8 __attribute__((ext_vector_type(8)));
@@ -1970,7 +2008,19 @@ sc_status sc_maxpool2d_nhwc(const void* x_dev, void* y_dev, int32_t dtype, int32
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
   const bool vec8 = dtype != SC_F32 && c % 8 == 0 && (((uintptr_t)x_dev | (uintptr_t)y_dev) & 15) == 0;
-  if (vec8) {
+  if (vec8 && k == 3 && total / 8 < ((int64_t)1 << 31)) {
+    dim3 vgrid((unsigned)((total / 8 + 255) / 256));
+    uint32_t cm, cs, wm, ws_, hm, hs;
+    sc::magic_div((uint32_t)(c / 8), &cm, &cs);
+    sc::magic_div((uint32_t)wo, &wm, &ws_);
+    sc::magic_div((uint32_t)ho, &hm, &hs);
+    if (dtype == SC_F16)
+      hipLaunchKernelGGL(maxpool3_nhwc_vec8_kernel<_Float16>, vgrid, block, 0, stream, (const _Float16*)x_dev,
+                         (_Float16*)y_dev, n, h, w, c, s, p, ho, wo, cm, cs, wm, ws_, hm, hs);
+    else
+      hipLaunchKernelGGL(maxpool3_nhwc_vec8_kernel<__bf16>, vgrid, block, 0, stream, (const __bf16*)x_dev,
+                         (__bf16*)y_dev, n, h, w, c, s, p, ho, wo, cm, cs, wm, ws_, hm, hs);
+  } else if (vec8) {
     dim3 vgrid((unsigned)((total / 8 + 255) / 256));
     if (dtype == SC_F16)
       hipLaunchKernelGGL(maxpool_nhwc_vec8_kernel<_Float16>, vgrid, block, 0, stream, (const _Float16*)x_dev,

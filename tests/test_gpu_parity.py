@@ -604,6 +604,18 @@ def test_glue_ops_match_oracle():
         assert np.array_equal(R.to_host_f32(z), want)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("k,s,p", [(3, 2, 1), (3, 1, 1), (3, 2, 0), (3, 3, 1), (2, 2, 0), (5, 2, 2)])
+def test_maxpool_windows(k, s, p, dtype):
+    # the 3x3 window has a kernel of its own (nine unconditional loads); other windows walk their taps
+    rng = np.random.default_rng(80 + k + s + p)
+    for shape in ((2, 17, 21, 64), (1, 8, 8, 8), (3, 5, 30, 40)):
+        x = W.quantize(rng.standard_normal(shape).astype(np.float32), dtype)
+        x[0, 0, 0, :] = -np.inf
+        y = B.sc_maxpool2d_nhwc(R.to_device(x, dtype), k, s, p)
+        assert np.array_equal(R.to_host_f32(y), oracle.maxpool2d_nhwc(x, k, s, p))
+
+
 def _run_network_both(ops, bs, batch_note=""):
     """Run an op list through the HIP path and through the oracle from the same synthetic input."""
     params = {}
