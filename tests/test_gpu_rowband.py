@@ -57,6 +57,18 @@ def test_band_heights_and_block_shapes(bh, sp, monkeypatch):
     assert B.sparse_conv_plan_tiles(layer.plan, 0)[0] == -bh
 
 
+def test_large_slabs(monkeypatch):
+    # more 16-byte pieces than one pass of the workgroup stages (19 rows of 127 pieces), and more than 128 slab rows
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", "3")
+    spec = spec_of(1, 6, 40, 168, 32, k=7, kw=3, s=3, sw=1, p=2, pw=1, d=2, dw=1, dtype="bf16", sp=0.5)
+    layer = check_layer(W.make_conv_inputs(spec, 1451))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_row_segments" and B.sparse_conv_plan_tiles(layer.plan, 0)[0] == -3
+    monkeypatch.setenv("SPARSE_CONV_BAND_HEIGHT", "1")
+    spec = spec_of(2, 1, 150, 8, 16, k=8, kw=3, s=1, sw=2, p=3, pw=1, d=19, dw=1, dtype="f16", sp=0.4)
+    layer = check_layer(W.make_conv_inputs(spec, 1452))
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_row_segments"
+
+
 def test_scatter_only_empty_and_single_row():
     spec = spec_of(2, 3, 18, 24, 64, k=7, s=2, p=3, dtype="bf16", sp=0.5)
     ci = W.make_conv_inputs(spec, 1460)
