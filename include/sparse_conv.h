@@ -132,7 +132,8 @@ sc_status sparse_conv_plan_set_filters(sc_plan* plan, const void* w_dev, void* h
  * launches that divide K among workgroups -- chosen automatically on deep layers, and by SC_OPT_SPLIT_K /
  * SC_OPT_STREAM_K; sparse_conv_plan_kernel reports "tile_split_k", "tile_stream_k", or "tile_slab" with more
  * workgroups than output tiles -- keep partial sums and arrival counters there; and plans of 16-bit NHWC layers
- * with few input channels ("tile_row_segments", e.g. a 3-channel stem) rewrite a zero-margined copy of x there in
+ * with few input channels whose launch is "tile_row_segments" (forced tiles, compact operands or fused shortcuts on,
+ * e.g., a 3-channel stem; "band_row_segments" keeps no such state) rewrite a zero-margined copy of x there in
  * every run.  Overlapping runs of such a plan race and give wrong results without an error: use one plan per stream.
  */
 sc_status sparse_conv_run(const sc_plan* plan, const void* x_dev, const float* bias_dev, void* y_dev,
@@ -211,7 +212,7 @@ sc_status sparse_conv_plan_tiles(const sc_plan* plan, int32_t which, int32_t* ti
                                  int64_t* workgroups);
 
 /* Name of the kernel the sparse (which = 0) or dense (which = 1) launch uses: "band",
- * "band_alternating", "band_tap", "band_stream", "tile_row_panel", "tile_split_k", "tile_masked_store", "tile_stream_k", "tile_lds_direct",
+ * "band_alternating", "band_tap", "band_stream", "band_row_segments", "tile_row_panel", "tile_slab", "tile_split_k", "tile_masked_store", "tile_stream_k", "tile_lds_direct",
  * "tile_registers", "tile_row_segments", "tile_elements" or "depthwise".
  * A static string; NULL for a NULL plan or an unknown `which`. */
 const char* sparse_conv_plan_kernel(const sc_plan* plan, int32_t which);

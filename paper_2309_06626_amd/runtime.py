@@ -179,7 +179,7 @@ def plan_shortcut_fusions(ops, layers: Dict[str, "ConvLayer"], row_formats: Opti
             # the fused launch must not be a step down from the plain one: the same band kernel, or a tiled
             # kernel where the plain run takes one too (runs with compact operands always do)
             if not fmt.get(mine, False):
-                if plain in ("band", "band_stream", "tile_row_panel"):
+                if plain in ("band", "band_stream", "band_row_segments", "tile_row_panel"):
                     continue
                 if plain in ("band_alternating", "band_tap") and B.sparse_conv_plan_fused_kernel(plan, 1 if dense else 0) != plain:
                     continue
