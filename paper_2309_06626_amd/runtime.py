@@ -239,6 +239,9 @@ class NetworkRunner:
                 out, other, relu = fused_conv[op.spec.name]
                 xf, yf = fmt(op.src), fmt(out)
                 t[out] = torch.empty_like(t[other])
+                if tune and xf == B.SC_ROWS_DENSE and yf == B.SC_ROWS_DENSE:
+                    # (the measured tile serves the fused launch too; its output buffer is scratch for the measurement)
+                    B.sparse_conv_plan_tune(layer.plan, t[op.src], layer.bias, t[out])
                 self.calls.append(B.prepared_run_residual(layer.plan, t[op.src], layer.bias, t[other], t[out], relu, xf, yf,
                                                           dense=dense))
                 continue
