@@ -561,7 +561,8 @@ static int device_cus();
 
 // Band kernel of the small-channel layers (row-segment K order): window starts must be 4-byte aligned in the slab, K
 // at most 24 groups of 16 bytes, 64 output channels per workgroup, bands of at most 512 output pixels.  The tallest
-// such band that still leaves four workgroups per compute unit.
+// such band that still leaves four workgroups per compute unit.  SPARSE_CONV_BAND_KERNEL=none keeps such a layer on the
+// tiled row-segment kernel, SPARSE_CONV_BAND_HEIGHT=<bh> fixes the band height (tuning and tests).
 static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
   BandPlan bp;
   std::memset(&bp, 0, sizeof(bp));
