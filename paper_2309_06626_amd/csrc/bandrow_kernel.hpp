@@ -106,15 +106,16 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
       r_pre[b][mi] = p.row_idx ? p.band_rows[r_lo + jc] : r_lo + jc;
     }
   const int zc = t % CPR, zr = t / CPR;
-  // (one register per mask byte: packed into fewer, the bytes would be waited for right here)
-  int mk[ZIT];
+  unsigned char mk[ZIT];
+  if (p.zero_fill) {
 #pragma unroll
-  for (int u = 0; u < ZIT; ++u) {
-    const int r = min(r_lo + zr + u * RPI, r_hi - 1);         // clamped, and fetched by dense runs too: no branch
-    mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
+    for (int u = 0; u < ZIT; ++u) {
+      const int r = min(r_lo + zr + u * RPI, r_hi - 1);       // clamped: the loads stay unconditional
+      mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
+    }
   }
   float bias_v = 0.0f;
-  if (p.bias) bias_v = p.bias[min(n0 + (t & (BN - 1)), p.c_out - 1)];      // (every thread: no divergent branch around a load)
+  if (t < BN && p.bias && n0 + t < p.c_out) bias_v = p.bias[n0 + t];
 
   // ---- filters and slab: every load of a pass is issued before the first LDS write ---------------------------------
   // filters: 64 rows of `groups` 16-byte groups, 400 bytes apart in LDS; four threads per row
@@ -124,7 +125,8 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
 #pragma unroll
     for (int u = 0; u < kRowBandMostGroups / 4; ++u) {
       const int g = (t & 3) + 4 * u;
-      wv[u] = gw[min(g, groups - 1)];          // (groups beyond K re-read the last one and are not stored)
+      wv[u] = v4i{0, 0, 0, 0};
+      if (g < groups) wv[u] = gw[g];
     }
   }
   // slab: 16-byte pieces of LDS, piece i = (slab row i / cpr, piece i % cpr of the row); a piece inside the input row
@@ -140,31 +142,23 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
     const unsigned char* ximg = reinterpret_cast<const unsigned char*>(x) + (int64_t)img * p.h * row_bytes;
     const int e0 = (lead & 15) ? lead >> 4 : -1, e1 = ((lead + row_bytes) & 15) ? (lead + row_bytes) >> 4 : -1;
     // end piece e = (row e / 2, front or back end): its eight halfwords, those outside the row zero
-    auto end_piece_load = [&](int e, unsigned short (&hw)[8]) -> int {
+    auto end_piece = [&](int e, v4i* v) -> int {
       const int r = e >> 1, c = (e & 1) ? e1 : e0;
       const int iy = iy_base + r;
-      const bool have = e < 2 * in_rows && c >= 0 && (unsigned)iy < (unsigned)p.h;
-      const unsigned char* src = ximg + (int64_t)min(max(iy, 0), p.h - 1) * row_bytes;
-      const int at = 16 * max(c, 0) - lead;
-#pragma unroll
-      for (int k = 0; k < 8; ++k)          // every load unconditional at a clamped address, the choice afterwards
-        hw[k] = *reinterpret_cast<const unsigned short*>(src + min(max(at + 2 * k, 0), row_bytes - 2));
-      return have ? r * cpr + c : -1;
-    };
-    auto end_piece_value = [&](int end_at, const unsigned short (&hw)[8]) -> v4i {
-      const int at = 16 * (end_at - fast_div(end_at, q.div_cpr_mul, q.div_cpr_shift) * cpr) - lead;
-      v4i v;
+      if (e >= 2 * in_rows || c < 0 || (unsigned)iy >= (unsigned)p.h) return -1;
+      const unsigned char* src = ximg + (int64_t)iy * row_bytes;
+      const int at = 16 * c - lead;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        const unsigned lo = at + 4 * k >= 0 && at + 4 * k < row_bytes ? hw[2 * k] : 0;
-        const unsigned hi = at + 4 * k + 2 >= 0 && at + 4 * k + 2 < row_bytes ? hw[2 * k + 1] : 0;
-        v[k] = (int)(lo | (hi << 16));
+        unsigned short lo = 0, hi = 0;
+        if (at + 4 * k >= 0 && at + 4 * k < row_bytes) lo = *reinterpret_cast<const unsigned short*>(src + at + 4 * k);
+        if (at + 4 * k + 2 >= 0 && at + 4 * k + 2 < row_bytes) hi = *reinterpret_cast<const unsigned short*>(src + at + 4 * k + 2);
+        (*v)[k] = (int)((unsigned)lo | ((unsigned)hi << 16));
       }
-      return v;
+      return r * cpr + c;
     };
     for (int base = 0; base < pieces; base += kThreads * U) {
-      v4i v[U];
-      unsigned short ehw[8];
+      v4i v[U], ev;
       bool whole[U];
       int end_at = -1;
 #pragma unroll
@@ -176,12 +170,11 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
         const int iy = iy_base + r;
         const bool row_ok = (unsigned)iy < (unsigned)p.h;
         const unsigned char* src = ximg + (int64_t)(row_ok ? iy : 0) * row_bytes;
+        v[u] = v4i{0, 0, 0, 0};
         whole[u] = i < pieces && !(row_ok && (c == e0 || c == e1));      // (end pieces belong to end_piece)
-        // (unconditional at a clamped address, zeros chosen afterwards: a load inside a divergent branch is waited for there)
-        __builtin_memcpy(&v[u], reinterpret_cast<const unsigned short*>(src + min(max(at, 0), row_bytes - 16)), 16);
-        if (!(i < pieces && row_ok && at >= 0 && at + 16 <= row_bytes)) v[u] = v4i{0, 0, 0, 0};
+        if (i < pieces && row_ok && at >= 0 && at + 16 <= row_bytes) __builtin_memcpy(&v[u], reinterpret_cast<const unsigned short*>(src + at), 16);
       }
-      if (base == 0) end_at = end_piece_load(t, ehw);
+      if (base == 0) end_at = end_piece(t, &ev);
       if (base == 0) {
         // zero fill of the band's dropped rows (Alg. 2, mask == 0 branch): issued behind the loads, drains under the
         // matrix work
@@ -202,7 +195,7 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
           const int g = (t & 3) + 4 * u;
           if (g < groups) *reinterpret_cast<v4i*>(smem + (t >> 2) * kRowBandFilterPitch + g * 16) = wv[u];
         }
-        if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = end_piece_value(end_at, ehw);
+        if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -211,9 +204,9 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
       }
     }
     for (int e = t + kThreads; e < 2 * in_rows; e += kThreads) {       // (slabs of more than 128 rows)
-      unsigned short hw[8];
-      const int end_at = end_piece_load(e, hw);
-      if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = end_piece_value(end_at, hw);
+      v4i ev;
+      const int end_at = end_piece(e, &ev);
+      if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
     }
     if (t < 16) *reinterpret_cast<v4i*>(smem + kRowBandZeroAt + t * 16) = v4i{0, 0, 0, 0};
     if (t < BN) s_bias[t] = bias_v;
