@@ -10,7 +10,8 @@
 //   * stages the band's input rows once into LDS, each with zero margins left and right and zero rows above / below
 //     the image, so that no window entry needs a bounds check: a lane's fragment of (ky, group) is the 16 bytes at
 //     [its pixel's slab address] + ky * row pitch + 16 * group -- immediates on one register per 32-row block;
-//   * keeps the 64 filter rows of its channel tile in LDS (400 bytes apart: sixteen rows, sixteen bank groups);
+//   * keeps the 64 filter rows of its channel tile in LDS (an odd number of 16-byte groups apart: sixteen rows, sixteen
+//     bank groups);
 //   * masks the entries of a window row's last group that lie beyond the window (their filter entries are zero, but a
 //     non-finite neighbour pixel must not meet them);
 //   * writes the band's outputs once: results of kept rows, zeros of dropped rows (Alg. 2), as the other band kernels.
@@ -19,18 +20,18 @@
 //
 //   workgroup  = one band (BH output rows x all Wo columns of one image) x 64 output channels, four wavefronts
 //   wavefront  = 64-row MFMA block pairs b = wave, wave + 4, ... of the band's kept rows
-//   LDS        = filters [64][400 B] | 256 B zeros | bias [64] | slab [IH rows][pitch]
+//   LDS        = filters [64][fpitch] | 256 B zeros | bias [64] | slab [IH rows][pitch]
 #pragma once
 #include "band_kernel.hpp"
 #include "igemm_dma_kernel.hpp"
 
 namespace sc {
 
-constexpr int kRowBandFilterPitch = 400;                       // bytes between filter rows in LDS
-constexpr int kRowBandMostGroups = 24;                         // 16-byte groups of K at most (24 * 16 = 384 <= pitch)
-constexpr int kRowBandFilterBytes = 64 * kRowBandFilterPitch;
-constexpr int kRowBandZeroAt = kRowBandFilterBytes, kRowBandBiasAt = kRowBandZeroAt + 256;
-constexpr int kRowBandSlabAt = kRowBandBiasAt + 256;
+constexpr int kRowBandMostGroups = 24;                         // 16-byte groups of K at most
+// LDS layout: 64 filter rows `fpitch` bytes apart, 256 bytes of zeros, 64 bias floats, the slab.  fpitch = 16 * (an odd
+// number of groups >= K's): sixteen consecutive rows then start in sixteen different 16-byte bank groups.
+constexpr int rowband_filter_pitch(int groups) { return 16 * (groups | 1); }
+constexpr int rowband_slab_at(int groups) { return 64 * rowband_filter_pitch(groups) + 512; }
 constexpr int kRowBandMaxRows = 512;                           // tallest band (output rows x width)
 
 struct RowBandParams {
@@ -41,6 +42,7 @@ struct RowBandParams {
   int32_t gpw;               // 16-byte groups per window row (ceil(kw * Cin / 8))
   int32_t groups;            // kh * gpw
   int32_t tail;              // entries of a window row's last group that lie inside the window (1 .. 8)
+  int32_t fpitch;            // bytes between filter rows in LDS: rowband_filter_pitch(groups)
   uint32_t div_cpr_mul, div_cpr_shift;   // n / (pitch / 16) as (n * mul) >> shift
 };
 
@@ -51,8 +53,9 @@ __device__ __forceinline__ v4i lds_load_4dwords(unsigned addr) {
 }
 
 // KH, GPW > 0 fix the window rows and the groups per window row at compile time (the K loop unrolls); 0 = run-time shape.
+// (32-row blocks leave room for four wavefronts per SIMD, 64-row blocks for three)
 template <int DT, int MI, int KH, int GPW>
-__global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParams q) {
+__global__ __launch_bounds__(kThreads, MI == 1 ? 4 : 3) void bandrow_kernel(const RowBandParams q) {
   using E = Elem<DT>;
   using T = typename E::T;
   constexpr int EB = sizeof(T);
@@ -69,7 +72,9 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
 
   extern __shared__ __align__(16) unsigned char smem[];
   const unsigned lds0 = lds_addr_of(smem);
-  float* s_bias = reinterpret_cast<float*>(smem + kRowBandBiasAt);
+  const int fpitch = KH ? rowband_filter_pitch(KH * GPW) : q.fpitch;
+  const int zero_at = 64 * fpitch, bias_at = zero_at + 256, slab_at = bias_at + 256;
+  float* s_bias = reinterpret_cast<float*>(smem + bias_at);
 
   SC_STAMP(0);
   const int nwg = p.n_bands * p.n_tiles;
@@ -118,7 +123,7 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
   if (t < BN && p.bias && n0 + t < p.c_out) bias_v = p.bias[n0 + t];
 
   // ---- filters and slab: every load of a pass is issued before the first LDS write ---------------------------------
-  // filters: 64 rows of `groups` 16-byte groups, 400 bytes apart in LDS; four threads per row
+  // filters: 64 rows of `groups` 16-byte groups, fpitch bytes apart in LDS; four threads per row
   v4i wv[kRowBandMostGroups / 4];
   {
     const v4i* gw = reinterpret_cast<const v4i*>(static_cast<const T*>(p.wp) + (int64_t)(n0 + (t >> 2)) * p.k_stride);
@@ -193,22 +198,22 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
 #pragma unroll
         for (int u = 0; u < kRowBandMostGroups / 4; ++u) {
           const int g = (t & 3) + 4 * u;
-          if (g < groups) *reinterpret_cast<v4i*>(smem + (t >> 2) * kRowBandFilterPitch + g * 16) = wv[u];
+          if (g < groups) *reinterpret_cast<v4i*>(smem + (t >> 2) * fpitch + g * 16) = wv[u];
         }
-        if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
+        if (end_at >= 0) *reinterpret_cast<v4i*>(smem + slab_at + end_at * 16) = ev;
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = base + u * kThreads + t;
-        if (whole[u]) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + i * 16) = v[u];
+        if (whole[u]) *reinterpret_cast<v4i*>(smem + slab_at + i * 16) = v[u];
       }
     }
     for (int e = t + kThreads; e < 2 * in_rows; e += kThreads) {       // (slabs of more than 128 rows)
       v4i ev;
       const int end_at = end_piece(e, &ev);
-      if (end_at >= 0) *reinterpret_cast<v4i*>(smem + kRowBandSlabAt + end_at * 16) = ev;
+      if (end_at >= 0) *reinterpret_cast<v4i*>(smem + slab_at + end_at * 16) = ev;
     }
-    if (t < 16) *reinterpret_cast<v4i*>(smem + kRowBandZeroAt + t * 16) = v4i{0, 0, 0, 0};
+    if (t < 16) *reinterpret_cast<v4i*>(smem + zero_at + t * 16) = v4i{0, 0, 0, 0};
     if (t < BN) s_bias[t] = bias_v;
   }
   SC_STAMP(1);
@@ -220,8 +225,8 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
   v4i tail_mask;
 #pragma unroll
   for (int i = 0; i < 4; ++i) tail_mask[i] = q.tail >= 2 * i + 2 ? -1 : q.tail == 2 * i + 1 ? 0xffff : 0;
-  const unsigned zaddr = lds0 + kRowBandZeroAt;
-  const unsigned slab = lds0 + kRowBandSlabAt;
+  const unsigned zaddr = lds0 + zero_at;
+  const unsigned slab = lds0 + slab_at;
   const int steps = (groups + 1) >> 1;
   const int ky_pitch = p.dil_h * q.pitch;     // bytes between window rows in the slab
   const int nblk = (cnt + 32 * MI - 1) / (32 * MI);
@@ -263,9 +268,9 @@ __global__ __launch_bounds__(kThreads, 3) void bandrow_kernel(const RowBandParam
       last = part == gpw - 1;
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) xf[mi] = lds_load_4dwords(g_ok ? a_base[mi] + off : zaddr);
-      const unsigned wat = lds0 + (unsigned)(fp * kRowBandFilterPitch + g * 16);   // (groups beyond K: zeros for both operands)
+      const unsigned wat = lds0 + (unsigned)(fp * fpitch + g * 16);   // (groups beyond K: zeros for both operands)
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) wf[ni] = lds_load16(g_ok ? wat + ni * 32 * kRowBandFilterPitch : zaddr);
+      for (int ni = 0; ni < NI; ++ni) wf[ni] = lds_load16(g_ok ? wat + ni * 32 * fpitch : zaddr);
       if constexpr (GPW == 0) {          // next step's window row and group (gpw >= 1: at most two rows further)
         part += 2;
         if (part >= gpw) { part -= gpw; ++ky; }

@@ -579,7 +579,7 @@ static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
   const int forced_bh = env ? std::atoi(env) : 0;
   auto fits = [&](int bh) {
     const int64_t in_rows = (int64_t)(bh - 1) * d.stride_h + (int64_t)(d.kh - 1) * d.dil_h + 1;
-    return (int64_t)bh * g.wo <= kRowBandMaxRows && kRowBandSlabAt + in_rows * pitch <= (int64_t)kLdsLimit;
+    return (int64_t)bh * g.wo <= kRowBandMaxRows && rowband_slab_at(d.kh * gpw) + in_rows * pitch <= (int64_t)kLdsLimit;
   };
   if (!fits(1)) return bp;
   int bh = 1;
@@ -598,9 +598,9 @@ static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
   bp.rb_in_rows = (bh - 1) * d.stride_h + (d.kh - 1) * d.dil_h + 1;
   bp.rb_gpw = gpw;
   bp.rb_tail = d.kw * d.c_in - (gpw - 1) * 8;
-  bp.b_bytes = kRowBandFilterBytes;
+  bp.b_bytes = (size_t)64 * rowband_filter_pitch(d.kh * gpw);
   bp.x_bytes = (size_t)bp.rb_in_rows * pitch;
-  bp.lds = kRowBandSlabAt + bp.x_bytes;
+  bp.lds = rowband_slab_at(d.kh * gpw) + bp.x_bytes;
   return bp;
 }
 
@@ -1198,9 +1198,11 @@ static sc_status launch_conv(const sc_plan* pl, bool dense, const void* x, const
       rq.b = q;
       rq.pitch = b.rb_pitch; rq.left = b.rb_left; rq.in_rows = b.rb_in_rows;
       rq.gpw = b.rb_gpw; rq.groups = d.kh * b.rb_gpw; rq.tail = b.rb_tail;
+      rq.fpitch = rowband_filter_pitch(rq.groups);
       magic_div((uint32_t)(b.rb_pitch / 16), &rq.div_cpr_mul, &rq.div_cpr_shift);
       int mi_idx = 0;
       band_units(dense || identity ? (double)(std::min(b.bh, g.ho) * g.wo) : (double)b.max_kept, &mi_idx);
+      if (4 * b.lds <= kLdsLimit) mi_idx = 0;      // four workgroups per compute unit: only the 32-row form has the registers
       RowBandLaunchFn fn = bandrow_kernel_for(d.dtype == SC_BF16 ? kBF16 : kF16, mi_idx + 1, d.kh, b.rb_gpw);
       if (!fn) return SC_ERR_UNSUPPORTED;
       SC_HIP(fn(rq, b.lds, stream));
