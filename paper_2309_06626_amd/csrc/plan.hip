@@ -561,7 +561,7 @@ static int device_cus();
 
 // Band kernel of the small-channel layers (row-segment K order): window starts must be 4-byte aligned in the slab, K
 // at most 24 groups of 16 bytes, 64 output channels per workgroup, bands of at most 512 output pixels.  The tallest
-// such band that still leaves four workgroups per compute unit.  SPARSE_CONV_BAND_KERNEL=none keeps such a layer on the
+// such band that still leaves a workgroup per compute unit.  SPARSE_CONV_BAND_KERNEL=none keeps such a layer on the
 // tiled row-segment kernel, SPARSE_CONV_BAND_HEIGHT=<bh> fixes the band height (tuning and tests).
 static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
   BandPlan bp;
@@ -585,7 +585,8 @@ static BandPlan plan_rowband(const sc_conv_desc& d, const Geometry& g) {
   int bh = 1;
   while (bh < g.ho && fits(bh + 1)) ++bh;
   const int n_tiles = (d.c_out + 63) / 64;
-  while (bh > 1 && (int64_t)d.n * ((g.ho + bh - 1) / bh) * n_tiles < 4 * (int64_t)device_cus()) bh = (bh + 1) / 2;
+  // (measured on the 7x7 stem at batch 4 .. 64: halving pays only while the bands do not cover the compute units once)
+  while (bh > 1 && (int64_t)d.n * ((g.ho + bh - 1) / bh) * n_tiles < (int64_t)device_cus()) bh = (bh + 1) / 2;
   if (forced_bh > 0) { if (!fits(forced_bh)) return bp; bh = forced_bh; }
   bp.ok = bp.rowband = true;
   bp.ni = 2; bp.ni_idx = 1;
