@@ -140,13 +140,6 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
   // zero fill: thread (zr, zc) covers 16-byte group zc of rows r_lo + zr + u*RPI
   const int zc = t % CPR, zr = t / CPR;
   unsigned char mk[ZIT];
-  if (p.zero_fill) {
-#pragma unroll
-    for (int u = 0; u < ZIT; ++u) {
-      const int r = min(r_lo + zr + u * RPI, r_hi - 1);       // clamped: the loads stay unconditional
-      mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
-    }
-  }
 
   float bias_v = 0.0f;
   if (t < BN && p.bias && n0 + t < p.c_out) bias_v = p.bias[n0 + t];
@@ -190,6 +183,15 @@ __global__ __launch_bounds__(kThreads) void band_kernel(const BandParams p) {
     for (int qb = (qx0 & ~63) + wave * 64; qb < q_end; qb += kThreads) {
       const int g = swz(qb + lane) - qx0;
       if (g >= 0 && g < nx) dma16(gx + g, s_x + qb);
+    }
+  }
+  // the mask bytes of the zero fill, behind the transfers: the compiler packs them four to a register and waits for
+  // them right here, which must not hold back the issue of the slabs
+  if (p.zero_fill) {
+#pragma unroll
+    for (int u = 0; u < ZIT; ++u) {
+      const int r = min(r_lo + zr + u * RPI, r_hi - 1);       // clamped: the loads stay unconditional
+      mk[u] = p.mask[p.mask_spatial ? r - img * ho_wo : r];
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
