@@ -156,3 +156,29 @@ def test_random_small_channel_layers(seed):
             os.environ.pop("SPARSE_CONV_BAND_HEIGHT", None)
         assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_row_segments"
         done += 1
+
+
+def test_refreshed_mask_and_filters_on_one_plan():
+    """Alg. 1, main loop, on a stem-like layer: new row masks and new filters go into the same plan step by step
+    (sparse_conv_plan_set_mask rebuilds the band tables, _set_filters the row-segment packing)."""
+    spec = spec_of(2, 3, 38, 48, 64, k=7, s=2, p=3, dtype="bf16", sp=0.5)
+    ci = W.make_conv_inputs(spec, 1495)
+    layer = R.ConvLayer(spec, ci.w, ci.bias, ci.mask)
+    assert B.sparse_conv_plan_kernel(layer.plan, 0) == "band_row_segments"
+    x = R.to_device(ci.x, spec.dtype)
+    rng = np.random.default_rng(1496)
+    keep = int(ci.mask.sum())
+    for step in range(3):
+        mask = np.zeros(spec.m, np.uint8)
+        mask[rng.permutation(spec.m)[:keep]] = 1
+        w_step = W.quantize(ci.w + np.float32(0.02) * rng.standard_normal(ci.w.shape).astype(np.float32), spec.dtype)
+        B.sparse_conv_plan_set_mask(layer.plan, torch.from_numpy(mask).to("cuda:0"))
+        B.sparse_conv_plan_set_filters(layer.plan, R.to_device(w_step, spec.dtype))
+        assert np.array_equal(B.plan_row_idx(layer.plan).cpu().numpy(), oracle.compact_rows(mask))
+        y = layer.new_output(fill_nan=True)
+        layer.sparse(x, y)
+        torch.cuda.synchronize()
+        ref, absum = oracle.masked_conv2d(spec, ci.x, w_step, ci.bias, mask, want_absum=True)
+        g, bits = rows_view(spec, R.to_host_f32(y)), rows_view(spec, R.bits_of(y))
+        assert (bits[mask == 0] == 0).all()
+        assert_close(g[mask == 1], rows_view(spec, ref)[mask == 1], rows_view(spec, absum)[mask == 1], TOL["bf16"], f"step {step}")
